@@ -1,0 +1,430 @@
+/*
+ * fsd_oracle.c -- TEST INFRASTRUCTURE, not the product.
+ *
+ * A plain, slow, float64 CPU statement of the candidate-verification step of
+ * Fuzzy Speculative Decoding, written directly from the paper's definitions.
+ * Only the tests, the smoke check and the bench's cpu_baseline leg may call it;
+ * the HIP library shares no code, header, table or helper with this file.
+ *
+ * What follows the paper:
+ *   - softmax of a logits row ("next token distributions", Sec. 4 below eq. 4)
+ *   - KL(target || draft), JS, TV                       (App. C.1, C.2, C.3)
+ *   - FSD acceptance: accept position i iff Div <= T    (Sec. 4, eq. 4; Fig. 1
+ *     caption and App. D word the rejection as "exceeds T", which is the
+ *     reading taken here -- it differs from the strict "<" only at Div == T)
+ *   - stop at the first rejection, emit one token drawn from the unmodified
+ *     target distribution at that position (Sec. 4, paragraph after eq. 4);
+ *     when every candidate is accepted the token comes from the target row
+ *     after the last candidate (the usual bonus token of Sec. 3's SD loop)
+ *   - strict SD: accept iff min(1, p/q) > y, y ~ U(0,1) (Sec. 3, eq. 1-2);
+ *     on rejection resample from the positive part of p - q, normalised
+ *     (Sec. 3, eq. 3, read as the rule of the works cited there)
+ *   - token trees (Sec. 6.4): a node carries the acceptance bit of
+ *     (target row of its parent context, its own draft row); the deepest node
+ *     whose ancestors are all accepted wins, lowest index on ties.
+ *
+ * What the paper leaves open and this file fixes (the HIP side implements the
+ * same published/specified procedures independently):
+ *   - random numbers: Philox4x32-10 (Salmon et al., SC'11), key = seed,
+ *     counter = ((idx>>2) | stream<<30, b, offset_lo, offset_hi), word idx&3;
+ *     stream 0 = Gumbel noise over the vocabulary, stream 1 = SD uniforms
+ *   - u = (2*(word>>9) + 1) * 2^-24, exact in binary32, inside (0,1)
+ *   - Gumbel noise G = -flog(-flog(u)) where flog is a binary32 routine made
+ *     only of IEEE-exact operations (see flog32 below), so that token ids can
+ *     be compared bit for bit; the score z + G is one rounded binary32 add and
+ *     the token is the argmax, lowest index on ties.
+ *
+ * parity pins: tests/test_oracle_pins.py (closed forms, bounds, brute force at
+ * V=8, Philox known-answer vectors, chi-square of the sampler, SD frequencies).
+ * Unpinned: nothing the paper prints is numeric for this step, so agreement
+ * with the authors' own implementation ("T-scale parity") is unpinned.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORACLE_F32 0
+#define ORACLE_BF16 1
+
+#define ORACLE_DIV_KL 0
+#define ORACLE_DIV_JS 1
+#define ORACLE_DIV_TV 2
+
+#define ORACLE_SAMPLE 0
+#define ORACLE_GREEDY 1
+
+#define ST_NONFINITE 1 /* NaN, +inf, or a row that is -inf everywhere, in a row the method reads */
+#define ST_BAD_PARENT 2 /* tree: parent index outside [-1, j) */
+#define ST_TOO_DEEP 4   /* tree: a node deeper than max_depth */
+#define ST_BAD_TOKEN 8  /* strict SD: candidate token id outside [0, V) */
+
+int fsd_oracle_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ------------------------------------------------------------------ loads */
+
+static float bf16_bits_to_float(uint16_t h) {
+    uint32_t w = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &w, 4);
+    return f;
+}
+
+/* element i of a row-major logits buffer, as the binary32 value it encodes */
+static float load_f(const void* base, size_t i, int dt) {
+    if (dt == ORACLE_BF16) return bf16_bits_to_float(((const uint16_t*)base)[i]);
+    return ((const float*)base)[i];
+}
+
+/* ------------------------------------------------------------ Philox4x32 */
+
+void fsd_oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int r = 0; r < 10; ++r) {
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* the 32-bit word the method draws for (stream, sequence b, index idx) */
+uint32_t fsd_oracle_random_word(uint64_t seed, uint64_t offset, uint32_t stream, uint32_t b, uint32_t idx) {
+    uint32_t ctr[4] = {(idx >> 2) | (stream << 30), b, (uint32_t)offset, (uint32_t)(offset >> 32)};
+    uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t out[4];
+    fsd_oracle_philox4x32_10(ctr, key, out);
+    return out[idx & 3];
+}
+
+/* ---------------------------------------------- binary32 Gumbel transform */
+
+/* uniform in (0,1): an odd 24-bit integer times 2^-24, exact in binary32 */
+float fsd_oracle_word_to_uniform(uint32_t w) {
+    return (float)(((w >> 9) << 1) | 1u) * 0x1p-24f;
+}
+
+/* natural log of a positive normal binary32 number from exact operations only:
+ * x = 2^e * m with m in [sqrt(1/2), sqrt(2)); ln m = 2 atanh(s), s = (m-1)/(m+1),
+ * atanh series to s^11 in Horner form with fused multiply-adds. */
+float fsd_oracle_flog32(float x) {
+    uint32_t bits;
+    memcpy(&bits, &x, 4);
+    int e = (int)(bits >> 23) - 127;
+    uint32_t mb = (bits & 0x007FFFFFu) | 0x3F800000u;
+    float m;
+    memcpy(&m, &mb, 4);
+    if (m >= 0x1.6a09e6p+0f) { m = m * 0.5f; e += 1; }
+    float num = m - 1.0f;
+    float den = m + 1.0f;
+    float s = num / den;
+    float s2 = s * s;
+    float poly = 0x1.745d18p-4f;              /* 1/11 */
+    poly = fmaf(poly, s2, 0x1.c71c72p-4f);    /* 1/9  */
+    poly = fmaf(poly, s2, 0x1.24924ap-3f);    /* 1/7  */
+    poly = fmaf(poly, s2, 0x1.99999ap-3f);    /* 1/5  */
+    poly = fmaf(poly, s2, 0x1.555556p-2f);    /* 1/3  */
+    poly = fmaf(poly, s2, 1.0f);
+    float lnm = (2.0f * s) * poly;
+    return fmaf((float)e, 0x1.62e43p-1f, lnm);
+}
+
+float fsd_oracle_gumbel(uint32_t w) {
+    float u = fsd_oracle_word_to_uniform(w);
+    float t = -fsd_oracle_flog32(u);
+    return -fsd_oracle_flog32(t);
+}
+
+/* ----------------------------------------------------------- row softmax */
+
+/* log-sum-exp of one row in float64; *bad set when the row holds NaN or +inf
+ * or is -inf everywhere (no distribution exists). */
+static double row_lse(const void* base, size_t off, long V, int dt, int* bad) {
+    double m = -INFINITY;
+    int b = 0;
+    for (long v = 0; v < V; ++v) {
+        double z = (double)load_f(base, off + (size_t)v, dt);
+        if (isnan(z) || z == INFINITY) b = 1;
+        if (z > m) m = z;
+    }
+    if (m == -INFINITY) b = 1;
+    if (b) { *bad = 1; return NAN; }
+    double S = 0.0;
+    for (long v = 0; v < V; ++v) S += exp((double)load_f(base, off + (size_t)v, dt) - m);
+    return m + log(S);
+}
+
+/* KL(p||q), JS(p,q), TV(p,q) for p = softmax(target row), q = softmax(draft row)
+ * (App. C.1-C.3), natural logarithm, 0 log 0 = 0.  out = {KL, JS, TV};
+ * lse = {lse_target, lse_draft}. Returns non-zero when either row is unusable. */
+int fsd_oracle_pair(const void* target, size_t toff, const void* draft, size_t doff, long V, int dt,
+                    double out[3], double lse[2]) {
+    int bad = 0;
+    double lt = row_lse(target, toff, V, dt, &bad);
+    double ld = row_lse(draft, doff, V, dt, &bad);
+    if (lse) { lse[0] = lt; lse[1] = ld; }
+    if (bad) { out[0] = out[1] = out[2] = NAN; return ST_NONFINITE; }
+    double kl = 0.0, js = 0.0, tv = 0.0;
+    for (long v = 0; v < V; ++v) {
+        double lp = (double)load_f(target, toff + (size_t)v, dt) - lt;
+        double lq = (double)load_f(draft, doff + (size_t)v, dt) - ld;
+        double p = exp(lp), q = exp(lq);
+        double m = 0.5 * (p + q);
+        if (p > 0.0) {
+            kl += p * (lp - lq);
+            js += 0.5 * p * log(p / m);
+        }
+        if (q > 0.0) js += 0.5 * q * log(q / m);
+        tv += fabs(p - q);
+    }
+    out[0] = kl; out[1] = js; out[2] = 0.5 * tv;
+    return 0;
+}
+
+/* -------------------------------------------------------------- sampling */
+
+/* Token from softmax(row) by Gumbel-max (mode SAMPLE) or argmax (GREEDY).
+ * gap (optional) = best score minus runner-up, a diagnostic for near ties. */
+static int32_t sample_row(const void* base, size_t off, long V, int dt, int mode, uint64_t seed,
+                          uint64_t offset, uint32_t b, float* gap) {
+    float best = -INFINITY, second = -INFINITY;
+    int32_t arg = -1;
+    for (long v = 0; v < V; ++v) {
+        float z = load_f(base, off + (size_t)v, dt);
+        float score = z;
+        if (mode == ORACLE_SAMPLE) {
+            float g = fsd_oracle_gumbel(fsd_oracle_random_word(seed, offset, 0u, b, (uint32_t)v));
+            score = z + g;
+        }
+        if (score > best || arg < 0) {
+            if (arg >= 0) second = best;
+            best = score; arg = (int32_t)v;
+        } else if (score > second) {
+            second = score;
+        }
+    }
+    if (gap) *gap = best - second;
+    return arg;
+}
+
+/* the row holds a usable distribution */
+static int row_is_bad(const void* base, size_t off, long V, int dt) {
+    int bad = 0;
+    (void)row_lse(base, off, V, dt, &bad);
+    return bad;
+}
+
+/* -------------------------------------------------------------- FSD chain */
+
+/* target [B,K+1,V], draft [B,K,V], cand [B,K].  Outputs: accept_len [B],
+ * out_tokens [B,K+1] (-1 padded), divs [B,K] (float64, chosen divergence),
+ * row_status [B], gap [B] (may be NULL). */
+int fsd_oracle_verify_chain(const void* target, const void* draft, const int32_t* cand, int B, int K,
+                            long V, int dt, int div_kind, double T, int mode, uint64_t seed,
+                            uint64_t offset, int32_t* accept_len, int32_t* out_tokens, double* divs,
+                            int32_t* row_status, float* gap) {
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        int status = 0;
+        int n = K;
+        for (int i = 0; i < K; ++i) {
+            double d3[3];
+            size_t toff = ((size_t)b * (size_t)(K + 1) + (size_t)i) * (size_t)V;
+            size_t doff = ((size_t)b * (size_t)K + (size_t)i) * (size_t)V;
+            status |= fsd_oracle_pair(target, toff, draft, doff, V, dt, d3, NULL);
+            double d = d3[div_kind];
+            divs[(size_t)b * K + i] = d;
+            int ok = (d <= T); /* NaN compares false */
+            if (!ok && i < n) n = i;
+        }
+        size_t soff = ((size_t)b * (size_t)(K + 1) + (size_t)n) * (size_t)V;
+        if (!status && row_is_bad(target, soff, V, dt)) status |= ST_NONFINITE;
+        for (int i = 0; i <= K; ++i) out_tokens[(size_t)b * (K + 1) + i] = -1;
+        if (gap) gap[b] = INFINITY;
+        if (status) {
+            accept_len[b] = 0;
+        } else {
+            accept_len[b] = n;
+            for (int i = 0; i < n; ++i) out_tokens[(size_t)b * (K + 1) + i] = cand[(size_t)b * K + i];
+            out_tokens[(size_t)b * (K + 1) + n] =
+                sample_row(target, soff, V, dt, mode, seed, offset, (uint32_t)b, gap ? &gap[b] : NULL);
+        }
+        row_status[b] = status;
+    }
+    return 0;
+}
+
+/* --------------------------------------------------------------- FSD tree */
+
+/* target [B,N+1,V] (row 0 = root context, row j+1 = context after node j),
+ * draft [B,N,V], node_tokens [B,N], parent [B,N] (-1 = child of the root,
+ * parent[j] < j).  Outputs: path_len [B], path_nodes [B,max_depth] (-1 padded),
+ * out_tokens [B,max_depth+1] (-1 padded), divs [B,N], row_status [B]. */
+int fsd_oracle_verify_tree(const void* target, const void* draft, const int32_t* node_tokens,
+                           const int32_t* parent, int B, int N, int max_depth, long V, int dt,
+                           int div_kind, double T, int mode, uint64_t seed, uint64_t offset,
+                           int32_t* path_len, int32_t* path_nodes, int32_t* out_tokens, double* divs,
+                           int32_t* row_status, float* gap) {
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        int status = 0;
+        const int32_t* par = parent + (size_t)b * N;
+        int* depth = (int*)malloc(sizeof(int) * (size_t)(N > 0 ? N : 1));
+        char* live = (char*)malloc((size_t)(N > 0 ? N : 1));
+        for (int j = 0; j < N; ++j)
+            if (par[j] < -1 || par[j] >= j) status |= ST_BAD_PARENT;
+        int win = -1, win_depth = 0;
+        if (!(status & ST_BAD_PARENT)) {
+            for (int j = 0; j < N; ++j) {
+                depth[j] = par[j] < 0 ? 1 : depth[par[j]] + 1;
+                if (depth[j] > max_depth) status |= ST_TOO_DEEP;
+            }
+        }
+        for (int j = 0; j < N; ++j) {
+            double d3[3];
+            double d = NAN;
+            if (!(status & ST_BAD_PARENT)) {
+                size_t toff = ((size_t)b * (size_t)(N + 1) + (size_t)(par[j] + 1)) * (size_t)V;
+                size_t doff = ((size_t)b * (size_t)N + (size_t)j) * (size_t)V;
+                status |= fsd_oracle_pair(target, toff, draft, doff, V, dt, d3, NULL);
+                d = d3[div_kind];
+            }
+            divs[(size_t)b * N + j] = d;
+            if (!(status & ST_BAD_PARENT)) {
+                int ok = (d <= T);
+                live[j] = (char)(ok && (par[j] < 0 || live[par[j]]));
+                if (live[j] && depth[j] > win_depth) { win = j; win_depth = depth[j]; }
+            }
+        }
+        size_t soff = ((size_t)b * (size_t)(N + 1) + (size_t)(win + 1)) * (size_t)V;
+        if (!status && row_is_bad(target, soff, V, dt)) status |= ST_NONFINITE;
+        for (int i = 0; i < max_depth; ++i) path_nodes[(size_t)b * max_depth + i] = -1;
+        for (int i = 0; i <= max_depth; ++i) out_tokens[(size_t)b * (max_depth + 1) + i] = -1;
+        if (gap) gap[b] = INFINITY;
+        if (status) {
+            path_len[b] = 0;
+        } else {
+            path_len[b] = win_depth;
+            int j = win;
+            for (int i = win_depth - 1; i >= 0; --i) {
+                path_nodes[(size_t)b * max_depth + i] = j;
+                out_tokens[(size_t)b * (max_depth + 1) + i] = node_tokens[(size_t)b * N + j];
+                j = par[j];
+            }
+            out_tokens[(size_t)b * (max_depth + 1) + win_depth] =
+                sample_row(target, soff, V, dt, mode, seed, offset, (uint32_t)b, gap ? &gap[b] : NULL);
+        }
+        row_status[b] = status;
+        free(depth);
+        free(live);
+    }
+    return 0;
+}
+
+/* -------------------------------------------------------------- strict SD */
+
+/* Token from the normalised positive part of p - q by Gumbel-max over
+ * ln(p_v - q_v) + G_v; falls back to p when p == q everywhere. */
+static int32_t sample_residual(const void* target, size_t toff, const void* draft, size_t doff, long V,
+                               int dt, int mode, uint64_t seed, uint64_t offset, uint32_t b,
+                               double lse_t, double lse_d, double* gap) {
+    double best = -INFINITY, second = -INFINITY;
+    int32_t arg = -1;
+    for (long v = 0; v < V; ++v) {
+        double p = exp((double)load_f(target, toff + (size_t)v, dt) - lse_t);
+        double q = exp((double)load_f(draft, doff + (size_t)v, dt) - lse_d);
+        double r = p - q;
+        if (!(r > 0.0)) continue;
+        double score = log(r);
+        if (mode == ORACLE_SAMPLE)
+            score += (double)fsd_oracle_gumbel(fsd_oracle_random_word(seed, offset, 0u, b, (uint32_t)v));
+        if (score > best || arg < 0) {
+            if (arg >= 0) second = best;
+            best = score; arg = (int32_t)v;
+        } else if (score > second) {
+            second = score;
+        }
+    }
+    if (gap) *gap = best - second;
+    return arg;
+}
+
+/* Same tensors as the chain call.  log_ratio [B,K] = ln p(x_i) - ln q(x_i);
+ * margin [B,K] = min(0, log_ratio) - ln u_i (accepted iff > 0), for near-tie
+ * reporting; gap [B] = sampler runner-up gap (float64). */
+int sd_oracle_verify_chain(const void* target, const void* draft, const int32_t* cand, int B, int K,
+                           long V, int dt, int mode, uint64_t seed, uint64_t offset,
+                           int32_t* accept_len, int32_t* out_tokens, double* log_ratio, double* margin,
+                           int32_t* row_status, double* gap) {
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        int status = 0;
+        int n = K;
+        double lse_n[2] = {NAN, NAN};
+        for (int i = 0; i < K; ++i) {
+            size_t toff = ((size_t)b * (size_t)(K + 1) + (size_t)i) * (size_t)V;
+            size_t doff = ((size_t)b * (size_t)K + (size_t)i) * (size_t)V;
+            int bad = 0;
+            double lt = row_lse(target, toff, V, dt, &bad);
+            double ld = row_lse(draft, doff, V, dt, &bad);
+            int32_t x = cand[(size_t)b * K + i];
+            double ratio = NAN, mar = NAN;
+            int ok = 0;
+            if (bad) status |= ST_NONFINITE;
+            if (x < 0 || x >= V) status |= ST_BAD_TOKEN;
+            if (!bad && x >= 0 && x < V) {
+                double lp = (double)load_f(target, toff + (size_t)x, dt) - lt;
+                double lq = (double)load_f(draft, doff + (size_t)x, dt) - ld;
+                ratio = (lp == -INFINITY) ? -INFINITY : lp - lq;
+                double u = (double)fsd_oracle_word_to_uniform(
+                    fsd_oracle_random_word(seed, offset, 1u, (uint32_t)b, (uint32_t)i));
+                double thr = ratio < 0.0 ? ratio : 0.0; /* ln min(1, p/q) */
+                mar = thr - log(u);
+                ok = (mar > 0.0); /* min(1,p/q) > u */
+            }
+            log_ratio[(size_t)b * K + i] = ratio;
+            margin[(size_t)b * K + i] = mar;
+            if (!ok && i < n) { n = i; lse_n[0] = lt; lse_n[1] = ld; }
+        }
+        size_t soff = ((size_t)b * (size_t)(K + 1) + (size_t)n) * (size_t)V;
+        if (!status && row_is_bad(target, soff, V, dt)) status |= ST_NONFINITE;
+        for (int i = 0; i <= K; ++i) out_tokens[(size_t)b * (K + 1) + i] = -1;
+        if (gap) gap[b] = INFINITY;
+        if (status) {
+            accept_len[b] = 0;
+        } else {
+            accept_len[b] = n;
+            for (int i = 0; i < n; ++i) out_tokens[(size_t)b * (K + 1) + i] = cand[(size_t)b * K + i];
+            int32_t y = -1;
+            if (n < K) {
+                size_t doff = ((size_t)b * (size_t)K + (size_t)n) * (size_t)V;
+                y = sample_residual(target, soff, draft, doff, V, dt, mode, seed, offset, (uint32_t)b,
+                                    lse_n[0], lse_n[1], gap ? &gap[b] : NULL);
+            }
+            if (y < 0) {
+                float g32;
+                y = sample_row(target, soff, V, dt, mode, seed, offset, (uint32_t)b, &g32);
+                if (gap) gap[b] = (double)g32;
+            }
+            out_tokens[(size_t)b * (K + 1) + n] = y;
+        }
+        row_status[b] = status;
+    }
+    return 0;
+}

@@ -1,0 +1,459 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these tests calls the HIP path.  Each check is independent of the oracle's own formulae:
+closed forms worked by hand (tests/golden/closed_forms.txt), inequalities between the three
+divergences, a brute force in exact-sum Python at V=8, published known-answer vectors for the
+random generator, and statistical checks of the two sampling rules.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from paper_2502_20704_amd import synth
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+LN2 = math.log(2.0)
+
+
+def _golden(name):
+    vals = {}
+    with open(os.path.join(GOLD, name)) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            k, v = line.split()
+            vals[k] = float(v)
+    return vals
+
+
+# ------------------------------------------------------------------ brute force (pure Python)
+
+def _softmax_exact(z):
+    m = max(z)
+    e = [math.exp(x - m) if x != -math.inf else 0.0 for x in z]
+    s = math.fsum(e)
+    return [x / s for x in e]
+
+
+def _brute_divs(zt, zd):
+    """App. C.1-C.3 written out term by term with exactly rounded sums."""
+    p, q = _softmax_exact(zt), _softmax_exact(zd)
+    kl = math.fsum(pi * math.log(pi / qi) if qi > 0 else math.inf for pi, qi in zip(p, q) if pi > 0)
+    mix = [(pi + qi) / 2 for pi, qi in zip(p, q)]
+    klpm = math.fsum(pi * math.log(pi / mi) for pi, mi in zip(p, mix) if pi > 0)
+    klqm = math.fsum(qi * math.log(qi / mi) for qi, mi in zip(q, mix) if qi > 0)
+    tv = 0.5 * math.fsum(abs(pi - qi) for pi, qi in zip(p, q))
+    return kl, 0.5 * klpm + 0.5 * klqm, tv
+
+
+# ------------------------------------------------------------------------------ random numbers
+
+def test_philox_known_answers(oracle):
+    n = 0
+    with open(os.path.join(GOLD, "philox4x32_10_kat.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            w = [int(x, 16) for x in line.split()]
+            got = oracle.philox4x32_10(w[0:4], w[4:6])
+            assert [int(x) for x in got] == w[6:10]
+            n += 1
+    assert n == 3
+
+
+def test_random_word_layout(oracle):
+    """word idx of stream s is lane idx&3 of block counter ((idx>>2)|s<<30, b, off_lo, off_hi)."""
+    seed, off = 0x0123456789ABCDEF, 0x1122334455667788
+    for stream in (0, 1):
+        for b in (0, 5):
+            for idx in (0, 1, 2, 3, 4, 1023, 128255):
+                blk = oracle.philox4x32_10([(idx >> 2) | (stream << 30), b, off & 0xFFFFFFFF, off >> 32],
+                                           [seed & 0xFFFFFFFF, seed >> 32])
+                assert oracle.random_word(seed, off, stream, b, idx) == int(blk[idx & 3])
+
+
+def test_uniform_map_exact_and_open(oracle):
+    assert oracle.word_to_uniform(0) == 2.0 ** -24
+    assert oracle.word_to_uniform(0xFFFFFFFF) == 1.0 - 2.0 ** -24
+    assert oracle.word_to_uniform(0x80000000) == 0.5 + 2.0 ** -24
+    for w in (1 << 9, 12345 << 9, 0xABCDEF12):
+        assert oracle.word_to_uniform(w) == (2 * (w >> 9) + 1) / 2.0 ** 24   # exact, no rounding
+
+
+def test_flog32_matches_log(oracle):
+    rng = np.random.default_rng(3)
+    xs = np.concatenate([rng.uniform(2.0 ** -24, 1.0, 2000), rng.uniform(1.0, 17.0, 2000),
+                         np.exp(rng.uniform(-16.0, 3.0, 2000)), [1.0, 2.0, 0.5, math.sqrt(2), 2.0 ** -24]])
+    for x in xs.astype(np.float32):
+        ref = math.log(float(x))
+        got = oracle.flog32(float(x))
+        assert abs(got - ref) <= 3e-7 * max(1.0, abs(ref)), (x, got, ref)
+    assert oracle.flog32(1.0) == 0.0
+
+
+def test_gumbel_moments(oracle):
+    """G = -ln(-ln u) has mean = Euler's constant and variance pi^2/6."""
+    n = 200_000
+    g = np.array([oracle.gumbel(oracle.random_word(11, 0, 0, 0, i)) for i in range(n)])
+    assert abs(g.mean() - 0.5772156649) < 4 * 1.2825 / math.sqrt(n)
+    assert abs(g.var() - math.pi ** 2 / 6) < 0.03
+    # monotone in the word: larger u gives larger G
+    ws = np.sort(np.random.default_rng(0).integers(0, 2 ** 32, 500, dtype=np.uint64))
+    gs = [oracle.gumbel(int(w)) for w in ws]
+    assert all(b >= a for a, b in zip(gs, gs[1:]))
+
+
+# -------------------------------------------------------------------------------- divergences
+
+def test_identical_rows_are_exactly_zero(oracle):
+    rng = np.random.default_rng(0)
+    z = (rng.standard_normal(1000) * 3).astype(np.float32)
+    d, lse, st = oracle.pair_divergences(z, z.copy())
+    assert st == 0 and tuple(d) == (0.0, 0.0, 0.0) and lse[0] == lse[1]
+    zb = synth.to_bf16_bits(z)
+    d, _, st = oracle.pair_divergences(zb, zb.copy())
+    assert st == 0 and tuple(d) == (0.0, 0.0, 0.0)
+
+
+def test_bernoulli_closed_form(oracle):
+    """V=2: p=(a,1-a), q=(b,1-b) written out by hand; also catches swapped operands in KL."""
+    for a, b in ((0.9, 0.5), (0.2, 0.7), (0.5, 0.01)):
+        zt = np.log(np.array([a, 1 - a])).astype(np.float32)
+        zd = np.log(np.array([b, 1 - b])).astype(np.float32)
+        p = _softmax_exact([float(x) for x in zt])
+        q = _softmax_exact([float(x) for x in zd])
+        a_, b_ = p[0], q[0]
+        kl = a_ * math.log(a_ / b_) + (1 - a_) * math.log((1 - a_) / (1 - b_))
+        m = (a_ + b_) / 2
+        js = 0.5 * (a_ * math.log(a_ / m) + (1 - a_) * math.log((1 - a_) / (1 - m))) + \
+            0.5 * (b_ * math.log(b_ / m) + (1 - b_) * math.log((1 - b_) / (1 - m)))
+        tv = abs(a_ - b_)
+        d, _, st = oracle.pair_divergences(zt, zd)
+        assert st == 0
+        assert d[0] == pytest.approx(kl, rel=1e-12)
+        assert d[1] == pytest.approx(js, rel=1e-12)
+        assert d[2] == pytest.approx(tv, rel=1e-12)
+        rev, _, _ = oracle.pair_divergences(zd, zt)
+        assert abs(rev[0] - kl) > 1e-3          # KL is directed: target || draft
+        assert rev[1] == pytest.approx(js, rel=1e-12) and rev[2] == pytest.approx(tv, rel=1e-12)
+
+
+@pytest.mark.parametrize("V", [8, 1000, 128256])
+def test_uniform_vs_half_uniform(oracle, V):
+    g = _golden("closed_forms.txt")
+    zt = np.zeros(V, dtype=np.float32)
+    zd = np.zeros(V, dtype=np.float32)
+    zd[V // 2:] = -np.inf
+    d, _, st = oracle.pair_divergences(zt, zd)
+    assert st == 0
+    assert d[0] == math.inf
+    assert d[1] == pytest.approx(g["uniform_vs_half_JS"], rel=1e-11)
+    assert d[2] == pytest.approx(g["uniform_vs_half_TV"], rel=1e-11)
+    rev, _, _ = oracle.pair_divergences(zd, zt)
+    assert rev[0] == pytest.approx(g["half_vs_uniform_KL"], rel=1e-11)
+    # same through the bf16 loader
+    d16, _, _ = oracle.pair_divergences(synth.to_bf16_bits(zt), synth.to_bf16_bits(zd))
+    assert d16[1] == pytest.approx(g["uniform_vs_half_JS"], rel=1e-11)
+
+
+def test_disjoint_supports(oracle):
+    g = _golden("closed_forms.txt")
+    V = 64
+    zt = np.full(V, -np.inf, dtype=np.float32)
+    zd = np.full(V, -np.inf, dtype=np.float32)
+    zt[:10] = np.linspace(-1, 1, 10)
+    zd[40:] = np.linspace(2, -2, 24)
+    d, _, st = oracle.pair_divergences(zt, zd)
+    assert st == 0 and d[0] == math.inf
+    assert d[1] == pytest.approx(g["disjoint_JS"], rel=1e-12)
+    assert d[2] == pytest.approx(g["disjoint_TV"], rel=1e-12)
+
+
+def test_brute_force_v8(oracle):
+    rng = np.random.default_rng(1)
+    for trial in range(200):
+        zt = (rng.standard_normal(8) * rng.uniform(0.5, 6)).astype(np.float32)
+        zd = (zt + rng.standard_normal(8) * rng.uniform(0.05, 4)).astype(np.float32)
+        if trial % 7 == 0:
+            zd[rng.integers(8)] = -np.inf
+        if trial % 11 == 0:
+            zt[rng.integers(8)] = -np.inf
+        kl, js, tv = _brute_divs([float(x) for x in zt], [float(x) for x in zd])
+        d, _, st = oracle.pair_divergences(zt, zd)
+        assert st == 0
+        if math.isinf(kl):
+            assert d[0] == math.inf
+        else:
+            assert d[0] == pytest.approx(kl, rel=1e-10, abs=1e-14)
+        assert d[1] == pytest.approx(js, rel=1e-10, abs=1e-14)
+        assert d[2] == pytest.approx(tv, rel=1e-10, abs=1e-14)
+
+
+def test_bounds_and_inequalities(oracle):
+    rng = np.random.default_rng(2)
+    for trial in range(60):
+        V = int(rng.integers(2, 3000))
+        zt = (rng.standard_normal(V) * rng.uniform(0.2, 5)).astype(np.float32)
+        zd = (zt + rng.standard_normal(V) * rng.uniform(0.01, 6)).astype(np.float32)
+        (kl, js, tv), _, _ = oracle.pair_divergences(zt, zd)
+        (klr, jsr, tvr), _, _ = oracle.pair_divergences(zd, zt)
+        assert kl >= 0 and js >= 0 and tv >= 0
+        assert js <= LN2 * (1 + 1e-12) and tv <= 1 + 1e-12
+        assert tv <= math.sqrt(kl / 2) * (1 + 1e-9)            # Pinsker
+        assert js <= LN2 * tv * (1 + 1e-9)                      # JS <= ln2 * TV
+        assert js <= 0.25 * (kl + klr) * (1 + 1e-9)             # convexity of KL in its 2nd argument
+        assert js == pytest.approx(jsr, rel=1e-12) and tv == pytest.approx(tvr, rel=1e-12)
+
+
+def test_shift_invariance(oracle):
+    rng = np.random.default_rng(4)
+    zt = (rng.standard_normal(500) * 2).astype(np.float64)
+    zd = zt + rng.standard_normal(500)
+    # shifts by powers of two keep float32 roundings aligned
+    a = oracle.pair_divergences(zt.astype(np.float32), zd.astype(np.float32))[0]
+    b = oracle.pair_divergences((zt.astype(np.float32) + np.float32(16.0)),
+                                (zd.astype(np.float32) - np.float32(32.0)))[0]
+    assert np.allclose(a, b, rtol=2e-5)
+
+
+def test_nonfinite_rows_flagged(oracle):
+    z = np.zeros(16, dtype=np.float32)
+    bad = z.copy()
+    bad[3] = np.nan
+    assert oracle.pair_divergences(bad, z)[2] == oracle.ST_NONFINITE
+    bad[3] = np.inf
+    assert oracle.pair_divergences(z, bad)[2] == oracle.ST_NONFINITE
+    assert oracle.pair_divergences(np.full(16, -np.inf, dtype=np.float32), z)[2] == oracle.ST_NONFINITE
+    ok = z.copy()
+    ok[5] = -np.inf
+    assert oracle.pair_divergences(ok, z)[2] == 0
+
+
+# ----------------------------------------------------------------------------- chain acceptance
+
+def _small_chain(seed, B=3, K=5, V=8, sigma=1.0):
+    rng = np.random.default_rng(seed)
+    t = (rng.standard_normal((B, K + 1, V)) * 2).astype(np.float32)
+    d = (t[:, :K] + rng.standard_normal((B, K, V)) * sigma).astype(np.float32)
+    cand = rng.integers(0, V, (B, K)).astype(np.int32)
+    return t, d, cand
+
+
+def test_threshold_special_cases(oracle):
+    t, d, cand = _small_chain(0)
+    K = cand.shape[1]
+    same = oracle.verify_chain(t, t[:, :K].copy(), cand, T=0.0)
+    assert (same["accept_len"] == K).all() and (same["divs"] == 0).all()
+    assert (same["out_tokens"][:, :K] == cand).all() and (same["out_tokens"][:, K] >= 0).all()
+    big = oracle.verify_chain(t, d, cand, T=1e9)
+    assert (big["accept_len"] == K).all()
+    neg = oracle.verify_chain(t, d, cand, T=-1e9)
+    assert (neg["accept_len"] == 0).all()
+    assert (neg["out_tokens"][:, 1:] == -1).all() and (neg["out_tokens"][:, 0] >= 0).all()
+
+
+@pytest.mark.parametrize("div", [0, 1, 2])
+def test_prefix_is_brute_force_over_positions(oracle, div):
+    for seed in range(20):
+        t, d, cand = _small_chain(seed, sigma=0.7)
+        B, K = cand.shape
+        T = 0.05 * (seed % 7)
+        out = oracle.verify_chain(t, d, cand, T=T, div=div)
+        for b in range(B):
+            divs = [_brute_divs([float(x) for x in t[b, i]], [float(x) for x in d[b, i]])[div]
+                    for i in range(K)]
+            n = 0
+            while n < K and divs[n] <= float(np.float32(T)):
+                n += 1
+            assert out["accept_len"][b] == n
+            assert list(out["out_tokens"][b, :n]) == list(cand[b, :n])
+            assert (out["out_tokens"][b, n + 1:] == -1).all()
+            assert np.allclose(out["divs"][b], divs, rtol=1e-9, atol=1e-14)
+
+
+def test_monotone_in_T_and_token_independent(oracle):
+    t, d, cand = _small_chain(5, B=6, K=7, sigma=1.2)
+    prev = None
+    for T in (0.0, 0.01, 0.05, 0.1, 0.2, 0.4, 0.7):
+        n = oracle.verify_chain(t, d, cand, T=T)["accept_len"]
+        if prev is not None:
+            assert (n >= prev).all()
+        prev = n
+    other = (cand + 3) % 8
+    assert (oracle.verify_chain(t, d, other, T=0.1)["accept_len"] ==
+            oracle.verify_chain(t, d, cand, T=0.1)["accept_len"]).all()
+
+
+def test_accepted_positions_respect_threshold(oracle):
+    """per-position statement behind the sequence-level bound (Sec. 4.2): accepted => Div <= T."""
+    t, d, cand = _small_chain(9, B=8, K=6, sigma=0.8)
+    out = oracle.verify_chain(t, d, cand, T=0.08, div=1)
+    for b in range(8):
+        n = out["accept_len"][b]
+        assert (out["divs"][b, :n] <= np.float32(0.08)).all()
+        if n < 6:
+            assert out["divs"][b, n] > np.float32(0.08)
+
+
+# ------------------------------------------------------------------------------------- sampler
+
+def test_greedy_is_argmax_lowest_index(oracle):
+    t, d, cand = _small_chain(2)
+    t[0, 0, 2] = t[0, 0, 6] = 50.0          # a tie: the lower index must win
+    out = oracle.verify_chain(t, d, cand, T=-1.0, mode=oracle.GREEDY)
+    assert out["out_tokens"][0, 0] == 2
+    assert list(out["out_tokens"][1:, 0]) == [int(np.argmax(t[b, 0])) for b in (1, 2)]
+
+
+def test_sampler_deterministic_in_seed_and_offset(oracle):
+    t, d, cand = _small_chain(3, V=8)
+    a = oracle.verify_chain(t, d, cand, T=0.05, seed=7, offset=3)["out_tokens"]
+    b = oracle.verify_chain(t, d, cand, T=0.05, seed=7, offset=3)["out_tokens"]
+    c = [oracle.verify_chain(t, d, cand, T=0.05, seed=7, offset=o)["out_tokens"] for o in range(4, 24)]
+    assert (a == b).all()
+    assert any((a != x).any() for x in c)
+
+
+def test_sampler_chi_square_v8(oracle):
+    """the emitted token is a draw from softmax(target row) (Sec. 4: sample from P_MT[i])."""
+    V, B = 8, 120_000
+    row = np.array([2.0, 0.5, -1.0, 1.0, 0.0, -3.0, 1.5, -0.5], dtype=np.float32)
+    t = np.broadcast_to(row, (B, 2, V)).copy()
+    d = t[:, :1].copy()
+    cand = np.zeros((B, 1), dtype=np.int32)
+    out = oracle.verify_chain(t, d, cand, T=-1.0, seed=99)      # reject at 0: sample row 0
+    tok = out["out_tokens"][:, 0]
+    p = np.array(_softmax_exact([float(x) for x in row]))
+    obs = np.bincount(tok, minlength=V)
+    chi2 = ((obs - B * p) ** 2 / (B * p)).sum()
+    assert chi2 < 29.9          # 7 degrees of freedom, p ~ 1e-4
+    # bonus row when everything is accepted: same law, row index K
+    out2 = oracle.verify_chain(t, d, cand, T=1.0, seed=5)
+    assert (out2["accept_len"] == 1).all()
+    obs2 = np.bincount(out2["out_tokens"][:, 1], minlength=V)
+    assert (((obs2 - B * p) ** 2 / (B * p)).sum()) < 29.9
+
+
+# ---------------------------------------------------------------------------------------- tree
+
+def _brute_tree(t, d, parent, T, div):
+    """every node checked against all its ancestors, by definition"""
+    N = len(parent)
+    ok = []
+    for j in range(N):
+        dv = _brute_divs([float(x) for x in t[parent[j] + 1]], [float(x) for x in d[j]])[div]
+        ok.append(dv <= float(np.float32(T)))
+    best, best_depth = -1, 0
+    for j in range(N):
+        chain, a = [], j
+        while a >= 0:
+            chain.append(a)
+            a = parent[a]
+        if all(ok[a] for a in chain) and len(chain) > best_depth:
+            best, best_depth = j, len(chain)
+    path, a = [], best
+    while a >= 0:
+        path.append(a)
+        a = parent[a]
+    return path[::-1]
+
+
+def test_tree_brute_force_v8(oracle):
+    rng = np.random.default_rng(8)
+    for trial in range(40):
+        N, V = 10, 8
+        parent = np.array([-1] + [int(rng.integers(-1, j)) for j in range(1, N)], dtype=np.int32)
+        t = (rng.standard_normal((1, N + 1, V)) * 2).astype(np.float32)
+        d = np.stack([t[0, parent[j] + 1] + rng.standard_normal(V) * rng.uniform(0.2, 1.5)
+                      for j in range(N)]).astype(np.float32)[None]
+        toks = rng.integers(0, V, (1, N)).astype(np.int32)
+        T = float(rng.uniform(0.0, 0.25))
+        out = oracle.verify_tree(t, d, toks, parent[None], max_depth=N, T=T, div=1)
+        path = _brute_tree(t[0], d[0], list(parent), T, 1)
+        L = out["path_len"][0]
+        assert L == len(path)
+        assert list(out["path_nodes"][0, :L]) == path
+        assert (out["path_nodes"][0, L:] == -1).all()
+        assert list(out["out_tokens"][0, :L]) == [int(toks[0, j]) for j in path]
+        assert out["out_tokens"][0, L] >= 0 and (out["out_tokens"][0, L + 1:] == -1).all()
+
+
+def test_chain_shaped_tree_equals_chain(oracle):
+    t, d, cand = _small_chain(4, B=4, K=6, sigma=0.9)
+    K = 6
+    parent = np.broadcast_to(np.arange(-1, K - 1, dtype=np.int32), (4, K)).copy()
+    for T in (0.0, 0.05, 0.15, 1e9):
+        c = oracle.verify_chain(t, d, cand, T=T, seed=3, offset=1)
+        tr = oracle.verify_tree(t, d, cand, parent, max_depth=K, T=T, seed=3, offset=1)
+        assert (c["accept_len"] == tr["path_len"]).all()
+        assert (c["out_tokens"] == tr["out_tokens"]).all()
+        assert np.array_equal(c["divs"], tr["divs"])
+
+
+def test_star_tree_picks_lowest_accepted_child(oracle):
+    rng = np.random.default_rng(12)
+    N, V = 6, 8
+    t = (rng.standard_normal((1, N + 1, V)) * 2).astype(np.float32)
+    d = np.repeat(t[:, :1], N, axis=1).copy()
+    d[0, 0] += 3 * rng.standard_normal(V).astype(np.float32)     # child 0 far from the root row
+    d[0, 1] += 3 * rng.standard_normal(V).astype(np.float32)     # child 1 too; 2.. are identical
+    parent = np.full((1, N), -1, dtype=np.int32)
+    out = oracle.verify_tree(t, d, np.arange(N, dtype=np.int32)[None], parent, max_depth=3, T=1e-3)
+    assert out["path_len"][0] == 1 and out["path_nodes"][0, 0] == 2
+
+
+def test_tree_rejects_bad_parents_and_depth(oracle):
+    t, d, cand = _small_chain(4, B=1, K=4)
+    bad = np.array([[-1, 0, 2, 1]], dtype=np.int32)               # parent[2] = 2 is not < 2
+    assert oracle.verify_tree(t, d, cand, bad, max_depth=4, T=1.0)["row_status"][0] & oracle.ST_BAD_PARENT
+    deep = np.array([[-1, 0, 1, 2]], dtype=np.int32)
+    out = oracle.verify_tree(t, d, cand, deep, max_depth=2, T=1.0)
+    assert out["row_status"][0] & oracle.ST_TOO_DEEP and out["path_len"][0] == 0
+
+
+# ------------------------------------------------------------------------------------ strict SD
+
+def test_sd_acceptance_frequency_and_output_law(oracle):
+    """Sec. 3: accept with probability min(1, p/q); the emitted token is then distributed as p."""
+    V, B = 8, 200_000
+    zt = np.array([1.5, 0.2, -0.7, 0.9, 0.0, -2.0, 1.1, -0.3], dtype=np.float32)
+    zd = np.array([0.3, 1.4, -0.2, 0.1, 0.8, -1.0, 0.6, -1.5], dtype=np.float32)
+    p = np.array(_softmax_exact([float(x) for x in zt]))
+    q = np.array(_softmax_exact([float(x) for x in zd]))
+    rng = np.random.default_rng(21)
+    cand = rng.choice(V, size=(B, 1), p=q).astype(np.int32)
+    t = np.broadcast_to(zt, (B, 2, V)).copy()
+    d = np.broadcast_to(zd, (B, 1, V)).copy()
+    out = oracle.sd_verify_chain(t, d, cand, seed=1234)
+    acc = out["accept_len"] == 1
+    # per-token acceptance frequency -> min(1, p/q)
+    for x in range(V):
+        sel = cand[:, 0] == x
+        want = min(1.0, p[x] / q[x])
+        sd = math.sqrt(max(want * (1 - want), 1e-4) / sel.sum())
+        assert abs(acc[sel].mean() - want) < 5 * sd + 1e-9
+    # marginal acceptance -> 1 - TV(p, q)
+    tv = 0.5 * np.abs(p - q).sum()
+    assert abs(acc.mean() - (1 - tv)) < 5 * math.sqrt(tv * (1 - tv) / B)
+    # rejected rows resample from norm(max(0, p-q))
+    res = np.maximum(p - q, 0)
+    res /= res.sum()
+    rej_tok = out["out_tokens"][~acc, 0]
+    obs = np.bincount(rej_tok, minlength=V)
+    assert (obs[res == 0] == 0).all()
+    m = res > 0
+    assert (((obs[m] - obs.sum() * res[m]) ** 2 / (obs.sum() * res[m])).sum()) < 29.9
+    # first emitted token is distributed exactly as the target
+    first = out["out_tokens"][:, 0]
+    obs = np.bincount(first, minlength=V)
+    assert (((obs - B * p) ** 2 / (B * p)).sum()) < 29.9
+    assert np.allclose(out["log_ratio"][:, 0], np.log(p[cand[:, 0]] / q[cand[:, 0]]), atol=1e-9)
+
+
+def test_sd_identical_models_accept_everything(oracle):
+    t, d, cand = _small_chain(6, B=50, K=5)
+    out = oracle.sd_verify_chain(t, t[:, :5].copy(), cand, seed=2)
+    assert (out["accept_len"] == 5).all() and (out["log_ratio"] == 0).all()
+    assert (out["out_tokens"][:, 5] >= 0).all()
