@@ -1,0 +1,170 @@
+#!/usr/bin/env python3
+"""Benchmark of the FSD candidate-verification step on one MI355X.
+
+A step is one complete fsd_verify_chain call (counter reset, vocabulary reduction, acceptance
+scan and Gumbel-max token) on one batch of synthetic logits already resident in HBM.  The
+workload is configuration C2 (B=64 sequences, K=8 candidates, V=128256, bfloat16, JS divergence,
+T=0.1); several distinct input sets are rotated so that the working set exceeds the on-die caches.
+
+Prints one JSON line: verified candidate positions per second, plus the roofline of the
+vocabulary-reduction kernel (algorithmic bytes / its event-timed duration against the 8 TB/s HBM
+peak) and the CPU oracle's rate on the host cores as a reported baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published peak
+
+
+def traffic_from_profile(workload: str):
+    """HBM bytes per launch of the reduction kernel, from the committed counter summary (or None)."""
+    path = os.path.join(ROOT, "profiles", f"pair_reduce_{workload}_pmc.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch"):
+                    return float(line.split()[1])
+    except OSError:
+        pass
+    return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="C2", choices=["C2", "C3", "C4"])
+    ap.add_argument("--div", default="js", choices=["kl", "js", "tv"])
+    ap.add_argument("--sets", type=int, default=0, help="distinct input sets to rotate (0 = enough for > 1 GB)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2502_20704_amd as fsd
+    from paper_2502_20704_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    fsd.library()
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.config]
+    div = {"kl": fsd.DIV_KL, "js": fsd.DIV_JS, "tv": fsd.DIV_TV}[args.div]
+    T = cfg["T"][0]
+    tree = cfg["shape"] == "tree"
+    rows = cfg["N"] if tree else cfg["K"]
+    B, V = cfg["B"], cfg["V"]
+    es = 2 if cfg["dtype"] == "bf16" else 4
+    set_bytes = B * (2 * rows + 1) * V * es
+    nsets = args.sets or max(2, -(-(1200 << 20) // set_bytes))
+    if set_bytes * nsets > (24 << 30):
+        nsets = max(1, (24 << 30) // set_bytes)
+
+    sets, host_sets = [], []
+    for s in range(nsets):
+        inp = synth.config_inputs(args.config, seed=100 + s)
+        if s < 4:
+            host_sets.append(inp)
+        if tree:
+            dev = {k: synth.as_torch(inp[k]) for k in ("target", "draft", "node_tokens", "parent")}
+            dev["max_depth"] = int(inp["max_depth"])
+        else:
+            dev = {k: synth.as_torch(inp[k]) for k in ("target", "draft", "cand")}
+        sets.append(dev)
+    dt_code = fsd.BF16 if cfg["dtype"] == "bf16" else fsd.F32
+    ws = torch.empty(fsd.fsd_workspace_bytes(B, rows, V, dt_code) + 256, dtype=torch.uint8, device="cuda")
+    outs = [None] * nsets
+
+    def step(i):
+        d = sets[i % nsets]
+        if tree:
+            outs[i % nsets] = fsd.fsd_verify_tree(d["target"], d["draft"], d["node_tokens"], d["parent"],
+                                                  d["max_depth"], T, div, fsd.SAMPLE, seed=1, offset=i,
+                                                  out=outs[i % nsets], workspace=ws)
+        else:
+            outs[i % nsets] = fsd.fsd_verify_chain(d["target"], d["draft"], d["cand"], T, div, fsd.SAMPLE, seed=1,
+                                                   offset=i, out=outs[i % nsets], workspace=ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    fsd.profile_enable(True)
+    fsd.profile_collect()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    n_ev, k1_mean_ms, k1_min_ms = fsd.profile_collect()
+    fsd.profile_enable(False)
+
+    positions = B * rows
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = positions * args.steps / (t1 - t0)
+    alg_bytes = 2 * V * es * positions          # one target row + one draft row per position, read once
+    achieved = alg_bytes / (k1_mean_ms * 1e-3) / 1e9 if n_ev else None
+    workload = (f"{args.config}: {'tree' if tree else 'chain'} verify B={B} {'N' if tree else 'K'}={rows} V={V} "
+                f"{cfg['dtype']} {args.div.upper()} T={T}")
+
+    result = {
+        "metric": "verified candidate positions/sec and achieved HBM GB/s (% peak) at V=128256",
+        "value": value,
+        "unit": "positions/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": workload, "input_sets_rotated": nsets, "input_bytes_per_set": set_bytes,
+                   "logits_dtype": cfg["dtype"], "whole_call_GBps": (alg_bytes + B * V * es) / (ms_per_step * 1e-3) / 1e9},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
+                     "traffic": traffic_from_profile(args.config), "kernel": "pair_reduce",
+                     "kernel_ms_mean": k1_mean_ms, "kernel_ms_min": k1_min_ms, "launches_timed": n_ev,
+                     "algorithmic_bytes_per_launch": alg_bytes},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+
+        t0 = time.perf_counter()
+        npos = 0
+        for inp in host_sets:
+            if tree:
+                nb = min(B, 8)
+                oracle.verify_tree(inp["target"][:nb], inp["draft"][:nb], inp["node_tokens"][:nb], inp["parent"][:nb],
+                                   int(inp["max_depth"]), T, div, seed=1)
+            else:
+                nb = min(B, 64)
+                oracle.verify_chain(inp["target"][:nb], inp["draft"][:nb], inp["cand"][:nb], T, div, seed=1)
+            npos += nb * rows
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": npos / dt, "unit": "positions/s", "cores": oracle.num_threads(),
+                                  "kind": "oracle",
+                                  "sample": f"{npos} positions of the same workload ({len(host_sets)} input sets), "
+                                            f"{dt:.2f} s wall"}
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

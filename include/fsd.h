@@ -1,0 +1,177 @@
+/*
+ * fsd.h -- C ABI of the MI355X (gfx950) candidate-verification library for
+ * Fuzzy Speculative Decoding (FSD).
+ *
+ * One call verifies, for a batch of sequences, every candidate position a
+ * draft model proposed: it turns the target-model and draft-model logits of
+ * each position into next-token distributions, measures the divergence
+ * between them, accepts the position when the divergence is within the
+ * threshold T, finds the accepted prefix (or accepted tree path) and draws the
+ * one extra token from the target distribution.
+ *
+ * Conventions shared by all entry points
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller; the
+ *     library never allocates, frees or keeps it.  Tensors are dense and
+ *     row-major.  Logits are binary32 (FSD_F32) or bfloat16 (FSD_BF16).
+ *     Rows that start on 16-byte boundaries (V * element size a multiple of
+ *     16 and aligned base pointers) take the 128-bit load path; anything else
+ *     is still correct through an element-wise path.
+ *   - -inf logits are legal (masked vocabulary entries).  A NaN or +inf logit,
+ *     or a row that is -inf everywhere, in a row the method reads is reported
+ *     per sequence in row_status (FSD_ROW_NONFINITE): that sequence gets
+ *     accept_len / path_len 0, all its output tokens -1 and NaN divergences
+ *     for the affected positions.
+ *   - Calls are asynchronous on `hip_stream` (a hipStream_t, NULL = the null
+ *     stream), do no host synchronisation and no host<->device copy.
+ *   - `workspace` is device memory of at least fsd_workspace_bytes(...) bytes,
+ *     256-byte aligned, private to the call while it runs; its contents need
+ *     no initialisation and mean nothing afterwards.
+ *   - The return value is an fsd_status.  Argument errors are found before
+ *     anything is launched and leave all outputs untouched.
+ *   - Random numbers: Philox4x32-10 keyed by `seed`; `offset` selects the
+ *     decode step (counter words 2,3), the sequence index is counter word 1 and
+ *     the vocabulary (or position) index picks counter word 0 and the lane.
+ *     Equal (seed, offset, inputs) give equal outputs on every launch.
+ */
+#ifndef FSD_H_
+#define FSD_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FSD_OK = 0,
+    FSD_ERR_NULL = -1,      /* a required pointer is NULL */
+    FSD_ERR_SHAPE = -2,     /* B, K, N, V, max_depth out of range, or T is NaN */
+    FSD_ERR_DTYPE = -3,     /* dtype is not an fsd_dtype */
+    FSD_ERR_DIV = -4,       /* div is not an fsd_div */
+    FSD_ERR_WORKSPACE = -5, /* workspace NULL, misaligned or too small */
+    FSD_ERR_MODE = -6,      /* mode is not an fsd_mode */
+    FSD_ERR_LAUNCH = -7     /* the HIP runtime refused a launch */
+} fsd_status;
+
+typedef enum { FSD_F32 = 0, FSD_BF16 = 1 } fsd_dtype;
+
+/* Divergence between the target distribution p and the draft distribution q
+ * (paper App. C): KL is KL(p || q) (C.1), JS the Jensen-Shannon divergence
+ * with the even mixture (C.2), TV the total-variation distance (C.3).
+ * Natural logarithm. */
+typedef enum { FSD_DIV_KL = 0, FSD_DIV_JS = 1, FSD_DIV_TV = 2 } fsd_div;
+
+/* How the extra token is drawn from the target row (paper Sec. 4, "whatever
+ * sampling method the user sets", and Sec. 6.3): an exact categorical draw
+ * from softmax(logits) by Gumbel-max, or the argmax (lowest index on ties). */
+typedef enum { FSD_SAMPLE = 0, FSD_GREEDY = 1 } fsd_mode;
+
+/* bits of row_status[b] */
+enum {
+    FSD_ROW_NONFINITE = 1,  /* NaN / +inf / all -inf row among the rows read */
+    FSD_ROW_BAD_PARENT = 2, /* tree: parent[j] outside [-1, j) */
+    FSD_ROW_TOO_DEEP = 4,   /* tree: a node deeper than max_depth */
+    FSD_ROW_BAD_TOKEN = 8,  /* strict SD: candidate token id outside [0, V) */
+    FSD_ROW_INTERNAL = 16   /* a bounded device-side wait expired (never expected) */
+};
+
+/* Limits: 1 <= V <= fsd_max_vocab(dtype); 1 <= K, N, max_depth <= 2048; B <= 65535;
+ * B*K (B*N) < 2^24. */
+int64_t fsd_max_vocab(int dtype);
+
+/* Bytes of workspace a call with these sizes needs (rows_per_seq = K or N).
+ * Returns 0 for arguments no call would accept. */
+size_t fsd_workspace_bytes(int B, int rows_per_seq, int V, int dtype);
+
+const char* fsd_status_string(int status);
+
+/*
+ * FSD verification of linear candidate sequences (paper Sec. 4, eq. 4).
+ *
+ *   target_logits [B, K+1, V]  row i < K: target model's logits for position i;
+ *                              row K: the position after the last candidate
+ *   draft_logits  [B, K, V]    draft model's logits for position i
+ *   cand_tokens   [B, K]       the K candidate token ids (copied to the output;
+ *                              the FSD decision does not depend on them)
+ *   div, T                     accept position i iff div(p_i, q_i) <= T
+ *                              (T may be +-inf; NaN is rejected)
+ *   accept_len    [B]   out    n_b = number of leading accepted positions
+ *   out_tokens    [B, K+1] out cand[b, :n_b], then the token drawn from
+ *                              softmax(target[b, n_b]), then -1 padding
+ *   divergences   [B, K] out   optional (NULL to skip), the chosen divergence
+ *   row_status    [B]   out    optional (NULL to skip), see FSD_ROW_*
+ */
+int fsd_verify_chain(const void* target_logits, const void* draft_logits, const int32_t* cand_tokens,
+                     int B, int K, int V, int dtype, int div, float T, int mode, uint64_t seed,
+                     uint64_t offset, int32_t* accept_len, int32_t* out_tokens, float* divergences,
+                     int32_t* row_status, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * FSD verification of a token tree (paper Sec. 6.4: FSD on top of a
+ * tree-drafting method; the rule below is this library's statement of it).
+ *
+ *   target_logits [B, N+1, V]  row 0: target logits at the root context;
+ *                              row j+1: at the context that ends with node j
+ *   draft_logits  [B, N, V]    row j: the draft logits node j was proposed from
+ *   node_tokens   [B, N]       token id of node j
+ *   parent        [B, N]       parent node of j, -1 for children of the root;
+ *                              parent[j] < j (checked on the device)
+ *   max_depth                  longest path the outputs can hold
+ *
+ * Node j is accepted iff div(softmax(target[parent[j]+1]), softmax(draft[j])) <= T
+ * and its parent is accepted.  The deepest accepted node wins (lowest index on
+ * ties); the extra token is drawn from the target row of the winner's context
+ * (row 0 when no node is accepted).
+ *
+ *   path_len   [B]              out  depth of the winner (0 = none)
+ *   path_nodes [B, max_depth]   out  node indices root-to-winner, -1 padded
+ *   out_tokens [B, max_depth+1] out  tokens of the path, the drawn token, -1 padding
+ *   divergences [B, N] out optional; row_status [B] out optional
+ */
+int fsd_verify_tree(const void* target_logits, const void* draft_logits, const int32_t* node_tokens,
+                    const int32_t* parent, int B, int N, int max_depth, int V, int dtype, int div,
+                    float T, int mode, uint64_t seed, uint64_t offset, int32_t* path_len,
+                    int32_t* path_nodes, int32_t* out_tokens, float* divergences, int32_t* row_status,
+                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Strict speculative decoding on the same tensors (paper Sec. 3, eq. 1-3), the
+ * baseline FSD generalises: position i is accepted iff min(1, p_i(x_i)/q_i(x_i)) > y_i
+ * with y_i uniform in (0,1) from the Philox stream; at the first rejection the
+ * token is drawn from the normalised positive part of p - q, and from the row
+ * after the last candidate when everything is accepted.
+ *
+ *   log_ratio [B, K] out  optional, ln p_i(x_i) - ln q_i(x_i)
+ */
+int sd_verify_chain(const void* target_logits, const void* draft_logits, const int32_t* cand_tokens,
+                    int B, int K, int V, int dtype, int mode, uint64_t seed, uint64_t offset,
+                    int32_t* accept_len, int32_t* out_tokens, float* log_ratio, int32_t* row_status,
+                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Timing of the vocabulary-reduction kernel, for benchmarks.  After
+ * fsd_profile_enable(1) every verify call brackets that kernel with a pair of
+ * events on the call's stream (up to 4096 pairs are kept; later calls are
+ * not recorded).  fsd_profile_collect waits for the recorded events, returns
+ * the number of pairs and their mean / minimum duration in milliseconds, and
+ * forgets them.  Not thread-safe; meant for a single benchmarking thread.
+ */
+int fsd_profile_enable(int on);
+int fsd_profile_collect(float* mean_ms, float* min_ms);
+
+/* Test hook: number of polls a workgroup spends waiting for the other
+ * workgroups that share its row pair before it gives up and flags
+ * FSD_ROW_INTERNAL (default 1<<22).  Returns the previous value. */
+unsigned fsd_debug_set_spin_limit(unsigned polls);
+
+/* Tuning hook: workgroup shape of the vocabulary-reduction kernel, as wavefronts
+ * per workgroup (4 or 8) and 16-byte slots of each row held per thread (4 or 8);
+ * (0, 0) restores the library's own choice.  Results do not depend on it beyond
+ * the rounding order of the partial sums. */
+int fsd_debug_set_shape(int wavefronts, int slots_per_thread);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FSD_H_ */

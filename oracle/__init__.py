@@ -54,13 +54,13 @@ def lib() -> ctypes.CDLL:
         L.fsd_oracle_gumbel.restype = c.c_float
         L.fsd_oracle_pair.argtypes = [vp, c.c_size_t, vp, c.c_size_t, i64, i32, vp, vp]
         L.fsd_oracle_pair.restype = c.c_int
-        L.fsd_oracle_verify_chain.argtypes = [vp, vp, vp, i32, i32, i64, i32, i32, dbl, i32, u64, u64,
+        L.fsd_oracle_verify_chain.argtypes = [vp, vp, vp, i32, i32, i64, i32, i32, dbl, i32, u64, u64, i32,
                                               vp, vp, vp, vp, vp]
         L.fsd_oracle_verify_chain.restype = c.c_int
         L.fsd_oracle_verify_tree.argtypes = [vp, vp, vp, vp, i32, i32, i32, i64, i32, i32, dbl, i32,
-                                             u64, u64, vp, vp, vp, vp, vp, vp]
+                                             u64, u64, i32, vp, vp, vp, vp, vp, vp]
         L.fsd_oracle_verify_tree.restype = c.c_int
-        L.sd_oracle_verify_chain.argtypes = [vp, vp, vp, i32, i32, i64, i32, i32, u64, u64,
+        L.sd_oracle_verify_chain.argtypes = [vp, vp, vp, i32, i32, i64, i32, i32, u64, u64, i32,
                                              vp, vp, vp, vp, vp, vp]
         L.sd_oracle_verify_chain.restype = c.c_int
         _lib = L
@@ -122,7 +122,7 @@ def pair_divergences(t_row: np.ndarray, d_row: np.ndarray):
     return out, lse, int(st)
 
 
-def verify_chain(target, draft, cand, T, div=DIV_JS, mode=SAMPLE, seed=0, offset=0):
+def verify_chain(target, draft, cand, T, div=DIV_JS, mode=SAMPLE, seed=0, offset=0, seq_offset=0):
     target, draft = _c(target), _c(draft)
     cand = _c(np.asarray(cand, dtype=np.int32))
     B, K1, V = target.shape
@@ -131,14 +131,15 @@ def verify_chain(target, draft, cand, T, div=DIV_JS, mode=SAMPLE, seed=0, offset
     out = dict(accept_len=np.zeros(B, np.int32), out_tokens=np.zeros((B, K + 1), np.int32),
                divs=np.zeros((B, K)), row_status=np.zeros(B, np.int32), gap=np.zeros(B, np.float32))
     lib().fsd_oracle_verify_chain(_p(target), _p(draft), _p(cand), B, K, V, _dt(target), div,
-                                  float(np.float32(T)), mode, seed, offset, _p(out["accept_len"]),
-                                  _p(out["out_tokens"]), _p(out["divs"]), _p(out["row_status"]),
+                                  float(np.float32(T)), mode, seed, offset, seq_offset,
+                                  _p(out["accept_len"]), _p(out["out_tokens"]), _p(out["divs"]),
+                                  _p(out["row_status"]),
                                   _p(out["gap"]))
     return out
 
 
 def verify_tree(target, draft, node_tokens, parent, max_depth, T, div=DIV_JS, mode=SAMPLE, seed=0,
-                offset=0):
+                offset=0, seq_offset=0):
     target, draft = _c(target), _c(draft)
     node_tokens = _c(np.asarray(node_tokens, dtype=np.int32))
     parent = _c(np.asarray(parent, dtype=np.int32))
@@ -149,13 +150,13 @@ def verify_tree(target, draft, node_tokens, parent, max_depth, T, div=DIV_JS, mo
                out_tokens=np.zeros((B, max_depth + 1), np.int32), divs=np.zeros((B, N)),
                row_status=np.zeros(B, np.int32), gap=np.zeros(B, np.float32))
     lib().fsd_oracle_verify_tree(_p(target), _p(draft), _p(node_tokens), _p(parent), B, N, max_depth, V,
-                                 _dt(target), div, float(np.float32(T)), mode, seed, offset,
+                                 _dt(target), div, float(np.float32(T)), mode, seed, offset, seq_offset,
                                  _p(out["path_len"]), _p(out["path_nodes"]), _p(out["out_tokens"]),
                                  _p(out["divs"]), _p(out["row_status"]), _p(out["gap"]))
     return out
 
 
-def sd_verify_chain(target, draft, cand, mode=SAMPLE, seed=0, offset=0):
+def sd_verify_chain(target, draft, cand, mode=SAMPLE, seed=0, offset=0, seq_offset=0):
     target, draft = _c(target), _c(draft)
     cand = _c(np.asarray(cand, dtype=np.int32))
     B, K1, V = target.shape
@@ -165,7 +166,7 @@ def sd_verify_chain(target, draft, cand, mode=SAMPLE, seed=0, offset=0):
                log_ratio=np.zeros((B, K)), margin=np.zeros((B, K)), row_status=np.zeros(B, np.int32),
                gap=np.zeros(B))
     lib().sd_oracle_verify_chain(_p(target), _p(draft), _p(cand), B, K, V, _dt(target), mode, seed,
-                                 offset, _p(out["accept_len"]), _p(out["out_tokens"]),
+                                 offset, seq_offset, _p(out["accept_len"]), _p(out["out_tokens"]),
                                  _p(out["log_ratio"]), _p(out["margin"]), _p(out["row_status"]),
                                  _p(out["gap"]))
     return out

@@ -234,11 +234,13 @@ static int row_is_bad(const void* base, size_t off, long V, int dt) {
 
 /* target [B,K+1,V], draft [B,K,V], cand [B,K].  Outputs: accept_len [B],
  * out_tokens [B,K+1] (-1 padded), divs [B,K] (float64, chosen divergence),
- * row_status [B], gap [B] (may be NULL). */
+ * row_status [B], gap [B] (may be NULL).  seq_offset: the arrays hold sequences
+ * seq_offset .. seq_offset+B-1 of a larger batch (it only enters the random
+ * stream, whose counter carries the sequence index). */
 int fsd_oracle_verify_chain(const void* target, const void* draft, const int32_t* cand, int B, int K,
                             long V, int dt, int div_kind, double T, int mode, uint64_t seed,
-                            uint64_t offset, int32_t* accept_len, int32_t* out_tokens, double* divs,
-                            int32_t* row_status, float* gap) {
+                            uint64_t offset, int seq_offset, int32_t* accept_len, int32_t* out_tokens,
+                            double* divs, int32_t* row_status, float* gap) {
 #pragma omp parallel for schedule(dynamic, 1)
     for (int b = 0; b < B; ++b) {
         int status = 0;
@@ -263,7 +265,7 @@ int fsd_oracle_verify_chain(const void* target, const void* draft, const int32_t
             accept_len[b] = n;
             for (int i = 0; i < n; ++i) out_tokens[(size_t)b * (K + 1) + i] = cand[(size_t)b * K + i];
             out_tokens[(size_t)b * (K + 1) + n] =
-                sample_row(target, soff, V, dt, mode, seed, offset, (uint32_t)b, gap ? &gap[b] : NULL);
+                sample_row(target, soff, V, dt, mode, seed, offset, (uint32_t)(b + seq_offset), gap ? &gap[b] : NULL);
         }
         row_status[b] = status;
     }
@@ -279,7 +281,7 @@ int fsd_oracle_verify_chain(const void* target, const void* draft, const int32_t
 int fsd_oracle_verify_tree(const void* target, const void* draft, const int32_t* node_tokens,
                            const int32_t* parent, int B, int N, int max_depth, long V, int dt,
                            int div_kind, double T, int mode, uint64_t seed, uint64_t offset,
-                           int32_t* path_len, int32_t* path_nodes, int32_t* out_tokens, double* divs,
+                           int seq_offset, int32_t* path_len, int32_t* path_nodes, int32_t* out_tokens, double* divs,
                            int32_t* row_status, float* gap) {
 #pragma omp parallel for schedule(dynamic, 1)
     for (int b = 0; b < B; ++b) {
@@ -328,7 +330,7 @@ int fsd_oracle_verify_tree(const void* target, const void* draft, const int32_t*
                 j = par[j];
             }
             out_tokens[(size_t)b * (max_depth + 1) + win_depth] =
-                sample_row(target, soff, V, dt, mode, seed, offset, (uint32_t)b, gap ? &gap[b] : NULL);
+                sample_row(target, soff, V, dt, mode, seed, offset, (uint32_t)(b + seq_offset), gap ? &gap[b] : NULL);
         }
         row_status[b] = status;
         free(depth);
@@ -369,7 +371,7 @@ static int32_t sample_residual(const void* target, size_t toff, const void* draf
  * margin [B,K] = min(0, log_ratio) - ln u_i (accepted iff > 0), for near-tie
  * reporting; gap [B] = sampler runner-up gap (float64). */
 int sd_oracle_verify_chain(const void* target, const void* draft, const int32_t* cand, int B, int K,
-                           long V, int dt, int mode, uint64_t seed, uint64_t offset,
+                           long V, int dt, int mode, uint64_t seed, uint64_t offset, int seq_offset,
                            int32_t* accept_len, int32_t* out_tokens, double* log_ratio, double* margin,
                            int32_t* row_status, double* gap) {
 #pragma omp parallel for schedule(dynamic, 1)
@@ -393,7 +395,7 @@ int sd_oracle_verify_chain(const void* target, const void* draft, const int32_t*
                 double lq = (double)load_f(draft, doff + (size_t)x, dt) - ld;
                 ratio = (lp == -INFINITY) ? -INFINITY : lp - lq;
                 double u = (double)fsd_oracle_word_to_uniform(
-                    fsd_oracle_random_word(seed, offset, 1u, (uint32_t)b, (uint32_t)i));
+                    fsd_oracle_random_word(seed, offset, 1u, (uint32_t)(b + seq_offset), (uint32_t)i));
                 double thr = ratio < 0.0 ? ratio : 0.0; /* ln min(1, p/q) */
                 mar = thr - log(u);
                 ok = (mar > 0.0); /* min(1,p/q) > u */
@@ -414,12 +416,12 @@ int sd_oracle_verify_chain(const void* target, const void* draft, const int32_t*
             int32_t y = -1;
             if (n < K) {
                 size_t doff = ((size_t)b * (size_t)K + (size_t)n) * (size_t)V;
-                y = sample_residual(target, soff, draft, doff, V, dt, mode, seed, offset, (uint32_t)b,
+                y = sample_residual(target, soff, draft, doff, V, dt, mode, seed, offset, (uint32_t)(b + seq_offset),
                                     lse_n[0], lse_n[1], gap ? &gap[b] : NULL);
             }
             if (y < 0) {
                 float g32;
-                y = sample_row(target, soff, V, dt, mode, seed, offset, (uint32_t)b, &g32);
+                y = sample_row(target, soff, V, dt, mode, seed, offset, (uint32_t)(b + seq_offset), &g32);
                 if (gap) gap[b] = (double)g32;
             }
             out_tokens[(size_t)b * (K + 1) + n] = y;

@@ -1,0 +1,221 @@
+"""ctypes binding of libfsd.so: argument marshalling only.
+
+torch is used for device memory (outputs, workspace) and for the current stream handle; no
+arithmetic of the method happens here.  There is no fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+F32, BF16 = 0, 1
+DIV_KL, DIV_JS, DIV_TV = 0, 1, 2
+SAMPLE, GREEDY = 0, 1
+ROW_NONFINITE, ROW_BAD_PARENT, ROW_TOO_DEEP, ROW_BAD_TOKEN, ROW_INTERNAL = 1, 2, 4, 8, 16
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfsd.so")
+_lib = None
+
+
+class FsdError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = library().fsd_status_string(status).decode()
+        super().__init__(f"{where}: {msg} (status {status})")
+
+
+def library() -> ctypes.CDLL:
+    """The loaded C ABI.  Raises if libfsd.so has not been built (python -m paper_2502_20704_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2502_20704_amd.build` "
+                "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        c = ctypes
+        vp, i32, u64, f32, sz = c.c_void_p, c.c_int, c.c_uint64, c.c_float, c.c_size_t
+        L.fsd_max_vocab.argtypes = [i32]
+        L.fsd_max_vocab.restype = c.c_int64
+        L.fsd_workspace_bytes.argtypes = [i32, i32, i32, i32]
+        L.fsd_workspace_bytes.restype = sz
+        L.fsd_status_string.argtypes = [i32]
+        L.fsd_status_string.restype = c.c_char_p
+        L.fsd_verify_chain.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, f32, i32, u64, u64,
+                                       vp, vp, vp, vp, vp, sz, vp]
+        L.fsd_verify_chain.restype = i32
+        L.fsd_verify_tree.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, f32, i32, u64, u64,
+                                      vp, vp, vp, vp, vp, vp, sz, vp]
+        L.fsd_verify_tree.restype = i32
+        L.sd_verify_chain.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, u64, u64,
+                                      vp, vp, vp, vp, vp, sz, vp]
+        L.sd_verify_chain.restype = i32
+        L.fsd_profile_enable.argtypes = [i32]
+        L.fsd_profile_enable.restype = i32
+        L.fsd_profile_collect.argtypes = [vp, vp]
+        L.fsd_profile_collect.restype = i32
+        L.fsd_debug_set_shape.argtypes = [i32, i32]
+        L.fsd_debug_set_shape.restype = i32
+        L.fsd_debug_set_spin_limit.argtypes = [c.c_uint]
+        L.fsd_debug_set_spin_limit.restype = c.c_uint
+        _lib = L
+    return _lib
+
+
+def fsd_workspace_bytes(B: int, rows_per_seq: int, V: int, dtype: int) -> int:
+    return int(library().fsd_workspace_bytes(B, rows_per_seq, V, dtype))
+
+
+def _dtype_code(t) -> int:
+    import torch
+
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"logits must be float32 or bfloat16, got {t.dtype}")
+
+
+def _check(t, name, shape=None, dtype=None):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} has dtype {t.dtype}, expected {dtype}")
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def _workspace(workspace, need, device):
+    import torch
+
+    if workspace is None:
+        workspace = torch.empty(need + 256, dtype=torch.uint8, device=device)
+    base = workspace.data_ptr()
+    pad = (-base) % 256
+    return workspace, ctypes.c_void_p(base + pad), workspace.numel() - pad
+
+
+def _stream(stream):
+    import torch
+
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def fsd_verify_chain(target, draft, cand, T, div=DIV_JS, mode=SAMPLE, seed=0, offset=0, *, out=None,
+                     workspace=None, stream=None):
+    """target [B,K+1,V], draft [B,K,V], cand int32 [B,K] on the GPU -> dict of device tensors
+    accept_len [B], out_tokens [B,K+1], divergences [B,K], row_status [B]."""
+    import torch
+
+    B, K1, V = target.shape
+    K = K1 - 1
+    dt = _dtype_code(target)
+    _check(target, "target")
+    _check(draft, "draft", (B, K, V), target.dtype)
+    _check(cand, "cand", (B, K), torch.int32)
+    dev = target.device
+    if out is None:
+        out = dict(accept_len=torch.empty(B, dtype=torch.int32, device=dev),
+                   out_tokens=torch.empty((B, K + 1), dtype=torch.int32, device=dev),
+                   divergences=torch.empty((B, K), dtype=torch.float32, device=dev),
+                   row_status=torch.empty(B, dtype=torch.int32, device=dev))
+    need = fsd_workspace_bytes(B, K, V, dt)
+    workspace, wptr, wbytes = _workspace(workspace, need, dev)
+    st = library().fsd_verify_chain(_ptr(target), _ptr(draft), _ptr(cand), B, K, V, dt, div, float(T), mode,
+                                    seed, offset, _ptr(out["accept_len"]), _ptr(out["out_tokens"]),
+                                    _ptr(out.get("divergences")), _ptr(out.get("row_status")), wptr, wbytes,
+                                    _stream(stream))
+    if st != 0:
+        raise FsdError(st, "fsd_verify_chain")
+    out["_workspace"] = workspace
+    return out
+
+
+def fsd_verify_tree(target, draft, node_tokens, parent, max_depth, T, div=DIV_JS, mode=SAMPLE, seed=0,
+                    offset=0, *, out=None, workspace=None, stream=None):
+    """target [B,N+1,V], draft [B,N,V], node_tokens / parent int32 [B,N] -> dict of device tensors
+    path_len [B], path_nodes [B,max_depth], out_tokens [B,max_depth+1], divergences [B,N], row_status [B]."""
+    import torch
+
+    B, N1, V = target.shape
+    N = N1 - 1
+    dt = _dtype_code(target)
+    _check(target, "target")
+    _check(draft, "draft", (B, N, V), target.dtype)
+    _check(node_tokens, "node_tokens", (B, N), torch.int32)
+    _check(parent, "parent", (B, N), torch.int32)
+    dev = target.device
+    if out is None:
+        out = dict(path_len=torch.empty(B, dtype=torch.int32, device=dev),
+                   path_nodes=torch.empty((B, max_depth), dtype=torch.int32, device=dev),
+                   out_tokens=torch.empty((B, max_depth + 1), dtype=torch.int32, device=dev),
+                   divergences=torch.empty((B, N), dtype=torch.float32, device=dev),
+                   row_status=torch.empty(B, dtype=torch.int32, device=dev))
+    need = fsd_workspace_bytes(B, N, V, dt)
+    workspace, wptr, wbytes = _workspace(workspace, need, dev)
+    st = library().fsd_verify_tree(_ptr(target), _ptr(draft), _ptr(node_tokens), _ptr(parent), B, N, max_depth,
+                                   V, dt, div, float(T), mode, seed, offset, _ptr(out["path_len"]),
+                                   _ptr(out["path_nodes"]), _ptr(out["out_tokens"]),
+                                   _ptr(out.get("divergences")), _ptr(out.get("row_status")), wptr, wbytes,
+                                   _stream(stream))
+    if st != 0:
+        raise FsdError(st, "fsd_verify_tree")
+    out["_workspace"] = workspace
+    return out
+
+
+def sd_verify_chain(target, draft, cand, mode=SAMPLE, seed=0, offset=0, *, out=None, workspace=None,
+                    stream=None):
+    """strict speculative decoding on the chain tensors -> accept_len, out_tokens, log_ratio, row_status."""
+    import torch
+
+    B, K1, V = target.shape
+    K = K1 - 1
+    dt = _dtype_code(target)
+    _check(target, "target")
+    _check(draft, "draft", (B, K, V), target.dtype)
+    _check(cand, "cand", (B, K), torch.int32)
+    dev = target.device
+    if out is None:
+        out = dict(accept_len=torch.empty(B, dtype=torch.int32, device=dev),
+                   out_tokens=torch.empty((B, K + 1), dtype=torch.int32, device=dev),
+                   log_ratio=torch.empty((B, K), dtype=torch.float32, device=dev),
+                   row_status=torch.empty(B, dtype=torch.int32, device=dev))
+    need = fsd_workspace_bytes(B, K, V, dt)
+    workspace, wptr, wbytes = _workspace(workspace, need, dev)
+    st = library().sd_verify_chain(_ptr(target), _ptr(draft), _ptr(cand), B, K, V, dt, mode, seed, offset,
+                                   _ptr(out["accept_len"]), _ptr(out["out_tokens"]), _ptr(out.get("log_ratio")),
+                                   _ptr(out.get("row_status")), wptr, wbytes, _stream(stream))
+    if st != 0:
+        raise FsdError(st, "sd_verify_chain")
+    out["_workspace"] = workspace
+    return out
+
+
+def profile_enable(on: bool) -> None:
+    library().fsd_profile_enable(1 if on else 0)
+
+
+def profile_collect():
+    """(count, mean_ms, min_ms) of the vocabulary-reduction kernel since the last collect."""
+    mean, mn = ctypes.c_float(0), ctypes.c_float(0)
+    n = library().fsd_profile_collect(ctypes.byref(mean), ctypes.byref(mn))
+    return int(n), float(mean.value), float(mn.value)
+
+
+def debug_set_spin_limit(polls: int) -> int:
+    return int(library().fsd_debug_set_spin_limit(polls))
+
+
+def debug_set_shape(wavefronts: int, slots_per_thread: int) -> None:
+    st = library().fsd_debug_set_shape(wavefronts, slots_per_thread)
+    if st != 0:
+        raise FsdError(st, "fsd_debug_set_shape")

@@ -1,0 +1,1315 @@
+// HIP kernels and C ABI of the FSD candidate-verification step for gfx950 (MI355X).
+//
+// Three launches per call:
+//   zero_counters   clears the few counters the next two kernels use
+//   pair_reduce     the vocabulary reduction: one (target row, draft row) pair is split over a
+//                   team of G workgroups; every workgroup loads its slice of both rows ONCE into
+//                   registers with 128-bit loads, the team exchanges the softmax normalisers
+//                   through device-scope atomics, and the divergence (paper App. C.1-C.3) is
+//                   accumulated from the registers.  The last workgroup of a team to finish adds
+//                   the team's partial sums in a fixed order, so results are run-to-run identical.
+//   accept_sample   per sequence: the accepted prefix (Sec. 4, eq. 4) or accepted tree path
+//                   (Sec. 6.4) or the strict-SD acceptance (Sec. 3, eq. 1-2), then the extra token
+//                   by Gumbel-max over the vocabulary of one target row, split over GS workgroups.
+//
+// Nothing here is shared with the CPU oracle: Philox4x32-10 and the exact-operation logarithm
+// are implemented a second time from their published / stated definitions.
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <float.h>
+#include <math.h>
+
+#include "fsd.h"
+
+namespace {
+
+constexpr int kWG = 256;          // threads per workgroup (4 wavefronts of 64)
+constexpr int kMaxTeam = 64;      // team members are reduced by one wavefront
+constexpr int kMaxRows = 2048;    // K or N
+constexpr float kLog2e = 1.44269504088896340736f;
+constexpr double kLn2 = 0.69314718055994530942;
+
+// MODE_KL: single-pass KL (absolute error ~1e-7, enough for bfloat16 inputs); MODE_KLP: two-phase,
+// pointwise non-negative KL for binary32 inputs; MODE_LSE: normalisers only (strict SD)
+enum { MODE_KL = 0, MODE_JS = 1, MODE_TV = 2, MODE_LSE = 3, MODE_KLP = 4 };
+enum { KIND_CHAIN = 0, KIND_TREE = 1, KIND_SD = 2 };
+
+#define AGENT __HIP_MEMORY_SCOPE_AGENT
+
+// ------------------------------------------------------------------------------------------
+// small device helpers
+
+__device__ __forceinline__ float neg_inf() { return -__builtin_inff(); }
+
+__device__ __forceinline__ float hw_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float hw_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+// Wavefront reductions on the data-parallel-primitive path (no LDS traffic): four steps reduce
+// each row of 16 lanes (quad swaps, then mirrors), the four row totals are read back as scalars.
+// Every lane gets the result; the order of the additions is fixed.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+template <int CTRL>
+__device__ __forceinline__ int dpp_i(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, false);
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_d(double v) {
+    const int lo = dpp_i<CTRL>(__double2loint(v)), hi = dpp_i<CTRL>(__double2hiint(v));
+    return __hiloint2double(hi, lo);
+}
+constexpr int kDppSwap1 = 0xB1, kDppSwap2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140;
+
+__device__ __forceinline__ float lane_f(float v, int l) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
+}
+__device__ __forceinline__ double lane_d(double v, int l) {
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), l),
+                            __builtin_amdgcn_readlane(__double2loint(v), l));
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+    v = fmaxf(v, dpp_f<kDppSwap1>(v));
+    v = fmaxf(v, dpp_f<kDppSwap2>(v));
+    v = fmaxf(v, dpp_f<kDppHalfMirror>(v));
+    v = fmaxf(v, dpp_f<kDppMirror>(v));
+    return fmaxf(fmaxf(lane_f(v, 0), lane_f(v, 16)), fmaxf(lane_f(v, 32), lane_f(v, 48)));
+}
+__device__ __forceinline__ float wave_sumf(float v) {
+    v += dpp_f<kDppSwap1>(v);
+    v += dpp_f<kDppSwap2>(v);
+    v += dpp_f<kDppHalfMirror>(v);
+    v += dpp_f<kDppMirror>(v);
+    return (lane_f(v, 0) + lane_f(v, 16)) + (lane_f(v, 32) + lane_f(v, 48));
+}
+__device__ __forceinline__ double wave_sum(double v) {
+    v += dpp_d<kDppSwap1>(v);
+    v += dpp_d<kDppSwap2>(v);
+    v += dpp_d<kDppHalfMirror>(v);
+    v += dpp_d<kDppMirror>(v);
+    return (lane_d(v, 0) + lane_d(v, 16)) + (lane_d(v, 32) + lane_d(v, 48));
+}
+
+// One 16-byte slot of a logits row: 8 bfloat16 or 4 binary32 values.
+template <bool BF16> struct Slot { static constexpr int VE = BF16 ? 8 : 4; };
+
+template <bool BF16>
+__device__ __forceinline__ uint4 slot_neg_inf() {
+    const unsigned w = BF16 ? 0xFF80FF80u : 0xFF800000u;
+    return make_uint4(w, w, w, w);
+}
+
+// ALIGNED: rows start on 16-byte boundaries and V is a multiple of the slot width.
+// Otherwise elements are fetched one by one and the ragged tail is padded with -inf.
+template <bool BF16, bool ALIGNED>
+__device__ __forceinline__ uint4 load_slot(const char* row, long slot, long V) {
+    if constexpr (ALIGNED) {
+        return *reinterpret_cast<const uint4*>(row + slot * 16);
+    } else if constexpr (BF16) {
+        const unsigned short* p = reinterpret_cast<const unsigned short*>(row);
+        unsigned w[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const long e = slot * 8 + 2 * d;
+            const unsigned lo = (e < V) ? p[e] : 0xFF80u;
+            const unsigned hi = (e + 1 < V) ? p[e + 1] : 0xFF80u;
+            w[d] = lo | (hi << 16);
+        }
+        return make_uint4(w[0], w[1], w[2], w[3]);
+    } else {
+        const unsigned* p = reinterpret_cast<const unsigned*>(row);
+        unsigned w[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const long e = slot * 4 + d;
+            w[d] = (e < V) ? p[e] : 0xFF800000u;
+        }
+        return make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+template <bool BF16>
+__device__ __forceinline__ void unpack(const uint4& r, float* x) {
+    if constexpr (BF16) {
+        x[0] = __uint_as_float(r.x << 16); x[1] = __uint_as_float(r.x & 0xFFFF0000u);
+        x[2] = __uint_as_float(r.y << 16); x[3] = __uint_as_float(r.y & 0xFFFF0000u);
+        x[4] = __uint_as_float(r.z << 16); x[5] = __uint_as_float(r.z & 0xFFFF0000u);
+        x[6] = __uint_as_float(r.w << 16); x[7] = __uint_as_float(r.w & 0xFFFF0000u);
+    } else {
+        x[0] = __uint_as_float(r.x); x[1] = __uint_as_float(r.y);
+        x[2] = __uint_as_float(r.z); x[3] = __uint_as_float(r.w);
+    }
+}
+
+template <bool BF16>
+__device__ __forceinline__ float load_elem(const char* row, long e) {
+    if constexpr (BF16)
+        return __uint_as_float(static_cast<unsigned>(reinterpret_cast<const unsigned short*>(row)[e]) << 16);
+    else
+        return reinterpret_cast<const float*>(row)[e];
+}
+
+// ------------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11) and the exact-operation Gumbel transform
+
+struct U4 { unsigned x, y, z, w; };
+
+__device__ __forceinline__ U4 philox4x32_10(unsigned c0, unsigned c1, unsigned c2, unsigned c3, unsigned k0,
+                                            unsigned k1) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const unsigned hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const unsigned hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        const unsigned n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return U4{c0, c1, c2, c3};
+}
+
+// (2*(w>>9)+1) * 2^-24: an odd 24-bit integer scaled, exact in binary32, inside (0,1)
+__device__ __forceinline__ float word_to_uniform(unsigned w) {
+    return __fmul_rn(static_cast<float>(((w >> 9) << 1) | 1u), 0x1p-24f);
+}
+
+// ln x for positive normal x using only correctly rounded operations:
+// x = 2^e m, m in [sqrt(1/2), sqrt(2)); ln m = 2 atanh((m-1)/(m+1)), series to s^11.
+__device__ __forceinline__ float flog32(float x) {
+    const unsigned bits = __float_as_uint(x);
+    int e = static_cast<int>(bits >> 23) - 127;
+    float m = __uint_as_float((bits & 0x007FFFFFu) | 0x3F800000u);
+    if (m >= 0x1.6a09e6p+0f) { m = __fmul_rn(m, 0.5f); e += 1; }
+    const float s = __fdiv_rn(__fsub_rn(m, 1.0f), __fadd_rn(m, 1.0f));
+    const float s2 = __fmul_rn(s, s);
+    float poly = 0x1.745d18p-4f;
+    poly = __fmaf_rn(poly, s2, 0x1.c71c72p-4f);
+    poly = __fmaf_rn(poly, s2, 0x1.24924ap-3f);
+    poly = __fmaf_rn(poly, s2, 0x1.99999ap-3f);
+    poly = __fmaf_rn(poly, s2, 0x1.555556p-2f);
+    poly = __fmaf_rn(poly, s2, 1.0f);
+    const float lnm = __fmul_rn(__fmul_rn(2.0f, s), poly);
+    return __fmaf_rn(static_cast<float>(e), 0x1.62e43p-1f, lnm);
+}
+
+__device__ __forceinline__ float gumbel(unsigned w) {
+    const float t = -flog32(word_to_uniform(w));
+    return -flog32(t);
+}
+
+// ------------------------------------------------------------------------------------------
+// workspace view
+
+struct Ws {
+    unsigned* counters;  // 64 spare words, then arrive[R], done[R], sdone[B]
+    unsigned* arrive;    // [R] team members that posted their normaliser partials
+    unsigned* done;      // [R] team members that posted their divergence partial
+    unsigned* sdone;     // [B] sampler workgroups that posted
+    unsigned long long* part1;  // [R][G][4]: (kt,kd) | St | Sd | W
+    double* part2;       // [R][G][4] divergence words (one used, four for TV)
+    float* div;          // [R]
+    int* pst;            // [R] status bits per pair
+    double* lse2;        // [R][2] log2-sum-exp2 of the target / draft row of the pair
+    double* lr;          // [R] strict SD: ln p(x) - ln q(x)
+    unsigned long long* spart;  // [B][GS][4]
+};
+
+struct PairParams {
+    const char* target;
+    const char* draft;
+    const int32_t* parent;  // tree only
+    const int32_t* cand;    // strict SD only
+    int rows;               // K or N
+    int npairs;             // B * rows
+    long V;
+    long nslots;
+    int spm;                // slots per team member
+    int G;
+    unsigned spin_limit;
+    float* user_div;        // optional [R]
+    Ws ws;
+};
+
+// ------------------------------------------------------------------------------------------
+// kernel 0: clear the counters and the exchange words (a zero word means "not posted yet")
+
+__global__ void zero_counters(uint4* p, long n16) {
+    const long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n16) p[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
+// ------------------------------------------------------------------------------------------
+// kernel 1: vocabulary reduction over row pairs
+
+// The team's exchange goes through 64-bit words that are only ever touched with device-scope
+// atomic loads and stores, which are performed at the memory side: no cache write-back or
+// invalidate is needed to see them.  The words are cleared before the kernel starts and a posted
+// word is never zero (+0.0 is posted as -0.0), so each word says by itself whether it has
+// arrived: a reader polls the words it needs, and no counter or fence sits between a post and
+// its use.
+__device__ __forceinline__ void post64(unsigned long long* p, unsigned long long v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, AGENT);
+}
+__device__ __forceinline__ unsigned long long read64(const unsigned long long* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, AGENT);
+}
+__device__ __forceinline__ unsigned long long dbits(double x) {   // never 0
+    const unsigned long long u = static_cast<unsigned long long>(__double_as_longlong(x));
+    return u ? u : 0x8000000000000000ull;
+}
+__device__ __forceinline__ double bitsd(unsigned long long x) {
+    return __longlong_as_double(static_cast<long long>(x));
+}
+__device__ __forceinline__ unsigned fbits(float x) {              // never 0
+    const unsigned u = __float_as_uint(x);
+    return u ? u : 0x80000000u;
+}
+
+// Reference exponents are integers (k = ceil(max * log2e)), so moving a sum from one reference
+// to another is an exact scaling by a power of two.
+__device__ __forceinline__ int kdiff(float k, float M) { return static_cast<int>(k - M); }
+
+// One posted phase-1 partial (of a wavefront, a workgroup or a team member): reference exponents
+// kt, kd; St = sum 2^(a log2e - kt) over the target slice, Sd likewise for the draft;
+// W = sum 2^(a log2e - kt) (a - b), +inf when the draft masks an entry the target does not.
+struct Part1 { float kt, kd; double St, Sd, W; };
+
+// Merge the partials held by lanes 0..n-1 of the calling wavefront; every lane gets the result.
+__device__ __forceinline__ Part1 merge_part1(const Part1& r, bool with_w) {
+    Part1 o;
+    o.kt = wave_max((r.St > 0.0) ? r.kt : neg_inf());
+    o.kd = wave_max((r.Sd > 0.0) ? r.kd : neg_inf());
+    const bool nt = (r.St != r.St), nd = (r.Sd != r.Sd);
+    const double at = (r.St > 0.0) ? ldexp(r.St, kdiff(r.kt, o.kt)) : (nt ? r.St : 0.0);
+    const double ad = (r.Sd > 0.0) ? ldexp(r.Sd, kdiff(r.kd, o.kd)) : (nd ? r.Sd : 0.0);
+    o.St = wave_sum(at);
+    o.Sd = wave_sum(ad);
+    o.W = 0.0;
+    if (with_w) {
+        const bool inf = __any(r.W == __builtin_inf()) != 0;
+        const double aw = (r.St > 0.0 && r.W == r.W) ? ldexp(r.W, kdiff(r.kt, o.kt)) : 0.0;
+        o.W = inf ? __builtin_inf() : wave_sum(aw);
+    }
+    if (o.kt == neg_inf()) o.kt = 0.0f;   // no mass anywhere: St is 0 (or NaN) and says so
+    if (o.kd == neg_inf()) o.kd = 0.0f;
+    return o;
+}
+
+// Lane i < G polls member i's four words until all have arrived (at most `limit` polls).
+// Returns false if they did not.
+__device__ __forceinline__ bool poll_part1(const unsigned long long* p1, int G, unsigned limit, Part1& r) {
+    const int lane = threadIdx.x & 63;
+    unsigned long long w0 = 1, w1 = 1, w2 = 1, w3 = 1;
+    unsigned polls = 0;
+    bool ok = true;
+    for (;;) {
+        if (lane < G) {
+            w0 = read64(p1 + lane * 4 + 0);
+            w1 = read64(p1 + lane * 4 + 1);
+            w2 = read64(p1 + lane * 4 + 2);
+            w3 = read64(p1 + lane * 4 + 3);
+        }
+        const bool missing = (w0 == 0) | (w1 == 0) | (w2 == 0) | (w3 == 0);
+        if (!__any(missing)) break;
+        if (polls++ >= limit) { ok = false; break; }
+        __builtin_amdgcn_s_sleep(1);
+    }
+    r = Part1{0.0f, 0.0f, 0.0, 0.0, 0.0};
+    if (lane < G) {
+        r.kt = __uint_as_float(static_cast<unsigned>(w0));
+        r.kd = __uint_as_float(static_cast<unsigned>(w0 >> 32));
+        r.St = bitsd(w1);
+        r.Sd = bitsd(w2);
+        r.W = bitsd(w3);
+    }
+    return ok;
+}
+
+// Lane i < G polls the first NWORDS of member i's four divergence words.
+template <int NWORDS>
+__device__ __forceinline__ bool poll_part2(const unsigned long long* p2, int G, unsigned limit, double (&v)[NWORDS]) {
+    const int lane = threadIdx.x & 63;
+    unsigned long long w[NWORDS];
+#pragma unroll
+    for (int k = 0; k < NWORDS; ++k) w[k] = 1;
+    unsigned polls = 0;
+    bool ok = true;
+    for (;;) {
+        bool missing = false;
+        if (lane < G) {
+#pragma unroll
+            for (int k = 0; k < NWORDS; ++k) { w[k] = read64(p2 + lane * 4 + k); missing |= (w[k] == 0); }
+        }
+        if (!__any(missing)) break;
+        if (polls++ >= limit) { ok = false; break; }
+        __builtin_amdgcn_s_sleep(1);
+    }
+#pragma unroll
+    for (int k = 0; k < NWORDS; ++k) v[k] = (lane < G) ? bitsd(w[k]) : 0.0;
+    return ok;
+}
+
+// Persistent kernel: the grid is no larger than what is resident at once and a multiple of the
+// team size G.  Workgroup w is member w % G of team w / G and walks the row pairs
+// team, team + nteams, ...; the members of a team therefore meet at every pair they share.
+// Per pair a workgroup passes two barriers.  The loads of the next pair are issued as soon as
+// phase 1 has consumed the current ones, so they are in flight during the exchange and phase 2;
+// the bookkeeping of a pair (posting its divergence partial, finding out who finishes it) rides
+// along with the next pair's first barrier.
+template <bool BF16, int NV, int MODE, bool ALIGNED, int NW>
+__global__ __launch_bounds__(NW * 64) void pair_reduce(PairParams P) {
+    constexpr int VE = Slot<BF16>::VE;
+    constexpr int ES = BF16 ? 2 : 4;
+    constexpr int WGS = NW * 64;
+    constexpr bool WAITS = (MODE == MODE_JS || MODE == MODE_TV || MODE == MODE_KLP);
+    constexpr bool TRACKS_MASK = (MODE == MODE_KL || MODE == MODE_KLP);
+    // per-wavefront partials are double-buffered by pair parity: a wavefront may already write
+    // the next pair's while the first wavefront still reads this pair's
+    __shared__ double s_w[2][NW][3];   // per wavefront: St, Sd, W
+    __shared__ float s_k[2][NW][2];    // per wavefront: kt, kd
+    constexpr int PW = (MODE == MODE_TV) ? 4 : 1;   // divergence words a member posts
+    __shared__ double s_p[NW][4];   // per wavefront: phase-2 partials of the previous pair
+    __shared__ float s_x[6];        // team-wide: kt, kd, 1/St, 1/Sd, arrived?
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int G = P.G;
+    const int member = static_cast<int>(blockIdx.x) % G;
+    const int team = static_cast<int>(blockIdx.x) / G;
+    const int nteams = static_cast<int>(gridDim.x) / G;
+    const long s0 = static_cast<long>(member) * P.spm;
+    const long s1 = (s0 + P.spm < P.nslots) ? s0 + P.spm : P.nslots;
+
+    uint4 ra[NV], rb[NV];
+    auto row_ptrs = [&](int pair, const char*& tptr, const char*& dptr) {
+        const int b = pair / P.rows;
+        const int j = pair - b * P.rows;
+        int trow = j;
+        if (P.parent) {
+            const int par = P.parent[pair];
+            trow = (par >= -1 && par < j) ? par + 1 : 0;   // invalid parents are reported by the next kernel
+        }
+        tptr = P.target + (static_cast<size_t>(b) * (P.rows + 1) + trow) * static_cast<size_t>(P.V) * ES;
+        dptr = P.draft + static_cast<size_t>(pair) * static_cast<size_t>(P.V) * ES;
+    };
+    // ---- the only HBM reads of the reduction: NV slots of each row per thread
+    auto load_item = [&](int pair) {
+        const char *tptr, *dptr;
+        row_ptrs(pair, tptr, dptr);
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            const long s = s0 + k * WGS + tid;
+            if (s < s1) {
+                ra[k] = load_slot<BF16, ALIGNED>(tptr, s, P.V);
+                rb[k] = load_slot<BF16, ALIGNED>(dptr, s, P.V);
+            } else {
+                ra[k] = slot_neg_inf<BF16>();
+                rb[k] = slot_neg_inf<BF16>();
+            }
+        }
+    };
+
+    // ---- what the first wavefront does for a pair once all its members are through with it
+    auto finish_pair = [&](int pair) {
+        unsigned long long* p1 = P.ws.part1 + static_cast<size_t>(pair) * G * 4;
+        unsigned long long* p2 = reinterpret_cast<unsigned long long*>(P.ws.part2) + static_cast<size_t>(pair) * G * 4;
+        int status = 0;
+        double value = 0.0, lse2_t = 0.0, lse2_d = 0.0;
+        bool ok;
+        if constexpr (WAITS) {
+            double pv[PW];
+            ok = poll_part2<PW>(p2, G, P.spin_limit, pv);
+            if constexpr (MODE == MODE_TV) {
+                // sum of (p - q)+ and of (q - p)+ are the same number; the side that avoids the
+                // heavy entries (smaller sum of p + q over its entries) carries the smaller
+                // rounding error, which matters for nearly one-hot rows
+                const double A = wave_sum(pv[0]), Bn = wave_sum(pv[1]), MA = wave_sum(pv[2]), MB = wave_sum(pv[3]);
+                value = (MA != MA || MB != MB) ? __builtin_nan("") : (MA <= MB ? A : Bn);
+            } else {
+                const double total = wave_sum(pv[0]);
+                value = (MODE == MODE_JS) ? 0.25 * kLn2 * total : 0.5 * kLn2 * total;
+            }
+            if (value != value) status |= FSD_ROW_NONFINITE;   // NaN / +inf logits, or a row without mass
+        } else {
+            Part1 r;
+            ok = poll_part1(p1, G, P.spin_limit, r);
+            const Part1 m = merge_part1(r, MODE == MODE_KL);
+            const bool bad = !(m.St > 0.0) || !(m.Sd > 0.0) || !(m.St < __builtin_inf()) || !(m.Sd < __builtin_inf()) ||
+                             !(m.kt < __builtin_inff()) || !(m.kd < __builtin_inff());
+            if (bad) status |= FSD_ROW_NONFINITE;
+            lse2_t = static_cast<double>(m.kt) + log2(m.St);
+            lse2_d = static_cast<double>(m.kd) + log2(m.Sd);
+            if constexpr (MODE == MODE_KL) {
+                // KL = sum_v p_v (a_v - b_v) - (lse_t - lse_d), p_v = 2^(a log2e - kt) / St
+                value = (m.W == __builtin_inf()) ? __builtin_inf() : m.W / m.St - (lse2_t - lse2_d) * kLn2;
+            }
+        }
+        if (!ok) status |= FSD_ROW_INTERNAL;
+        if (value < 0.0) value = 0.0;
+        if (status) value = __builtin_nan("");
+        if (lane == 0) {
+            P.ws.div[pair] = static_cast<float>(value);
+            P.ws.lse2[2 * pair] = lse2_t;
+            P.ws.lse2[2 * pair + 1] = lse2_d;
+            if (P.user_div) P.user_div[pair] = static_cast<float>(value);
+            if constexpr (MODE == MODE_LSE) {
+                // strict SD: ln p(x) - ln q(x) at the candidate token (Sec. 3, eq. 1)
+                const int x = P.cand[pair];
+                double ratio = __builtin_nan("");
+                if (x < 0 || x >= P.V) {
+                    status |= FSD_ROW_BAD_TOKEN;
+                } else if (!(status & FSD_ROW_NONFINITE)) {
+                    const char *tptr, *dptr;
+                    row_ptrs(pair, tptr, dptr);
+                    const double lp = static_cast<double>(load_elem<BF16>(tptr, x)) - lse2_t * kLn2;
+                    const double lq = static_cast<double>(load_elem<BF16>(dptr, x)) - lse2_d * kLn2;
+                    ratio = (lp == -__builtin_inf()) ? -__builtin_inf() : lp - lq;
+                }
+                P.ws.lr[pair] = ratio;
+                if (P.user_div) P.user_div[pair] = static_cast<float>(ratio);
+            }
+            P.ws.pst[pair] = status;
+        }
+    };
+
+    // bookkeeping carried from one pair to the next (first wavefront only)
+    int pend_post = -1;          // pair whose phase-2 partial sits in s_p, not yet posted
+    int pend_fin = -1;           // pair whose done-counter this workgroup has bumped ...
+    unsigned pend_prev = 0;      // ... and what the counter read before (lane 0)
+
+    int pair = team;
+    int buf = 0;
+    if (pair < P.npairs) load_item(pair);
+    for (; pair < P.npairs; pair += nteams, buf ^= 1) {
+        // ---- phase 1, per wavefront: maximum, then sums of 2^(z log2e - k) with k = ceil(max log2e)
+        float mt = neg_inf(), md = neg_inf();
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            float a[VE], c[VE];
+            unpack<BF16>(ra[k], a);
+            unpack<BF16>(rb[k], c);
+#pragma unroll
+            for (int e = 0; e < VE; ++e) { mt = fmaxf(mt, a[e]); md = fmaxf(md, c[e]); }
+        }
+        mt = wave_max(mt);
+        md = wave_max(md);
+        const float kt = (mt == neg_inf()) ? 0.0f : ceilf(mt * kLog2e);
+        const float kd = (md == neg_inf()) ? 0.0f : ceilf(md * kLog2e);
+
+        // the exponentials are kept: phase 2 rescales them instead of touching the logits again
+        float ea[WAITS ? NV * VE : 1], eb[WAITS ? NV * VE : 1];
+        float st = 0.0f, sd = 0.0f, w = 0.0f, dmax = neg_inf();
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            float a[VE], c[VE];
+            unpack<BF16>(ra[k], a);
+            unpack<BF16>(rb[k], c);
+#pragma unroll
+            for (int e = 0; e < VE; ++e) {
+                const float xa = hw_exp2(fmaf(a[e], kLog2e, -kt));
+                const float xb = hw_exp2(fmaf(c[e], kLog2e, -kd));
+                if constexpr (WAITS) { ea[k * VE + e] = xa; eb[k * VE + e] = xb; }
+                st += xa;
+                sd += xb;
+                if constexpr (TRACKS_MASK) {
+                    const float diff = a[e] - c[e];
+                    dmax = fmaxf(dmax, diff);   // +inf iff the draft masks an entry the target does not
+                    if constexpr (MODE == MODE_KL) w = fmaf(xa, fminf(fmaxf(diff, -FLT_MAX), FLT_MAX), w);
+                }
+            }
+        }
+        // ---- the registers that held the logits are free: fetch the next pair behind the exchange
+        if (pair + nteams < P.npairs) load_item(pair + nteams);
+
+        {
+            const double wst = wave_sum(static_cast<double>(st));
+            const double wsd = wave_sum(static_cast<double>(sd));
+            double ww = 0.0;
+            if constexpr (MODE == MODE_KL) {
+                ww = wave_sum(static_cast<double>(w));
+                if (wave_max(dmax) == __builtin_inff()) ww = __builtin_inf();
+            }
+            if (lane == 0) {
+                s_w[buf][wave][0] = wst; s_w[buf][wave][1] = wsd; s_w[buf][wave][2] = ww;
+                s_k[buf][wave][0] = kt; s_k[buf][wave][1] = kd;
+            }
+        }
+        __syncthreads();   // barrier 1: wavefront partials of this pair (and s_p of the previous one) are in LDS
+
+        unsigned long long* p1 = P.ws.part1 + static_cast<size_t>(pair) * G * 4;
+        if (wave == 0) {
+            // the previous pair: post its divergence partial and bump its done-counter
+            if constexpr (WAITS) {
+                if (pend_post >= 0 && lane < PW) {
+                    double part = s_p[0][lane];
+#pragma unroll
+                    for (int k = 1; k < NW; ++k) part += s_p[k][lane];
+                    unsigned long long* q2 = reinterpret_cast<unsigned long long*>(P.ws.part2) + static_cast<size_t>(pend_post) * G * 4;
+                    post64(q2 + member * 4 + lane, dbits(part));
+                }
+            }
+            // ... and finish the one before if this workgroup was the last to bump its counter
+            if (pend_fin >= 0) {
+                const unsigned prev = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(pend_prev)));
+                if (prev == static_cast<unsigned>(G) - 1u) finish_pair(pend_fin);
+                pend_fin = -1;
+            }
+            if constexpr (WAITS) {
+                if (pend_post >= 0) {
+                    if (lane == 0) pend_prev = __hip_atomic_fetch_add(P.ws.done + pend_post, 1u, __ATOMIC_RELAXED, AGENT);
+                    pend_fin = pend_post;
+                    pend_post = -1;
+                }
+            }
+            // this pair: merge the wavefronts and post the workgroup's normaliser partial
+            Part1 r{0.0f, 0.0f, 0.0, 0.0, 0.0};
+            if (lane < NW) {
+                r.kt = s_k[buf][lane][0]; r.kd = s_k[buf][lane][1];
+                r.St = s_w[buf][lane][0]; r.Sd = s_w[buf][lane][1]; r.W = s_w[buf][lane][2];
+            }
+            const Part1 m = merge_part1(r, MODE == MODE_KL);
+            if (lane == 0) {
+                unsigned long long* slot = p1 + member * 4;
+                post64(slot + 0, static_cast<unsigned long long>(fbits(m.kt)) | (static_cast<unsigned long long>(fbits(m.kd)) << 32));
+                post64(slot + 1, dbits(m.St));
+                post64(slot + 2, dbits(m.Sd));
+                post64(slot + 3, dbits(m.W));
+            }
+            if constexpr (WAITS) {
+                // ---- exchange: wait for the whole team's partials (bounded), merge them
+                Part1 t;
+                const bool ok = poll_part1(p1, G, P.spin_limit, t);
+                const Part1 all = merge_part1(t, false);
+                if (lane == 0) {
+                    s_x[0] = all.kt; s_x[1] = all.kd;
+                    s_x[2] = 1.0f / static_cast<float>(all.St);   // inf for a row without mass, NaN for a bad one
+                    s_x[3] = 1.0f / static_cast<float>(all.Sd);
+                    s_x[4] = ok ? 1.0f : 0.0f;
+                    if (!ok) atomicOr(P.ws.counters + 1, 1u);
+                }
+            } else {
+                if (lane == 0) pend_prev = __hip_atomic_fetch_add(P.ws.done + pair, 1u, __ATOMIC_RELAXED, AGENT);
+                pend_fin = pair;
+            }
+        }
+
+        if constexpr (WAITS) {
+            __syncthreads();   // barrier 2: the team's normalisers are in s_x
+            // p = ea * ft with ft = 2^(kt - Kt) / St: exact power of two times one rounded reciprocal.
+            // A wavefront without mass has only zeros in ea; its factor is 0 (NaN if the row is unusable).
+            const bool mass_t = st > 0.0f || st != st, mass_d = sd > 0.0f || sd != sd;
+            const float ft = __any(mass_t) ? ldexpf(s_x[2], kdiff(kt, s_x[0])) : s_x[2] * 0.0f;
+            const float fd = __any(mass_d) ? ldexpf(s_x[3], kdiff(kd, s_x[1])) : s_x[3] * 0.0f;
+            const bool timed_out = (s_x[4] == 0.0f);
+
+            // ---- phase 2 from the registers.  Only relative errors enter p and q, and both
+            // divergences are evaluated as functions of (p, q) alone, so the result is the
+            // divergence of a slightly perturbed input.
+            float acc = 0.0f;
+            if constexpr (MODE == MODE_JS) {
+                // with s = p + q, r = (p - q)/s, u = 1 + r = 2p/s, v = 1 - r = 2q/s:
+                //   p ln(2p/s) + q ln(2q/s) = (s/2) ln2 [u log2 u + v log2 v]
+                // u log2 u + v log2 v is even in r and flat at r = 0: no cancellation for p ~ q.
+#pragma unroll
+                for (int i = 0; i < NV * VE; ++i) {
+                    const float p = __fmul_rn(ea[i], ft), q = __fmul_rn(eb[i], fd);   // rounded products: p == q for equal rows
+                    const float sum = p + q;
+                    const float r = (p - q) * __builtin_amdgcn_rcpf(fmaxf(sum, 1e-37f));
+                    // v = 2 - u is exact, so (u, v) stay symmetric about 1 and the rounding of 1 + r
+                    // only perturbs r instead of entering h to first order
+                    const float u = fminf(fmaxf(1.0f + r, 1e-37f), 2.0f), v = fmaxf(2.0f - u, 1e-37f);
+                    const float h = fmaf(v, hw_log2(v), u * hw_log2(u));
+                    acc = fmaf(sum, h, acc);
+                }
+            } else if constexpr (MODE == MODE_KLP) {
+                // p ln(p/q) + q - p = (s/2) [u ln(u/v) + v - u] >= 0 entry by entry (the added q - p
+                // sums to zero), second order in r, so neither the normalisers' errors nor those of
+                // the exponentials enter to first order.
+#pragma unroll
+                for (int i = 0; i < NV * VE; ++i) {
+                    const float p = __fmul_rn(ea[i], ft), q = __fmul_rn(eb[i], fd);   // rounded products: p == q for equal rows
+                    const float sum = p + q;
+                    const float r = (p - q) * __builtin_amdgcn_rcpf(fmaxf(sum, 1e-37f));
+                    const float u = fminf(fmaxf(1.0f + r, 1e-37f), 2.0f), v = fmaxf(2.0f - u, 1e-37f);
+                    const float h = fmaf(u, hw_log2(u) - hw_log2(v), (v - u) * kLog2e);
+                    acc = fmaf(sum, h, acc);
+                }
+            }
+            double part[PW];
+            if constexpr (MODE == MODE_TV) {
+                float A = 0.0f, Bn = 0.0f, MA = 0.0f, MB = 0.0f;
+#pragma unroll
+                for (int i = 0; i < NV * VE; ++i) {
+                    const float p = __fmul_rn(ea[i], ft), q = __fmul_rn(eb[i], fd);   // rounded products: p == q for equal rows
+                    const float d = p - q, sum = p + q;
+                    A += fmaxf(d, 0.0f);
+                    Bn += fmaxf(-d, 0.0f);
+                    MA += (d > 0.0f) ? sum : 0.0f;
+                    MB += (d < 0.0f) ? sum : 0.0f;
+                }
+                // max() drops NaN: an unusable row (NaN factor) is made to reach the side selection
+                if (ft != ft || fd != fd) { A = ft + fd; Bn = A; MA = A; MB = A; }
+                part[0] = wave_sum(static_cast<double>(A));
+                part[1] = wave_sum(static_cast<double>(Bn));
+                part[2] = wave_sum(static_cast<double>(MA));
+                part[3] = wave_sum(static_cast<double>(MB));
+            } else {
+                part[0] = wave_sum(static_cast<double>(acc));
+                if constexpr (MODE == MODE_KLP) {
+                    if (wave_max(dmax) == __builtin_inff()) part[0] += __builtin_inf();   // stays NaN for a bad row
+                }
+            }
+            if (lane == 0) {   // read after the next barrier 1 (or the one after the loop)
+#pragma unroll
+                for (int k = 0; k < PW; ++k) s_p[wave][k] = timed_out ? __builtin_nan("") : part[k];
+            }
+            pend_post = pair;
+        }
+    }
+
+    // ---- drain the bookkeeping of the last pairs
+    if constexpr (WAITS) {
+        __syncthreads();
+        if (wave == 0 && pend_post >= 0) {
+            if (lane < PW) {
+                double part = s_p[0][lane];
+#pragma unroll
+                for (int k = 1; k < NW; ++k) part += s_p[k][lane];
+                unsigned long long* q2 = reinterpret_cast<unsigned long long*>(P.ws.part2) + static_cast<size_t>(pend_post) * G * 4;
+                post64(q2 + member * 4 + lane, dbits(part));
+            }
+            if (pend_fin >= 0) {
+                const unsigned prev = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(pend_prev)));
+                if (prev == static_cast<unsigned>(G) - 1u) finish_pair(pend_fin);
+            }
+            if (lane == 0) pend_prev = __hip_atomic_fetch_add(P.ws.done + pend_post, 1u, __ATOMIC_RELAXED, AGENT);
+            pend_fin = pend_post;
+        }
+    }
+    if (wave == 0 && pend_fin >= 0) {
+        const unsigned prev = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(pend_prev)));
+        if (prev == static_cast<unsigned>(G) - 1u) finish_pair(pend_fin);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// kernel 2: acceptance + extra token
+
+struct SampleParams {
+    const char* target;
+    const char* draft;        // strict SD only
+    const int32_t* tokens;    // cand [B,K] or node_tokens [B,N]
+    const int32_t* parent;    // tree only
+    int rows;                 // K or N
+    int max_depth;            // tree only
+    long V;
+    long nslots;
+    int sps;                  // slots per sampler workgroup
+    int GS;
+    float T;
+    int mode;
+    unsigned seed_lo, seed_hi, off_lo, off_hi;
+    int32_t* out_len;
+    int32_t* out_tokens;
+    int32_t* path_nodes;      // tree only
+    int32_t* row_status;      // optional
+    Ws ws;
+};
+
+struct Best { float score; int idx; };
+
+__device__ __forceinline__ Best better(Best a, Best b) {
+    return (b.score > a.score || (b.score == a.score && b.idx < a.idx)) ? b : a;
+}
+__device__ __forceinline__ Best wave_best(Best v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        Best other{__shfl_xor(v.score, o), __shfl_xor(v.idx, o)};
+        v = better(v, other);
+    }
+    return v;
+}
+
+template <bool BF16, bool ALIGNED, int KIND>
+__global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
+    constexpr int VE = Slot<BF16>::VE;
+    constexpr int ES = BF16 ? 2 : 4;
+    extern __shared__ int s_dyn[];   // tree: par[N], anc[N], acc[N], dep[N]
+    __shared__ int s_n, s_st, s_key, s_last;
+    __shared__ Best s_best[8];
+    __shared__ int s_bad[4];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int gs = blockIdx.x, b = blockIdx.y;
+    const int rows = P.rows;
+
+    if (tid == 0) { s_n = rows; s_st = 0; s_key = 0; }
+    __syncthreads();
+
+    // ---- which positions are accepted
+    int n = 0;         // accepted prefix length / path depth
+    int sample_row = 0;
+    int winner = -1;
+    if constexpr (KIND == KIND_CHAIN || KIND == KIND_SD) {
+        for (int i = tid; i < rows; i += kWG) {
+            const int pr = b * rows + i;
+            const int st = P.ws.pst[pr];
+            bool ok;
+            if constexpr (KIND == KIND_CHAIN) {
+                ok = (P.ws.div[pr] <= P.T);   // Sec. 4 eq. 4 (NaN compares false)
+            } else {
+                // Sec. 3 eq. 1-2 in the log domain: min(1, p/q) > u  <=>  min(0, ln p - ln q) - ln u > 0
+                const double ratio = P.ws.lr[pr];
+                const U4 r = philox4x32_10((static_cast<unsigned>(i) >> 2) | (1u << 30), static_cast<unsigned>(b),
+                                           P.off_lo, P.off_hi, P.seed_lo, P.seed_hi);
+                const unsigned wsel = (i & 3) == 0 ? r.x : (i & 3) == 1 ? r.y : (i & 3) == 2 ? r.z : r.w;
+                const double u = static_cast<double>(word_to_uniform(wsel));
+                const double thr = ratio < 0.0 ? ratio : 0.0;
+                ok = (thr - log(u) > 0.0);
+            }
+            if (st) atomicOr(&s_st, st);
+            if (!ok) atomicMin(&s_n, i);
+        }
+        __syncthreads();
+        n = s_n;
+        sample_row = n;
+    } else {
+        int* par = s_dyn;
+        int* anc = s_dyn + rows;
+        int* acc = s_dyn + 2 * rows;
+        int* dep = s_dyn + 3 * rows;
+        for (int j = tid; j < rows; j += kWG) {
+            const int pr = b * rows + j;
+            int p = P.parent[pr];
+            if (p < -1 || p >= j) { atomicOr(&s_st, FSD_ROW_BAD_PARENT); p = -1; }
+            const int st = P.ws.pst[pr];
+            if (st) atomicOr(&s_st, st);
+            par[j] = p; anc[j] = p; dep[j] = 1;
+            acc[j] = (P.ws.div[pr] <= P.T) ? 1 : 0;
+        }
+        __syncthreads();
+        // pointer jumping: after r rounds anc[j] is the 2^r-th ancestor, acc/dep cover that stretch
+        for (int span = 1; span < rows; span <<= 1) {
+            int na[kMaxRows / kWG], nacc[kMaxRows / kWG], nd[kMaxRows / kWG];
+#pragma unroll
+            for (int q = 0; q < kMaxRows / kWG; ++q) {
+                const int j = tid + q * kWG;
+                if (j < rows) {
+                    const int a = anc[j];
+                    na[q] = a; nacc[q] = acc[j]; nd[q] = dep[j];
+                    if (a >= 0) { na[q] = anc[a]; nacc[q] = acc[j] & acc[a]; nd[q] = dep[j] + dep[a]; }
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < kMaxRows / kWG; ++q) {
+                const int j = tid + q * kWG;
+                if (j < rows) { anc[j] = na[q]; acc[j] = nacc[q]; dep[j] = nd[q]; }
+            }
+            __syncthreads();
+        }
+        for (int j = tid; j < rows; j += kWG) {
+            if (dep[j] > P.max_depth) atomicOr(&s_st, FSD_ROW_TOO_DEEP);
+            if (acc[j]) atomicMax(&s_key, (dep[j] << 11) | (kMaxRows - 1 - j));   // deepest, then lowest index
+        }
+        __syncthreads();
+        const int key = s_key;
+        if (key) { n = key >> 11; winner = kMaxRows - 1 - (key & (kMaxRows - 1)); }
+        sample_row = winner + 1;
+    }
+    int status = s_st;
+    if (P.ws.counters[1]) status |= FSD_ROW_INTERNAL;   // a bounded wait of the reduction kernel expired
+
+    // ---- Gumbel-max over this workgroup's share of the sampled target row
+    const char* trow = P.target + (static_cast<size_t>(b) * (rows + 1) + sample_row) * static_cast<size_t>(P.V) * ES;
+    bool residual = false;
+    const char* drow = nullptr;
+    float lt = 0.0f, ld = 0.0f;
+    if constexpr (KIND == KIND_SD) {
+        if (n < rows) {   // rejected at n: the residual of Sec. 3 eq. 3 needs the draft row as well
+            residual = true;
+            drow = P.draft + (static_cast<size_t>(b) * rows + n) * static_cast<size_t>(P.V) * ES;
+            lt = static_cast<float>(P.ws.lse2[2 * (b * rows + n)]);
+            ld = static_cast<float>(P.ws.lse2[2 * (b * rows + n) + 1]);
+        }
+    }
+    Best best{neg_inf(), 0x7FFFFFFF}, rbest{neg_inf(), 0x7FFFFFFF};
+    int bad = 0;
+    if (!status) {
+        const long s0 = static_cast<long>(gs) * P.sps;
+        const long s1 = (s0 + P.sps < P.nslots) ? s0 + P.sps : P.nslots;
+        for (long s = s0 + tid; s < s1; s += kWG) {
+            float z[VE], zd[VE];
+            const uint4 raw = load_slot<BF16, ALIGNED>(trow, s, P.V);
+            unpack<BF16>(raw, z);
+            if (residual) {
+                const uint4 rawd = load_slot<BF16, ALIGNED>(drow, s, P.V);
+                unpack<BF16>(rawd, zd);
+            }
+#pragma unroll
+            for (int blk = 0; blk < VE / 4; ++blk) {
+                const long e0 = s * VE + blk * 4;
+                unsigned w4[4] = {0u, 0u, 0u, 0u};
+                if (P.mode == FSD_SAMPLE) {
+                    const U4 r = philox4x32_10(static_cast<unsigned>(e0 >> 2), static_cast<unsigned>(b), P.off_lo,
+                                               P.off_hi, P.seed_lo, P.seed_hi);
+                    w4[0] = r.x; w4[1] = r.y; w4[2] = r.z; w4[3] = r.w;
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float zz = z[blk * 4 + q];
+                    const int idx = static_cast<int>(e0 + q);
+                    bad |= !(zz < __builtin_inff());
+                    const float g = (P.mode == FSD_SAMPLE) ? gumbel(w4[q]) : 0.0f;
+                    const float score = __fadd_rn(zz, g);
+                    if (score > best.score) best = Best{score, idx};
+                    if (residual) {
+                        const float p = hw_exp2(fmaf(zz, kLog2e, -lt));
+                        const float qq = hw_exp2(fmaf(zd[blk * 4 + q], kLog2e, -ld));
+                        const float r = p - qq;
+                        if (r > 0.0f) {
+                            const float rs = fmaf(hw_log2(r), static_cast<float>(kLn2), g);
+                            if (rs > rbest.score) rbest = Best{rs, idx};
+                        }
+                    }
+                }
+            }
+        }
+    }
+    best = wave_best(best);
+    rbest = wave_best(rbest);
+    bad = __any(bad);
+    if (lane == 0) { s_best[wave] = best; s_best[4 + wave] = rbest; s_bad[wave] = bad; }
+    __syncthreads();
+    if (tid == 0) {
+        Best m = s_best[0], r = s_best[4];
+        int bd = s_bad[0];
+        for (int k = 1; k < 4; ++k) { m = better(m, s_best[k]); r = better(r, s_best[4 + k]); bd |= s_bad[k]; }
+        unsigned long long* slot = P.ws.spart + (static_cast<size_t>(b) * P.GS + gs) * 4;
+        __hip_atomic_store(slot + 0, (static_cast<unsigned long long>(__float_as_uint(m.score)) << 32) | static_cast<unsigned>(m.idx), __ATOMIC_RELAXED, AGENT);
+        __hip_atomic_store(slot + 1, (static_cast<unsigned long long>(__float_as_uint(r.score)) << 32) | static_cast<unsigned>(r.idx), __ATOMIC_RELAXED, AGENT);
+        __hip_atomic_store(slot + 2, static_cast<unsigned long long>(bd), __ATOMIC_RELAXED, AGENT);
+        const unsigned prev = __hip_atomic_fetch_add(P.ws.sdone + b, 1u, __ATOMIC_ACQ_REL, AGENT);
+        s_last = (prev == static_cast<unsigned>(P.GS) - 1u) ? 1 : 0;
+    }
+    __syncthreads();
+    if (!s_last) return;
+
+    // ---- the last workgroup of the sequence merges the shares and writes the outputs
+    if (tid == 0) {
+        Best m{neg_inf(), 0x7FFFFFFF}, r{neg_inf(), 0x7FFFFFFF};
+        int bd = 0;
+        for (int k = 0; k < P.GS; ++k) {
+            const unsigned long long* slot = P.ws.spart + (static_cast<size_t>(b) * P.GS + k) * 4;
+            const unsigned long long w0 = __hip_atomic_load(slot + 0, __ATOMIC_RELAXED, AGENT);
+            const unsigned long long w1 = __hip_atomic_load(slot + 1, __ATOMIC_RELAXED, AGENT);
+            bd |= static_cast<int>(__hip_atomic_load(slot + 2, __ATOMIC_RELAXED, AGENT));
+            m = better(m, Best{__uint_as_float(static_cast<unsigned>(w0 >> 32)), static_cast<int>(static_cast<unsigned>(w0))});
+            r = better(r, Best{__uint_as_float(static_cast<unsigned>(w1 >> 32)), static_cast<int>(static_cast<unsigned>(w1))});
+        }
+        int st = status;
+        if (!st && (bd || m.idx == 0x7FFFFFFF)) st |= FSD_ROW_NONFINITE;
+        const int tok = (residual && r.idx != 0x7FFFFFFF) ? r.idx : m.idx;
+        s_st = st;
+        s_key = tok;
+    }
+    __syncthreads();
+    status = s_st;
+    const int token = s_key;
+    if (status) n = 0;
+    const int width = (KIND == KIND_TREE) ? P.max_depth + 1 : rows + 1;
+    int32_t* out = P.out_tokens + static_cast<size_t>(b) * width;
+    if constexpr (KIND == KIND_TREE) {
+        int32_t* pn = P.path_nodes + static_cast<size_t>(b) * P.max_depth;
+        for (int i = tid; i < P.max_depth; i += kWG) pn[i] = -1;
+        for (int i = tid; i < width; i += kWG) out[i] = (i == n && !status) ? token : -1;
+        __syncthreads();
+        if (tid == 0 && !status) {
+            const int* par = s_dyn;
+            int jn = winner;
+            for (int i = n - 1; i >= 0 && jn >= 0; --i) {
+                pn[i] = jn;
+                out[i] = P.tokens[static_cast<size_t>(b) * rows + jn];
+                jn = par[jn];
+            }
+        }
+    } else {
+        for (int i = tid; i < width; i += kWG) {
+            int v = -1;
+            if (!status) {
+                if (i < n) v = P.tokens[static_cast<size_t>(b) * rows + i];
+                else if (i == n) v = token;
+            }
+            out[i] = v;
+        }
+    }
+    if (tid == 0) {
+        P.out_len[b] = n;
+        if (P.row_status) P.row_status[b] = status;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// host side: planning, workspace, launches
+
+struct Plan {
+    int VE, NW, NV, G, spm, GS, sps;
+    long nslots;
+    size_t off_counters, n_counters, off_part1, off_part2, zero_bytes, off_div, off_pst, off_lse2, off_lr, off_spart,
+        bytes;
+};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int g_shape_nw = 0, g_shape_nv = 0;   // 0 = chosen by make_plan (see fsd_debug_set_shape)
+
+// team size for a workgroup of nw wavefronts holding nv slots of each row per thread
+long team_size(long nslots, int nw, int nv) {
+    const long per_wg = static_cast<long>(nw) * 64 * nv;
+    long G = (nslots + per_wg - 1) / per_wg;
+    if (G > 8) G = (G + 7) / 8 * 8;      // whole multiples of the 8 XCDs
+    return G;
+}
+
+bool make_plan(int B, int rows, long V, int dtype, Plan& p) {
+    if (B < 1 || B > 65535 || rows < 1 || rows > kMaxRows || V < 1) return false;
+    if (dtype != FSD_F32 && dtype != FSD_BF16) return false;
+    if (static_cast<long>(B) * rows >= (1L << 24)) return false;
+    if (V > fsd_max_vocab(dtype)) return false;
+    p.VE = (dtype == FSD_BF16) ? 8 : 4;
+    p.nslots = (V + p.VE - 1) / p.VE;
+    static const int shapes[4][2] = {{4, 4}, {4, 8}, {8, 4}, {8, 8}};
+    long G = 0;
+    if (g_shape_nw && g_shape_nv && team_size(p.nslots, g_shape_nw, g_shape_nv) <= kMaxTeam) {
+        p.NW = g_shape_nw; p.NV = g_shape_nv;
+        G = team_size(p.nslots, p.NW, p.NV);
+    } else {
+        for (int i = 0; i < 4; ++i) {
+            p.NW = shapes[i][0]; p.NV = shapes[i][1];
+            G = team_size(p.nslots, p.NW, p.NV);
+            if (G <= kMaxTeam) break;
+        }
+    }
+    if (G > kMaxTeam) return false;
+    p.G = static_cast<int>(G);
+    p.spm = static_cast<int>((p.nslots + G - 1) / G);
+    long GS = (1024 + B - 1) / B;
+    const long maxgs = (p.nslots + kWG - 1) / kWG;
+    if (GS > maxgs) GS = maxgs;
+    if (GS > 64) GS = 64;
+    if (GS < 1) GS = 1;
+    p.GS = static_cast<int>(GS);
+    p.sps = static_cast<int>((p.nslots + GS - 1) / GS);
+    // the workspace is sized for the largest team any shape can ask for, so that the size does
+    // not depend on the shape in use
+    const size_t R = static_cast<size_t>(B) * rows;
+    const size_t Gmax = static_cast<size_t>(team_size(p.nslots, 4, 4) < kMaxTeam ? team_size(p.nslots, 4, 4) : kMaxTeam);
+    size_t o = 0;
+    p.off_counters = o; p.n_counters = 64 + 2 * R + B; o = align_up(o + p.n_counters * 4, 256);
+    p.off_part1 = o; o = align_up(o + R * Gmax * 32, 256);
+    p.off_part2 = o; o = align_up(o + R * Gmax * 32, 256);
+    p.zero_bytes = o;
+    p.off_div = o; o = align_up(o + R * 4, 256);
+    p.off_pst = o; o = align_up(o + R * 4, 256);
+    p.off_lse2 = o; o = align_up(o + R * 16, 256);
+    p.off_lr = o; o = align_up(o + R * 8, 256);
+    p.off_spart = o; o = align_up(o + static_cast<size_t>(B) * p.GS * 32, 256);
+    p.bytes = o;
+    return true;
+}
+
+Ws carve(void* workspace, const Plan& p, int B, int rows) {
+    char* base = static_cast<char*>(workspace);
+    const size_t R = static_cast<size_t>(B) * rows;
+    Ws w;
+    w.counters = reinterpret_cast<unsigned*>(base + p.off_counters);
+    w.arrive = w.counters + 64;
+    w.done = w.arrive + R;
+    w.sdone = w.done + R;
+    w.part1 = reinterpret_cast<unsigned long long*>(base + p.off_part1);
+    w.part2 = reinterpret_cast<double*>(base + p.off_part2);
+    w.div = reinterpret_cast<float*>(base + p.off_div);
+    w.pst = reinterpret_cast<int*>(base + p.off_pst);
+    w.lse2 = reinterpret_cast<double*>(base + p.off_lse2);
+    w.lr = reinterpret_cast<double*>(base + p.off_lr);
+    w.spart = reinterpret_cast<unsigned long long*>(base + p.off_spart);
+    return w;
+}
+
+unsigned g_spin_limit = 1u << 22;
+
+// ---- optional event timing of pair_reduce
+constexpr int kMaxProf = 4096;
+bool g_prof_on = false;
+int g_prof_n = 0;
+hipEvent_t g_prof_ev[2 * kMaxProf];
+bool g_prof_made = false;
+
+// workgroups of one pair_reduce instantiation that are resident at once on the current device
+template <bool BF16, int NV, int MODE, bool ALIGNED, int NW>
+int resident_workgroups() {
+    static int cache[16] = {0};
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    if (dev < 0 || dev >= 16) dev = 0;
+    if (cache[dev] == 0) {
+        int per_cu = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pair_reduce<BF16, NV, MODE, ALIGNED, NW>, NW * 64, 0) !=
+            hipSuccess)
+            per_cu = 1;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 64;
+        if (per_cu < 1) per_cu = 1;
+        if (cus < 1) cus = 1;
+        cache[dev] = per_cu * cus;
+    }
+    return cache[dev];
+}
+
+template <bool BF16, int NV, int MODE, bool ALIGNED, int NW>
+void launch_pair_k(hipStream_t st, const PairParams& P) {
+    // persistent grid: whole teams only, never more than fits on the device at once
+    const long want = static_cast<long>(P.npairs) * P.G;
+    long cap = resident_workgroups<BF16, NV, MODE, ALIGNED, NW>() / P.G * static_cast<long>(P.G);
+    if (cap < P.G) cap = P.G;
+    const long grid = want < cap ? want : cap;
+    hipLaunchKernelGGL((pair_reduce<BF16, NV, MODE, ALIGNED, NW>), dim3(static_cast<unsigned>(grid)), dim3(NW * 64), 0,
+                       st, P);
+}
+template <bool BF16, int NV, int MODE, bool ALIGNED>
+void launch_pair_w(int nw, hipStream_t st, const PairParams& P) {
+    if (nw == 8) launch_pair_k<BF16, NV, MODE, ALIGNED, 8>(st, P);
+    else launch_pair_k<BF16, NV, MODE, ALIGNED, 4>(st, P);
+}
+template <bool BF16, int NV, int MODE>
+void launch_pair_a(bool aligned, int nw, hipStream_t st, const PairParams& P) {
+    if (aligned) launch_pair_w<BF16, NV, MODE, true>(nw, st, P);
+    else launch_pair_w<BF16, NV, MODE, false>(nw, st, P);
+}
+template <bool BF16, int NV>
+void launch_pair_m(int mode, bool aligned, int nw, hipStream_t st, const PairParams& P) {
+    switch (mode) {
+        case MODE_KL: launch_pair_a<BF16, NV, MODE_KL>(aligned, nw, st, P); break;
+        case MODE_JS: launch_pair_a<BF16, NV, MODE_JS>(aligned, nw, st, P); break;
+        case MODE_TV: launch_pair_a<BF16, NV, MODE_TV>(aligned, nw, st, P); break;
+        case MODE_KLP: launch_pair_a<BF16, NV, MODE_KLP>(aligned, nw, st, P); break;
+        default: launch_pair_a<BF16, NV, MODE_LSE>(aligned, nw, st, P); break;
+    }
+}
+void launch_pair(int dtype, int nw, int NV, int mode, bool aligned, hipStream_t st, const PairParams& P) {
+    const bool prof = g_prof_on && g_prof_n < kMaxProf;
+    if (prof) {
+        if (!g_prof_made) {
+            for (int i = 0; i < 2 * kMaxProf; ++i) (void)hipEventCreate(&g_prof_ev[i]);
+            g_prof_made = true;
+        }
+        (void)hipEventRecord(g_prof_ev[2 * g_prof_n], st);
+    }
+    if (dtype == FSD_BF16) {
+        if (NV == 4) launch_pair_m<true, 4>(mode, aligned, nw, st, P);
+        else launch_pair_m<true, 8>(mode, aligned, nw, st, P);
+    } else {
+        if (NV == 4) launch_pair_m<false, 4>(mode, aligned, nw, st, P);
+        else launch_pair_m<false, 8>(mode, aligned, nw, st, P);
+    }
+    if (prof) {
+        (void)hipEventRecord(g_prof_ev[2 * g_prof_n + 1], st);
+        ++g_prof_n;
+    }
+}
+
+template <bool BF16, bool ALIGNED>
+void launch_sample_k(int kind, dim3 grid, size_t lds, hipStream_t st, const SampleParams& P) {
+    switch (kind) {
+        case KIND_CHAIN: hipLaunchKernelGGL((accept_sample<BF16, ALIGNED, KIND_CHAIN>), grid, dim3(kWG), lds, st, P); break;
+        case KIND_TREE: hipLaunchKernelGGL((accept_sample<BF16, ALIGNED, KIND_TREE>), grid, dim3(kWG), lds, st, P); break;
+        default: hipLaunchKernelGGL((accept_sample<BF16, ALIGNED, KIND_SD>), grid, dim3(kWG), lds, st, P); break;
+    }
+}
+void launch_sample(int dtype, bool aligned, int kind, dim3 grid, size_t lds, hipStream_t st, const SampleParams& P) {
+    if (dtype == FSD_BF16) {
+        if (aligned) launch_sample_k<true, true>(kind, grid, lds, st, P);
+        else launch_sample_k<true, false>(kind, grid, lds, st, P);
+    } else {
+        if (aligned) launch_sample_k<false, true>(kind, grid, lds, st, P);
+        else launch_sample_k<false, false>(kind, grid, lds, st, P);
+    }
+}
+
+bool is_aligned(const void* a, const void* b, long V, int VE) {
+    return (V % VE == 0) && (reinterpret_cast<uintptr_t>(a) % 16 == 0) &&
+           (b == nullptr || reinterpret_cast<uintptr_t>(b) % 16 == 0);
+}
+
+// the common body of the three entry points
+int run(int kind, const void* target, const void* draft, const int32_t* tokens, const int32_t* parent, int B,
+        int rows, int max_depth, int V, int dtype, int div, float T, int mode, uint64_t seed, uint64_t offset,
+        int32_t* out_len, int32_t* path_nodes, int32_t* out_tokens, float* user_vals, int32_t* row_status,
+        void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!target || !draft || !tokens || !out_len || !out_tokens) return FSD_ERR_NULL;
+    if (kind == KIND_TREE && (!parent || !path_nodes)) return FSD_ERR_NULL;
+    if (dtype != FSD_F32 && dtype != FSD_BF16) return FSD_ERR_DTYPE;
+    if (kind != KIND_SD && (div < FSD_DIV_KL || div > FSD_DIV_TV)) return FSD_ERR_DIV;
+    if (mode != FSD_SAMPLE && mode != FSD_GREEDY) return FSD_ERR_MODE;
+    if (T != T) return FSD_ERR_SHAPE;
+    if (kind == KIND_TREE && (max_depth < 1 || max_depth > kMaxRows)) return FSD_ERR_SHAPE;
+    Plan p;
+    if (!make_plan(B, rows, V, dtype, p)) return FSD_ERR_SHAPE;
+    if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 != 0 || workspace_bytes < p.bytes)
+        return FSD_ERR_WORKSPACE;
+
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const Ws ws = carve(workspace, p, B, rows);
+    const bool aligned = is_aligned(target, draft, V, p.VE);
+    const int R = B * rows;
+
+    const long n16 = static_cast<long>(p.zero_bytes / 16);
+    hipLaunchKernelGGL(zero_counters, dim3(static_cast<unsigned>((n16 + 255) / 256)), dim3(256), 0, st,
+                       reinterpret_cast<uint4*>(ws.counters), n16);
+
+    PairParams pp;
+    pp.target = static_cast<const char*>(target);
+    pp.draft = static_cast<const char*>(draft);
+    pp.parent = (kind == KIND_TREE) ? parent : nullptr;
+    pp.cand = tokens;
+    pp.rows = rows;
+    pp.npairs = R;
+    pp.V = V;
+    pp.nslots = p.nslots;
+    pp.spm = p.spm;
+    pp.G = p.G;
+    pp.spin_limit = g_spin_limit;
+    pp.user_div = user_vals;
+    pp.ws = ws;
+    int k1mode = (kind == KIND_SD) ? MODE_LSE : div;
+    if (k1mode == MODE_KL && dtype == FSD_F32) k1mode = MODE_KLP;
+    launch_pair(dtype, p.NW, p.NV, k1mode, aligned, st, pp);
+
+    SampleParams sp;
+    sp.target = static_cast<const char*>(target);
+    sp.draft = static_cast<const char*>(draft);
+    sp.tokens = tokens;
+    sp.parent = parent;
+    sp.rows = rows;
+    sp.max_depth = max_depth;
+    sp.V = V;
+    sp.nslots = p.nslots;
+    sp.sps = p.sps;
+    sp.GS = p.GS;
+    sp.T = T;
+    sp.mode = mode;
+    sp.seed_lo = static_cast<unsigned>(seed);
+    sp.seed_hi = static_cast<unsigned>(seed >> 32);
+    sp.off_lo = static_cast<unsigned>(offset);
+    sp.off_hi = static_cast<unsigned>(offset >> 32);
+    sp.out_len = out_len;
+    sp.out_tokens = out_tokens;
+    sp.path_nodes = path_nodes;
+    sp.row_status = row_status;
+    sp.ws = ws;
+    const size_t lds = (kind == KIND_TREE) ? static_cast<size_t>(rows) * 16 : 0;
+    launch_sample(dtype, aligned, kind, dim3(p.GS, B), lds, st, sp);
+
+    return (hipGetLastError() == hipSuccess) ? FSD_OK : FSD_ERR_LAUNCH;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------
+// C ABI
+
+extern "C" {
+
+int64_t fsd_max_vocab(int dtype) {
+    if (dtype == FSD_BF16) return static_cast<int64_t>(kMaxTeam) * 512 * 8 * 8;
+    if (dtype == FSD_F32) return static_cast<int64_t>(kMaxTeam) * 512 * 8 * 4;
+    return 0;
+}
+
+size_t fsd_workspace_bytes(int B, int rows_per_seq, int V, int dtype) {
+    Plan p;
+    if (!make_plan(B, rows_per_seq, V, dtype, p)) return 0;
+    return p.bytes;
+}
+
+const char* fsd_status_string(int status) {
+    switch (status) {
+        case FSD_OK: return "ok";
+        case FSD_ERR_NULL: return "a required pointer is NULL";
+        case FSD_ERR_SHAPE: return "size out of range or T is NaN";
+        case FSD_ERR_DTYPE: return "unknown dtype";
+        case FSD_ERR_DIV: return "unknown divergence";
+        case FSD_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case FSD_ERR_MODE: return "unknown sampling mode";
+        case FSD_ERR_LAUNCH: return "kernel launch failed";
+        default: return "unknown status";
+    }
+}
+
+int fsd_verify_chain(const void* target_logits, const void* draft_logits, const int32_t* cand_tokens, int B, int K,
+                     int V, int dtype, int div, float T, int mode, uint64_t seed, uint64_t offset,
+                     int32_t* accept_len, int32_t* out_tokens, float* divergences, int32_t* row_status,
+                     void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return run(KIND_CHAIN, target_logits, draft_logits, cand_tokens, nullptr, B, K, 0, V, dtype, div, T, mode, seed,
+               offset, accept_len, nullptr, out_tokens, divergences, row_status, workspace, workspace_bytes,
+               hip_stream);
+}
+
+int fsd_verify_tree(const void* target_logits, const void* draft_logits, const int32_t* node_tokens,
+                    const int32_t* parent, int B, int N, int max_depth, int V, int dtype, int div, float T,
+                    int mode, uint64_t seed, uint64_t offset, int32_t* path_len, int32_t* path_nodes,
+                    int32_t* out_tokens, float* divergences, int32_t* row_status, void* workspace,
+                    size_t workspace_bytes, void* hip_stream) {
+    return run(KIND_TREE, target_logits, draft_logits, node_tokens, parent, B, N, max_depth, V, dtype, div, T, mode,
+               seed, offset, path_len, path_nodes, out_tokens, divergences, row_status, workspace,
+               workspace_bytes, hip_stream);
+}
+
+int sd_verify_chain(const void* target_logits, const void* draft_logits, const int32_t* cand_tokens, int B, int K,
+                    int V, int dtype, int mode, uint64_t seed, uint64_t offset, int32_t* accept_len,
+                    int32_t* out_tokens, float* log_ratio, int32_t* row_status, void* workspace,
+                    size_t workspace_bytes, void* hip_stream) {
+    return run(KIND_SD, target_logits, draft_logits, cand_tokens, nullptr, B, K, 0, V, dtype, FSD_DIV_KL, 0.0f, mode,
+               seed, offset, accept_len, nullptr, out_tokens, log_ratio, row_status, workspace, workspace_bytes,
+               hip_stream);
+}
+
+int fsd_profile_enable(int on) {
+    g_prof_on = (on != 0);
+    return FSD_OK;
+}
+
+int fsd_profile_collect(float* mean_ms, float* min_ms) {
+    const int n = g_prof_n;
+    double sum = 0.0;
+    float mn = 0.0f;
+    for (int i = 0; i < n; ++i) {
+        (void)hipEventSynchronize(g_prof_ev[2 * i + 1]);
+        float ms = 0.0f;
+        (void)hipEventElapsedTime(&ms, g_prof_ev[2 * i], g_prof_ev[2 * i + 1]);
+        sum += ms;
+        if (i == 0 || ms < mn) mn = ms;
+    }
+    if (mean_ms) *mean_ms = n ? static_cast<float>(sum / n) : 0.0f;
+    if (min_ms) *min_ms = mn;
+    g_prof_n = 0;
+    return n;
+}
+
+int fsd_debug_set_shape(int wavefronts, int slots_per_thread) {
+    const bool ok = (wavefronts == 0 && slots_per_thread == 0) ||
+                    ((wavefronts == 4 || wavefronts == 8) && (slots_per_thread == 4 || slots_per_thread == 8));
+    if (!ok) return FSD_ERR_SHAPE;
+    g_shape_nw = wavefronts;
+    g_shape_nv = slots_per_thread;
+    return FSD_OK;
+}
+
+unsigned fsd_debug_set_spin_limit(unsigned polls) {
+    const unsigned prev = g_spin_limit;
+    g_spin_limit = polls;
+    return prev;
+}
+
+}  // extern "C"

@@ -1,0 +1,94 @@
+"""Helpers of the GPU parity tests: run the HIP path and the CPU oracle on the same seeded
+inputs and compare element by element.
+
+Bars (from the benchmark spec): accepted lengths, paths and token ids bit-exact, except
+sequences whose decision hinges on a divergence within 1e-5 (relative) of T, which are counted
+and reported; divergences within 1e-5 relative for float32 logits and 2e-3 for bfloat16 logits,
+relative to max(|oracle|, 1e-6).
+"""
+import numpy as np
+
+from paper_2502_20704_amd import synth
+
+DIV_FLOOR = 1e-6
+NEAR_T = 1e-5
+
+
+def rel_tol(dtype_name):
+    return 1e-5 if dtype_name == "f32" else 2e-3
+
+
+def dtype_name(a):
+    return "bf16" if a.dtype == np.uint16 else "f32"
+
+
+def to_dev(inp, keys):
+    return {k: synth.as_torch(inp[k]) for k in keys}
+
+
+def check_divs(gpu, ora, tol, what=""):
+    gpu = np.asarray(gpu, dtype=np.float64)
+    ora = np.asarray(ora, dtype=np.float64)
+    assert gpu.shape == ora.shape
+    nan_o, nan_g = np.isnan(ora), np.isnan(gpu)
+    assert (nan_o == nan_g).all(), f"{what}: NaN pattern differs"
+    inf_o = np.isinf(ora)
+    assert (np.isinf(gpu) == inf_o).all(), f"{what}: inf pattern differs"
+    m = ~(nan_o | inf_o)
+    # a float32 output cannot hold more than its own rounding of the oracle's value
+    err = np.abs(gpu[m] - ora[m]) / np.maximum(np.abs(ora[m]), DIV_FLOOR)
+    worst = float(err.max()) if err.size else 0.0
+    assert worst <= tol, f"{what}: divergence rel err {worst:.3e} > {tol:.1e}"
+    return worst
+
+
+def near_threshold(ora_divs, T):
+    T = float(np.float32(T))
+    return np.abs(ora_divs - T) <= NEAR_T * abs(T)
+
+
+def check_chain(gpu, ora, T, tol, what=""):
+    """gpu: dict of numpy arrays from the HIP path; ora: the oracle's dict."""
+    assert (gpu["row_status"] == ora["row_status"]).all(), f"{what}: row_status differs"
+    worst = check_divs(gpu["divergences"], ora["divs"], tol, what)
+    near = near_threshold(ora["divs"], T)
+    B = ora["accept_len"].shape[0]
+    n_near = 0
+    for b in range(B):
+        ng, no = int(gpu["accept_len"][b]), int(ora["accept_len"][b])
+        if ng != no:
+            first = min(ng, no)
+            assert first < near.shape[1] and near[b, first], \
+                f"{what}: accept_len[{b}] gpu {ng} oracle {no}, div {ora['divs'][b]} T {T}"
+            n_near += 1
+            continue
+        assert (gpu["out_tokens"][b] == ora["out_tokens"][b]).all(), \
+            f"{what}: out_tokens[{b}] gpu {gpu['out_tokens'][b]} oracle {ora['out_tokens'][b]} gap {ora['gap'][b]}"
+    return dict(max_rel_err=worst, near_T_rows=n_near)
+
+
+def check_tree(gpu, ora, T, tol, what=""):
+    assert (gpu["row_status"] == ora["row_status"]).all(), f"{what}: row_status differs"
+    worst = check_divs(gpu["divergences"], ora["divs"], tol, what)
+    near = near_threshold(ora["divs"], T)
+    B = ora["path_len"].shape[0]
+    n_near = 0
+    for b in range(B):
+        same = (int(gpu["path_len"][b]) == int(ora["path_len"][b]) and
+                (gpu["path_nodes"][b] == ora["path_nodes"][b]).all())
+        if not same:
+            assert near[b].any(), f"{what}: tree {b} path differs: gpu {gpu['path_nodes'][b]} oracle {ora['path_nodes'][b]}"
+            n_near += 1
+            continue
+        assert (gpu["out_tokens"][b] == ora["out_tokens"][b]).all(), \
+            f"{what}: tree {b} tokens gpu {gpu['out_tokens'][b]} oracle {ora['out_tokens'][b]}"
+    return dict(max_rel_err=worst, near_T_rows=n_near)
+
+
+def host(out, keys):
+    return {k: out[k].cpu().numpy() for k in keys}
+
+
+CHAIN_KEYS = ("accept_len", "out_tokens", "divergences", "row_status")
+TREE_KEYS = ("path_len", "path_nodes", "out_tokens", "divergences", "row_status")
+SD_KEYS = ("accept_len", "out_tokens", "log_ratio", "row_status")

@@ -1,0 +1,100 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports what the header
+declares, plans workspaces, and turns bad arguments into error codes before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2502_20704_amd as fsd
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "fsd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b((?:fsd|sd)_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared()
+    assert {"fsd_verify_chain", "fsd_verify_tree", "sd_verify_chain", "fsd_workspace_bytes"} <= set(names)
+    L = fsd.library()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_workspace_planning():
+    assert fsd.fsd_workspace_bytes(64, 8, 128256, fsd.BF16) > 0
+    assert fsd.fsd_workspace_bytes(256, 16, 151936, fsd.F32) > 0
+    assert fsd.fsd_workspace_bytes(1, 1, 1, fsd.F32) > 0
+    # monotone in the batch
+    assert fsd.fsd_workspace_bytes(128, 8, 128256, fsd.BF16) > fsd.fsd_workspace_bytes(64, 8, 128256, fsd.BF16)
+    # refused sizes
+    assert fsd.fsd_workspace_bytes(0, 8, 1000, fsd.F32) == 0
+    assert fsd.fsd_workspace_bytes(1, 0, 1000, fsd.F32) == 0
+    assert fsd.fsd_workspace_bytes(1, 8, 0, fsd.F32) == 0
+    assert fsd.fsd_workspace_bytes(1, 8, 1000, 7) == 0
+    assert fsd.fsd_workspace_bytes(1, 8, int(fsd.library().fsd_max_vocab(fsd.F32)) + 1, fsd.F32) == 0
+    assert fsd.fsd_workspace_bytes(1, 4097, 1000, fsd.F32) == 0
+
+
+FAKE = ctypes.c_void_p(0x1000)      # never dereferenced: every case below fails validation first
+
+
+def _chain(**kw):
+    a = dict(target=FAKE, draft=FAKE, cand=FAKE, B=2, K=4, V=1000, dtype=fsd.F32, div=fsd.DIV_JS, T=0.1,
+             mode=fsd.SAMPLE, accept_len=FAKE, out_tokens=FAKE, ws=FAKE, ws_bytes=1 << 30)
+    a.update(kw)
+    return fsd.library().fsd_verify_chain(a["target"], a["draft"], a["cand"], a["B"], a["K"], a["V"], a["dtype"],
+                                          a["div"], a["T"], a["mode"], 0, 0, a["accept_len"], a["out_tokens"],
+                                          None, None, a["ws"], a["ws_bytes"], None)
+
+
+def test_chain_argument_errors():
+    assert _chain(target=None) == -1
+    assert _chain(draft=None) == -1
+    assert _chain(cand=None) == -1
+    assert _chain(accept_len=None) == -1
+    assert _chain(out_tokens=None) == -1
+    assert _chain(B=0) == -2
+    assert _chain(K=0) == -2
+    assert _chain(V=0) == -2
+    assert _chain(T=float("nan")) == -2
+    assert _chain(dtype=5) == -3
+    assert _chain(div=3) == -4
+    assert _chain(div=-1) == -4
+    assert _chain(mode=2) == -6
+    assert _chain(ws=None) == -5
+    assert _chain(ws=ctypes.c_void_p(0x1010)) == -5          # not 256-byte aligned
+    assert _chain(ws_bytes=16) == -5
+
+
+def test_tree_and_sd_argument_errors():
+    L = fsd.library()
+    big = 1 << 30
+    st = L.fsd_verify_tree(FAKE, FAKE, FAKE, None, 1, 4, 4, 100, fsd.F32, fsd.DIV_JS, 0.1, 0, 0, 0,
+                           FAKE, FAKE, FAKE, None, None, FAKE, big, None)
+    assert st == -1                                           # parent missing
+    st = L.fsd_verify_tree(FAKE, FAKE, FAKE, FAKE, 1, 4, 0, 100, fsd.F32, fsd.DIV_JS, 0.1, 0, 0, 0,
+                           FAKE, FAKE, FAKE, None, None, FAKE, big, None)
+    assert st == -2                                           # max_depth < 1
+    st = L.sd_verify_chain(FAKE, FAKE, FAKE, 1, 4, 100, 9, 0, 0, 0, FAKE, FAKE, None, None, FAKE, big, None)
+    assert st == -3
+    st = L.sd_verify_chain(FAKE, FAKE, FAKE, 1, 4, 100, fsd.F32, 0, 0, 0, FAKE, FAKE, None, None, FAKE, 8, None)
+    assert st == -5
+
+
+def test_status_strings():
+    L = fsd.library()
+    seen = {L.fsd_status_string(s) for s in range(-7, 1)}
+    assert len(seen) == 8 and all(x for x in seen)
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+
+    t = torch.zeros(1, 3, 16)
+    with pytest.raises(ValueError):
+        fsd.fsd_verify_chain(t, t[:, :2].contiguous(), torch.zeros(1, 2, dtype=torch.int32), 0.1)

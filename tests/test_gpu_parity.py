@@ -1,0 +1,311 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+
+import paper_2502_20704_amd as fsd
+from paper_2502_20704_amd import synth
+from tests import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    fsd.library()
+    return torch
+
+
+def run_chain(torch, inp, T, div, mode=fsd.SAMPLE, seed=0, offset=0):
+    d = pu.to_dev(inp, ("target", "draft", "cand"))
+    out = fsd.fsd_verify_chain(d["target"], d["draft"], d["cand"], T, div, mode, seed, offset)
+    torch.cuda.synchronize()
+    return pu.host(out, pu.CHAIN_KEYS)
+
+
+def run_tree(torch, inp, T, div, max_depth, mode=fsd.SAMPLE, seed=0, offset=0):
+    d = pu.to_dev(inp, ("target", "draft", "node_tokens", "parent"))
+    out = fsd.fsd_verify_tree(d["target"], d["draft"], d["node_tokens"], d["parent"], max_depth, T, div, mode,
+                              seed, offset)
+    torch.cuda.synchronize()
+    return pu.host(out, pu.TREE_KEYS)
+
+
+# ------------------------------------------------------------------------------ small shapes
+
+SMALL = [  # (B, K, V, dtype, kind, sigma): aligned and ragged V, one slot to several team members
+    (3, 5, 8, "f32", "gauss2", 1.0),
+    (2, 3, 100, "bf16", "gauss2", 0.5),
+    (4, 7, 1000, "f32", "peaked", 1.0),
+    (2, 4, 4097, "bf16", "peaked", 2.0),
+    (3, 2, 4099, "f32", "zipf", 1.0),
+    (5, 9, 32000, "bf16", "zipf", (0.25, 4.0)),
+    (2, 6, 40004, "f32", "gauss2", 0.25),
+    (1, 1, 1, "f32", "gauss2", 1.0),
+    (1, 64, 2048, "bf16", "peaked", 1.0),
+]
+
+
+@pytest.mark.parametrize("B,K,V,dtype,kind,sigma", SMALL)
+@pytest.mark.parametrize("div", [fsd.DIV_KL, fsd.DIV_JS, fsd.DIV_TV])
+def test_chain_small(torch_cuda, oracle, B, K, V, dtype, kind, sigma, div):
+    inp = synth.chain_inputs(B, K, V, dtype, kind, sigma, seed=17)
+    for T in (0.0, 0.03, 0.2, 1e9, -1.0):
+        print(f"chain B={B} K={K} V={V} {dtype} div={div} T={T}", flush=True)
+        g = run_chain(torch_cuda, inp, T, div, seed=5, offset=2)
+        o = oracle.verify_chain(inp["target"], inp["draft"], inp["cand"], T, div, seed=5, offset=2)
+        pu.check_chain(g, o, T, pu.rel_tol(dtype), f"B={B} K={K} V={V} {dtype} div={div} T={T}")
+
+
+def test_chain_greedy_and_determinism(torch_cuda, oracle):
+    inp = synth.chain_inputs(6, 5, 12345, "bf16", "peaked", 1.0, seed=3)
+    g = run_chain(torch_cuda, inp, 0.05, fsd.DIV_JS, mode=fsd.GREEDY)
+    o = oracle.verify_chain(inp["target"], inp["draft"], inp["cand"], 0.05, fsd.DIV_JS, mode=oracle.GREEDY)
+    pu.check_chain(g, o, 0.05, 2e-3, "greedy")
+    a = run_chain(torch_cuda, inp, 0.05, fsd.DIV_JS, seed=9)
+    for _ in range(3):
+        b = run_chain(torch_cuda, inp, 0.05, fsd.DIV_JS, seed=9)
+        for k in pu.CHAIN_KEYS:
+            assert np.array_equal(a[k].view(np.uint32) if a[k].dtype == np.float32 else a[k],
+                                  b[k].view(np.uint32) if b[k].dtype == np.float32 else b[k]), k
+
+
+def test_identical_rows_threshold_zero(torch_cuda, oracle):
+    """identical logits and T = 0 accept every candidate, for all three divergences."""
+    for dtype, V in (("f32", 32000), ("bf16", 128256), ("bf16", 999)):
+        inp = synth.chain_inputs(2, 4, V, dtype, "peaked", 1.0, seed=1)
+        inp["draft"] = inp["target"][:, :4].copy()
+        for div in (fsd.DIV_KL, fsd.DIV_JS, fsd.DIV_TV):
+            g = run_chain(torch_cuda, inp, 0.0, div)
+            assert (g["divergences"] == 0).all(), (dtype, V, div, g["divergences"])
+            assert (g["accept_len"] == 4).all()
+            o = oracle.verify_chain(inp["target"], inp["draft"], inp["cand"], 0.0, div)
+            pu.check_chain(g, o, 0.0, pu.rel_tol(dtype), "identical")
+
+
+def test_masked_entries_and_closed_form(torch_cuda, oracle):
+    """-inf logits are legal; uniform vs half-uniform has JS = 3/4 ln(4/3), TV = 1/2, KL = +inf."""
+    V = 128256
+    t = np.zeros((1, 2, V), dtype=np.float32)
+    d = np.zeros((1, 1, V), dtype=np.float32)
+    d[0, 0, V // 2:] = -np.inf
+    inp = dict(target=t, draft=d, cand=np.zeros((1, 1), dtype=np.int32))
+    g = run_chain(torch_cuda, inp, 0.3, fsd.DIV_JS)
+    assert g["divergences"][0, 0] == pytest.approx(0.75 * np.log(4 / 3), rel=1e-5)
+    assert g["accept_len"][0] == 1
+    g = run_chain(torch_cuda, inp, 0.3, fsd.DIV_TV)
+    assert g["divergences"][0, 0] == pytest.approx(0.5, rel=1e-5) and g["accept_len"][0] == 0
+    g = run_chain(torch_cuda, inp, 1e30, fsd.DIV_KL)
+    assert np.isinf(g["divergences"][0, 0]) and g["accept_len"][0] == 0
+    g = run_chain(torch_cuda, inp, float("inf"), fsd.DIV_KL)
+    assert g["accept_len"][0] == 1
+    # random masks on both sides, all divergences, both dtypes
+    for dtype in ("f32", "bf16"):
+        inp = synth.chain_inputs(3, 4, 5000, "f32", "gauss2", 1.0, seed=8)
+        rng = np.random.default_rng(0)
+        inp["target"][rng.random(inp["target"].shape) < 0.3] = -np.inf
+        inp["draft"][rng.random(inp["draft"].shape) < 0.3] = -np.inf
+        if dtype == "bf16":
+            inp["target"], inp["draft"] = synth.to_bf16_bits(inp["target"]), synth.to_bf16_bits(inp["draft"])
+        for div in (fsd.DIV_KL, fsd.DIV_JS, fsd.DIV_TV):
+            g = run_chain(torch_cuda, inp, 0.5, div)
+            o = oracle.verify_chain(inp["target"], inp["draft"], inp["cand"], 0.5, div)
+            pu.check_chain(g, o, 0.5, pu.rel_tol(dtype), f"masked {dtype} div={div}")
+
+
+def test_nonfinite_rows_are_flagged(torch_cuda, oracle):
+    inp = synth.chain_inputs(4, 3, 3000, "f32", "gauss2", 1.0, seed=2)
+    inp["target"][0, 1, 77] = np.nan
+    inp["draft"][1, 0, 5] = np.inf
+    inp["target"][2, 3, :] = -np.inf          # the bonus row of a sequence that accepts everything
+    for div in (fsd.DIV_KL, fsd.DIV_JS, fsd.DIV_TV):
+        g = run_chain(torch_cuda, inp, 1e9, div)
+        o = oracle.verify_chain(inp["target"], inp["draft"], inp["cand"], 1e9, div)
+        assert list(o["row_status"]) == [1, 1, 1, 0]
+        pu.check_chain(g, o, 1e9, 1e-5, f"nonfinite div={div}")
+        assert (g["out_tokens"][:3] == -1).all() and (g["accept_len"][:3] == 0).all()
+
+
+# ------------------------------------------------------------------- benchmark configurations
+
+def test_config_c0(torch_cuda, oracle):
+    inp = synth.config_inputs("C0", seed=0)
+    for div in (fsd.DIV_KL, fsd.DIV_JS, fsd.DIV_TV):
+        for T in synth.CONFIGS["C0"]["T"]:
+            g = run_chain(torch_cuda, inp, T, div, seed=1)
+            o = oracle.verify_chain(inp["target"], inp["draft"], inp["cand"], T, div, seed=1)
+            r = pu.check_chain(g, o, T, 1e-5, f"C0 div={div} T={T}")
+            print("C0", div, T, r, flush=True)
+
+
+def test_config_c1_sweep(torch_cuda, oracle):
+    for sigma in synth.CONFIGS["C1"]["sigma"]:
+        inp = synth.config_inputs("C1", seed=0, sigma=sigma)
+        for T in synth.CONFIGS["C1"]["T"]:
+            g = run_chain(torch_cuda, inp, T, fsd.DIV_JS, seed=2)
+            o = oracle.verify_chain(inp["target"], inp["draft"], inp["cand"], T, fsd.DIV_JS, seed=2)
+            r = pu.check_chain(g, o, T, 2e-3, f"C1 sigma={sigma} T={T}")
+            print("C1", sigma, T, r, o["divs"][0, :3], flush=True)
+
+
+def test_config_c2_full(torch_cuda, oracle):
+    inp = synth.config_inputs("C2", seed=0)
+    for div in (fsd.DIV_JS, fsd.DIV_KL, fsd.DIV_TV):
+        g = run_chain(torch_cuda, inp, 0.1, div, seed=3, offset=11)
+        o = oracle.verify_chain(inp["target"], inp["draft"], inp["cand"], 0.1, div, seed=3, offset=11)
+        r = pu.check_chain(g, o, 0.1, 2e-3, f"C2 div={div}")
+        print("C2", div, r, "accept_len histogram", np.bincount(o["accept_len"], minlength=9), flush=True)
+
+
+def test_config_c2_strict_sd(torch_cuda, oracle):
+    inp = synth.config_inputs("C2", seed=0)
+    d = pu.to_dev(inp, ("target", "draft", "cand"))
+    out = fsd.sd_verify_chain(d["target"], d["draft"], d["cand"], seed=4, offset=1)
+    torch_cuda.cuda.synchronize()
+    g = pu.host(out, pu.SD_KEYS)
+    o = oracle.sd_verify_chain(inp["target"], inp["draft"], inp["cand"], seed=4, offset=1)
+    check_sd(g, o, "C2 SD")
+
+
+def check_sd(g, o, what):
+    assert (g["row_status"] == o["row_status"]).all()
+    fin = np.isfinite(o["log_ratio"])
+    assert (np.isfinite(g["log_ratio"]) == fin).all()
+    assert np.allclose(g["log_ratio"][fin], o["log_ratio"][fin], rtol=2e-5, atol=2e-5), what
+    near = np.abs(o["margin"]) <= 1e-5
+    n_near = n_tie = 0
+    for b in range(o["accept_len"].shape[0]):
+        ng, no = int(g["accept_len"][b]), int(o["accept_len"][b])
+        if ng != no:
+            assert near[b, min(ng, no)], f"{what}: accept_len[{b}] gpu {ng} oracle {no} margin {o['margin'][b]}"
+            n_near += 1
+            continue
+        if not (g["out_tokens"][b] == o["out_tokens"][b]).all():
+            # the residual score ln(p - q) is float32 on the GPU, float64 in the oracle: a
+            # runner-up within 1e-4 of the winner may overtake it
+            assert o["gap"][b] < 1e-4, f"{what}: tokens[{b}] gpu {g['out_tokens'][b]} oracle {o['out_tokens'][b]} gap {o['gap'][b]}"
+            n_tie += 1
+    print(what, "near-threshold rows", n_near, "near-tie rows", n_tie,
+          "accept_len histogram", np.bincount(o["accept_len"]), flush=True)
+    assert n_near + n_tie <= max(2, o["accept_len"].shape[0] // 20)
+
+
+def test_strict_sd_small(torch_cuda, oracle):
+    for (B, K, V, dtype, kind, sigma) in SMALL[:7]:
+        inp = synth.chain_inputs(B, K, V, dtype, kind, sigma, seed=23)
+        d = pu.to_dev(inp, ("target", "draft", "cand"))
+        for mode in (fsd.SAMPLE, fsd.GREEDY):
+            out = fsd.sd_verify_chain(d["target"], d["draft"], d["cand"], mode, seed=6, offset=3)
+            torch_cuda.cuda.synchronize()
+            g = pu.host(out, pu.SD_KEYS)
+            o = oracle.sd_verify_chain(inp["target"], inp["draft"], inp["cand"], mode, seed=6, offset=3)
+            check_sd(g, o, f"SD B={B} K={K} V={V} {dtype} mode={mode}")
+
+
+def test_config_c3_sampled(torch_cuda, oracle):
+    """full-size C3 on the GPU; the oracle checks a sample of its sequences one by one."""
+    c = synth.CONFIGS["C3"]
+    inp = synth.config_inputs("C3", seed=0)
+    print("C3 inputs ready", flush=True)
+    for div in (fsd.DIV_JS, fsd.DIV_KL):
+        g = run_chain(torch_cuda, inp, 0.3, div, seed=5)
+        assert (g["row_status"] == 0).all()
+        for b in (0, 1, 97, 255):
+            o = oracle.verify_chain(inp["target"][b:b + 1], inp["draft"][b:b + 1], inp["cand"][b:b + 1], 0.3, div,
+                                    seed=5, seq_offset=b)
+            gb = {k: v[b:b + 1] for k, v in g.items()}
+            r = pu.check_chain(gb, o, 0.3, 1e-5, f"C3 div={div} b={b}")
+            print("C3", div, b, r, o["accept_len"], flush=True)
+        # properties that hold for every sequence
+        d = g["divergences"]
+        assert (d >= 0).all() and np.isfinite(d).all()
+        ok = d <= np.float32(0.3)
+        first_rej = np.where(ok.all(axis=1), c["K"], np.argmin(ok, axis=1))
+        assert (g["accept_len"] == first_rej).all()
+        for b in range(c["B"]):
+            n = g["accept_len"][b]
+            assert (g["out_tokens"][b, :n] == inp["cand"][b, :n]).all()
+            assert 0 <= g["out_tokens"][b, n] < c["V"] and (g["out_tokens"][b, n + 1:] == -1).all()
+
+
+def test_config_c4_tree_full(torch_cuda, oracle):
+    inp = synth.config_inputs("C4", seed=0)
+    md = int(inp["max_depth"])
+    print("C4 inputs ready, max depth", md, flush=True)
+    g = run_tree(torch_cuda, inp, 0.15, fsd.DIV_JS, md, seed=6)
+    o = oracle.verify_tree(inp["target"], inp["draft"], inp["node_tokens"], inp["parent"], md, 0.15, fsd.DIV_JS,
+                           seed=6)
+    r = pu.check_tree(g, o, 0.15, 2e-3, "C4")
+    print("C4", r, "path_len histogram", np.bincount(o["path_len"]), flush=True)
+
+
+# ----------------------------------------------------------------------------------- trees
+
+def test_tree_small_random(torch_cuda, oracle):
+    rng = np.random.default_rng(5)
+    for trial, (N, V, dtype) in enumerate([(10, 8, "f32"), (33, 1000, "bf16"), (60, 4097, "f32"), (200, 512, "bf16"),
+                                           (1, 64, "f32")]):
+        B = 3
+        parent = np.stack([np.array([-1] + [int(rng.integers(-1, j)) for j in range(1, N)], dtype=np.int32)
+                           for _ in range(B)])
+        t = (rng.standard_normal((B, N + 1, V)) * 2).astype(np.float32)
+        d = np.empty((B, N, V), dtype=np.float32)
+        for b in range(B):
+            for j in range(N):
+                d[b, j] = t[b, parent[b, j] + 1] + rng.standard_normal(V) * rng.uniform(0.2, 1.2)
+        toks = rng.integers(0, V, (B, N)).astype(np.int32)
+        if dtype == "bf16":
+            t, d = synth.to_bf16_bits(t), synth.to_bf16_bits(d)
+        inp = dict(target=t, draft=d, node_tokens=toks, parent=parent)
+        for T in (0.0, 0.05, 0.12, 1e9):
+            for div in (fsd.DIV_JS, fsd.DIV_TV):
+                print(f"tree N={N} V={V} {dtype} T={T} div={div}", flush=True)
+                g = run_tree(torch_cuda, inp, T, div, N, seed=trial)
+                o = oracle.verify_tree(t, d, toks, parent, N, T, div, seed=trial)
+                pu.check_tree(g, o, T, pu.rel_tol(dtype), f"tree N={N} V={V} T={T} div={div}")
+
+
+def test_chain_shaped_tree_equals_chain(torch_cuda):
+    inp = synth.chain_inputs(4, 6, 9000, "bf16", "peaked", 1.0, seed=4)
+    parent = np.broadcast_to(np.arange(-1, 5, dtype=np.int32), (4, 6)).copy()
+    tinp = dict(target=inp["target"], draft=inp["draft"], node_tokens=inp["cand"], parent=parent)
+    for T in (0.0, 0.1, 1e9):
+        c = run_chain(torch_cuda, inp, T, fsd.DIV_JS, seed=8)
+        t = run_tree(torch_cuda, tinp, T, fsd.DIV_JS, 6, seed=8)
+        assert (c["accept_len"] == t["path_len"]).all()
+        assert (c["out_tokens"] == t["out_tokens"]).all()
+        assert np.array_equal(c["divergences"], t["divergences"])
+
+
+def test_tree_bad_parent_and_depth(torch_cuda, oracle):
+    inp = synth.chain_inputs(2, 4, 500, "f32", "gauss2", 1.0, seed=4)
+    parent = np.array([[-1, 0, 2, 1], [-1, 0, 1, 2]], dtype=np.int32)
+    tinp = dict(target=inp["target"], draft=inp["draft"], node_tokens=inp["cand"], parent=parent)
+    g = run_tree(torch_cuda, tinp, 1e9, fsd.DIV_JS, 2)
+    o = oracle.verify_tree(inp["target"], inp["draft"], inp["cand"], parent, 2, 1e9, fsd.DIV_JS)
+    assert list(o["row_status"]) == [fsd.ROW_BAD_PARENT, fsd.ROW_TOO_DEEP]
+    assert list(g["row_status"]) == list(o["row_status"])
+    assert (g["path_len"] == 0).all() and (g["out_tokens"] == -1).all() and (g["path_nodes"] == -1).all()
+
+
+# ------------------------------------------------------------------------------- robustness
+
+def test_bounded_wait_expires_cleanly(torch_cuda, oracle):
+    """with a zero poll budget a workgroup may give up waiting for its team: the kernel still ends,
+    and the call either is correct throughout or flags FSD_ROW_INTERNAL on every sequence."""
+    inp = synth.chain_inputs(4, 4, 128256, "bf16", "peaked", 1.0, seed=6)
+    o = oracle.verify_chain(inp["target"], inp["draft"], inp["cand"], 0.1, fsd.DIV_JS)
+    prev = fsd.debug_set_spin_limit(0)
+    try:
+        g = run_chain(torch_cuda, inp, 0.1, fsd.DIV_JS)
+    finally:
+        fsd.debug_set_spin_limit(prev)
+    if (g["row_status"] == 0).all():
+        pu.check_chain(g, o, 0.1, 2e-3, "zero poll budget, nothing expired")
+    else:
+        assert ((g["row_status"] & fsd.ROW_INTERNAL) != 0).all()
+        assert (g["accept_len"] == 0).all() and (g["out_tokens"] == -1).all()
+    g = run_chain(torch_cuda, inp, 0.1, fsd.DIV_JS)
+    pu.check_chain(g, o, 0.1, 2e-3, "after restoring the poll budget")
