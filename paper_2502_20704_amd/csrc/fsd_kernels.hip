@@ -820,6 +820,7 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
         sample_row = winner + 1;
     }
     int status = s_st;
+    if (status & FSD_ROW_BAD_PARENT) status &= ~FSD_ROW_TOO_DEEP;   // depths mean nothing in a malformed tree
     if (P.ws.counters[1]) status |= FSD_ROW_INTERNAL;   // a bounded wait of the reduction kernel expired
 
     // ---- Gumbel-max over this workgroup's share of the sampled target row
