@@ -171,6 +171,10 @@ unsigned fsd_debug_set_spin_limit(unsigned polls);
  * the rounding order of the partial sums. */
 int fsd_debug_set_shape(int wavefronts, int slots_per_thread);
 
+/* Test hook: grid size of the last vocabulary-reduction launch and the resident
+ * workgroups per CU it was derived from. */
+void fsd_debug_last_launch(int* grid, int* per_cu);
+
 #ifdef __cplusplus
 }
 #endif

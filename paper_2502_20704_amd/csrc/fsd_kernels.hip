@@ -37,6 +37,13 @@ enum { KIND_CHAIN = 0, KIND_TREE = 1, KIND_SD = 2 };
 
 #define AGENT __HIP_MEMORY_SCOPE_AGENT
 
+// Optional phase timing of pair_reduce (development builds only: -DFSD_PHASE_TIMING).
+#ifdef FSD_PHASE_TIMING
+#define PT(i) do { const unsigned long long pt_now = __builtin_readcyclecounter(); pt_acc[i] += pt_now - pt_last; pt_last = pt_now; } while (0)
+#else
+#define PT(i) do { } while (0)
+#endif
+
 // ------------------------------------------------------------------------------------------
 // small device helpers
 
@@ -204,9 +211,7 @@ __device__ __forceinline__ float gumbel(unsigned w) {
 // workspace view
 
 struct Ws {
-    unsigned* counters;  // 64 spare words, then arrive[R], done[R], sdone[B]
-    unsigned* arrive;    // [R] team members that posted their normaliser partials
-    unsigned* done;      // [R] team members that posted their divergence partial
+    unsigned* counters;  // 64 words ([1]: a bounded wait expired), then sdone[B]
     unsigned* sdone;     // [B] sampler workgroups that posted
     unsigned long long* part1;  // [R][G][4]: (kt,kd) | St | Sd | W
     double* part2;       // [R][G][4] divergence words (one used, four for TV)
@@ -229,6 +234,9 @@ struct PairParams {
     int spm;                // slots per team member
     int G;
     unsigned spin_limit;
+#ifdef FSD_PHASE_TIMING
+    unsigned long long* dbg;   // [grid][2 wavefronts][10]
+#endif
     float* user_div;        // optional [R]
     Ws ws;
 };
@@ -474,11 +482,19 @@ __global__ __launch_bounds__(NW * 64) void pair_reduce(PairParams P) {
         }
     };
 
-    // bookkeeping carried from one pair to the next (first wavefront only)
+    // Bookkeeping carried from one pair to the next (first wavefront only).  Each pair has a
+    // designated finisher among the team (the members take turns); it adds up what the others
+    // posted one step later, when the words have normally long arrived.
     int pend_post = -1;          // pair whose phase-2 partial sits in s_p, not yet posted
-    int pend_fin = -1;           // pair whose done-counter this workgroup has bumped ...
-    unsigned pend_prev = 0;      // ... and what the counter read before (lane 0)
+    int pend_fin = -1;           // pair this workgroup has to finish
+    int pend_fin_next = -1;      // (waiting modes) the pair to finish one step after that
+    int iter = 0;
 
+#ifdef FSD_PHASE_TIMING
+    unsigned long long pt_acc[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+    const unsigned long long pt_start = __builtin_readcyclecounter();
+    unsigned long long pt_last = pt_start;
+#endif
     int pair = team;
     int buf = 0;
     if (pair < P.npairs) load_item(pair);
@@ -520,13 +536,24 @@ __global__ __launch_bounds__(NW * 64) void pair_reduce(PairParams P) {
                 }
             }
         }
-        // ---- the registers that held the logits are free: fetch the next pair behind the exchange
-        if (pair + nteams < P.npairs) load_item(pair + nteams);
+        PT(0);
+        // ---- the registers that held the logits are free: fetch the next pair behind the exchange.
+        // Loads return in issue order, so the wavefront that is about to poll the team's words
+        // issues its share only after the poll: otherwise every poll would wait for these loads.
+        const bool more = pair + nteams < P.npairs;
+        if (more && !(WAITS && wave == 0)) load_item(pair + nteams);
 
         {
-            const double wst = wave_sum(static_cast<double>(st));
-            const double wsd = wave_sum(static_cast<double>(sd));
-            double ww = 0.0;
+            // the waiting modes only need the normalisers to a relative 1e-7 (they enter p and q
+            // as common factors); the single-pass modes take them through a logarithm
+            double wst, wsd, ww = 0.0;
+            if constexpr (WAITS) {
+                wst = static_cast<double>(wave_sumf(st));
+                wsd = static_cast<double>(wave_sumf(sd));
+            } else {
+                wst = wave_sum(static_cast<double>(st));
+                wsd = wave_sum(static_cast<double>(sd));
+            }
             if constexpr (MODE == MODE_KL) {
                 ww = wave_sum(static_cast<double>(w));
                 if (wave_max(dmax) == __builtin_inff()) ww = __builtin_inf();
@@ -536,11 +563,13 @@ __global__ __launch_bounds__(NW * 64) void pair_reduce(PairParams P) {
                 s_k[buf][wave][0] = kt; s_k[buf][wave][1] = kd;
             }
         }
+        PT(1);
         __syncthreads();   // barrier 1: wavefront partials of this pair (and s_p of the previous one) are in LDS
+        PT(2);
 
         unsigned long long* p1 = P.ws.part1 + static_cast<size_t>(pair) * G * 4;
         if (wave == 0) {
-            // the previous pair: post its divergence partial and bump its done-counter
+            // the previous pair: post its divergence partial
             if constexpr (WAITS) {
                 if (pend_post >= 0 && lane < PW) {
                     double part = s_p[0][lane];
@@ -549,27 +578,35 @@ __global__ __launch_bounds__(NW * 64) void pair_reduce(PairParams P) {
                     unsigned long long* q2 = reinterpret_cast<unsigned long long*>(P.ws.part2) + static_cast<size_t>(pend_post) * G * 4;
                     post64(q2 + member * 4 + lane, dbits(part));
                 }
+                pend_post = -1;
             }
-            // ... and finish the one before if this workgroup was the last to bump its counter
-            if (pend_fin >= 0) {
-                const unsigned prev = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(pend_prev)));
-                if (prev == static_cast<unsigned>(G) - 1u) finish_pair(pend_fin);
-                pend_fin = -1;
+            // finish the pair this workgroup is the finisher of, once everybody has posted for it
+            if (pend_fin >= 0) finish_pair(pend_fin);
+            pend_fin = pend_fin_next;
+            pend_fin_next = -1;
+            PT(3);
+            // this pair: merge the wavefronts (a handful of values, done by every lane alike) and
+            // post the workgroup's normaliser partial
+            Part1 m{neg_inf(), neg_inf(), 0.0, 0.0, 0.0};
+#pragma unroll
+            for (int k = 0; k < NW; ++k) {
+                if (s_w[buf][k][0] > 0.0) m.kt = fmaxf(m.kt, s_k[buf][k][0]);
+                if (s_w[buf][k][1] > 0.0) m.kd = fmaxf(m.kd, s_k[buf][k][1]);
             }
-            if constexpr (WAITS) {
-                if (pend_post >= 0) {
-                    if (lane == 0) pend_prev = __hip_atomic_fetch_add(P.ws.done + pend_post, 1u, __ATOMIC_RELAXED, AGENT);
-                    pend_fin = pend_post;
-                    pend_post = -1;
+            bool winf = false;
+#pragma unroll
+            for (int k = 0; k < NW; ++k) {
+                const double a0 = s_w[buf][k][0], a1 = s_w[buf][k][1], a2 = s_w[buf][k][2];
+                m.St += (a0 > 0.0) ? ldexp(a0, kdiff(s_k[buf][k][0], m.kt)) : (a0 != a0 ? a0 : 0.0);
+                m.Sd += (a1 > 0.0) ? ldexp(a1, kdiff(s_k[buf][k][1], m.kd)) : (a1 != a1 ? a1 : 0.0);
+                if constexpr (MODE == MODE_KL) {
+                    winf |= (a2 == __builtin_inf());
+                    m.W += (a0 > 0.0 && a2 == a2 && a2 != __builtin_inf()) ? ldexp(a2, kdiff(s_k[buf][k][0], m.kt)) : 0.0;
                 }
             }
-            // this pair: merge the wavefronts and post the workgroup's normaliser partial
-            Part1 r{0.0f, 0.0f, 0.0, 0.0, 0.0};
-            if (lane < NW) {
-                r.kt = s_k[buf][lane][0]; r.kd = s_k[buf][lane][1];
-                r.St = s_w[buf][lane][0]; r.Sd = s_w[buf][lane][1]; r.W = s_w[buf][lane][2];
-            }
-            const Part1 m = merge_part1(r, MODE == MODE_KL);
+            if (winf) m.W = __builtin_inf();
+            if (m.kt == neg_inf()) m.kt = 0.0f;
+            if (m.kd == neg_inf()) m.kd = 0.0f;
             if (lane == 0) {
                 unsigned long long* slot = p1 + member * 4;
                 post64(slot + 0, static_cast<unsigned long long>(fbits(m.kt)) | (static_cast<unsigned long long>(fbits(m.kd)) << 32));
@@ -577,26 +614,37 @@ __global__ __launch_bounds__(NW * 64) void pair_reduce(PairParams P) {
                 post64(slot + 2, dbits(m.Sd));
                 post64(slot + 3, dbits(m.W));
             }
+            // whose turn is it to finish this pair?
+            if (iter % G == member) {
+                if constexpr (WAITS) pend_fin_next = pair;   // its divergence words are posted one step from now
+                else pend_fin = pair;
+            }
+            PT(4);
             if constexpr (WAITS) {
-                // ---- exchange: wait for the whole team's partials (bounded), merge them
+                // ---- exchange: wait for the whole team's partials (bounded), merge them in binary32
                 Part1 t;
                 const bool ok = poll_part1(p1, G, P.spin_limit, t);
-                const Part1 all = merge_part1(t, false);
+                if (more) load_item(pair + nteams);
+                const float tSt = static_cast<float>(t.St), tSd = static_cast<float>(t.Sd);
+                float Kt = wave_max((tSt > 0.0f) ? t.kt : neg_inf());
+                float Kd = wave_max((tSd > 0.0f) ? t.kd : neg_inf());
+                const float zt = wave_sumf((tSt > 0.0f) ? ldexpf(tSt, kdiff(t.kt, Kt)) : (tSt != tSt ? tSt : 0.0f));
+                const float zd = wave_sumf((tSd > 0.0f) ? ldexpf(tSd, kdiff(t.kd, Kd)) : (tSd != tSd ? tSd : 0.0f));
                 if (lane == 0) {
-                    s_x[0] = all.kt; s_x[1] = all.kd;
-                    s_x[2] = 1.0f / static_cast<float>(all.St);   // inf for a row without mass, NaN for a bad one
-                    s_x[3] = 1.0f / static_cast<float>(all.Sd);
+                    s_x[0] = (Kt == neg_inf()) ? 0.0f : Kt;
+                    s_x[1] = (Kd == neg_inf()) ? 0.0f : Kd;
+                    s_x[2] = 1.0f / zt;   // inf for a row without mass, NaN for a bad one
+                    s_x[3] = 1.0f / zd;
                     s_x[4] = ok ? 1.0f : 0.0f;
                     if (!ok) atomicOr(P.ws.counters + 1, 1u);
                 }
-            } else {
-                if (lane == 0) pend_prev = __hip_atomic_fetch_add(P.ws.done + pair, 1u, __ATOMIC_RELAXED, AGENT);
-                pend_fin = pair;
             }
+            PT(5);
         }
 
         if constexpr (WAITS) {
             __syncthreads();   // barrier 2: the team's normalisers are in s_x
+            PT(6);
             // p = ea * ft with ft = 2^(kt - Kt) / St: exact power of two times one rounded reciprocal.
             // A wavefront without mass has only zeros in ea; its factor is 0 (NaN if the row is unusable).
             const bool mass_t = st > 0.0f || st != st, mass_d = sd > 0.0f || sd != sd;
@@ -651,12 +699,12 @@ __global__ __launch_bounds__(NW * 64) void pair_reduce(PairParams P) {
                 }
                 // max() drops NaN: an unusable row (NaN factor) is made to reach the side selection
                 if (ft != ft || fd != fd) { A = ft + fd; Bn = A; MA = A; MB = A; }
-                part[0] = wave_sum(static_cast<double>(A));
-                part[1] = wave_sum(static_cast<double>(Bn));
-                part[2] = wave_sum(static_cast<double>(MA));
-                part[3] = wave_sum(static_cast<double>(MB));
+                part[0] = static_cast<double>(wave_sumf(A));
+                part[1] = static_cast<double>(wave_sumf(Bn));
+                part[2] = static_cast<double>(wave_sumf(MA));
+                part[3] = static_cast<double>(wave_sumf(MB));
             } else {
-                part[0] = wave_sum(static_cast<double>(acc));
+                part[0] = static_cast<double>(wave_sumf(acc));
                 if constexpr (MODE == MODE_KLP) {
                     if (wave_max(dmax) == __builtin_inff()) part[0] += __builtin_inf();   // stays NaN for a bad row
                 }
@@ -666,31 +714,346 @@ __global__ __launch_bounds__(NW * 64) void pair_reduce(PairParams P) {
                 for (int k = 0; k < PW; ++k) s_p[wave][k] = timed_out ? __builtin_nan("") : part[k];
             }
             pend_post = pair;
+            PT(7);
         }
+#ifdef FSD_PHASE_TIMING
+        pt_acc[8] += 1;
+#endif
+        ++iter;
     }
 
     // ---- drain the bookkeeping of the last pairs
     if constexpr (WAITS) {
         __syncthreads();
-        if (wave == 0 && pend_post >= 0) {
-            if (lane < PW) {
-                double part = s_p[0][lane];
+        if (wave == 0 && pend_post >= 0 && lane < PW) {
+            double part = s_p[0][lane];
 #pragma unroll
-                for (int k = 1; k < NW; ++k) part += s_p[k][lane];
-                unsigned long long* q2 = reinterpret_cast<unsigned long long*>(P.ws.part2) + static_cast<size_t>(pend_post) * G * 4;
-                post64(q2 + member * 4 + lane, dbits(part));
-            }
-            if (pend_fin >= 0) {
-                const unsigned prev = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(pend_prev)));
-                if (prev == static_cast<unsigned>(G) - 1u) finish_pair(pend_fin);
-            }
-            if (lane == 0) pend_prev = __hip_atomic_fetch_add(P.ws.done + pend_post, 1u, __ATOMIC_RELAXED, AGENT);
-            pend_fin = pend_post;
+            for (int k = 1; k < NW; ++k) part += s_p[k][lane];
+            unsigned long long* q2 = reinterpret_cast<unsigned long long*>(P.ws.part2) + static_cast<size_t>(pend_post) * G * 4;
+            post64(q2 + member * 4 + lane, dbits(part));
         }
     }
-    if (wave == 0 && pend_fin >= 0) {
-        const unsigned prev = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(pend_prev)));
-        if (prev == static_cast<unsigned>(G) - 1u) finish_pair(pend_fin);
+    if (wave == 0) {
+        if (pend_fin >= 0) finish_pair(pend_fin);
+        if (pend_fin_next >= 0) finish_pair(pend_fin_next);
+    }
+#ifdef FSD_PHASE_TIMING
+    if (P.dbg && lane == 0 && wave < 2) {
+        unsigned long long* d = P.dbg + (static_cast<size_t>(blockIdx.x) * 2 + wave) * 10;
+        for (int i = 0; i < 8; ++i) d[i] = pt_acc[i];
+        d[8] = pt_start;
+        d[9] = __builtin_readcyclecounter() - pt_start;
+    }
+#endif
+}
+
+// ------------------------------------------------------------------------------------------
+// kernel 1b: two-phase divergences (JS, TV, pointwise KL) with the exchange off the critical path.
+//
+// Same persistent team layout as pair_reduce, but software-pipelined by one pair: in step j a
+// workgroup runs phase 1 of pair j (its exponentials stay in registers) and then phase 2 of pair
+// j-1, whose team-wide normalisers were posted a whole step earlier.  The polling loads for pair
+// j-1 are issued at the top of the step and consumed after phase 1, so in the normal case nobody
+// waits: one barrier per pair, and every wavefront polls and merges the team's words by itself.
+template <bool BF16, int NV, int MODE, bool ALIGNED, int NW>
+__global__ __launch_bounds__(NW * 64) void pair_divergence(PairParams P) {
+    constexpr int VE = Slot<BF16>::VE;
+    constexpr int ES = BF16 ? 2 : 4;
+    constexpr int WGS = NW * 64;
+    constexpr int NE = NV * VE;
+    constexpr int PW = (MODE == MODE_TV) ? 4 : 1;   // divergence words a member posts
+    constexpr float kTiny = 2e-38f;   // smallest normal scale: keeps p + q > 0 without changing any result
+    __shared__ float s_w[2][NW][2];    // per wavefront: St, Sd          (double-buffered by step parity)
+    __shared__ float s_k[2][NW][2];    // per wavefront: kt, kd
+    __shared__ double s_p[2][NW][4];   // per wavefront: phase-2 partials
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int G = P.G;
+    const int member = static_cast<int>(blockIdx.x) % G;
+    const int team = static_cast<int>(blockIdx.x) / G;
+    const int nteams = static_cast<int>(gridDim.x) / G;
+    const long s0 = static_cast<long>(member) * P.spm;
+    const long s1 = (s0 + P.spm < P.nslots) ? s0 + P.spm : P.nslots;
+    unsigned long long* const part2 = reinterpret_cast<unsigned long long*>(P.ws.part2);
+
+    uint4 ra[NV], rb[NV];
+    auto load_item = [&](int pair) __attribute__((always_inline)) {
+        const int b = pair / P.rows;
+        const int j = pair - b * P.rows;
+        int trow = j;
+        if (P.parent) {
+            const int par = P.parent[pair];
+            trow = (par >= -1 && par < j) ? par + 1 : 0;   // invalid parents are reported by the next kernel
+        }
+        const char* tptr = P.target + (static_cast<size_t>(b) * (P.rows + 1) + trow) * static_cast<size_t>(P.V) * ES;
+        const char* dptr = P.draft + static_cast<size_t>(pair) * static_cast<size_t>(P.V) * ES;
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            const long s = s0 + k * WGS + tid;
+            if (s < s1) {
+                ra[k] = load_slot<BF16, ALIGNED>(tptr, s, P.V);
+                rb[k] = load_slot<BF16, ALIGNED>(dptr, s, P.V);
+            } else {
+                ra[k] = slot_neg_inf<BF16>();
+                rb[k] = slot_neg_inf<BF16>();
+            }
+        }
+    };
+
+    // first wavefront: add up a finished pair's divergence words (fixed member order) and write it out
+    auto finish_pair = [&](int pair) __attribute__((always_inline)) {
+        double pv[PW];
+        const bool ok = poll_part2<PW>(part2 + static_cast<size_t>(pair) * G * 4, G, P.spin_limit, pv);
+        double value;
+        if constexpr (MODE == MODE_TV) {
+            // sum of (p - q)+ and of (q - p)+ are the same number; the side that avoids the heavy
+            // entries (smaller sum of p + q over its entries) carries the smaller rounding error,
+            // which matters for nearly one-hot rows
+            const double A = wave_sum(pv[0]), Bn = wave_sum(pv[1]), MA = wave_sum(pv[2]), MB = wave_sum(pv[3]);
+            value = (MA != MA || MB != MB) ? __builtin_nan("") : (MA <= MB ? A : Bn);
+        } else {
+            value = 0.5 * kLn2 * wave_sum(pv[0]);
+        }
+        int status = 0;
+        if (value != value) status |= FSD_ROW_NONFINITE;   // NaN / +inf logits, or a row without mass
+        if (!ok) status |= FSD_ROW_INTERNAL;
+        if (value < 0.0) value = 0.0;
+        if (status) value = __builtin_nan("");
+        if (lane == 0) {
+            P.ws.div[pair] = static_cast<float>(value);
+            P.ws.lse2[2 * pair] = 0.0;
+            P.ws.lse2[2 * pair + 1] = 0.0;
+            if (P.user_div) P.user_div[pair] = static_cast<float>(value);
+            P.ws.pst[pair] = status;
+        }
+    };
+    auto post_part2 = [&](int pair, int b) __attribute__((always_inline)) {   // first wavefront, from s_p[b]
+        if (lane < PW) {
+            double part = s_p[b][0][lane];
+#pragma unroll
+            for (int k = 1; k < NW; ++k) part += s_p[b][k][lane];
+            post64(part2 + (static_cast<size_t>(pair) * G + member) * 4 + lane, dbits(part));
+        }
+    };
+
+    // ---- per-wavefront state of the previous pair, whose phase 2 is still to come
+    float pkt = 0.0f, pkd = 0.0f;
+    bool pmass_t = false, pmass_d = false, pmask = false;
+    int prev_pair = -1;
+    int p2_pair = -1;                      // pair whose phase-2 partials sit in s_p[buf ^ 1]
+    int fin0 = -1, fin1 = -1, fin2 = -1;   // first wavefront: pairs to finish now / in one / in two steps
+    int iter = 0, buf = 0;
+
+    // phase 2 of the previous pair from its kept exponentials; lane i < G holds member i's words in w[]
+    auto phase2 = [&](const float (&et)[NE], const float (&ed)[NE], unsigned long long (&w)[4], int b)
+                      __attribute__((always_inline)) {
+        const unsigned long long* p1 = P.ws.part1 + static_cast<size_t>(prev_pair) * G * 4;
+        // the words were requested at the top of the step; ask again only if some had not arrived
+        bool ok = true;
+        unsigned polls = 0;
+        for (;;) {
+            const bool missing = (w[0] == 0) | (w[1] == 0) | (w[2] == 0) | (w[3] == 0);
+            if (!__any(missing)) break;
+            if (polls++ >= P.spin_limit) { ok = false; break; }
+            __builtin_amdgcn_s_sleep(1);
+            if (lane < G) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) w[k] = read64(p1 + lane * 4 + k);
+            }
+        }
+        // merge the team's normalisers in binary32 (they enter p and q as common factors)
+        float tk_t = neg_inf(), tk_d = neg_inf(), tSt = 0.0f, tSd = 0.0f;
+        if (lane < G) {
+            tk_t = __uint_as_float(static_cast<unsigned>(w[0]));
+            tk_d = __uint_as_float(static_cast<unsigned>(w[0] >> 32));
+            tSt = static_cast<float>(bitsd(w[1]));
+            tSd = static_cast<float>(bitsd(w[2]));
+        }
+        const float Kt = wave_max((tSt > 0.0f) ? tk_t : neg_inf());
+        const float Kd = wave_max((tSd > 0.0f) ? tk_d : neg_inf());
+        const float zt = wave_sumf((tSt > 0.0f) ? ldexpf(tSt, kdiff(tk_t, Kt)) : (tSt != tSt ? tSt : 0.0f));
+        const float zd = wave_sumf((tSd > 0.0f) ? ldexpf(tSd, kdiff(tk_d, Kd)) : (tSd != tSd ? tSd : 0.0f));
+        const float rzt = 1.0f / zt, rzd = 1.0f / zd;   // inf for a row without mass, NaN for a bad one
+        // p = e * ft with ft = 2^(k_wave - K) / S: an exact power of two times one rounded reciprocal.
+        // A wavefront without mass has only zeros in e; its factor is 0 (NaN if the row is unusable).
+        const float ft = pmass_t ? ldexpf(rzt, kdiff(pkt, Kt)) : rzt * 0.0f;
+        const float fd = pmass_d ? ldexpf(rzd, kdiff(pkd, Kd)) : rzd * 0.0f;
+
+        // Only relative errors enter p and q, and the divergences below are functions of (p, q)
+        // alone, second order in r = (p - q)/(p + q): the result is the divergence of a slightly
+        // perturbed input.  u = 1 + r = 2p/s and v = 2 - u = 2q/s (exact subtraction).
+        double part[PW];
+        if constexpr (MODE == MODE_TV) {
+            float A = 0.0f, Bn = 0.0f, MA = 0.0f, MB = 0.0f;
+#pragma unroll
+            for (int i = 0; i < NE; ++i) {
+                const float p = et[i] * ft, q = ed[i] * fd;   // separately rounded: p == q for equal rows
+                const float d = p - q, sum = p + q;
+                A += fmaxf(d, 0.0f);
+                Bn += fmaxf(-d, 0.0f);
+                MA += (d > 0.0f) ? sum : 0.0f;
+                MB += (d < 0.0f) ? sum : 0.0f;
+            }
+            // max() drops NaN: an unusable row (NaN factor) is made to reach the side selection
+            if (ft != ft || fd != fd) { A = ft + fd; Bn = A; MA = A; MB = A; }
+            part[0] = static_cast<double>(wave_sumf(A));
+            part[1] = static_cast<double>(wave_sumf(Bn));
+            part[2] = static_cast<double>(wave_sumf(MA));
+            part[3] = static_cast<double>(wave_sumf(MB));
+        } else {
+            float acc = 0.0f;
+#pragma unroll
+            for (int i = 0; i < NE; ++i) {
+                const float p = fmaf(et[i], ft, kTiny), q = fmaf(ed[i], fd, kTiny);
+                const float d = p - q, sum = p + q;
+                const float inv = __builtin_amdgcn_rcpf(sum);
+                const float u = fmaxf(fmaf(d, inv, 1.0f), kTiny), v = fmaxf(2.0f - u, kTiny);
+                if constexpr (MODE == MODE_JS) {
+                    // p ln(2p/s) + q ln(2q/s) = ln2 (p log2 u + q log2 v)
+                    acc = fmaf(p, hw_log2(u), acc);
+                    acc = fmaf(q, hw_log2(v), acc);
+                } else {
+                    // p ln(p/q) + q - p = (s/2) [u ln(u/v) + v - u] >= 0 entry by entry (the added q - p
+                    // sums to zero).  Written in (u, v) only, the rounding of u = 1 + r cancels between
+                    // the two parts; p ln(u/v) - (p - q) would keep it to first order.
+                    acc = fmaf(sum, fmaf(u, hw_log2(u) - hw_log2(v), (v - u) * kLog2e), acc);
+                }
+            }
+            part[0] = static_cast<double>(wave_sumf(acc));
+            if constexpr (MODE == MODE_KLP) {
+                if (__any(pmask)) part[0] += __builtin_inf();   // draft masks an entry the target keeps; NaN stays NaN
+            }
+        }
+        if (!ok) {
+            if (lane == 0) atomicOr(P.ws.counters + 1, 1u);
+#pragma unroll
+            for (int k = 0; k < PW; ++k) part[k] = __builtin_nan("");
+        }
+        if (lane == 0) {
+#pragma unroll
+            for (int k = 0; k < PW; ++k) s_p[b][wave][k] = part[k];
+        }
+    };
+
+    // one step: phase 1 of `pair` into (ect, ecd), then phase 2 of the previous pair from (ept, epd)
+    auto step = [&](float (&ect)[NE], float (&ecd)[NE], const float (&ept)[NE], const float (&epd)[NE], int pair)
+                    __attribute__((always_inline)) {
+        // request the previous pair's team words now; they are consumed after phase 1
+        unsigned long long w[4] = {1, 1, 1, 1};
+        if (prev_pair >= 0 && lane < G) {
+            const unsigned long long* p1 = P.ws.part1 + static_cast<size_t>(prev_pair) * G * 4;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) w[k] = read64(p1 + lane * 4 + k);
+        }
+        // ---- phase 1, per wavefront: maximum, then sums of 2^(z log2e - k) with k = ceil(max log2e)
+        float mt = neg_inf(), md = neg_inf();
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            float a[VE], c[VE];
+            unpack<BF16>(ra[k], a);
+            unpack<BF16>(rb[k], c);
+#pragma unroll
+            for (int e = 0; e < VE; e += 2) { mt = fmaxf(fmaxf(mt, a[e]), a[e + 1]); md = fmaxf(fmaxf(md, c[e]), c[e + 1]); }
+        }
+        mt = wave_max(mt);
+        md = wave_max(md);
+        const float kt = (mt == neg_inf()) ? 0.0f : ceilf(mt * kLog2e);
+        const float kd = (md == neg_inf()) ? 0.0f : ceilf(md * kLog2e);
+        float st = 0.0f, sd = 0.0f, dmax = neg_inf();
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            float a[VE], c[VE];
+            unpack<BF16>(ra[k], a);
+            unpack<BF16>(rb[k], c);
+#pragma unroll
+            for (int e = 0; e < VE; ++e) {
+                const float xa = hw_exp2(fmaf(a[e], kLog2e, -kt));
+                const float xb = hw_exp2(fmaf(c[e], kLog2e, -kd));
+                ect[k * VE + e] = xa;
+                ecd[k * VE + e] = xb;
+                st += xa;
+                sd += xb;
+                if constexpr (MODE == MODE_KLP) dmax = fmaxf(dmax, a[e] - c[e]);   // +inf iff only the draft masks the entry
+            }
+        }
+        // ---- the registers that held the logits are free: fetch the next pair
+        if (pair + nteams < P.npairs) load_item(pair + nteams);
+        st = wave_sumf(st);
+        sd = wave_sumf(sd);
+        if (lane == 0) { s_w[buf][wave][0] = st; s_w[buf][wave][1] = sd; s_k[buf][wave][0] = kt; s_k[buf][wave][1] = kd; }
+        __syncthreads();   // the only barrier of the step
+
+        if (wave == 0) {
+            // bookkeeping of older pairs: post the partials of the pair whose phase 2 ran last step,
+            // finish the pair whose turn has come
+            if (p2_pair >= 0) post_part2(p2_pair, buf ^ 1);
+            if (fin0 >= 0) finish_pair(fin0);
+            fin0 = fin1; fin1 = fin2; fin2 = (iter % G == member) ? pair : -1;
+            // this pair: merge the wavefronts (a handful of values) and post the workgroup's partial
+            float mkt = neg_inf(), mkd = neg_inf();
+#pragma unroll
+            for (int k = 0; k < NW; ++k) {
+                if (s_w[buf][k][0] > 0.0f) mkt = fmaxf(mkt, s_k[buf][k][0]);
+                if (s_w[buf][k][1] > 0.0f) mkd = fmaxf(mkd, s_k[buf][k][1]);
+            }
+            float mSt = 0.0f, mSd = 0.0f;
+#pragma unroll
+            for (int k = 0; k < NW; ++k) {
+                const float a0 = s_w[buf][k][0], a1 = s_w[buf][k][1];
+                mSt += (a0 > 0.0f) ? ldexpf(a0, kdiff(s_k[buf][k][0], mkt)) : (a0 != a0 ? a0 : 0.0f);
+                mSd += (a1 > 0.0f) ? ldexpf(a1, kdiff(s_k[buf][k][1], mkd)) : (a1 != a1 ? a1 : 0.0f);
+            }
+            if (mkt == neg_inf()) mkt = 0.0f;
+            if (mkd == neg_inf()) mkd = 0.0f;
+            if (lane == 0) {
+                unsigned long long* slot = P.ws.part1 + (static_cast<size_t>(pair) * G + member) * 4;
+                post64(slot + 0, static_cast<unsigned long long>(fbits(mkt)) | (static_cast<unsigned long long>(fbits(mkd)) << 32));
+                post64(slot + 1, dbits(static_cast<double>(mSt)));
+                post64(slot + 2, dbits(static_cast<double>(mSd)));
+                post64(slot + 3, dbits(0.0));
+            }
+        }
+        p2_pair = -1;
+        if (prev_pair >= 0) {
+            phase2(ept, epd, w, buf);
+            p2_pair = prev_pair;
+        }
+        // this pair becomes the previous one
+        pkt = kt; pkd = kd;
+        pmass_t = (st > 0.0f) || (st != st);
+        pmass_d = (sd > 0.0f) || (sd != sd);
+        pmask = (dmax == __builtin_inff());
+        prev_pair = pair;
+        buf ^= 1;
+        ++iter;
+    };
+
+    float e0t[NE], e0d[NE], e1t[NE], e1d[NE];
+#pragma unroll
+    for (int i = 0; i < NE; ++i) { e0t[i] = 0.0f; e0d[i] = 0.0f; e1t[i] = 0.0f; e1d[i] = 0.0f; }
+    int pair = team;
+    if (pair < P.npairs) load_item(pair);
+    for (;;) {
+        if (pair >= P.npairs) break;
+        step(e0t, e0d, e1t, e1d, pair);
+        pair += nteams;
+        if (pair >= P.npairs) break;
+        step(e1t, e1d, e0t, e0d, pair);
+        pair += nteams;
+    }
+    // ---- drain: phase 2 of the last pair, then the postings and finishes still owed
+    if (prev_pair >= 0) {
+        unsigned long long w[4] = {0, 0, 0, 0};
+        if (lane >= G) { w[0] = w[1] = w[2] = w[3] = 1; }
+        if (iter & 1) phase2(e0t, e0d, w, buf); else phase2(e1t, e1d, w, buf);
+    }
+    __syncthreads();
+    if (wave == 0) {
+        if (p2_pair >= 0) post_part2(p2_pair, buf ^ 1);
+        if (prev_pair >= 0) post_part2(prev_pair, buf);
+        if (fin0 >= 0) finish_pair(fin0);
+        if (fin1 >= 0) finish_pair(fin1);
+        if (fin2 >= 0) finish_pair(fin2);
     }
 }
 
@@ -981,13 +1344,20 @@ bool make_plan(int B, int rows, long V, int dtype, Plan& p) {
     if (V > fsd_max_vocab(dtype)) return false;
     p.VE = (dtype == FSD_BF16) ? 8 : 4;
     p.nslots = (V + p.VE - 1) / p.VE;
-    static const int shapes[4][2] = {{4, 4}, {4, 8}, {8, 4}, {8, 8}};
+    // (wavefronts per workgroup, slots of each row per thread); bfloat16 holds 8 entries per slot and
+    // the two-phase kernel keeps two sets of exponentials, so it stops at 4 slots
+    static const int shapes_f32[4][2] = {{4, 4}, {4, 8}, {8, 4}, {8, 8}};
+    static const int shapes_bf16[2][2] = {{4, 4}, {8, 4}};
+    const int (*shapes)[2] = (dtype == FSD_BF16) ? shapes_bf16 : shapes_f32;
+    const int nshapes = (dtype == FSD_BF16) ? 2 : 4;
     long G = 0;
-    if (g_shape_nw && g_shape_nv && team_size(p.nslots, g_shape_nw, g_shape_nv) <= kMaxTeam) {
+    const bool override_ok = g_shape_nw && g_shape_nv && !(dtype == FSD_BF16 && g_shape_nv > 4) &&
+                             team_size(p.nslots, g_shape_nw, g_shape_nv) <= kMaxTeam;
+    if (override_ok) {
         p.NW = g_shape_nw; p.NV = g_shape_nv;
         G = team_size(p.nslots, p.NW, p.NV);
     } else {
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < nshapes; ++i) {
             p.NW = shapes[i][0]; p.NV = shapes[i][1];
             G = team_size(p.nslots, p.NW, p.NV);
             if (G <= kMaxTeam) break;
@@ -1006,9 +1376,9 @@ bool make_plan(int B, int rows, long V, int dtype, Plan& p) {
     // the workspace is sized for the largest team any shape can ask for, so that the size does
     // not depend on the shape in use
     const size_t R = static_cast<size_t>(B) * rows;
-    const size_t Gmax = static_cast<size_t>(team_size(p.nslots, 4, 4) < kMaxTeam ? team_size(p.nslots, 4, 4) : kMaxTeam);
+    const size_t Gmax = kMaxTeam;
     size_t o = 0;
-    p.off_counters = o; p.n_counters = 64 + 2 * R + B; o = align_up(o + p.n_counters * 4, 256);
+    p.off_counters = o; p.n_counters = 64 + B; o = align_up(o + p.n_counters * 4, 256);
     p.off_part1 = o; o = align_up(o + R * Gmax * 32, 256);
     p.off_part2 = o; o = align_up(o + R * Gmax * 32, 256);
     p.zero_bytes = o;
@@ -1026,9 +1396,7 @@ Ws carve(void* workspace, const Plan& p, int B, int rows) {
     const size_t R = static_cast<size_t>(B) * rows;
     Ws w;
     w.counters = reinterpret_cast<unsigned*>(base + p.off_counters);
-    w.arrive = w.counters + 64;
-    w.done = w.arrive + R;
-    w.sdone = w.done + R;
+    w.sdone = w.counters + 64;
     w.part1 = reinterpret_cast<unsigned long long*>(base + p.off_part1);
     w.part2 = reinterpret_cast<double*>(base + p.off_part2);
     w.div = reinterpret_cast<float*>(base + p.off_div);
@@ -1040,6 +1408,9 @@ Ws carve(void* workspace, const Plan& p, int B, int rows) {
 }
 
 unsigned g_spin_limit = 1u << 22;
+#ifdef FSD_PHASE_TIMING
+unsigned long long* g_dbg = nullptr;
+#endif
 
 // ---- optional event timing of pair_reduce
 constexpr int kMaxProf = 4096;
@@ -1048,35 +1419,71 @@ int g_prof_n = 0;
 hipEvent_t g_prof_ev[2 * kMaxProf];
 bool g_prof_made = false;
 
-// workgroups of one pair_reduce instantiation that are resident at once on the current device
-template <bool BF16, int NV, int MODE, bool ALIGNED, int NW>
-int resident_workgroups() {
-    static int cache[16] = {0};
+// How many workgroups of one pair_reduce instantiation are resident at once on the current
+// device, and how much unused dynamic LDS to ask for so that the hardware cannot place more than
+// that number on any one CU.  Without the padding a grid that does not fill every slot may be
+// spread unevenly (some CUs full, others half empty), and the team members that share a pair then
+// all run at the pace of the most crowded CU.
+struct Residency { int total; unsigned pad_lds; };
+
+int g_last_grid = 0, g_last_per_cu = 0;
+
+template <typename Kernel>
+Residency residency_of(Kernel kernel, int threads, Residency (&cache)[16]) {
     int dev = 0;
     (void)hipGetDevice(&dev);
     if (dev < 0 || dev >= 16) dev = 0;
-    if (cache[dev] == 0) {
-        int per_cu = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pair_reduce<BF16, NV, MODE, ALIGNED, NW>, NW * 64, 0) !=
-            hipSuccess)
-            per_cu = 1;
+    if (cache[dev].total == 0) {
+        int per_cu = 0, cus = 0, lds_cu = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess) per_cu = 1;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 64;
+        if (hipDeviceGetAttribute(&lds_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev) != hipSuccess) lds_cu = 0;
         if (per_cu < 1) per_cu = 1;
         if (cus < 1) cus = 1;
-        cache[dev] = per_cu * cus;
+        unsigned pad = 0;
+        hipFuncAttributes attr;
+        if (lds_cu > 16384 && hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(kernel)) == hipSuccess) {
+            // leave 8 KB of slack: per_cu workgroups must still fit, one more must not
+            const long stat = static_cast<long>(attr.sharedSizeBytes);
+            const long want = ((static_cast<long>(lds_cu) - 8192) / per_cu - stat) / 1024 * 1024;
+            if (want > 0 && (stat + want) * (per_cu + 1) > lds_cu) {
+                bool ok = true;
+                if (stat + want > 65536)
+                    ok = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             static_cast<int>(want)) == hipSuccess;
+                int check = 0;
+                if (ok && hipOccupancyMaxActiveBlocksPerMultiprocessor(&check, kernel, threads, static_cast<size_t>(want)) == hipSuccess &&
+                    check == per_cu)
+                    pad = static_cast<unsigned>(want);
+            }
+        }
+        (void)hipGetLastError();
+        g_last_per_cu = per_cu;
+        cache[dev] = Residency{per_cu * cus, pad};
     }
+    g_last_per_cu = cache[dev].total;
     return cache[dev];
 }
 
 template <bool BF16, int NV, int MODE, bool ALIGNED, int NW>
 void launch_pair_k(hipStream_t st, const PairParams& P) {
     // persistent grid: whole teams only, never more than fits on the device at once
+    constexpr bool TWO_PHASE = (MODE == MODE_JS || MODE == MODE_TV || MODE == MODE_KLP);
+    static Residency cache[16] = {};
+    Residency res;
+    if constexpr (TWO_PHASE) res = residency_of(pair_divergence<BF16, NV, MODE, ALIGNED, NW>, NW * 64, cache);
+    else res = residency_of(pair_reduce<BF16, NV, MODE, ALIGNED, NW>, NW * 64, cache);
     const long want = static_cast<long>(P.npairs) * P.G;
-    long cap = resident_workgroups<BF16, NV, MODE, ALIGNED, NW>() / P.G * static_cast<long>(P.G);
+    long cap = res.total / P.G * static_cast<long>(P.G);
     if (cap < P.G) cap = P.G;
     const long grid = want < cap ? want : cap;
-    hipLaunchKernelGGL((pair_reduce<BF16, NV, MODE, ALIGNED, NW>), dim3(static_cast<unsigned>(grid)), dim3(NW * 64), 0,
-                       st, P);
+    g_last_grid = static_cast<int>(grid);
+    if constexpr (TWO_PHASE)
+        hipLaunchKernelGGL((pair_divergence<BF16, NV, MODE, ALIGNED, NW>), dim3(static_cast<unsigned>(grid)), dim3(NW * 64),
+                           res.pad_lds, st, P);
+    else
+        hipLaunchKernelGGL((pair_reduce<BF16, NV, MODE, ALIGNED, NW>), dim3(static_cast<unsigned>(grid)), dim3(NW * 64),
+                           res.pad_lds, st, P);
 }
 template <bool BF16, int NV, int MODE, bool ALIGNED>
 void launch_pair_w(int nw, hipStream_t st, const PairParams& P) {
@@ -1108,10 +1515,11 @@ void launch_pair(int dtype, int nw, int NV, int mode, bool aligned, hipStream_t 
         (void)hipEventRecord(g_prof_ev[2 * g_prof_n], st);
     }
     if (dtype == FSD_BF16) {
-        if (NV == 4) launch_pair_m<true, 4>(mode, aligned, nw, st, P);
-        else launch_pair_m<true, 8>(mode, aligned, nw, st, P);
+        if (NV == 2) launch_pair_m<true, 2>(mode, aligned, nw, st, P);
+        else launch_pair_m<true, 4>(mode, aligned, nw, st, P);
     } else {
-        if (NV == 4) launch_pair_m<false, 4>(mode, aligned, nw, st, P);
+        if (NV == 2) launch_pair_m<false, 2>(mode, aligned, nw, st, P);
+        else if (NV == 4) launch_pair_m<false, 4>(mode, aligned, nw, st, P);
         else launch_pair_m<false, 8>(mode, aligned, nw, st, P);
     }
     if (prof) {
@@ -1181,6 +1589,9 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
     pp.spm = p.spm;
     pp.G = p.G;
     pp.spin_limit = g_spin_limit;
+#ifdef FSD_PHASE_TIMING
+    pp.dbg = g_dbg;
+#endif
     pp.user_div = user_vals;
     pp.ws = ws;
     int k1mode = (kind == KIND_SD) ? MODE_LSE : div;
@@ -1223,7 +1634,7 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
 extern "C" {
 
 int64_t fsd_max_vocab(int dtype) {
-    if (dtype == FSD_BF16) return static_cast<int64_t>(kMaxTeam) * 512 * 8 * 8;
+    if (dtype == FSD_BF16) return static_cast<int64_t>(kMaxTeam) * 512 * 4 * 8;
     if (dtype == FSD_F32) return static_cast<int64_t>(kMaxTeam) * 512 * 8 * 4;
     return 0;
 }
@@ -1300,11 +1711,20 @@ int fsd_profile_collect(float* mean_ms, float* min_ms) {
 
 int fsd_debug_set_shape(int wavefronts, int slots_per_thread) {
     const bool ok = (wavefronts == 0 && slots_per_thread == 0) ||
-                    ((wavefronts == 4 || wavefronts == 8) && (slots_per_thread == 4 || slots_per_thread == 8));
+                    ((wavefronts == 4 || wavefronts == 8) && (slots_per_thread == 2 || slots_per_thread == 4 || slots_per_thread == 8));
     if (!ok) return FSD_ERR_SHAPE;
     g_shape_nw = wavefronts;
     g_shape_nv = slots_per_thread;
     return FSD_OK;
+}
+
+#ifdef FSD_PHASE_TIMING
+void fsd_debug_set_dbg(void* p) { g_dbg = static_cast<unsigned long long*>(p); }
+#endif
+
+void fsd_debug_last_launch(int* grid, int* per_cu) {
+    if (grid) *grid = g_last_grid;
+    if (per_cu) *per_cu = g_last_per_cu;
 }
 
 unsigned fsd_debug_set_spin_limit(unsigned polls) {
