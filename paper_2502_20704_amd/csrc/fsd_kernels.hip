@@ -25,7 +25,6 @@
 namespace {
 
 constexpr int kWG = 256;          // threads per workgroup (4 wavefronts of 64)
-constexpr int kMaxTeam = 64;      // team members are reduced by one wavefront
 constexpr int kMaxRows = 2048;    // K or N
 constexpr float kLog2e = 1.44269504088896340736f;
 constexpr double kLn2 = 0.69314718055994530942;
@@ -251,12 +250,34 @@ __global__ void zero_counters(uint4* p, long n16) {
 
 // ------------------------------------------------------------------------------------------
 // kernel 1: vocabulary reduction over row pairs
+//
+// One (target row, draft row) pair is split over a team of GW wavefronts.  Every wavefront loads
+// its slice of both rows ONCE into registers (NV 16-byte slots of each row per lane) and works on
+// its own: there is no barrier and no shared memory, the wavefronts of a team only meet through
+// 64-bit words in the workspace.
+//
+//   phase 1   maximum of the slice (DPP reduction), integer reference exponent k = ceil(max log2e),
+//             e = 2^(z log2e - k) for every entry, their sums; posted as four words.
+//   exchange  (two-phase divergences) every wavefront reads the whole team's words and merges them
+//             into row-wide normalisers.
+//   phase 2   from the kept exponentials: p = e_t f_t, q = e_d f_d, the divergence's terms, one
+//             (TV: four) partial sum(s) posted.
+//   finish    the team's wavefronts take turns as finisher of a pair: it adds the posted partial
+//             sums in member order (fixed order: results are bit-identical run to run) and writes
+//             divergence and status.
+//
+// The kernel is persistent and software-pipelined by one pair: in a step a wavefront runs phase 1
+// of pair j and then phase 2 of pair j-1, whose team words were posted a whole step earlier and
+// requested at the top of the step, so in the normal case nothing waits; the loads of pair j+1 are
+// issued as soon as phase 1 has consumed the registers.  The single-pass modes (bfloat16 KL, the
+// normalisers of strict SD) have no phase 2.  Waiting is bounded (spin_limit polls, then
+// FSD_ROW_INTERNAL), so every wavefront reaches the end of the kernel whatever happens; all team
+// members are resident by construction (the grid never exceeds what fits on the device at once).
 
-// The team's exchange goes through 64-bit words that are only ever touched with device-scope
-// atomic loads and stores, which are performed at the memory side: no cache write-back or
-// invalidate is needed to see them.  The words are cleared before the kernel starts and a posted
-// word is never zero (+0.0 is posted as -0.0), so each word says by itself whether it has
-// arrived: a reader polls the words it needs, and no counter or fence sits between a post and
+// The exchange words are only ever touched with device-scope atomic loads and stores, which are
+// performed at the memory side: no cache write-back or invalidate is needed to see them.  They are
+// cleared before the kernel starts and a posted word is never zero (+0.0 is posted as -0.0), so
+// each word says by itself whether it has arrived: no counter or fence sits between a post and
 // its use.
 __device__ __forceinline__ void post64(unsigned long long* p, unsigned long long v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, AGENT);
@@ -280,118 +301,92 @@ __device__ __forceinline__ unsigned fbits(float x) {              // never 0
 // to another is an exact scaling by a power of two.
 __device__ __forceinline__ int kdiff(float k, float M) { return static_cast<int>(k - M); }
 
-// One posted phase-1 partial (of a wavefront, a workgroup or a team member): reference exponents
-// kt, kd; St = sum 2^(a log2e - kt) over the target slice, Sd likewise for the draft;
-// W = sum 2^(a log2e - kt) (a - b), +inf when the draft masks an entry the target does not.
-struct Part1 { float kt, kd; double St, Sd, W; };
-
-// Merge the partials held by lanes 0..n-1 of the calling wavefront; every lane gets the result.
-__device__ __forceinline__ Part1 merge_part1(const Part1& r, bool with_w) {
-    Part1 o;
-    o.kt = wave_max((r.St > 0.0) ? r.kt : neg_inf());
-    o.kd = wave_max((r.Sd > 0.0) ? r.kd : neg_inf());
-    const bool nt = (r.St != r.St), nd = (r.Sd != r.Sd);
-    const double at = (r.St > 0.0) ? ldexp(r.St, kdiff(r.kt, o.kt)) : (nt ? r.St : 0.0);
-    const double ad = (r.Sd > 0.0) ? ldexp(r.Sd, kdiff(r.kd, o.kd)) : (nd ? r.Sd : 0.0);
-    o.St = wave_sum(at);
-    o.Sd = wave_sum(ad);
-    o.W = 0.0;
-    if (with_w) {
-        const bool inf = __any(r.W == __builtin_inf()) != 0;
-        const double aw = (r.St > 0.0 && r.W == r.W) ? ldexp(r.W, kdiff(r.kt, o.kt)) : 0.0;
-        o.W = inf ? __builtin_inf() : wave_sum(aw);
-    }
-    if (o.kt == neg_inf()) o.kt = 0.0f;   // no mass anywhere: St is 0 (or NaN) and says so
-    if (o.kd == neg_inf()) o.kd = 0.0f;
-    return o;
+// Lane l reads member (base + l)'s four phase-1 words.  Lanes beyond the team re-read the last
+// member's words (no branch around the loads, see load_item); nothing looks at the values here, so
+// the loads stay in flight until await_words.
+__device__ __forceinline__ void request_words(const unsigned long long* p1, int GW, int base, unsigned long long (&w)[4]) {
+    const int m = base + (threadIdx.x & 63);
+    const int mm = (m < GW) ? m : GW - 1;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) w[k] = read64(p1 + mm * 4 + k);
 }
+// The words of the first 64 members are normally there when they are looked at.  Everything that
+// loops over memory (asking again, further rounds of 64 members) lives in functions that are NOT
+// inlined: the compiler's bookkeeping of outstanding memory operations stays exact in the caller,
+// whose phase 2 then never waits for the prefetch it has just issued.
+struct Words { unsigned long long w[4]; bool ok; };
 
-// Lane i < G polls member i's four words until all have arrived (at most `limit` polls).
-// Returns false if they did not.
-__device__ __forceinline__ bool poll_part1(const unsigned long long* p1, int G, unsigned limit, Part1& r) {
-    const int lane = threadIdx.x & 63;
-    unsigned long long w0 = 1, w1 = 1, w2 = 1, w3 = 1;
+__device__ __noinline__ Words repoll_words(const unsigned long long* p1, int GW, int base, unsigned limit) {
+    Words r;
+    r.ok = true;
     unsigned polls = 0;
-    bool ok = true;
     for (;;) {
-        if (lane < G) {
-            w0 = read64(p1 + lane * 4 + 0);
-            w1 = read64(p1 + lane * 4 + 1);
-            w2 = read64(p1 + lane * 4 + 2);
-            w3 = read64(p1 + lane * 4 + 3);
-        }
-        const bool missing = (w0 == 0) | (w1 == 0) | (w2 == 0) | (w3 == 0);
+        request_words(p1, GW, base, r.w);
+        const bool missing = (r.w[0] == 0) | (r.w[1] == 0) | (r.w[2] == 0) | (r.w[3] == 0);   // duplicates included: harmless
         if (!__any(missing)) break;
-        if (polls++ >= limit) { ok = false; break; }
+        if (polls++ >= limit) { r.ok = false; break; }
         __builtin_amdgcn_s_sleep(1);
     }
-    r = Part1{0.0f, 0.0f, 0.0, 0.0, 0.0};
-    if (lane < G) {
-        r.kt = __uint_as_float(static_cast<unsigned>(w0));
-        r.kd = __uint_as_float(static_cast<unsigned>(w0 >> 32));
-        r.St = bitsd(w1);
-        r.Sd = bitsd(w2);
-        r.W = bitsd(w3);
-    }
-    return ok;
+    return r;
+}
+__device__ __forceinline__ bool await_words(const unsigned long long* p1, int GW, int base, unsigned limit,
+                                            unsigned long long (&w)[4]) {
+    const bool missing = (w[0] == 0) | (w[1] == 0) | (w[2] == 0) | (w[3] == 0);
+    if (!__any(missing)) return true;
+    const Words r = repoll_words(p1, GW, base, limit);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) w[k] = r.w[k];
+    return r.ok;
 }
 
-// Lane i < G polls the first NWORDS of member i's four divergence words.
-template <int NWORDS>
-__device__ __forceinline__ bool poll_part2(const unsigned long long* p2, int G, unsigned limit, double (&v)[NWORDS]) {
-    const int lane = threadIdx.x & 63;
-    unsigned long long w[NWORDS];
-#pragma unroll
-    for (int k = 0; k < NWORDS; ++k) w[k] = 1;
-    unsigned polls = 0;
-    bool ok = true;
-    for (;;) {
-        bool missing = false;
-        if (lane < G) {
-#pragma unroll
-            for (int k = 0; k < NWORDS; ++k) { w[k] = read64(p2 + lane * 4 + k); missing |= (w[k] == 0); }
-        }
-        if (!__any(missing)) break;
-        if (polls++ >= limit) { ok = false; break; }
-        __builtin_amdgcn_s_sleep(1);
+// binary32 merge of one round of team words into running (K, z) pairs: reference exponents and
+// sums of both rows.  Exact power-of-two rescaling between references.
+struct TeamNorm { float Kt, Kd, zt, zd; bool ok; };
+
+__device__ __forceinline__ void merge_round(const unsigned long long (&w)[4], bool in, TeamNorm& n) {
+    const float tk_t = __uint_as_float(static_cast<unsigned>(w[0])), tk_d = __uint_as_float(static_cast<unsigned>(w[0] >> 32));
+    const float tSt = in ? static_cast<float>(bitsd(w[1])) : 0.0f, tSd = in ? static_cast<float>(bitsd(w[2])) : 0.0f;
+    const float nKt = fmaxf(n.Kt, wave_max((tSt > 0.0f) ? tk_t : neg_inf()));
+    const float nKd = fmaxf(n.Kd, wave_max((tSd > 0.0f) ? tk_d : neg_inf()));
+    n.zt = ((n.zt > 0.0f) ? ldexpf(n.zt, kdiff(n.Kt, nKt)) : n.zt) +
+           wave_sumf((tSt > 0.0f) ? ldexpf(tSt, kdiff(tk_t, nKt)) : (tSt != tSt ? tSt : 0.0f));
+    n.zd = ((n.zd > 0.0f) ? ldexpf(n.zd, kdiff(n.Kd, nKd)) : n.zd) +
+           wave_sumf((tSd > 0.0f) ? ldexpf(tSd, kdiff(tk_d, nKd)) : (tSd != tSd ? tSd : 0.0f));
+    n.Kt = nKt;
+    n.Kd = nKd;
+}
+// teams of more than 64 wavefronts: the members beyond the first round
+__device__ __noinline__ TeamNorm merge_more_rounds(const unsigned long long* p1, int GW, unsigned limit, TeamNorm n) {
+    for (int base = 64; base < GW; base += 64) {
+        const Words r = repoll_words(p1, GW, base, limit);
+        if (!r.ok) n.ok = false;
+        merge_round(r.w, base + static_cast<int>(threadIdx.x & 63) < GW, n);
     }
-#pragma unroll
-    for (int k = 0; k < NWORDS; ++k) v[k] = (lane < G) ? bitsd(w[k]) : 0.0;
-    return ok;
+    return n;
 }
 
-// Persistent kernel: the grid is no larger than what is resident at once and a multiple of the
-// team size G.  Workgroup w is member w % G of team w / G and walks the row pairs
-// team, team + nteams, ...; the members of a team therefore meet at every pair they share.
-// Per pair a workgroup passes two barriers.  The loads of the next pair are issued as soon as
-// phase 1 has consumed the current ones, so they are in flight during the exchange and phase 2;
-// the bookkeeping of a pair (posting its divergence partial, finding out who finishes it) rides
-// along with the next pair's first barrier.
-template <bool BF16, int NV, int MODE, bool ALIGNED, int NW>
-__global__ __launch_bounds__(NW * 64) void pair_reduce(PairParams P) {
+template <bool BF16, int NV, int MODE, bool ALIGNED>
+__global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
     constexpr int VE = Slot<BF16>::VE;
     constexpr int ES = BF16 ? 2 : 4;
-    constexpr int WGS = NW * 64;
-    constexpr bool WAITS = (MODE == MODE_JS || MODE == MODE_TV || MODE == MODE_KLP);
-    constexpr bool TRACKS_MASK = (MODE == MODE_KL || MODE == MODE_KLP);
-    // per-wavefront partials are double-buffered by pair parity: a wavefront may already write
-    // the next pair's while the first wavefront still reads this pair's
-    __shared__ double s_w[2][NW][3];   // per wavefront: St, Sd, W
-    __shared__ float s_k[2][NW][2];    // per wavefront: kt, kd
+    constexpr bool TWO_PHASE = (MODE == MODE_JS || MODE == MODE_TV || MODE == MODE_KLP);
+    constexpr int NE = TWO_PHASE ? NV * VE : 1;   // exponentials kept per row and lane
     constexpr int PW = (MODE == MODE_TV) ? 4 : 1;   // divergence words a member posts
-    __shared__ double s_p[NW][4];   // per wavefront: phase-2 partials of the previous pair
-    __shared__ float s_x[6];        // team-wide: kt, kd, 1/St, 1/Sd, arrived?
+    constexpr float kTiny = 2e-38f;   // keeps p + q > 0 without changing any result
+    constexpr int kWavesPerWG = kWG / 64;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int G = P.G;
-    const int member = static_cast<int>(blockIdx.x) % G;
-    const int team = static_cast<int>(blockIdx.x) / G;
-    const int nteams = static_cast<int>(gridDim.x) / G;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int GW = P.G;                                   // wavefronts per pair
+    const int wgs_per_team = GW / kWavesPerWG;
+    const int team = static_cast<int>(blockIdx.x) / wgs_per_team;
+    const int nteams = static_cast<int>(gridDim.x) / wgs_per_team;
+    const int member = (static_cast<int>(blockIdx.x) % wgs_per_team) * kWavesPerWG + wave;
     const long s0 = static_cast<long>(member) * P.spm;
     const long s1 = (s0 + P.spm < P.nslots) ? s0 + P.spm : P.nslots;
+    unsigned long long* const part1 = P.ws.part1;
+    unsigned long long* const part2 = reinterpret_cast<unsigned long long*>(P.ws.part2);
 
-    uint4 ra[NV], rb[NV];
-    auto row_ptrs = [&](int pair, const char*& tptr, const char*& dptr) {
+    auto row_ptrs = [&](int pair, const char*& tptr, const char*& dptr) __attribute__((always_inline)) {
         const int b = pair / P.rows;
         const int j = pair - b * P.rows;
         int trow = j;
@@ -402,59 +397,122 @@ __global__ __launch_bounds__(NW * 64) void pair_reduce(PairParams P) {
         tptr = P.target + (static_cast<size_t>(b) * (P.rows + 1) + trow) * static_cast<size_t>(P.V) * ES;
         dptr = P.draft + static_cast<size_t>(pair) * static_cast<size_t>(P.V) * ES;
     };
-    // ---- the only HBM reads of the reduction: NV slots of each row per thread
-    auto load_item = [&](int pair) {
+    // ---- the only HBM reads of the reduction: NV slots of each row per lane
+    // Every lane always loads (a lane without a slot of its own re-reads a valid one and the value is
+    // replaced by -inf afterwards): loads that sit inside branches would make the compiler wait for
+    // all outstanding memory operations at every later use, and the prefetch would no longer overlap.
+    uint4 ra[NV], rb[NV];
+    long slot_of[NV];
+    bool own[NV];
+    bool all_own = true;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        const long s = s0 + k * 64 + lane;
+        own[k] = s < s1;
+        all_own &= own[k];
+        slot_of[k] = own[k] ? s : ((s1 > s0) ? s1 - 1 : 0);
+    }
+    const bool fill_needed = __any(!all_own) != 0;   // wavefront-uniform
+    auto load_item = [&](int pair) __attribute__((always_inline)) {
         const char *tptr, *dptr;
         row_ptrs(pair, tptr, dptr);
 #pragma unroll
         for (int k = 0; k < NV; ++k) {
-            const long s = s0 + k * WGS + tid;
-            if (s < s1) {
-                ra[k] = load_slot<BF16, ALIGNED>(tptr, s, P.V);
-                rb[k] = load_slot<BF16, ALIGNED>(dptr, s, P.V);
-            } else {
-                ra[k] = slot_neg_inf<BF16>();
-                rb[k] = slot_neg_inf<BF16>();
+            ra[k] = load_slot<BF16, ALIGNED>(tptr, slot_of[k], P.V);
+            rb[k] = load_slot<BF16, ALIGNED>(dptr, slot_of[k], P.V);
+        }
+    };
+    auto fill_unowned = [&]() __attribute__((always_inline)) {
+        if (fill_needed) {
+#pragma unroll
+            for (int k = 0; k < NV; ++k) {
+                if (!own[k]) { ra[k] = slot_neg_inf<BF16>(); rb[k] = slot_neg_inf<BF16>(); }
             }
         }
     };
 
-    // ---- what the first wavefront does for a pair once all its members are through with it
-    auto finish_pair = [&](int pair) {
-        unsigned long long* p1 = P.ws.part1 + static_cast<size_t>(pair) * G * 4;
-        unsigned long long* p2 = reinterpret_cast<unsigned long long*>(P.ws.part2) + static_cast<size_t>(pair) * G * 4;
-        int status = 0;
-        double value = 0.0, lse2_t = 0.0, lse2_d = 0.0;
-        bool ok;
-        if constexpr (WAITS) {
-            double pv[PW];
-            ok = poll_part2<PW>(p2, G, P.spin_limit, pv);
-            if constexpr (MODE == MODE_TV) {
-                // sum of (p - q)+ and of (q - p)+ are the same number; the side that avoids the
-                // heavy entries (smaller sum of p + q over its entries) carries the smaller
-                // rounding error, which matters for nearly one-hot rows
-                const double A = wave_sum(pv[0]), Bn = wave_sum(pv[1]), MA = wave_sum(pv[2]), MB = wave_sum(pv[3]);
-                value = (MA != MA || MB != MB) ? __builtin_nan("") : (MA <= MB ? A : Bn);
-            } else {
-                const double total = wave_sum(pv[0]);
-                value = (MODE == MODE_JS) ? 0.25 * kLn2 * total : 0.5 * kLn2 * total;
+    // ---- finishing a pair: add what the team posted for it, in member order
+    auto finish_two_phase = [&](int pair) __attribute__((always_inline)) {
+        const unsigned long long* p2 = part2 + static_cast<size_t>(pair) * GW * 4;
+        double sum[PW];
+#pragma unroll
+        for (int k = 0; k < PW; ++k) sum[k] = 0.0;
+        bool ok = true;
+        for (int base = 0; base < GW; base += 64) {
+            const int m = base + lane;
+            unsigned long long w[PW];
+            unsigned polls = 0;
+            for (;;) {
+                bool missing = false;
+#pragma unroll
+                for (int k = 0; k < PW; ++k) { w[k] = (m < GW) ? read64(p2 + m * 4 + k) : 1ull; missing |= (w[k] == 0); }
+                if (!__any(missing)) break;
+                if (polls++ >= P.spin_limit) { ok = false; break; }
+                __builtin_amdgcn_s_sleep(1);
             }
-            if (value != value) status |= FSD_ROW_NONFINITE;   // NaN / +inf logits, or a row without mass
-        } else {
-            Part1 r;
-            ok = poll_part1(p1, G, P.spin_limit, r);
-            const Part1 m = merge_part1(r, MODE == MODE_KL);
-            const bool bad = !(m.St > 0.0) || !(m.Sd > 0.0) || !(m.St < __builtin_inf()) || !(m.Sd < __builtin_inf()) ||
-                             !(m.kt < __builtin_inff()) || !(m.kd < __builtin_inff());
-            if (bad) status |= FSD_ROW_NONFINITE;
-            lse2_t = static_cast<double>(m.kt) + log2(m.St);
-            lse2_d = static_cast<double>(m.kd) + log2(m.Sd);
-            if constexpr (MODE == MODE_KL) {
-                // KL = sum_v p_v (a_v - b_v) - (lse_t - lse_d), p_v = 2^(a log2e - kt) / St
-                value = (m.W == __builtin_inf()) ? __builtin_inf() : m.W / m.St - (lse2_t - lse2_d) * kLn2;
-            }
+#pragma unroll
+            for (int k = 0; k < PW; ++k) sum[k] += wave_sum((m < GW) ? bitsd(w[k]) : 0.0);
         }
+        double value;
+        if constexpr (MODE == MODE_TV) {
+            // the sums of (p - q)+ and of (q - p)+ are the same number; the side that avoids the
+            // heavy entries (smaller sum of p + q over its entries) carries the smaller rounding
+            // error, which matters for nearly one-hot rows
+            value = (sum[2] != sum[2] || sum[3] != sum[3]) ? __builtin_nan("") : (sum[2] <= sum[3] ? sum[0] : sum[1]);
+        } else {
+            value = 0.5 * kLn2 * sum[0];
+        }
+        int status = 0;
+        if (value != value) status |= FSD_ROW_NONFINITE;   // NaN / +inf logits, or a row without mass
         if (!ok) status |= FSD_ROW_INTERNAL;
+        if (value < 0.0) value = 0.0;
+        if (status) value = __builtin_nan("");
+        if (lane == 0) {
+            P.ws.div[pair] = static_cast<float>(value);
+            P.ws.lse2[2 * pair] = 0.0;
+            P.ws.lse2[2 * pair + 1] = 0.0;
+            if (P.user_div) P.user_div[pair] = static_cast<float>(value);
+            P.ws.pst[pair] = status;
+        }
+    };
+    auto finish_single_pass = [&](int pair) __attribute__((always_inline)) {
+        const unsigned long long* p1 = part1 + static_cast<size_t>(pair) * GW * 4;
+        // online merge over rounds of 64 members, float64, exact rescaling between references
+        float Kt = neg_inf(), Kd = neg_inf();
+        double Zt = 0.0, Zd = 0.0, Wt = 0.0;
+        bool ok = true, winf = false;
+        for (int base = 0; base < GW; base += 64) {
+            unsigned long long w[4];
+            request_words(p1, GW, base, w);
+            ok &= await_words(p1, GW, base, P.spin_limit, w);
+            const bool in = base + lane < GW;
+            const float kt = __uint_as_float(static_cast<unsigned>(w[0])), kd = __uint_as_float(static_cast<unsigned>(w[0] >> 32));
+            const double St = in ? bitsd(w[1]) : 0.0, Sd = in ? bitsd(w[2]) : 0.0, W = in ? bitsd(w[3]) : 0.0;
+            const float nKt = fmaxf(Kt, wave_max((St > 0.0) ? kt : neg_inf()));
+            const float nKd = fmaxf(Kd, wave_max((Sd > 0.0) ? kd : neg_inf()));
+            Zt = ((Zt > 0.0) ? ldexp(Zt, kdiff(Kt, nKt)) : Zt) +
+                 wave_sum((St > 0.0) ? ldexp(St, kdiff(kt, nKt)) : (St != St ? St : 0.0));
+            Zd = ((Zd > 0.0) ? ldexp(Zd, kdiff(Kd, nKd)) : Zd) +
+                 wave_sum((Sd > 0.0) ? ldexp(Sd, kdiff(kd, nKd)) : (Sd != Sd ? Sd : 0.0));
+            if constexpr (MODE == MODE_KL) {
+                winf |= __any(in && W == __builtin_inf()) != 0;
+                Wt = ((Kt > neg_inf()) ? ldexp(Wt, kdiff(Kt, nKt)) : Wt) +
+                     wave_sum((St > 0.0 && W == W && W != __builtin_inf()) ? ldexp(W, kdiff(kt, nKt)) : 0.0);
+            }
+            Kt = nKt;
+            Kd = nKd;
+        }
+        int status = 0;
+        const bool bad = !(Zt > 0.0) || !(Zd > 0.0) || !(Zt < __builtin_inf()) || !(Zd < __builtin_inf()) ||
+                         !(Kt < __builtin_inff()) || !(Kd < __builtin_inff());
+        if (bad) status |= FSD_ROW_NONFINITE;
+        if (!ok) status |= FSD_ROW_INTERNAL;
+        const double lse2_t = static_cast<double>(Kt) + log2(Zt), lse2_d = static_cast<double>(Kd) + log2(Zd);
+        double value = 0.0;
+        if constexpr (MODE == MODE_KL) {
+            // KL = sum_v p_v (a_v - b_v) - (lse_t - lse_d), p_v = 2^(a log2e - Kt) / Zt
+            value = winf ? __builtin_inf() : Wt / Zt - (lse2_t - lse2_d) * kLn2;
+        }
         if (value < 0.0) value = 0.0;
         if (status) value = __builtin_nan("");
         if (lane == 0) {
@@ -482,403 +540,35 @@ __global__ __launch_bounds__(NW * 64) void pair_reduce(PairParams P) {
         }
     };
 
-    // Bookkeeping carried from one pair to the next (first wavefront only).  Each pair has a
-    // designated finisher among the team (the members take turns); it adds up what the others
-    // posted one step later, when the words have normally long arrived.
-    int pend_post = -1;          // pair whose phase-2 partial sits in s_p, not yet posted
-    int pend_fin = -1;           // pair this workgroup has to finish
-    int pend_fin_next = -1;      // (waiting modes) the pair to finish one step after that
-    int iter = 0;
-
-#ifdef FSD_PHASE_TIMING
-    unsigned long long pt_acc[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
-    const unsigned long long pt_start = __builtin_readcyclecounter();
-    unsigned long long pt_last = pt_start;
-#endif
-    int pair = team;
-    int buf = 0;
-    if (pair < P.npairs) load_item(pair);
-    for (; pair < P.npairs; pair += nteams, buf ^= 1) {
-        // ---- phase 1, per wavefront: maximum, then sums of 2^(z log2e - k) with k = ceil(max log2e)
-        float mt = neg_inf(), md = neg_inf();
-#pragma unroll
-        for (int k = 0; k < NV; ++k) {
-            float a[VE], c[VE];
-            unpack<BF16>(ra[k], a);
-            unpack<BF16>(rb[k], c);
-#pragma unroll
-            for (int e = 0; e < VE; ++e) { mt = fmaxf(mt, a[e]); md = fmaxf(md, c[e]); }
-        }
-        mt = wave_max(mt);
-        md = wave_max(md);
-        const float kt = (mt == neg_inf()) ? 0.0f : ceilf(mt * kLog2e);
-        const float kd = (md == neg_inf()) ? 0.0f : ceilf(md * kLog2e);
-
-        // the exponentials are kept: phase 2 rescales them instead of touching the logits again
-        float ea[WAITS ? NV * VE : 1], eb[WAITS ? NV * VE : 1];
-        float st = 0.0f, sd = 0.0f, w = 0.0f, dmax = neg_inf();
-#pragma unroll
-        for (int k = 0; k < NV; ++k) {
-            float a[VE], c[VE];
-            unpack<BF16>(ra[k], a);
-            unpack<BF16>(rb[k], c);
-#pragma unroll
-            for (int e = 0; e < VE; ++e) {
-                const float xa = hw_exp2(fmaf(a[e], kLog2e, -kt));
-                const float xb = hw_exp2(fmaf(c[e], kLog2e, -kd));
-                if constexpr (WAITS) { ea[k * VE + e] = xa; eb[k * VE + e] = xb; }
-                st += xa;
-                sd += xb;
-                if constexpr (TRACKS_MASK) {
-                    const float diff = a[e] - c[e];
-                    dmax = fmaxf(dmax, diff);   // +inf iff the draft masks an entry the target does not
-                    if constexpr (MODE == MODE_KL) w = fmaf(xa, fminf(fmaxf(diff, -FLT_MAX), FLT_MAX), w);
-                }
-            }
-        }
-        PT(0);
-        // ---- the registers that held the logits are free: fetch the next pair behind the exchange.
-        // Loads return in issue order, so the wavefront that is about to poll the team's words
-        // issues its share only after the poll: otherwise every poll would wait for these loads.
-        const bool more = pair + nteams < P.npairs;
-        if (more && !(WAITS && wave == 0)) load_item(pair + nteams);
-
-        {
-            // the waiting modes only need the normalisers to a relative 1e-7 (they enter p and q
-            // as common factors); the single-pass modes take them through a logarithm
-            double wst, wsd, ww = 0.0;
-            if constexpr (WAITS) {
-                wst = static_cast<double>(wave_sumf(st));
-                wsd = static_cast<double>(wave_sumf(sd));
-            } else {
-                wst = wave_sum(static_cast<double>(st));
-                wsd = wave_sum(static_cast<double>(sd));
-            }
-            if constexpr (MODE == MODE_KL) {
-                ww = wave_sum(static_cast<double>(w));
-                if (wave_max(dmax) == __builtin_inff()) ww = __builtin_inf();
-            }
-            if (lane == 0) {
-                s_w[buf][wave][0] = wst; s_w[buf][wave][1] = wsd; s_w[buf][wave][2] = ww;
-                s_k[buf][wave][0] = kt; s_k[buf][wave][1] = kd;
-            }
-        }
-        PT(1);
-        __syncthreads();   // barrier 1: wavefront partials of this pair (and s_p of the previous one) are in LDS
-        PT(2);
-
-        unsigned long long* p1 = P.ws.part1 + static_cast<size_t>(pair) * G * 4;
-        if (wave == 0) {
-            // the previous pair: post its divergence partial
-            if constexpr (WAITS) {
-                if (pend_post >= 0 && lane < PW) {
-                    double part = s_p[0][lane];
-#pragma unroll
-                    for (int k = 1; k < NW; ++k) part += s_p[k][lane];
-                    unsigned long long* q2 = reinterpret_cast<unsigned long long*>(P.ws.part2) + static_cast<size_t>(pend_post) * G * 4;
-                    post64(q2 + member * 4 + lane, dbits(part));
-                }
-                pend_post = -1;
-            }
-            // finish the pair this workgroup is the finisher of, once everybody has posted for it
-            if (pend_fin >= 0) finish_pair(pend_fin);
-            pend_fin = pend_fin_next;
-            pend_fin_next = -1;
-            PT(3);
-            // this pair: merge the wavefronts (a handful of values, done by every lane alike) and
-            // post the workgroup's normaliser partial
-            Part1 m{neg_inf(), neg_inf(), 0.0, 0.0, 0.0};
-#pragma unroll
-            for (int k = 0; k < NW; ++k) {
-                if (s_w[buf][k][0] > 0.0) m.kt = fmaxf(m.kt, s_k[buf][k][0]);
-                if (s_w[buf][k][1] > 0.0) m.kd = fmaxf(m.kd, s_k[buf][k][1]);
-            }
-            bool winf = false;
-#pragma unroll
-            for (int k = 0; k < NW; ++k) {
-                const double a0 = s_w[buf][k][0], a1 = s_w[buf][k][1], a2 = s_w[buf][k][2];
-                m.St += (a0 > 0.0) ? ldexp(a0, kdiff(s_k[buf][k][0], m.kt)) : (a0 != a0 ? a0 : 0.0);
-                m.Sd += (a1 > 0.0) ? ldexp(a1, kdiff(s_k[buf][k][1], m.kd)) : (a1 != a1 ? a1 : 0.0);
-                if constexpr (MODE == MODE_KL) {
-                    winf |= (a2 == __builtin_inf());
-                    m.W += (a0 > 0.0 && a2 == a2 && a2 != __builtin_inf()) ? ldexp(a2, kdiff(s_k[buf][k][0], m.kt)) : 0.0;
-                }
-            }
-            if (winf) m.W = __builtin_inf();
-            if (m.kt == neg_inf()) m.kt = 0.0f;
-            if (m.kd == neg_inf()) m.kd = 0.0f;
-            if (lane == 0) {
-                unsigned long long* slot = p1 + member * 4;
-                post64(slot + 0, static_cast<unsigned long long>(fbits(m.kt)) | (static_cast<unsigned long long>(fbits(m.kd)) << 32));
-                post64(slot + 1, dbits(m.St));
-                post64(slot + 2, dbits(m.Sd));
-                post64(slot + 3, dbits(m.W));
-            }
-            // whose turn is it to finish this pair?
-            if (iter % G == member) {
-                if constexpr (WAITS) pend_fin_next = pair;   // its divergence words are posted one step from now
-                else pend_fin = pair;
-            }
-            PT(4);
-            if constexpr (WAITS) {
-                // ---- exchange: wait for the whole team's partials (bounded), merge them in binary32
-                Part1 t;
-                const bool ok = poll_part1(p1, G, P.spin_limit, t);
-                if (more) load_item(pair + nteams);
-                const float tSt = static_cast<float>(t.St), tSd = static_cast<float>(t.Sd);
-                float Kt = wave_max((tSt > 0.0f) ? t.kt : neg_inf());
-                float Kd = wave_max((tSd > 0.0f) ? t.kd : neg_inf());
-                const float zt = wave_sumf((tSt > 0.0f) ? ldexpf(tSt, kdiff(t.kt, Kt)) : (tSt != tSt ? tSt : 0.0f));
-                const float zd = wave_sumf((tSd > 0.0f) ? ldexpf(tSd, kdiff(t.kd, Kd)) : (tSd != tSd ? tSd : 0.0f));
-                if (lane == 0) {
-                    s_x[0] = (Kt == neg_inf()) ? 0.0f : Kt;
-                    s_x[1] = (Kd == neg_inf()) ? 0.0f : Kd;
-                    s_x[2] = 1.0f / zt;   // inf for a row without mass, NaN for a bad one
-                    s_x[3] = 1.0f / zd;
-                    s_x[4] = ok ? 1.0f : 0.0f;
-                    if (!ok) atomicOr(P.ws.counters + 1, 1u);
-                }
-            }
-            PT(5);
-        }
-
-        if constexpr (WAITS) {
-            __syncthreads();   // barrier 2: the team's normalisers are in s_x
-            PT(6);
-            // p = ea * ft with ft = 2^(kt - Kt) / St: exact power of two times one rounded reciprocal.
-            // A wavefront without mass has only zeros in ea; its factor is 0 (NaN if the row is unusable).
-            const bool mass_t = st > 0.0f || st != st, mass_d = sd > 0.0f || sd != sd;
-            const float ft = __any(mass_t) ? ldexpf(s_x[2], kdiff(kt, s_x[0])) : s_x[2] * 0.0f;
-            const float fd = __any(mass_d) ? ldexpf(s_x[3], kdiff(kd, s_x[1])) : s_x[3] * 0.0f;
-            const bool timed_out = (s_x[4] == 0.0f);
-
-            // ---- phase 2 from the registers.  Only relative errors enter p and q, and both
-            // divergences are evaluated as functions of (p, q) alone, so the result is the
-            // divergence of a slightly perturbed input.
-            float acc = 0.0f;
-            if constexpr (MODE == MODE_JS) {
-                // with s = p + q, r = (p - q)/s, u = 1 + r = 2p/s, v = 1 - r = 2q/s:
-                //   p ln(2p/s) + q ln(2q/s) = (s/2) ln2 [u log2 u + v log2 v]
-                // u log2 u + v log2 v is even in r and flat at r = 0: no cancellation for p ~ q.
-#pragma unroll
-                for (int i = 0; i < NV * VE; ++i) {
-                    const float p = __fmul_rn(ea[i], ft), q = __fmul_rn(eb[i], fd);   // rounded products: p == q for equal rows
-                    const float sum = p + q;
-                    const float r = (p - q) * __builtin_amdgcn_rcpf(fmaxf(sum, 1e-37f));
-                    // v = 2 - u is exact, so (u, v) stay symmetric about 1 and the rounding of 1 + r
-                    // only perturbs r instead of entering h to first order
-                    const float u = fminf(fmaxf(1.0f + r, 1e-37f), 2.0f), v = fmaxf(2.0f - u, 1e-37f);
-                    const float h = fmaf(v, hw_log2(v), u * hw_log2(u));
-                    acc = fmaf(sum, h, acc);
-                }
-            } else if constexpr (MODE == MODE_KLP) {
-                // p ln(p/q) + q - p = (s/2) [u ln(u/v) + v - u] >= 0 entry by entry (the added q - p
-                // sums to zero), second order in r, so neither the normalisers' errors nor those of
-                // the exponentials enter to first order.
-#pragma unroll
-                for (int i = 0; i < NV * VE; ++i) {
-                    const float p = __fmul_rn(ea[i], ft), q = __fmul_rn(eb[i], fd);   // rounded products: p == q for equal rows
-                    const float sum = p + q;
-                    const float r = (p - q) * __builtin_amdgcn_rcpf(fmaxf(sum, 1e-37f));
-                    const float u = fminf(fmaxf(1.0f + r, 1e-37f), 2.0f), v = fmaxf(2.0f - u, 1e-37f);
-                    const float h = fmaf(u, hw_log2(u) - hw_log2(v), (v - u) * kLog2e);
-                    acc = fmaf(sum, h, acc);
-                }
-            }
-            double part[PW];
-            if constexpr (MODE == MODE_TV) {
-                float A = 0.0f, Bn = 0.0f, MA = 0.0f, MB = 0.0f;
-#pragma unroll
-                for (int i = 0; i < NV * VE; ++i) {
-                    const float p = __fmul_rn(ea[i], ft), q = __fmul_rn(eb[i], fd);   // rounded products: p == q for equal rows
-                    const float d = p - q, sum = p + q;
-                    A += fmaxf(d, 0.0f);
-                    Bn += fmaxf(-d, 0.0f);
-                    MA += (d > 0.0f) ? sum : 0.0f;
-                    MB += (d < 0.0f) ? sum : 0.0f;
-                }
-                // max() drops NaN: an unusable row (NaN factor) is made to reach the side selection
-                if (ft != ft || fd != fd) { A = ft + fd; Bn = A; MA = A; MB = A; }
-                part[0] = static_cast<double>(wave_sumf(A));
-                part[1] = static_cast<double>(wave_sumf(Bn));
-                part[2] = static_cast<double>(wave_sumf(MA));
-                part[3] = static_cast<double>(wave_sumf(MB));
-            } else {
-                part[0] = static_cast<double>(wave_sumf(acc));
-                if constexpr (MODE == MODE_KLP) {
-                    if (wave_max(dmax) == __builtin_inff()) part[0] += __builtin_inf();   // stays NaN for a bad row
-                }
-            }
-            if (lane == 0) {   // read after the next barrier 1 (or the one after the loop)
-#pragma unroll
-                for (int k = 0; k < PW; ++k) s_p[wave][k] = timed_out ? __builtin_nan("") : part[k];
-            }
-            pend_post = pair;
-            PT(7);
-        }
-#ifdef FSD_PHASE_TIMING
-        pt_acc[8] += 1;
-#endif
-        ++iter;
-    }
-
-    // ---- drain the bookkeeping of the last pairs
-    if constexpr (WAITS) {
-        __syncthreads();
-        if (wave == 0 && pend_post >= 0 && lane < PW) {
-            double part = s_p[0][lane];
-#pragma unroll
-            for (int k = 1; k < NW; ++k) part += s_p[k][lane];
-            unsigned long long* q2 = reinterpret_cast<unsigned long long*>(P.ws.part2) + static_cast<size_t>(pend_post) * G * 4;
-            post64(q2 + member * 4 + lane, dbits(part));
-        }
-    }
-    if (wave == 0) {
-        if (pend_fin >= 0) finish_pair(pend_fin);
-        if (pend_fin_next >= 0) finish_pair(pend_fin_next);
-    }
-#ifdef FSD_PHASE_TIMING
-    if (P.dbg && lane == 0 && wave < 2) {
-        unsigned long long* d = P.dbg + (static_cast<size_t>(blockIdx.x) * 2 + wave) * 10;
-        for (int i = 0; i < 8; ++i) d[i] = pt_acc[i];
-        d[8] = pt_start;
-        d[9] = __builtin_readcyclecounter() - pt_start;
-    }
-#endif
-}
-
-// ------------------------------------------------------------------------------------------
-// kernel 1b: two-phase divergences (JS, TV, pointwise KL) with the exchange off the critical path.
-//
-// Same persistent team layout as pair_reduce, but software-pipelined by one pair: in step j a
-// workgroup runs phase 1 of pair j (its exponentials stay in registers) and then phase 2 of pair
-// j-1, whose team-wide normalisers were posted a whole step earlier.  The polling loads for pair
-// j-1 are issued at the top of the step and consumed after phase 1, so in the normal case nobody
-// waits: one barrier per pair, and every wavefront polls and merges the team's words by itself.
-template <bool BF16, int NV, int MODE, bool ALIGNED, int NW>
-__global__ __launch_bounds__(NW * 64) void pair_divergence(PairParams P) {
-    constexpr int VE = Slot<BF16>::VE;
-    constexpr int ES = BF16 ? 2 : 4;
-    constexpr int WGS = NW * 64;
-    constexpr int NE = NV * VE;
-    constexpr int PW = (MODE == MODE_TV) ? 4 : 1;   // divergence words a member posts
-    constexpr float kTiny = 2e-38f;   // smallest normal scale: keeps p + q > 0 without changing any result
-    __shared__ float s_w[2][NW][2];    // per wavefront: St, Sd          (double-buffered by step parity)
-    __shared__ float s_k[2][NW][2];    // per wavefront: kt, kd
-    __shared__ double s_p[2][NW][4];   // per wavefront: phase-2 partials
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int G = P.G;
-    const int member = static_cast<int>(blockIdx.x) % G;
-    const int team = static_cast<int>(blockIdx.x) / G;
-    const int nteams = static_cast<int>(gridDim.x) / G;
-    const long s0 = static_cast<long>(member) * P.spm;
-    const long s1 = (s0 + P.spm < P.nslots) ? s0 + P.spm : P.nslots;
-    unsigned long long* const part2 = reinterpret_cast<unsigned long long*>(P.ws.part2);
-
-    uint4 ra[NV], rb[NV];
-    auto load_item = [&](int pair) __attribute__((always_inline)) {
-        const int b = pair / P.rows;
-        const int j = pair - b * P.rows;
-        int trow = j;
-        if (P.parent) {
-            const int par = P.parent[pair];
-            trow = (par >= -1 && par < j) ? par + 1 : 0;   // invalid parents are reported by the next kernel
-        }
-        const char* tptr = P.target + (static_cast<size_t>(b) * (P.rows + 1) + trow) * static_cast<size_t>(P.V) * ES;
-        const char* dptr = P.draft + static_cast<size_t>(pair) * static_cast<size_t>(P.V) * ES;
-#pragma unroll
-        for (int k = 0; k < NV; ++k) {
-            const long s = s0 + k * WGS + tid;
-            if (s < s1) {
-                ra[k] = load_slot<BF16, ALIGNED>(tptr, s, P.V);
-                rb[k] = load_slot<BF16, ALIGNED>(dptr, s, P.V);
-            } else {
-                ra[k] = slot_neg_inf<BF16>();
-                rb[k] = slot_neg_inf<BF16>();
-            }
-        }
-    };
-
-    // first wavefront: add up a finished pair's divergence words (fixed member order) and write it out
-    auto finish_pair = [&](int pair) __attribute__((always_inline)) {
-        double pv[PW];
-        const bool ok = poll_part2<PW>(part2 + static_cast<size_t>(pair) * G * 4, G, P.spin_limit, pv);
-        double value;
-        if constexpr (MODE == MODE_TV) {
-            // sum of (p - q)+ and of (q - p)+ are the same number; the side that avoids the heavy
-            // entries (smaller sum of p + q over its entries) carries the smaller rounding error,
-            // which matters for nearly one-hot rows
-            const double A = wave_sum(pv[0]), Bn = wave_sum(pv[1]), MA = wave_sum(pv[2]), MB = wave_sum(pv[3]);
-            value = (MA != MA || MB != MB) ? __builtin_nan("") : (MA <= MB ? A : Bn);
-        } else {
-            value = 0.5 * kLn2 * wave_sum(pv[0]);
-        }
-        int status = 0;
-        if (value != value) status |= FSD_ROW_NONFINITE;   // NaN / +inf logits, or a row without mass
-        if (!ok) status |= FSD_ROW_INTERNAL;
-        if (value < 0.0) value = 0.0;
-        if (status) value = __builtin_nan("");
-        if (lane == 0) {
-            P.ws.div[pair] = static_cast<float>(value);
-            P.ws.lse2[2 * pair] = 0.0;
-            P.ws.lse2[2 * pair + 1] = 0.0;
-            if (P.user_div) P.user_div[pair] = static_cast<float>(value);
-            P.ws.pst[pair] = status;
-        }
-    };
-    auto post_part2 = [&](int pair, int b) __attribute__((always_inline)) {   // first wavefront, from s_p[b]
-        if (lane < PW) {
-            double part = s_p[b][0][lane];
-#pragma unroll
-            for (int k = 1; k < NW; ++k) part += s_p[b][k][lane];
-            post64(part2 + (static_cast<size_t>(pair) * G + member) * 4 + lane, dbits(part));
-        }
-    };
-
-    // ---- per-wavefront state of the previous pair, whose phase 2 is still to come
+    // ---- state of the previous pair, whose phase 2 is still to come (two-phase modes)
     float pkt = 0.0f, pkd = 0.0f;
     bool pmass_t = false, pmass_d = false, pmask = false;
     int prev_pair = -1;
-    int p2_pair = -1;                      // pair whose phase-2 partials sit in s_p[buf ^ 1]
-    int fin0 = -1, fin1 = -1, fin2 = -1;   // first wavefront: pairs to finish now / in one / in two steps
-    int iter = 0, buf = 0;
+    // pairs this wavefront has to finish: now / one / two steps from now
+    int fin0 = -1, fin1 = -1, fin2 = -1;
+    int iter = 0;
 
-    // phase 2 of the previous pair from its kept exponentials; lane i < G holds member i's words in w[]
-    auto phase2 = [&](const float (&et)[NE], const float (&ed)[NE], unsigned long long (&w)[4], int b)
-                      __attribute__((always_inline)) {
-        const unsigned long long* p1 = P.ws.part1 + static_cast<size_t>(prev_pair) * G * 4;
-        // the words were requested at the top of the step; ask again only if some had not arrived
-        bool ok = true;
-        unsigned polls = 0;
-        for (;;) {
-            const bool missing = (w[0] == 0) | (w[1] == 0) | (w[2] == 0) | (w[3] == 0);
-            if (!__any(missing)) break;
-            if (polls++ >= P.spin_limit) { ok = false; break; }
-            __builtin_amdgcn_s_sleep(1);
-            if (lane < G) {
-#pragma unroll
-                for (int k = 0; k < 4; ++k) w[k] = read64(p1 + lane * 4 + k);
-            }
-        }
-        // merge the team's normalisers in binary32 (they enter p and q as common factors)
-        float tk_t = neg_inf(), tk_d = neg_inf(), tSt = 0.0f, tSd = 0.0f;
-        if (lane < G) {
-            tk_t = __uint_as_float(static_cast<unsigned>(w[0]));
-            tk_d = __uint_as_float(static_cast<unsigned>(w[0] >> 32));
-            tSt = static_cast<float>(bitsd(w[1]));
-            tSd = static_cast<float>(bitsd(w[2]));
-        }
-        const float Kt = wave_max((tSt > 0.0f) ? tk_t : neg_inf());
-        const float Kd = wave_max((tSd > 0.0f) ? tk_d : neg_inf());
-        const float zt = wave_sumf((tSt > 0.0f) ? ldexpf(tSt, kdiff(tk_t, Kt)) : (tSt != tSt ? tSt : 0.0f));
-        const float zd = wave_sumf((tSd > 0.0f) ? ldexpf(tSd, kdiff(tk_d, Kd)) : (tSd != tSd ? tSd : 0.0f));
+    // the previous pair's row-wide normalisers from the team's words (w holds the first 64 members'):
+    // factors ft, fd with p = e_t ft, q = e_d fd
+    auto merge_team = [&](unsigned long long (&w)[4], float& ft, float& fd) __attribute__((always_inline)) -> bool {
+        const unsigned long long* p1 = part1 + static_cast<size_t>(prev_pair) * GW * 4;
+        // binary32 is enough: the normalisers enter p and q as common factors
+        TeamNorm n{neg_inf(), neg_inf(), 0.0f, 0.0f, true};
+        n.ok = await_words(p1, GW, 0, P.spin_limit, w);
+        merge_round(w, lane < GW, n);
+        if (GW > 64) n = merge_more_rounds(p1, GW, P.spin_limit, n);
+        const float Kt = n.Kt, Kd = n.Kd, zt = n.zt, zd = n.zd;
+        const bool ok = n.ok;
         const float rzt = 1.0f / zt, rzd = 1.0f / zd;   // inf for a row without mass, NaN for a bad one
-        // p = e * ft with ft = 2^(k_wave - K) / S: an exact power of two times one rounded reciprocal.
-        // A wavefront without mass has only zeros in e; its factor is 0 (NaN if the row is unusable).
-        const float ft = pmass_t ? ldexpf(rzt, kdiff(pkt, Kt)) : rzt * 0.0f;
-        const float fd = pmass_d ? ldexpf(rzd, kdiff(pkd, Kd)) : rzd * 0.0f;
+        // ft = 2^(k_wave - K) / S: an exact power of two times one rounded reciprocal.  A wavefront
+        // without mass has only zeros in e; its factor is 0 (NaN if the row is unusable).
+        ft = pmass_t ? ldexpf(rzt, kdiff(pkt, Kt)) : rzt * 0.0f;
+        fd = pmass_d ? ldexpf(rzd, kdiff(pkd, Kd)) : rzd * 0.0f;
+        return ok;
+    };
 
+    // phase 2 of the previous pair from its kept exponentials
+    auto phase2 = [&](const float (&et)[NE], const float (&ed)[NE], float ft, float fd, bool ok) __attribute__((always_inline)) {
         // Only relative errors enter p and q, and the divergences below are functions of (p, q)
         // alone, second order in r = (p - q)/(p + q): the result is the divergence of a slightly
         // perturbed input.  u = 1 + r = 2p/s and v = 2 - u = 2q/s (exact subtraction).
@@ -909,13 +599,14 @@ __global__ __launch_bounds__(NW * 64) void pair_divergence(PairParams P) {
                 const float inv = __builtin_amdgcn_rcpf(sum);
                 const float u = fmaxf(fmaf(d, inv, 1.0f), kTiny), v = fmaxf(2.0f - u, kTiny);
                 if constexpr (MODE == MODE_JS) {
-                    // p ln(2p/s) + q ln(2q/s) = ln2 (p log2 u + q log2 v)
+                    // p ln(2p/s) + q ln(2q/s) = ln2 (p log2 u + q log2 v); the rounding of u = 1 + r
+                    // cancels between the two terms because p/u = q/v
                     acc = fmaf(p, hw_log2(u), acc);
                     acc = fmaf(q, hw_log2(v), acc);
                 } else {
                     // p ln(p/q) + q - p = (s/2) [u ln(u/v) + v - u] >= 0 entry by entry (the added q - p
-                    // sums to zero).  Written in (u, v) only, the rounding of u = 1 + r cancels between
-                    // the two parts; p ln(u/v) - (p - q) would keep it to first order.
+                    // sums to zero).  Written in (u, v) only, the rounding of u cancels between the
+                    // two parts; p ln(u/v) - (p - q) would keep it to first order.
                     acc = fmaf(sum, fmaf(u, hw_log2(u) - hw_log2(v), (v - u) * kLog2e), acc);
                 }
             }
@@ -929,23 +620,22 @@ __global__ __launch_bounds__(NW * 64) void pair_divergence(PairParams P) {
 #pragma unroll
             for (int k = 0; k < PW; ++k) part[k] = __builtin_nan("");
         }
-        if (lane == 0) {
+        if (lane < PW) {
+            double mine = part[0];
 #pragma unroll
-            for (int k = 0; k < PW; ++k) s_p[b][wave][k] = part[k];
+            for (int k = 1; k < PW; ++k) mine = (lane == k) ? part[k] : mine;
+            post64(part2 + (static_cast<size_t>(prev_pair) * GW + member) * 4 + lane, dbits(mine));
         }
     };
 
-    // one step: phase 1 of `pair` into (ect, ecd), then phase 2 of the previous pair from (ept, epd)
+    // One step: phase 1 of `pair` into (ect, ecd), then phase 2 of the previous pair from (ept, epd).
+    // Order matters for overlap: the team words of the previous pair are requested while phase 1
+    // computes and consumed before the next pair's loads are issued, so that no wait ever has the
+    // big prefetch in front of it; the prefetch then flies during phase 2.
     auto step = [&](float (&ect)[NE], float (&ecd)[NE], const float (&ept)[NE], const float (&epd)[NE], int pair)
                     __attribute__((always_inline)) {
-        // request the previous pair's team words now; they are consumed after phase 1
-        unsigned long long w[4] = {1, 1, 1, 1};
-        if (prev_pair >= 0 && lane < G) {
-            const unsigned long long* p1 = P.ws.part1 + static_cast<size_t>(prev_pair) * G * 4;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) w[k] = read64(p1 + lane * 4 + k);
-        }
-        // ---- phase 1, per wavefront: maximum, then sums of 2^(z log2e - k) with k = ceil(max log2e)
+        fill_unowned();
+        // ---- phase 1: maximum, then sums of 2^(z log2e - k) with k = ceil(max log2e)
         float mt = neg_inf(), md = neg_inf();
 #pragma unroll
         for (int k = 0; k < NV; ++k) {
@@ -955,11 +645,18 @@ __global__ __launch_bounds__(NW * 64) void pair_divergence(PairParams P) {
 #pragma unroll
             for (int e = 0; e < VE; e += 2) { mt = fmaxf(fmaxf(mt, a[e]), a[e + 1]); md = fmaxf(fmaxf(md, c[e]), c[e + 1]); }
         }
+        // the logits have arrived: request the previous pair's team words behind the arithmetic
+        unsigned long long w[4] = {1, 1, 1, 1};
+        if constexpr (TWO_PHASE) {
+            asm volatile("" ::: "memory");
+            if (prev_pair >= 0) request_words(part1 + static_cast<size_t>(prev_pair) * GW * 4, GW, 0, w);
+            asm volatile("" ::: "memory");
+        }
         mt = wave_max(mt);
         md = wave_max(md);
         const float kt = (mt == neg_inf()) ? 0.0f : ceilf(mt * kLog2e);
         const float kd = (md == neg_inf()) ? 0.0f : ceilf(md * kLog2e);
-        float st = 0.0f, sd = 0.0f, dmax = neg_inf();
+        float st = 0.0f, sd = 0.0f, wacc = 0.0f, dmax = neg_inf();
 #pragma unroll
         for (int k = 0; k < NV; ++k) {
             float a[VE], c[VE];
@@ -969,91 +666,101 @@ __global__ __launch_bounds__(NW * 64) void pair_divergence(PairParams P) {
             for (int e = 0; e < VE; ++e) {
                 const float xa = hw_exp2(fmaf(a[e], kLog2e, -kt));
                 const float xb = hw_exp2(fmaf(c[e], kLog2e, -kd));
-                ect[k * VE + e] = xa;
-                ecd[k * VE + e] = xb;
+                if constexpr (TWO_PHASE) { ect[k * VE + e] = xa; ecd[k * VE + e] = xb; }
                 st += xa;
                 sd += xb;
-                if constexpr (MODE == MODE_KLP) dmax = fmaxf(dmax, a[e] - c[e]);   // +inf iff only the draft masks the entry
+                if constexpr (MODE == MODE_KL || MODE == MODE_KLP) {
+                    const float diff = a[e] - c[e];
+                    dmax = fmaxf(dmax, diff);   // +inf iff the draft masks an entry the target does not
+                    if constexpr (MODE == MODE_KL) wacc = fmaf(xa, fminf(fmaxf(diff, -FLT_MAX), FLT_MAX), wacc);
+                }
             }
         }
-        // ---- the registers that held the logits are free: fetch the next pair
+        // ---- the previous pair's normalisers (its words were requested above)
+        float ft = 0.0f, fd = 0.0f;
+        bool ok2 = true;
+        if constexpr (TWO_PHASE) {
+            if (prev_pair >= 0) ok2 = merge_team(w, ft, fd);
+            asm volatile("" ::: "memory");
+        }
+        // post this wavefront's partial (stores go out before the prefetch, so that nothing that has to
+        // wait for them later also waits for the prefetch).  The two-phase modes need the normalisers
+        // to a relative 1e-7 only (common factors of p and q); the single-pass modes take them through
+        // a logarithm.
+        double pst_, psd_, pw_ = 0.0;
+        if constexpr (TWO_PHASE) {
+            st = wave_sumf(st);
+            sd = wave_sumf(sd);
+            pst_ = static_cast<double>(st);
+            psd_ = static_cast<double>(sd);
+        } else {
+            pst_ = wave_sum(static_cast<double>(st));
+            psd_ = wave_sum(static_cast<double>(sd));
+            if constexpr (MODE == MODE_KL) {
+                pw_ = wave_sum(static_cast<double>(wacc));
+                if (wave_max(dmax) == __builtin_inff()) pw_ = __builtin_inf();
+            }
+        }
+        const unsigned long long w0 = static_cast<unsigned long long>(fbits(kt)) | (static_cast<unsigned long long>(fbits(kd)) << 32);
+        const unsigned long long mine = (lane == 0) ? w0 : (lane == 1) ? dbits(pst_) : (lane == 2) ? dbits(psd_) : dbits(pw_);
+        unsigned long long* const post_at = part1 + (static_cast<size_t>(pair) * GW + member) * 4 + (lane & 3);
+        // ---- the registers that held the logits are free: fetch the next pair, then post
+        asm volatile("" ::: "memory");
         if (pair + nteams < P.npairs) load_item(pair + nteams);
-        st = wave_sumf(st);
-        sd = wave_sumf(sd);
-        if (lane == 0) { s_w[buf][wave][0] = st; s_w[buf][wave][1] = sd; s_k[buf][wave][0] = kt; s_k[buf][wave][1] = kd; }
-        __syncthreads();   // the only barrier of the step
-
-        if (wave == 0) {
-            // bookkeeping of older pairs: post the partials of the pair whose phase 2 ran last step,
-            // finish the pair whose turn has come
-            if (p2_pair >= 0) post_part2(p2_pair, buf ^ 1);
-            if (fin0 >= 0) finish_pair(fin0);
-            fin0 = fin1; fin1 = fin2; fin2 = (iter % G == member) ? pair : -1;
-            // this pair: merge the wavefronts (a handful of values) and post the workgroup's partial
-            float mkt = neg_inf(), mkd = neg_inf();
-#pragma unroll
-            for (int k = 0; k < NW; ++k) {
-                if (s_w[buf][k][0] > 0.0f) mkt = fmaxf(mkt, s_k[buf][k][0]);
-                if (s_w[buf][k][1] > 0.0f) mkd = fmaxf(mkd, s_k[buf][k][1]);
-            }
-            float mSt = 0.0f, mSd = 0.0f;
-#pragma unroll
-            for (int k = 0; k < NW; ++k) {
-                const float a0 = s_w[buf][k][0], a1 = s_w[buf][k][1];
-                mSt += (a0 > 0.0f) ? ldexpf(a0, kdiff(s_k[buf][k][0], mkt)) : (a0 != a0 ? a0 : 0.0f);
-                mSd += (a1 > 0.0f) ? ldexpf(a1, kdiff(s_k[buf][k][1], mkd)) : (a1 != a1 ? a1 : 0.0f);
-            }
-            if (mkt == neg_inf()) mkt = 0.0f;
-            if (mkd == neg_inf()) mkd = 0.0f;
-            if (lane == 0) {
-                unsigned long long* slot = P.ws.part1 + (static_cast<size_t>(pair) * G + member) * 4;
-                post64(slot + 0, static_cast<unsigned long long>(fbits(mkt)) | (static_cast<unsigned long long>(fbits(mkd)) << 32));
-                post64(slot + 1, dbits(static_cast<double>(mSt)));
-                post64(slot + 2, dbits(static_cast<double>(mSd)));
-                post64(slot + 3, dbits(0.0));
-            }
+        asm volatile("" ::: "memory");
+        if (lane < 4) post64(post_at, mine);
+        if constexpr (TWO_PHASE) {
+            if (prev_pair >= 0) phase2(ept, epd, ft, fd, ok2);
+            // the posted value and its address stay in their registers until here: reusing them
+            // earlier would make phase 2 wait for the store, and with it for the prefetch
+            asm volatile("" ::"v"(mine), "v"(post_at));
+            pkt = kt; pkd = kd;
+            pmass_t = (st > 0.0f) || (st != st);
+            pmass_d = (sd > 0.0f) || (sd != sd);
+            pmask = (dmax == __builtin_inff());
         }
-        p2_pair = -1;
-        if (prev_pair >= 0) {
-            phase2(ept, epd, w, buf);
-            p2_pair = prev_pair;
+        // ---- finishing duties: the pair whose turn has come, then note this pair if it is ours
+        if (fin0 >= 0) {
+            if constexpr (TWO_PHASE) finish_two_phase(fin0); else finish_single_pass(fin0);
         }
-        // this pair becomes the previous one
-        pkt = kt; pkd = kd;
-        pmass_t = (st > 0.0f) || (st != st);
-        pmass_d = (sd > 0.0f) || (sd != sd);
-        pmask = (dmax == __builtin_inff());
+        fin0 = fin1; fin1 = fin2; fin2 = -1;
+        if (iter % GW == member) {
+            // two-phase: the divergence words of this pair are posted in the next step and read two
+            // steps after that; single-pass: the phase-1 words are all that is needed, read next step
+            if constexpr (TWO_PHASE) fin2 = pair; else fin0 = pair;
+        }
         prev_pair = pair;
-        buf ^= 1;
         ++iter;
     };
 
     float e0t[NE], e0d[NE], e1t[NE], e1d[NE];
-#pragma unroll
-    for (int i = 0; i < NE; ++i) { e0t[i] = 0.0f; e0d[i] = 0.0f; e1t[i] = 0.0f; e1d[i] = 0.0f; }
     int pair = team;
     if (pair < P.npairs) load_item(pair);
-    for (;;) {
-        if (pair >= P.npairs) break;
-        step(e0t, e0d, e1t, e1d, pair);
-        pair += nteams;
-        if (pair >= P.npairs) break;
-        step(e1t, e1d, e0t, e0d, pair);
-        pair += nteams;
-    }
-    // ---- drain: phase 2 of the last pair, then the postings and finishes still owed
-    if (prev_pair >= 0) {
-        unsigned long long w[4] = {0, 0, 0, 0};
-        if (lane >= G) { w[0] = w[1] = w[2] = w[3] = 1; }
-        if (iter & 1) phase2(e0t, e0d, w, buf); else phase2(e1t, e1d, w, buf);
-    }
-    __syncthreads();
-    if (wave == 0) {
-        if (p2_pair >= 0) post_part2(p2_pair, buf ^ 1);
-        if (prev_pair >= 0) post_part2(prev_pair, buf);
-        if (fin0 >= 0) finish_pair(fin0);
-        if (fin1 >= 0) finish_pair(fin1);
-        if (fin2 >= 0) finish_pair(fin2);
+    if constexpr (TWO_PHASE) {
+#pragma unroll
+        for (int i = 0; i < NE; ++i) { e0t[i] = 0.0f; e0d[i] = 0.0f; e1t[i] = 0.0f; e1d[i] = 0.0f; }
+        for (;;) {
+            if (pair >= P.npairs) break;
+            step(e0t, e0d, e1t, e1d, pair);
+            pair += nteams;
+            if (pair >= P.npairs) break;
+            step(e1t, e1d, e0t, e0d, pair);
+            pair += nteams;
+        }
+        // ---- drain: phase 2 of the last pair, then the finishes still owed
+        if (prev_pair >= 0) {
+            unsigned long long w[4];
+            float ft, fd;
+            request_words(part1 + static_cast<size_t>(prev_pair) * GW * 4, GW, 0, w);
+            const bool ok2 = merge_team(w, ft, fd);
+            if (iter & 1) phase2(e0t, e0d, ft, fd, ok2); else phase2(e1t, e1d, ft, fd, ok2);
+        }
+        if (fin0 >= 0) finish_two_phase(fin0);
+        if (fin1 >= 0) finish_two_phase(fin1);
+        if (fin2 >= 0) finish_two_phase(fin2);
+    } else {
+        for (; pair < P.npairs; pair += nteams) step(e0t, e0d, e1t, e1d, pair);
+        if (fin0 >= 0) finish_single_pass(fin0);
     }
 }
 
@@ -1319,7 +1026,7 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
 // host side: planning, workspace, launches
 
 struct Plan {
-    int VE, NW, NV, G, spm, GS, sps;
+    int VE, NV, G, spm, GS, sps;   // G = wavefronts per pair
     long nslots;
     size_t off_counters, n_counters, off_part1, off_part2, zero_bytes, off_div, off_pst, off_lse2, off_lr, off_spart,
         bytes;
@@ -1327,14 +1034,14 @@ struct Plan {
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-int g_shape_nw = 0, g_shape_nv = 0;   // 0 = chosen by make_plan (see fsd_debug_set_shape)
+constexpr int kMaxTeam = 256;     // wavefronts per pair (merged in rounds of 64)
+int g_shape_nv = 0;               // 0 = chosen by make_plan (see fsd_debug_set_shape)
 
-// team size for a workgroup of nw wavefronts holding nv slots of each row per thread
-long team_size(long nslots, int nw, int nv) {
-    const long per_wg = static_cast<long>(nw) * 64 * nv;
-    long G = (nslots + per_wg - 1) / per_wg;
-    if (G > 8) G = (G + 7) / 8 * 8;      // whole multiples of the 8 XCDs
-    return G;
+// wavefronts per pair when every lane holds nv slots of each row: whole workgroups
+long team_size(long nslots, int nv) {
+    const long per_wave = 64L * nv;
+    const long G = (nslots + per_wave - 1) / per_wave;
+    return (G + 3) / 4 * 4;
 }
 
 bool make_plan(int B, int rows, long V, int dtype, Plan& p) {
@@ -1344,25 +1051,10 @@ bool make_plan(int B, int rows, long V, int dtype, Plan& p) {
     if (V > fsd_max_vocab(dtype)) return false;
     p.VE = (dtype == FSD_BF16) ? 8 : 4;
     p.nslots = (V + p.VE - 1) / p.VE;
-    // (wavefronts per workgroup, slots of each row per thread); bfloat16 holds 8 entries per slot and
-    // the two-phase kernel keeps two sets of exponentials, so it stops at 4 slots
-    static const int shapes_f32[4][2] = {{4, 4}, {4, 8}, {8, 4}, {8, 8}};
-    static const int shapes_bf16[2][2] = {{4, 4}, {8, 4}};
-    const int (*shapes)[2] = (dtype == FSD_BF16) ? shapes_bf16 : shapes_f32;
-    const int nshapes = (dtype == FSD_BF16) ? 2 : 4;
-    long G = 0;
-    const bool override_ok = g_shape_nw && g_shape_nv && !(dtype == FSD_BF16 && g_shape_nv > 4) &&
-                             team_size(p.nslots, g_shape_nw, g_shape_nv) <= kMaxTeam;
-    if (override_ok) {
-        p.NW = g_shape_nw; p.NV = g_shape_nv;
-        G = team_size(p.nslots, p.NW, p.NV);
-    } else {
-        for (int i = 0; i < nshapes; ++i) {
-            p.NW = shapes[i][0]; p.NV = shapes[i][1];
-            G = team_size(p.nslots, p.NW, p.NV);
-            if (G <= kMaxTeam) break;
-        }
-    }
+    // 32 vocabulary entries of each row per lane: 4 slots of bfloat16, 8 of binary32
+    p.NV = (dtype == FSD_BF16) ? 4 : 8;
+    if (g_shape_nv && !(dtype == FSD_BF16 && g_shape_nv > 4) && team_size(p.nslots, g_shape_nv) <= kMaxTeam) p.NV = g_shape_nv;
+    const long G = team_size(p.nslots, p.NV);
     if (G > kMaxTeam) return false;
     p.G = static_cast<int>(G);
     p.spm = static_cast<int>((p.nslots + G - 1) / G);
@@ -1373,14 +1065,11 @@ bool make_plan(int B, int rows, long V, int dtype, Plan& p) {
     if (GS < 1) GS = 1;
     p.GS = static_cast<int>(GS);
     p.sps = static_cast<int>((p.nslots + GS - 1) / GS);
-    // the workspace is sized for the largest team any shape can ask for, so that the size does
-    // not depend on the shape in use
     const size_t R = static_cast<size_t>(B) * rows;
-    const size_t Gmax = kMaxTeam;
     size_t o = 0;
     p.off_counters = o; p.n_counters = 64 + B; o = align_up(o + p.n_counters * 4, 256);
-    p.off_part1 = o; o = align_up(o + R * Gmax * 32, 256);
-    p.off_part2 = o; o = align_up(o + R * Gmax * 32, 256);
+    p.off_part1 = o; o = align_up(o + R * p.G * 32, 256);
+    p.off_part2 = o; o = align_up(o + R * p.G * 32, 256);
     p.zero_bytes = o;
     p.off_div = o; o = align_up(o + R * 4, 256);
     p.off_pst = o; o = align_up(o + R * 4, 256);
@@ -1419,14 +1108,15 @@ int g_prof_n = 0;
 hipEvent_t g_prof_ev[2 * kMaxProf];
 bool g_prof_made = false;
 
-// How many workgroups of one pair_reduce instantiation are resident at once on the current
-// device, and how much unused dynamic LDS to ask for so that the hardware cannot place more than
-// that number on any one CU.  Without the padding a grid that does not fill every slot may be
-// spread unevenly (some CUs full, others half empty), and the team members that share a pair then
-// all run at the pace of the most crowded CU.
+// How many workgroups of a kernel are resident at once on the current device, and how much unused
+// dynamic LDS to ask for so that the hardware cannot place more than that number on any one CU.
+// Without the padding a grid that does not fill every slot may be spread unevenly (some CUs full,
+// others half empty), and the team members that share a pair then all run at the pace of the most
+// crowded CU.  The padding leaves 8 KB of slack so that it can only lower the count it is checked
+// against, never the number of workgroups that really fit.
 struct Residency { int total; unsigned pad_lds; };
 
-int g_last_grid = 0, g_last_per_cu = 0;
+int g_last_grid = 0, g_last_total = 0;
 
 template <typename Kernel>
 Residency residency_of(Kernel kernel, int threads, Residency (&cache)[16]) {
@@ -1443,7 +1133,6 @@ Residency residency_of(Kernel kernel, int threads, Residency (&cache)[16]) {
         unsigned pad = 0;
         hipFuncAttributes attr;
         if (lds_cu > 16384 && hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(kernel)) == hipSuccess) {
-            // leave 8 KB of slack: per_cu workgroups must still fit, one more must not
             const long stat = static_cast<long>(attr.sharedSizeBytes);
             const long want = ((static_cast<long>(lds_cu) - 8192) / per_cu - stat) / 1024 * 1024;
             if (want > 0 && (stat + want) * (per_cu + 1) > lds_cu) {
@@ -1458,54 +1147,41 @@ Residency residency_of(Kernel kernel, int threads, Residency (&cache)[16]) {
             }
         }
         (void)hipGetLastError();
-        g_last_per_cu = per_cu;
         cache[dev] = Residency{per_cu * cus, pad};
     }
-    g_last_per_cu = cache[dev].total;
+    g_last_total = cache[dev].total;
     return cache[dev];
 }
 
-template <bool BF16, int NV, int MODE, bool ALIGNED, int NW>
+template <bool BF16, int NV, int MODE, bool ALIGNED>
 void launch_pair_k(hipStream_t st, const PairParams& P) {
     // persistent grid: whole teams only, never more than fits on the device at once
-    constexpr bool TWO_PHASE = (MODE == MODE_JS || MODE == MODE_TV || MODE == MODE_KLP);
     static Residency cache[16] = {};
-    Residency res;
-    if constexpr (TWO_PHASE) res = residency_of(pair_divergence<BF16, NV, MODE, ALIGNED, NW>, NW * 64, cache);
-    else res = residency_of(pair_reduce<BF16, NV, MODE, ALIGNED, NW>, NW * 64, cache);
-    const long want = static_cast<long>(P.npairs) * P.G;
-    long cap = res.total / P.G * static_cast<long>(P.G);
-    if (cap < P.G) cap = P.G;
+    const Residency res = residency_of(pair_kernel<BF16, NV, MODE, ALIGNED>, kWG, cache);
+    const long wgs_per_team = P.G / (kWG / 64);
+    const long want = static_cast<long>(P.npairs) * wgs_per_team;
+    long cap = res.total / wgs_per_team * wgs_per_team;
+    if (cap < wgs_per_team) cap = wgs_per_team;
     const long grid = want < cap ? want : cap;
     g_last_grid = static_cast<int>(grid);
-    if constexpr (TWO_PHASE)
-        hipLaunchKernelGGL((pair_divergence<BF16, NV, MODE, ALIGNED, NW>), dim3(static_cast<unsigned>(grid)), dim3(NW * 64),
-                           res.pad_lds, st, P);
-    else
-        hipLaunchKernelGGL((pair_reduce<BF16, NV, MODE, ALIGNED, NW>), dim3(static_cast<unsigned>(grid)), dim3(NW * 64),
-                           res.pad_lds, st, P);
-}
-template <bool BF16, int NV, int MODE, bool ALIGNED>
-void launch_pair_w(int nw, hipStream_t st, const PairParams& P) {
-    if (nw == 8) launch_pair_k<BF16, NV, MODE, ALIGNED, 8>(st, P);
-    else launch_pair_k<BF16, NV, MODE, ALIGNED, 4>(st, P);
+    hipLaunchKernelGGL((pair_kernel<BF16, NV, MODE, ALIGNED>), dim3(static_cast<unsigned>(grid)), dim3(kWG), res.pad_lds, st, P);
 }
 template <bool BF16, int NV, int MODE>
-void launch_pair_a(bool aligned, int nw, hipStream_t st, const PairParams& P) {
-    if (aligned) launch_pair_w<BF16, NV, MODE, true>(nw, st, P);
-    else launch_pair_w<BF16, NV, MODE, false>(nw, st, P);
+void launch_pair_a(bool aligned, hipStream_t st, const PairParams& P) {
+    if (aligned) launch_pair_k<BF16, NV, MODE, true>(st, P);
+    else launch_pair_k<BF16, NV, MODE, false>(st, P);
 }
 template <bool BF16, int NV>
-void launch_pair_m(int mode, bool aligned, int nw, hipStream_t st, const PairParams& P) {
+void launch_pair_m(int mode, bool aligned, hipStream_t st, const PairParams& P) {
     switch (mode) {
-        case MODE_KL: launch_pair_a<BF16, NV, MODE_KL>(aligned, nw, st, P); break;
-        case MODE_JS: launch_pair_a<BF16, NV, MODE_JS>(aligned, nw, st, P); break;
-        case MODE_TV: launch_pair_a<BF16, NV, MODE_TV>(aligned, nw, st, P); break;
-        case MODE_KLP: launch_pair_a<BF16, NV, MODE_KLP>(aligned, nw, st, P); break;
-        default: launch_pair_a<BF16, NV, MODE_LSE>(aligned, nw, st, P); break;
+        case MODE_KL: launch_pair_a<BF16, NV, MODE_KL>(aligned, st, P); break;
+        case MODE_JS: launch_pair_a<BF16, NV, MODE_JS>(aligned, st, P); break;
+        case MODE_TV: launch_pair_a<BF16, NV, MODE_TV>(aligned, st, P); break;
+        case MODE_KLP: launch_pair_a<BF16, NV, MODE_KLP>(aligned, st, P); break;
+        default: launch_pair_a<BF16, NV, MODE_LSE>(aligned, st, P); break;
     }
 }
-void launch_pair(int dtype, int nw, int NV, int mode, bool aligned, hipStream_t st, const PairParams& P) {
+void launch_pair(int dtype, int NV, int mode, bool aligned, hipStream_t st, const PairParams& P) {
     const bool prof = g_prof_on && g_prof_n < kMaxProf;
     if (prof) {
         if (!g_prof_made) {
@@ -1515,12 +1191,12 @@ void launch_pair(int dtype, int nw, int NV, int mode, bool aligned, hipStream_t 
         (void)hipEventRecord(g_prof_ev[2 * g_prof_n], st);
     }
     if (dtype == FSD_BF16) {
-        if (NV == 2) launch_pair_m<true, 2>(mode, aligned, nw, st, P);
-        else launch_pair_m<true, 4>(mode, aligned, nw, st, P);
+        if (NV == 2) launch_pair_m<true, 2>(mode, aligned, st, P);
+        else launch_pair_m<true, 4>(mode, aligned, st, P);
     } else {
-        if (NV == 2) launch_pair_m<false, 2>(mode, aligned, nw, st, P);
-        else if (NV == 4) launch_pair_m<false, 4>(mode, aligned, nw, st, P);
-        else launch_pair_m<false, 8>(mode, aligned, nw, st, P);
+        if (NV == 2) launch_pair_m<false, 2>(mode, aligned, st, P);
+        else if (NV == 4) launch_pair_m<false, 4>(mode, aligned, st, P);
+        else launch_pair_m<false, 8>(mode, aligned, st, P);
     }
     if (prof) {
         (void)hipEventRecord(g_prof_ev[2 * g_prof_n + 1], st);
@@ -1596,7 +1272,7 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
     pp.ws = ws;
     int k1mode = (kind == KIND_SD) ? MODE_LSE : div;
     if (k1mode == MODE_KL && dtype == FSD_F32) k1mode = MODE_KLP;
-    launch_pair(dtype, p.NW, p.NV, k1mode, aligned, st, pp);
+    launch_pair(dtype, p.NV, k1mode, aligned, st, pp);
 
     SampleParams sp;
     sp.target = static_cast<const char*>(target);
@@ -1634,8 +1310,8 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
 extern "C" {
 
 int64_t fsd_max_vocab(int dtype) {
-    if (dtype == FSD_BF16) return static_cast<int64_t>(kMaxTeam) * 512 * 4 * 8;
-    if (dtype == FSD_F32) return static_cast<int64_t>(kMaxTeam) * 512 * 8 * 4;
+    // 256 wavefronts per pair, 64 lanes, 32 entries of each row per lane
+    if (dtype == FSD_BF16 || dtype == FSD_F32) return static_cast<int64_t>(kMaxTeam) * 64 * 32;
     return 0;
 }
 
@@ -1710,21 +1386,16 @@ int fsd_profile_collect(float* mean_ms, float* min_ms) {
 }
 
 int fsd_debug_set_shape(int wavefronts, int slots_per_thread) {
-    const bool ok = (wavefronts == 0 && slots_per_thread == 0) ||
-                    ((wavefronts == 4 || wavefronts == 8) && (slots_per_thread == 2 || slots_per_thread == 4 || slots_per_thread == 8));
+    const bool ok = (wavefronts == 0 || wavefronts == 4) &&
+                    (slots_per_thread == 0 || slots_per_thread == 2 || slots_per_thread == 4 || slots_per_thread == 8);
     if (!ok) return FSD_ERR_SHAPE;
-    g_shape_nw = wavefronts;
     g_shape_nv = slots_per_thread;
     return FSD_OK;
 }
 
-#ifdef FSD_PHASE_TIMING
-void fsd_debug_set_dbg(void* p) { g_dbg = static_cast<unsigned long long*>(p); }
-#endif
-
 void fsd_debug_last_launch(int* grid, int* per_cu) {
     if (grid) *grid = g_last_grid;
-    if (per_cu) *per_cu = g_last_per_cu;
+    if (per_cu) *per_cu = g_last_total;
 }
 
 unsigned fsd_debug_set_spin_limit(unsigned polls) {
