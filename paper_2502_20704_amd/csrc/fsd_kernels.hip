@@ -68,6 +68,7 @@ __device__ __forceinline__ double dpp_d(double v) {
     return __hiloint2double(hi, lo);
 }
 constexpr int kDppSwap1 = 0xB1, kDppSwap2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140;
+constexpr int kDppBcast15 = 0x142, kDppBcast31 = 0x143;   // last lane of a row to the next row(s)
 
 __device__ __forceinline__ float lane_f(float v, int l) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
@@ -76,27 +77,62 @@ __device__ __forceinline__ double lane_d(double v, int l) {
     return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), l),
                             __builtin_amdgcn_readlane(__double2loint(v), l));
 }
-
-__device__ __forceinline__ float wave_max(float v) {
-    v = fmaxf(v, dpp_f<kDppSwap1>(v));
-    v = fmaxf(v, dpp_f<kDppSwap2>(v));
-    v = fmaxf(v, dpp_f<kDppHalfMirror>(v));
-    v = fmaxf(v, dpp_f<kDppMirror>(v));
-    return fmaxf(fmaxf(lane_f(v, 0), lane_f(v, 16)), fmaxf(lane_f(v, 32), lane_f(v, 48)));
+// the other rows' partial, or the neutral element 0 in rows the broadcast does not reach
+template <int CTRL, int ROWS>
+__device__ __forceinline__ double bcast_d(double v) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, ROWS, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, ROWS, 0xF, false);
+    return __hiloint2double(hi, lo);
 }
+
+// Maximum over the wavefront, NaN ignored.  The compiler's own lowering of fmaxf() around a DPP
+// move costs four instructions a step (it has to quieten a possible signalling NaN); the max
+// instruction with a DPP operand does the same in one.  Each step waits two states for the
+// previous write of its operand, as DPP reads require.
+__device__ __forceinline__ float wave_max(float v) {
+    asm("s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_max_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+        "s_nop 1"
+        : "+v"(v));
+    return lane_f(v, 63);
+}
+// Sums over the wavefront in a fixed order: within rows of 16 lanes, then row 0 into row 1 and
+// row 2 into row 3, then rows 0-1 into rows 2-3; lane 63 holds the total.
 __device__ __forceinline__ float wave_sumf(float v) {
-    v += dpp_f<kDppSwap1>(v);
-    v += dpp_f<kDppSwap2>(v);
-    v += dpp_f<kDppHalfMirror>(v);
-    v += dpp_f<kDppMirror>(v);
-    return (lane_f(v, 0) + lane_f(v, 16)) + (lane_f(v, 32) + lane_f(v, 48));
+    asm("s_nop 1\n\t"
+        "v_add_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_add_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_add_f32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_add_f32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_add_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_add_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+        "s_nop 1"
+        : "+v"(v));
+    return lane_f(v, 63);
 }
 __device__ __forceinline__ double wave_sum(double v) {
     v += dpp_d<kDppSwap1>(v);
     v += dpp_d<kDppSwap2>(v);
     v += dpp_d<kDppHalfMirror>(v);
     v += dpp_d<kDppMirror>(v);
-    return (lane_d(v, 0) + lane_d(v, 16)) + (lane_d(v, 32) + lane_d(v, 48));
+    v += bcast_d<kDppBcast15, 0xA>(v);
+    v += bcast_d<kDppBcast31, 0xC>(v);
+    return lane_d(v, 63);
 }
 
 // One 16-byte slot of a logits row: 8 bfloat16 or 4 binary32 values.
@@ -234,7 +270,7 @@ struct PairParams {
     int G;
     unsigned spin_limit;
 #ifdef FSD_PHASE_TIMING
-    unsigned long long* dbg;   // [grid][2 wavefronts][10]
+    unsigned long long* dbg;   // [grid][4 wavefronts][10]
 #endif
     float* user_div;        // optional [R]
     Ws ws;
@@ -385,6 +421,12 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
     const long s1 = (s0 + P.spm < P.nslots) ? s0 + P.spm : P.nslots;
     unsigned long long* const part1 = P.ws.part1;
     unsigned long long* const part2 = reinterpret_cast<unsigned long long*>(P.ws.part2);
+#ifdef FSD_PHASE_TIMING
+    unsigned long long pt_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const unsigned long long pt_wall = wall_clock64();
+    const unsigned long long pt_first = __builtin_readcyclecounter();
+    unsigned long long pt_last = pt_first;
+#endif
 
     auto row_ptrs = [&](int pair, const char*& tptr, const char*& dptr) __attribute__((always_inline)) {
         const int b = pair / P.rows;
@@ -645,6 +687,7 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
 #pragma unroll
             for (int e = 0; e < VE; e += 2) { mt = fmaxf(fmaxf(mt, a[e]), a[e + 1]); md = fmaxf(fmaxf(md, c[e]), c[e + 1]); }
         }
+        PT(0);   // load wait + max pass
         // the logits have arrived: request the previous pair's team words behind the arithmetic
         unsigned long long w[4] = {1, 1, 1, 1};
         if constexpr (TWO_PHASE) {
@@ -676,6 +719,7 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
                 }
             }
         }
+        PT(1);   // reductions + exp pass
         // ---- the previous pair's normalisers (its words were requested above)
         float ft = 0.0f, fd = 0.0f;
         bool ok2 = true;
@@ -683,6 +727,7 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
             if (prev_pair >= 0) ok2 = merge_team(w, ft, fd);
             asm volatile("" ::: "memory");
         }
+        PT(2);   // team merge (wait for the team's words)
         // post this wavefront's partial (stores go out before the prefetch, so that nothing that has to
         // wait for them later also waits for the prefetch).  The two-phase modes need the normalisers
         // to a relative 1e-7 only (common factors of p and q); the single-pass modes take them through
@@ -709,8 +754,10 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
         if (pair + nteams < P.npairs) load_item(pair + nteams);
         asm volatile("" ::: "memory");
         if (lane < 4) post64(post_at, mine);
+        PT(3);   // wave sums, prefetch issue, post
         if constexpr (TWO_PHASE) {
             if (prev_pair >= 0) phase2(ept, epd, ft, fd, ok2);
+            PT(4);   // phase 2
             // the posted value and its address stay in their registers until here: reusing them
             // earlier would make phase 2 wait for the store, and with it for the prefetch
             asm volatile("" ::"v"(mine), "v"(post_at));
@@ -723,6 +770,7 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
         if (fin0 >= 0) {
             if constexpr (TWO_PHASE) finish_two_phase(fin0); else finish_single_pass(fin0);
         }
+        PT(5);   // finishing duty
         fin0 = fin1; fin1 = fin2; fin2 = -1;
         if (iter % GW == member) {
             // two-phase: the divergence words of this pair are posted in the next step and read two
@@ -762,6 +810,15 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
         for (; pair < P.npairs; pair += nteams) step(e0t, e0d, e1t, e1d, pair);
         if (fin0 >= 0) finish_single_pass(fin0);
     }
+#ifdef FSD_PHASE_TIMING
+    PT(6);   // drain
+    if (P.dbg && lane == 0) {
+        unsigned long long* o = P.dbg + (static_cast<size_t>(blockIdx.x) * kWavesPerWG + wave) * 10;
+        for (int i = 0; i < 8; ++i) o[i] = pt_acc[i];
+        o[8] = pt_wall;
+        o[9] = pt_last - pt_first;
+    }
+#endif
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1403,5 +1460,9 @@ unsigned fsd_debug_set_spin_limit(unsigned polls) {
     g_spin_limit = polls;
     return prev;
 }
+
+#ifdef FSD_PHASE_TIMING
+void fsd_debug_set_dbg(void* p) { g_dbg = static_cast<unsigned long long*>(p); }
+#endif
 
 }  // extern "C"
