@@ -337,51 +337,69 @@ __device__ __forceinline__ unsigned fbits(float x) {              // never 0
 // to another is an exact scaling by a power of two.
 __device__ __forceinline__ int kdiff(float k, float M) { return static_cast<int>(k - M); }
 
-// Lane l reads member (base + l)'s four phase-1 words.  Lanes beyond the team re-read the last
-// member's words (no branch around the loads, see load_item); nothing looks at the values here, so
-// the loads stay in flight until await_words.
-__device__ __forceinline__ void request_words(const unsigned long long* p1, int GW, int base, unsigned long long (&w)[4]) {
-    const int m = base + (threadIdx.x & 63);
-    const int mm = (m < GW) ? m : GW - 1;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) w[k] = read64(p1 + mm * 4 + k);
+// two binary32 values in one exchange word (never 0: +0.0 in the low half is posted as -0.0)
+__device__ __forceinline__ unsigned long long pack2(float lo, float hi) {
+    return static_cast<unsigned long long>(fbits(lo)) | (static_cast<unsigned long long>(__float_as_uint(hi)) << 32);
 }
-// The words of the first 64 members are normally there when they are looked at.  Everything that
-// loops over memory (asking again, further rounds of 64 members) lives in functions that are NOT
-// inlined: the compiler's bookkeeping of outstanding memory operations stays exact in the caller,
-// whose phase 2 then never waits for the prefetch it has just issued.
-struct Words { unsigned long long w[4]; bool ok; };
+__device__ __forceinline__ float lo_f(unsigned long long w) { return __uint_as_float(static_cast<unsigned>(w)); }
+__device__ __forceinline__ float hi_f(unsigned long long w) { return __uint_as_float(static_cast<unsigned>(w >> 32)); }
 
-__device__ __noinline__ Words repoll_words(const unsigned long long* p1, int GW, int base, unsigned limit) {
-    Words r;
+// A pair owns 4 GW words of an exchange array: word k of member m sits at [k GW + m], so that the
+// 64 lanes of a request touch consecutive words.  Lane l reads the first N words of member
+// (base + l); lanes beyond the team re-read the last member's (no branch around the loads, see
+// load_item).  Nothing looks at the values here, so the loads stay in flight until they are
+// awaited.  With spread == false every lane reads member 0 (a request whose result is not needed
+// costs one cache line).
+template <int N>
+__device__ __forceinline__ void request_n(const unsigned long long* p, int GW, int base, unsigned long long (&w)[N],
+                                          bool spread = true) {
+    const int m = base + static_cast<int>(threadIdx.x & 63);
+    const int mm = spread ? ((m < GW) ? m : GW - 1) : 0;
+#pragma unroll
+    for (int k = 0; k < N; ++k) w[k] = read64(p + k * GW + mm);
+}
+// The words are normally there when they are looked at.  Everything that loops over memory (asking
+// again, further rounds of 64 members) lives in functions that are NOT inlined: the compiler's
+// bookkeeping of outstanding memory operations stays exact in the caller, which then never waits
+// for the logits it has just requested for the next pair.
+template <int N> struct WordsN { unsigned long long w[N]; bool ok; };
+
+template <int N>
+__device__ __noinline__ WordsN<N> repoll_n(const unsigned long long* p, int GW, int base, unsigned limit) {
+    WordsN<N> r;
     r.ok = true;
     unsigned polls = 0;
     for (;;) {
-        request_words(p1, GW, base, r.w);
-        const bool missing = (r.w[0] == 0) | (r.w[1] == 0) | (r.w[2] == 0) | (r.w[3] == 0);   // duplicates included: harmless
+        request_n<N>(p, GW, base, r.w);
+        bool missing = false;   // duplicates included: harmless
+#pragma unroll
+        for (int k = 0; k < N; ++k) missing |= (r.w[k] == 0);
         if (!__any(missing)) break;
         if (polls++ >= limit) { r.ok = false; break; }
         __builtin_amdgcn_s_sleep(1);
     }
     return r;
 }
-__device__ __forceinline__ bool await_words(const unsigned long long* p1, int GW, int base, unsigned limit,
-                                            unsigned long long (&w)[4]) {
-    const bool missing = (w[0] == 0) | (w[1] == 0) | (w[2] == 0) | (w[3] == 0);
-    if (!__any(missing)) return true;
-    const Words r = repoll_words(p1, GW, base, limit);
+template <int N>
+__device__ __forceinline__ bool await_n(const unsigned long long* p, int GW, int base, unsigned limit,
+                                        unsigned long long (&w)[N]) {
+    bool missing = false;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) w[k] = r.w[k];
+    for (int k = 0; k < N; ++k) missing |= (w[k] == 0);
+    if (!__any(missing)) return true;
+    const WordsN<N> r = repoll_n<N>(p, GW, base, limit);
+#pragma unroll
+    for (int k = 0; k < N; ++k) w[k] = r.w[k];
     return r.ok;
 }
 
-// binary32 merge of one round of team words into running (K, z) pairs: reference exponents and
-// sums of both rows.  Exact power-of-two rescaling between references.
+// binary32 merge of one round of team words (two-phase format: word 0 = the two reference
+// exponents, word 1 = the two sums) into running (K, z) pairs.  Exact power-of-two rescaling.
 struct TeamNorm { float Kt, Kd, zt, zd; bool ok; };
 
-__device__ __forceinline__ void merge_round(const unsigned long long (&w)[4], bool in, TeamNorm& n) {
-    const float tk_t = __uint_as_float(static_cast<unsigned>(w[0])), tk_d = __uint_as_float(static_cast<unsigned>(w[0] >> 32));
-    const float tSt = in ? static_cast<float>(bitsd(w[1])) : 0.0f, tSd = in ? static_cast<float>(bitsd(w[2])) : 0.0f;
+__device__ __forceinline__ void merge_round(const unsigned long long (&w)[2], bool in, TeamNorm& n) {
+    const float tk_t = lo_f(w[0]), tk_d = hi_f(w[0]);
+    const float tSt = in ? lo_f(w[1]) : 0.0f, tSd = in ? hi_f(w[1]) : 0.0f;
     const float nKt = fmaxf(n.Kt, wave_max((tSt > 0.0f) ? tk_t : neg_inf()));
     const float nKd = fmaxf(n.Kd, wave_max((tSd > 0.0f) ? tk_d : neg_inf()));
     n.zt = ((n.zt > 0.0f) ? ldexpf(n.zt, kdiff(n.Kt, nKt)) : n.zt) +
@@ -394,11 +412,29 @@ __device__ __forceinline__ void merge_round(const unsigned long long (&w)[4], bo
 // teams of more than 64 wavefronts: the members beyond the first round
 __device__ __noinline__ TeamNorm merge_more_rounds(const unsigned long long* p1, int GW, unsigned limit, TeamNorm n) {
     for (int base = 64; base < GW; base += 64) {
-        const Words r = repoll_words(p1, GW, base, limit);
+        const WordsN<2> r = repoll_n<2>(p1, GW, base, limit);
         if (!r.ok) n.ok = false;
         merge_round(r.w, base + static_cast<int>(threadIdx.x & 63) < GW, n);
     }
     return n;
+}
+// the divergence words of the members beyond the first round, added in member order (each word
+// holds two binary32 partial sums)
+template <int N> struct Sums { double lo[N], hi[N]; bool ok; };
+
+template <int N>
+__device__ __noinline__ Sums<N> sum_more_rounds(const unsigned long long* p2, int GW, unsigned limit, Sums<N> s) {
+    for (int base = 64; base < GW; base += 64) {
+        const WordsN<N> r = repoll_n<N>(p2, GW, base, limit);
+        if (!r.ok) s.ok = false;
+        const bool in = base + static_cast<int>(threadIdx.x & 63) < GW;
+#pragma unroll
+        for (int k = 0; k < N; ++k) {
+            s.lo[k] += wave_sum(in ? static_cast<double>(lo_f(r.w[k])) : 0.0);
+            s.hi[k] += wave_sum(in ? static_cast<double>(hi_f(r.w[k])) : 0.0);
+        }
+    }
+    return s;
 }
 
 template <bool BF16, int NV, int MODE, bool ALIGNED>
@@ -407,7 +443,8 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
     constexpr int ES = BF16 ? 2 : 4;
     constexpr bool TWO_PHASE = (MODE == MODE_JS || MODE == MODE_TV || MODE == MODE_KLP);
     constexpr int NE = TWO_PHASE ? NV * VE : 1;   // exponentials kept per row and lane
-    constexpr int PW = (MODE == MODE_TV) ? 4 : 1;   // divergence words a member posts
+    constexpr int PW = (MODE == MODE_TV) ? 2 : 1;   // divergence words a member posts (two sums each)
+    constexpr int FW = TWO_PHASE ? PW : 4;          // words per member the finisher reads
     constexpr float kTiny = 2e-38f;   // keeps p + q > 0 without changing any result
     constexpr int kWavesPerWG = kWG / 64;
 
@@ -421,6 +458,8 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
     const long s1 = (s0 + P.spm < P.nslots) ? s0 + P.spm : P.nslots;
     unsigned long long* const part1 = P.ws.part1;
     unsigned long long* const part2 = reinterpret_cast<unsigned long long*>(P.ws.part2);
+    // the words the finisher of a pair reads: divergence sums (two-phase) or phase-1 words
+    unsigned long long* const finw = TWO_PHASE ? part2 : part1;
 #ifdef FSD_PHASE_TIMING
     unsigned long long pt_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     const unsigned long long pt_wall = wall_clock64();
@@ -455,13 +494,14 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
         slot_of[k] = own[k] ? s : ((s1 > s0) ? s1 - 1 : 0);
     }
     const bool fill_needed = __any(!all_own) != 0;   // wavefront-uniform
-    auto load_item = [&](int pair) __attribute__((always_inline)) {
+    auto load_item = [&](int pair, bool wanted = true) __attribute__((always_inline)) {
         const char *tptr, *dptr;
         row_ptrs(pair, tptr, dptr);
 #pragma unroll
         for (int k = 0; k < NV; ++k) {
-            ra[k] = load_slot<BF16, ALIGNED>(tptr, slot_of[k], P.V);
-            rb[k] = load_slot<BF16, ALIGNED>(dptr, slot_of[k], P.V);
+            const long sl = wanted ? slot_of[k] : 0;   // not wanted: one cached slot for all lanes
+            ra[k] = load_slot<BF16, ALIGNED>(tptr, sl, P.V);
+            rb[k] = load_slot<BF16, ALIGNED>(dptr, sl, P.V);
         }
     };
     auto fill_unowned = [&]() __attribute__((always_inline)) {
@@ -473,40 +513,34 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
         }
     };
 
-    // ---- finishing a pair: add what the team posted for it, in member order
-    auto finish_two_phase = [&](int pair) __attribute__((always_inline)) {
+    // ---- finishing a pair: add what the team posted for it, in member order.  fw holds the words of
+    // the first 64 members, requested earlier.
+    auto finish_two_phase = [&](int pair, unsigned long long (&fw)[FW]) __attribute__((always_inline)) {
         const unsigned long long* p2 = part2 + static_cast<size_t>(pair) * GW * 4;
-        double sum[PW];
+        unsigned long long f[PW];
 #pragma unroll
-        for (int k = 0; k < PW; ++k) sum[k] = 0.0;
-        bool ok = true;
-        for (int base = 0; base < GW; base += 64) {
-            const int m = base + lane;
-            unsigned long long w[PW];
-            unsigned polls = 0;
-            for (;;) {
-                bool missing = false;
+        for (int k = 0; k < PW; ++k) f[k] = fw[k % FW];
+        Sums<PW> s;
+        s.ok = await_n<PW>(p2, GW, 0, P.spin_limit, f);
 #pragma unroll
-                for (int k = 0; k < PW; ++k) { w[k] = (m < GW) ? read64(p2 + m * 4 + k) : 1ull; missing |= (w[k] == 0); }
-                if (!__any(missing)) break;
-                if (polls++ >= P.spin_limit) { ok = false; break; }
-                __builtin_amdgcn_s_sleep(1);
-            }
-#pragma unroll
-            for (int k = 0; k < PW; ++k) sum[k] += wave_sum((m < GW) ? bitsd(w[k]) : 0.0);
+        for (int k = 0; k < PW; ++k) {
+            s.lo[k] = wave_sum((lane < GW) ? static_cast<double>(lo_f(f[k])) : 0.0);
+            s.hi[k] = wave_sum((lane < GW) ? static_cast<double>(hi_f(f[k])) : 0.0);
         }
+        if (GW > 64) s = sum_more_rounds<PW>(p2, GW, P.spin_limit, s);
         double value;
         if constexpr (MODE == MODE_TV) {
             // the sums of (p - q)+ and of (q - p)+ are the same number; the side that avoids the
             // heavy entries (smaller sum of p + q over its entries) carries the smaller rounding
             // error, which matters for nearly one-hot rows
-            value = (sum[2] != sum[2] || sum[3] != sum[3]) ? __builtin_nan("") : (sum[2] <= sum[3] ? sum[0] : sum[1]);
+            const double A = s.lo[0], Bn = s.hi[0], MA = s.lo[1], MB = s.hi[1];
+            value = (MA != MA || MB != MB) ? __builtin_nan("") : (MA <= MB ? A : Bn);
         } else {
-            value = 0.5 * kLn2 * sum[0];
+            value = 0.5 * kLn2 * s.lo[0];
         }
         int status = 0;
         if (value != value) status |= FSD_ROW_NONFINITE;   // NaN / +inf logits, or a row without mass
-        if (!ok) status |= FSD_ROW_INTERNAL;
+        if (!s.ok) status |= FSD_ROW_INTERNAL;
         if (value < 0.0) value = 0.0;
         if (status) value = __builtin_nan("");
         if (lane == 0) {
@@ -517,7 +551,7 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
             P.ws.pst[pair] = status;
         }
     };
-    auto finish_single_pass = [&](int pair) __attribute__((always_inline)) {
+    auto finish_single_pass = [&](int pair, unsigned long long (&fw)[FW]) __attribute__((always_inline)) {
         const unsigned long long* p1 = part1 + static_cast<size_t>(pair) * GW * 4;
         // online merge over rounds of 64 members, float64, exact rescaling between references
         float Kt = neg_inf(), Kd = neg_inf();
@@ -525,10 +559,18 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
         bool ok = true, winf = false;
         for (int base = 0; base < GW; base += 64) {
             unsigned long long w[4];
-            request_words(p1, GW, base, w);
-            ok &= await_words(p1, GW, base, P.spin_limit, w);
+            if (base == 0) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) w[k] = fw[k % FW];
+                ok &= await_n<4>(p1, GW, 0, P.spin_limit, w);
+            } else {
+                const WordsN<4> r = repoll_n<4>(p1, GW, base, P.spin_limit);
+                ok &= r.ok;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) w[k] = r.w[k];
+            }
             const bool in = base + lane < GW;
-            const float kt = __uint_as_float(static_cast<unsigned>(w[0])), kd = __uint_as_float(static_cast<unsigned>(w[0] >> 32));
+            const float kt = lo_f(w[0]), kd = hi_f(w[0]);
             const double St = in ? bitsd(w[1]) : 0.0, Sd = in ? bitsd(w[2]) : 0.0, W = in ? bitsd(w[3]) : 0.0;
             const float nKt = fmaxf(Kt, wave_max((St > 0.0) ? kt : neg_inf()));
             const float nKd = fmaxf(Kd, wave_max((Sd > 0.0) ? kd : neg_inf()));
@@ -581,6 +623,9 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
             P.ws.pst[pair] = status;
         }
     };
+    auto finish = [&](int pair, unsigned long long (&fw)[FW]) __attribute__((always_inline)) {
+        if constexpr (TWO_PHASE) finish_two_phase(pair, fw); else finish_single_pass(pair, fw);
+    };
 
     // ---- state of the previous pair, whose phase 2 is still to come (two-phase modes)
     float pkt = 0.0f, pkd = 0.0f;
@@ -592,11 +637,11 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
 
     // the previous pair's row-wide normalisers from the team's words (w holds the first 64 members'):
     // factors ft, fd with p = e_t ft, q = e_d fd
-    auto merge_team = [&](unsigned long long (&w)[4], float& ft, float& fd) __attribute__((always_inline)) -> bool {
+    auto merge_team = [&](unsigned long long (&w)[2], float& ft, float& fd) __attribute__((always_inline)) -> bool {
         const unsigned long long* p1 = part1 + static_cast<size_t>(prev_pair) * GW * 4;
         // binary32 is enough: the normalisers enter p and q as common factors
         TeamNorm n{neg_inf(), neg_inf(), 0.0f, 0.0f, true};
-        n.ok = await_words(p1, GW, 0, P.spin_limit, w);
+        n.ok = await_n<2>(p1, GW, 0, P.spin_limit, w);
         merge_round(w, lane < GW, n);
         if (GW > 64) n = merge_more_rounds(p1, GW, P.spin_limit, n);
         const float Kt = n.Kt, Kd = n.Kd, zt = n.zt, zd = n.zd;
@@ -614,7 +659,7 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
         // Only relative errors enter p and q, and the divergences below are functions of (p, q)
         // alone, second order in r = (p - q)/(p + q): the result is the divergence of a slightly
         // perturbed input.  u = 1 + r = 2p/s and v = 2 - u = 2q/s (exact subtraction).
-        double part[PW];
+        unsigned long long word[PW];
         if constexpr (MODE == MODE_TV) {
             float A = 0.0f, Bn = 0.0f, MA = 0.0f, MB = 0.0f;
 #pragma unroll
@@ -628,10 +673,13 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
             }
             // max() drops NaN: an unusable row (NaN factor) is made to reach the side selection
             if (ft != ft || fd != fd) { A = ft + fd; Bn = A; MA = A; MB = A; }
-            part[0] = static_cast<double>(wave_sumf(A));
-            part[1] = static_cast<double>(wave_sumf(Bn));
-            part[2] = static_cast<double>(wave_sumf(MA));
-            part[3] = static_cast<double>(wave_sumf(MB));
+            A = wave_sumf(A);
+            Bn = wave_sumf(Bn);
+            MA = wave_sumf(MA);
+            MB = wave_sumf(MB);
+            if (!ok) { A = __builtin_nanf(""); MA = A; }
+            word[0] = pack2(A, Bn);
+            word[1] = pack2(MA, MB);
         } else {
             float acc = 0.0f;
 #pragma unroll
@@ -652,30 +700,39 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
                     acc = fmaf(sum, fmaf(u, hw_log2(u) - hw_log2(v), (v - u) * kLog2e), acc);
                 }
             }
-            part[0] = static_cast<double>(wave_sumf(acc));
+            acc = wave_sumf(acc);
             if constexpr (MODE == MODE_KLP) {
-                if (__any(pmask)) part[0] += __builtin_inf();   // draft masks an entry the target keeps; NaN stays NaN
+                if (__any(pmask)) acc += __builtin_inff();   // draft masks an entry the target keeps; NaN stays NaN
             }
+            if (!ok) acc = __builtin_nanf("");
+            word[0] = pack2(acc, 0.0f);
         }
-        if (!ok) {
-            if (lane == 0) atomicOr(P.ws.counters + 1, 1u);
-#pragma unroll
-            for (int k = 0; k < PW; ++k) part[k] = __builtin_nan("");
-        }
+        if (!ok && lane == 0) atomicOr(P.ws.counters + 1, 1u);
         if (lane < PW) {
-            double mine = part[0];
+            unsigned long long mine = word[0];
 #pragma unroll
-            for (int k = 1; k < PW; ++k) mine = (lane == k) ? part[k] : mine;
-            post64(part2 + (static_cast<size_t>(prev_pair) * GW + member) * 4 + lane, dbits(mine));
+            for (int k = 1; k < PW; ++k) mine = (lane == k) ? word[k] : mine;
+            post64(part2 + static_cast<size_t>(prev_pair) * GW * 4 + lane * GW + member, mine);
         }
     };
 
     // One step: phase 1 of `pair` into (ect, ecd), then phase 2 of the previous pair from (ept, epd).
-    // Order matters for overlap: the team words of the previous pair are requested while phase 1
-    // computes and consumed before the next pair's loads are issued, so that no wait ever has the
-    // big prefetch in front of it; the prefetch then flies during phase 2.
+    // Memory operations return in the order they were issued, so the order of the requests decides
+    // what can overlap: the small exchange words (the previous pair's team words, and the words of a
+    // pair this wavefront has to finish) are requested first, at the top of the step, where they sit
+    // behind the logits that are about to be used anyway; the logits of the next pair are requested
+    // as soon as phase 1 has consumed the registers; and nothing after that waits on memory unless a
+    // team member is late (then the words are asked for again, behind the prefetch).
     auto step = [&](float (&ect)[NE], float (&ecd)[NE], const float (&ept)[NE], const float (&epd)[NE], int pair)
                     __attribute__((always_inline)) {
+        unsigned long long w[2] = {1, 1};
+        unsigned long long fw[FW];
+        const int fpair = fin0;
+        asm volatile("" ::: "memory");
+        if constexpr (TWO_PHASE)
+            request_n<2>(part1 + static_cast<size_t>(prev_pair >= 0 ? prev_pair : pair) * GW * 4, GW, 0, w);
+        request_n<FW>(finw + static_cast<size_t>(fpair >= 0 ? fpair : pair) * GW * 4, GW, 0, fw, fpair >= 0);
+        asm volatile("" ::: "memory");
         fill_unowned();
         // ---- phase 1: maximum, then sums of 2^(z log2e - k) with k = ceil(max log2e)
         float mt = neg_inf(), md = neg_inf();
@@ -688,13 +745,6 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
             for (int e = 0; e < VE; e += 2) { mt = fmaxf(fmaxf(mt, a[e]), a[e + 1]); md = fmaxf(fmaxf(md, c[e]), c[e + 1]); }
         }
         PT(0);   // load wait + max pass
-        // the logits have arrived: request the previous pair's team words behind the arithmetic
-        unsigned long long w[4] = {1, 1, 1, 1};
-        if constexpr (TWO_PHASE) {
-            asm volatile("" ::: "memory");
-            if (prev_pair >= 0) request_words(part1 + static_cast<size_t>(prev_pair) * GW * 4, GW, 0, w);
-            asm volatile("" ::: "memory");
-        }
         mt = wave_max(mt);
         md = wave_max(md);
         const float kt = (mt == neg_inf()) ? 0.0f : ceilf(mt * kLog2e);
@@ -720,44 +770,45 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
             }
         }
         PT(1);   // reductions + exp pass
-        // ---- the previous pair's normalisers (its words were requested above)
-        float ft = 0.0f, fd = 0.0f;
-        bool ok2 = true;
-        if constexpr (TWO_PHASE) {
-            if (prev_pair >= 0) ok2 = merge_team(w, ft, fd);
-            asm volatile("" ::: "memory");
+        // ---- the registers that held the logits are free: fetch the next pair (the request is
+        // unconditional: the last step asks for one slot of its own pair, which the caches hold)
+        asm volatile("" ::: "memory");
+        {
+            const bool more = pair + nteams < P.npairs;
+            load_item(more ? pair + nteams : pair, more);
         }
-        PT(2);   // team merge (wait for the team's words)
-        // post this wavefront's partial (stores go out before the prefetch, so that nothing that has to
-        // wait for them later also waits for the prefetch).  The two-phase modes need the normalisers
-        // to a relative 1e-7 only (common factors of p and q); the single-pass modes take them through
-        // a logarithm.
-        double pst_, psd_, pw_ = 0.0;
+        asm volatile("" ::: "memory");
+        // ---- post this wavefront's partial.  The two-phase modes need the normalisers to a relative
+        // 1e-7 only (common factors of p and q); the single-pass modes take them through a logarithm.
+        const unsigned long long w0 = pack2(kt, kd);
+        unsigned long long mine;
         if constexpr (TWO_PHASE) {
             st = wave_sumf(st);
             sd = wave_sumf(sd);
-            pst_ = static_cast<double>(st);
-            psd_ = static_cast<double>(sd);
+            mine = (lane == 0) ? w0 : pack2(st, sd);
         } else {
-            pst_ = wave_sum(static_cast<double>(st));
-            psd_ = wave_sum(static_cast<double>(sd));
+            const double pst_ = wave_sum(static_cast<double>(st));
+            const double psd_ = wave_sum(static_cast<double>(sd));
+            double pw_ = 0.0;
             if constexpr (MODE == MODE_KL) {
                 pw_ = wave_sum(static_cast<double>(wacc));
                 if (wave_max(dmax) == __builtin_inff()) pw_ = __builtin_inf();
             }
+            mine = (lane == 0) ? w0 : (lane == 1) ? dbits(pst_) : (lane == 2) ? dbits(psd_) : dbits(pw_);
         }
-        const unsigned long long w0 = static_cast<unsigned long long>(fbits(kt)) | (static_cast<unsigned long long>(fbits(kd)) << 32);
-        const unsigned long long mine = (lane == 0) ? w0 : (lane == 1) ? dbits(pst_) : (lane == 2) ? dbits(psd_) : dbits(pw_);
-        unsigned long long* const post_at = part1 + (static_cast<size_t>(pair) * GW + member) * 4 + (lane & 3);
-        // ---- the registers that held the logits are free: fetch the next pair, then post
-        asm volatile("" ::: "memory");
-        if (pair + nteams < P.npairs) load_item(pair + nteams);
-        asm volatile("" ::: "memory");
-        if (lane < 4) post64(post_at, mine);
+        constexpr int kPosted = TWO_PHASE ? 2 : 4;
+        unsigned long long* const post_at = part1 + static_cast<size_t>(pair) * GW * 4 + (lane & 3) * GW + member;
+        if (lane < kPosted) post64(post_at, mine);
         PT(3);   // wave sums, prefetch issue, post
         if constexpr (TWO_PHASE) {
-            if (prev_pair >= 0) phase2(ept, epd, ft, fd, ok2);
-            PT(4);   // phase 2
+            if (prev_pair >= 0) {
+                // ---- the previous pair's normalisers, then its phase 2
+                float ft, fd;
+                const bool ok2 = merge_team(w, ft, fd);
+                PT(2);   // team merge (wait for the team's words)
+                phase2(ept, epd, ft, fd, ok2);
+                PT(4);   // phase 2
+            }
             // the posted value and its address stay in their registers until here: reusing them
             // earlier would make phase 2 wait for the store, and with it for the prefetch
             asm volatile("" ::"v"(mine), "v"(post_at));
@@ -767,9 +818,7 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
             pmask = (dmax == __builtin_inff());
         }
         // ---- finishing duties: the pair whose turn has come, then note this pair if it is ours
-        if (fin0 >= 0) {
-            if constexpr (TWO_PHASE) finish_two_phase(fin0); else finish_single_pass(fin0);
-        }
+        if (fpair >= 0) finish(fpair, fw);
         PT(5);   // finishing duty
         fin0 = fin1; fin1 = fin2; fin2 = -1;
         if (iter % GW == member) {
@@ -779,6 +828,11 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
         }
         prev_pair = pair;
         ++iter;
+    };
+    auto finish_now = [&](int pair) __attribute__((always_inline)) {
+        unsigned long long fw[FW];
+        request_n<FW>(finw + static_cast<size_t>(pair) * GW * 4, GW, 0, fw);
+        finish(pair, fw);
     };
 
     float e0t[NE], e0d[NE], e1t[NE], e1d[NE];
@@ -797,19 +851,18 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
         }
         // ---- drain: phase 2 of the last pair, then the finishes still owed
         if (prev_pair >= 0) {
-            unsigned long long w[4];
+            unsigned long long w[2];
             float ft, fd;
-            request_words(part1 + static_cast<size_t>(prev_pair) * GW * 4, GW, 0, w);
+            request_n<2>(part1 + static_cast<size_t>(prev_pair) * GW * 4, GW, 0, w);
             const bool ok2 = merge_team(w, ft, fd);
             if (iter & 1) phase2(e0t, e0d, ft, fd, ok2); else phase2(e1t, e1d, ft, fd, ok2);
         }
-        if (fin0 >= 0) finish_two_phase(fin0);
-        if (fin1 >= 0) finish_two_phase(fin1);
-        if (fin2 >= 0) finish_two_phase(fin2);
     } else {
         for (; pair < P.npairs; pair += nteams) step(e0t, e0d, e1t, e1d, pair);
-        if (fin0 >= 0) finish_single_pass(fin0);
     }
+    if (fin0 >= 0) finish_now(fin0);
+    if (fin1 >= 0) finish_now(fin1);
+    if (fin2 >= 0) finish_now(fin2);
 #ifdef FSD_PHASE_TIMING
     PT(6);   // drain
     if (P.dbg && lane == 0) {
