@@ -1021,7 +1021,16 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
     if (!status) {
         const long s0 = static_cast<long>(gs) * P.sps;
         const long s1 = (s0 + P.sps < P.nslots) ? s0 + P.sps : P.nslots;
-        for (long s = s0 + tid; s < s1; s += kWG) {
+        // Scores already seen anywhere in the wavefront: an entry whose score cannot reach them cannot
+        // be the argmax, and its Gumbel variate (two logarithms) is not evaluated.  The bound:
+        // G = -ln(-ln u) <= -ln(1 - u), and 1 - u = m 2^-24 with the integer m below, so
+        // G <= ln2 (24 - floor(log2 m)) = ln2 (clz(m) - 7); 1e-3 covers the rounding of the
+        // logarithm routine by a wide margin.
+        float thr = neg_inf(), rthr = neg_inf();
+        // the trip count is the same for every lane: the thresholds are wavefront reductions
+        for (long sb = s0; sb < s1; sb += kWG) {
+            const long s = sb + tid;
+            if (s < s1) {
             float z[VE], zd[VE];
             const uint4 raw = load_slot<BF16, ALIGNED>(trow, s, P.V);
             unpack<BF16>(raw, z);
@@ -1043,19 +1052,36 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
                     const float zz = z[blk * 4 + q];
                     const int idx = static_cast<int>(e0 + q);
                     bad |= !(zz < __builtin_inff());
-                    const float g = (P.mode == FSD_SAMPLE) ? gumbel(w4[q]) : 0.0f;
-                    const float score = __fadd_rn(zz, g);
-                    if (score > best.score) best = Best{score, idx};
+                    float lnr = neg_inf();
                     if (residual) {
                         const float p = hw_exp2(fmaf(zz, kLog2e, -lt));
                         const float qq = hw_exp2(fmaf(zd[blk * 4 + q], kLog2e, -ld));
                         const float r = p - qq;
-                        if (r > 0.0f) {
-                            const float rs = fmaf(hw_log2(r), static_cast<float>(kLn2), g);
-                            if (rs > rbest.score) rbest = Best{rs, idx};
+                        if (r > 0.0f) lnr = hw_log2(r) * static_cast<float>(kLn2);
+                    }
+                    if (P.mode == FSD_SAMPLE) {
+                        const unsigned m = 0x00FFFFFFu ^ ((w4[q] >> 9) << 1);   // (1 - u) 2^24, odd, >= 1
+                        const float gb = fmaf(static_cast<float>(__clz(static_cast<int>(m)) - 7), 0.693148f, 1e-3f);
+                        const bool may = !(__fadd_rn(zz, gb) < thr) || (residual && !(__fadd_rn(lnr, gb) < rthr));
+                        if (may) {
+                            const float g = gumbel(w4[q]);
+                            const float score = __fadd_rn(zz, g);
+                            if (score > best.score) best = Best{score, idx};
+                            if (lnr > neg_inf()) {
+                                const float rs = __fadd_rn(lnr, g);
+                                if (rs > rbest.score) rbest = Best{rs, idx};
+                            }
                         }
+                    } else {
+                        if (zz > best.score) best = Best{zz, idx};
+                        if (lnr > rbest.score) rbest = Best{lnr, idx};
                     }
                 }
+            }
+            }
+            if (P.mode == FSD_SAMPLE) {
+                thr = wave_max(best.score);
+                if (residual) rthr = wave_max(rbest.score);
             }
         }
     }
@@ -1072,7 +1098,12 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
         __hip_atomic_store(slot + 0, (static_cast<unsigned long long>(__float_as_uint(m.score)) << 32) | static_cast<unsigned>(m.idx), __ATOMIC_RELAXED, AGENT);
         __hip_atomic_store(slot + 1, (static_cast<unsigned long long>(__float_as_uint(r.score)) << 32) | static_cast<unsigned>(r.idx), __ATOMIC_RELAXED, AGENT);
         __hip_atomic_store(slot + 2, static_cast<unsigned long long>(bd), __ATOMIC_RELAXED, AGENT);
-        const unsigned prev = __hip_atomic_fetch_add(P.ws.sdone + b, 1u, __ATOMIC_ACQ_REL, AGENT);
+        // The three words above are device-scope atomic stores, performed at the memory side; the
+        // wait for their completion orders them before the count (a device-scope release would also
+        // write the whole L2 back, which costs far more than the kernel's arithmetic).  The reader
+        // uses device-scope atomic loads, so it needs no invalidate either.
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        const unsigned prev = __hip_atomic_fetch_add(P.ws.sdone + b, 1u, __ATOMIC_RELAXED, AGENT);
         s_last = (prev == static_cast<unsigned>(P.GS) - 1u) ? 1 : 0;
     }
     __syncthreads();
