@@ -171,11 +171,6 @@ unsigned fsd_debug_set_spin_limit(unsigned polls);
  * the rounding order of the partial sums. */
 int fsd_debug_set_shape(int wavefronts, int slots_per_thread);
 
-/* Test hook: 0 makes bfloat16 JS calls skip the fast kernel and use the exact
- * two-phase kernel for every pair (the one that otherwise only re-does the
- * pairs the fast kernel hands on); 1 (default) restores the normal path. */
-void fsd_debug_set_fast(int on);
-
 /* Test hook: grid size of the last vocabulary-reduction launch and the resident
  * workgroups per CU it was derived from. */
 void fsd_debug_last_launch(int* grid, int* per_cu);

@@ -55,8 +55,6 @@ def library() -> ctypes.CDLL:
         L.fsd_profile_enable.restype = i32
         L.fsd_profile_collect.argtypes = [vp, vp]
         L.fsd_profile_collect.restype = i32
-        L.fsd_debug_set_fast.argtypes = [i32]
-        L.fsd_debug_set_fast.restype = None
         L.fsd_debug_set_shape.argtypes = [i32, i32]
         L.fsd_debug_set_shape.restype = i32
         L.fsd_debug_set_spin_limit.argtypes = [c.c_uint]
@@ -215,10 +213,6 @@ def profile_collect():
 
 def debug_set_spin_limit(polls: int) -> int:
     return int(library().fsd_debug_set_spin_limit(polls))
-
-
-def debug_set_fast(on: bool) -> None:
-    library().fsd_debug_set_fast(1 if on else 0)
 
 
 def debug_set_shape(wavefronts: int, slots_per_thread: int) -> None:

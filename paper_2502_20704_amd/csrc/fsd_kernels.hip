@@ -31,7 +31,7 @@ constexpr double kLn2 = 0.69314718055994530942;
 
 // MODE_KL: single-pass KL (absolute error ~1e-7, enough for bfloat16 inputs); MODE_KLP: two-phase,
 // pointwise non-negative KL for binary32 inputs; MODE_LSE: normalisers only (strict SD)
-enum { MODE_KL = 0, MODE_JS = 1, MODE_TV = 2, MODE_LSE = 3, MODE_KLP = 4, MODE_JSF = 5 };
+enum { MODE_KL = 0, MODE_JS = 1, MODE_TV = 2, MODE_LSE = 3, MODE_KLP = 4 };
 enum { KIND_CHAIN = 0, KIND_TREE = 1, KIND_SD = 2 };
 
 #define AGENT __HIP_MEMORY_SCOPE_AGENT
@@ -249,7 +249,7 @@ __device__ __forceinline__ float gumbel(unsigned w) {
 // workspace view
 
 struct Ws {
-    unsigned* counters;  // 64 words ([1]: a bounded wait expired, [2]: length of redo), then sdone[B]
+    unsigned* counters;  // 64 words ([1]: a bounded wait expired), then sdone[B]
     unsigned* sdone;     // [B] sampler workgroups that posted
     unsigned long long* part1;  // [R][G][4]: (kt,kd) | St | Sd | W
     double* part2;       // [R][G][4] divergence words (one used, four for TV)
@@ -258,7 +258,6 @@ struct Ws {
     double* lse2;        // [R][2] log2-sum-exp2 of the target / draft row of the pair
     double* lr;          // [R] strict SD: ln p(x) - ln q(x)
     unsigned long long* spart;  // [B][GS][4]
-    int32_t* redo;       // [R] pairs the fast JS kernel hands to the exact one (count in counters[2])
 };
 
 struct PairParams {
@@ -268,7 +267,6 @@ struct PairParams {
     const int32_t* cand;    // strict SD only
     int rows;               // K or N
     int npairs;             // B * rows
-    int use_list;           // 1: work through ws.redo[0 .. counters[2]) instead of all pairs
     long V;
     long nslots;
     int spm;                // slots per team member
@@ -443,14 +441,13 @@ __device__ __noinline__ Sums<N> sum_more_rounds(const unsigned long long* p2, in
 }
 
 template <bool BF16, int NV, int MODE, bool ALIGNED>
-__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(2))) void pair_kernel(PairParams P) {
+__global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
     constexpr int VE = Slot<BF16>::VE;
     constexpr int ES = BF16 ? 2 : 4;
-    constexpr bool FAST = (MODE == MODE_JSF);
-    constexpr bool TWO_PHASE = (MODE == MODE_JS || MODE == MODE_TV || MODE == MODE_KLP || FAST);
+    constexpr bool TWO_PHASE = (MODE == MODE_JS || MODE == MODE_TV || MODE == MODE_KLP);
     constexpr int NE = TWO_PHASE ? NV * VE : 1;   // exponentials kept per row and lane
     constexpr int PW = (MODE == MODE_TV) ? 2 : 1;   // divergence words a member posts (two sums each)
-    constexpr int FW = FAST ? 4 : TWO_PHASE ? PW : 4;   // words per member the finisher reads
+    constexpr int FW = TWO_PHASE ? PW : 4;          // words per member the finisher reads
     constexpr float kTiny = 2e-38f;   // keeps p + q > 0 without changing any result
     constexpr int kWavesPerWG = kWG / 64;
 
@@ -459,9 +456,6 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(2))) void p
     const int wgs_per_team = GW / kWavesPerWG;
     const int team = static_cast<int>(blockIdx.x) / wgs_per_team;
     const int nteams = static_cast<int>(gridDim.x) / wgs_per_team;
-    // list mode: the pairs to work on are ws.redo[0 .. counters[2]), written by the kernel before
-    const int nwork = P.use_list ? static_cast<int>(P.ws.counters[2]) : P.npairs;
-    auto pair_at = [&](int i) __attribute__((always_inline)) { return P.use_list ? P.ws.redo[i] : i; };
     const int member = (static_cast<int>(blockIdx.x) % wgs_per_team) * kWavesPerWG + wave;
     const long s0 = static_cast<long>(member) * P.spm;
     const long s1 = (s0 + P.spm < P.nslots) ? s0 + P.spm : P.nslots;
@@ -632,78 +626,8 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(2))) void p
             P.ws.pst[pair] = status;
         }
     };
-    // the fast JS kernel: everything the divergence needs comes from sums the members posted.
-    //   JS / ln2 = 1/2 sum p log2 p + 1/2 sum q log2 q - sum m log2 m,   m = (p + q)/2.
-    // With p = e f (e = 2^y, y = z log2e - k, f the member's factor) the first sum is, member by
-    // member, f (W + S log2 f) with S = sum e and W = sum e y taken in phase 1; the last sum is the
-    // member's phase-2 word.  The factors are rebuilt here by the very merge the members ran (same
-    // inputs, same order: the same binary32 values), so an error of the normaliser moves p in all
-    // three sums alike and only scales the result.  What remains are the rounding errors of sums of
-    // size O(entropy): a few 1e-7 absolute.  That is far inside the tolerance of bfloat16 logits
-    // unless the divergence itself is tiny, so results below kRedoBelow (and anything not finite)
-    // are not written: the pair goes on the list of the exact kernel, which runs next.
-    auto finish_fast = [&](int pair, unsigned long long (&fw)[FW]) __attribute__((always_inline)) {
-        constexpr double kRedoBelow = 1e-3;
-        unsigned long long* const p1 = part1 + static_cast<size_t>(pair) * GW * 4;
-        unsigned long long* const p2 = part2 + static_cast<size_t>(pair) * GW * 4;
-        unsigned long long a[3] = {fw[0], fw[1 % FW], fw[2 % FW]};
-        unsigned long long bw[1] = {fw[3 % FW]};
-        bool ok = await_n<3>(p1, GW, 0, P.spin_limit, a);
-        ok &= await_n<1>(p2, GW, 0, P.spin_limit, bw);
-        const bool in = lane < GW;
-        TeamNorm n{neg_inf(), neg_inf(), 0.0f, 0.0f, true};
-        {
-            const unsigned long long w2[2] = {a[0], a[1]};
-            merge_round(w2, in, n);
-        }
-        const float rzt = 1.0f / n.zt, rzd = 1.0f / n.zd;
-        const float kt = lo_f(a[0]), kd = hi_f(a[0]);
-        const float St = in ? lo_f(a[1]) : 0.0f, Sd = in ? hi_f(a[1]) : 0.0f;
-        const double Wt = static_cast<double>(lo_f(a[2])), Wd = static_cast<double>(hi_f(a[2]));
-        double At = 0.0, Ad = 0.0;
-        if (St > 0.0f) {
-            const int dk = kdiff(kt, n.Kt);
-            At = ldexp(static_cast<double>(rzt), dk) * (Wt + (dk + log2(static_cast<double>(rzt))) * static_cast<double>(St));
-        }
-        if (Sd > 0.0f) {
-            const int dk = kdiff(kd, n.Kd);
-            Ad = ldexp(static_cast<double>(rzd), dk) * (Wd + (dk + log2(static_cast<double>(rzd))) * static_cast<double>(Sd));
-        }
-        const double At_sum = wave_sum(At), Ad_sum = wave_sum(Ad);
-        const double Bm = wave_sum(in ? static_cast<double>(lo_f(bw[0])) : 0.0);
-        const double value = kLn2 * (0.5 * (At_sum + Ad_sum) - Bm);
-        const bool bad_norm = !(n.zt > 0.0f) || !(n.zd > 0.0f) || !(n.zt < __builtin_inff()) || !(n.zd < __builtin_inff()) ||
-                              (__any(in && (St != St || Sd != Sd)) != 0);
-        const bool keep = ok && !bad_norm && (value >= kRedoBelow) && (value < __builtin_inf());
-        if (keep) {
-            if (lane == 0) {
-                P.ws.div[pair] = static_cast<float>(value);
-                P.ws.lse2[2 * pair] = 0.0;
-                P.ws.lse2[2 * pair + 1] = 0.0;
-                if (P.user_div) P.user_div[pair] = static_cast<float>(value);
-                P.ws.pst[pair] = 0;
-            }
-        } else {
-            // every member has read these words (their divergence words are all here), nobody will
-            // again: clear them for the exact kernel, which uses the same places
-            for (int i = lane; i < 4 * GW; i += 64) { post64(p1 + i, 0ull); post64(p2 + i, 0ull); }
-            if (lane == 0) P.ws.redo[atomicAdd(P.ws.counters + 2, 1u)] = pair;
-        }
-    };
     auto finish = [&](int pair, unsigned long long (&fw)[FW]) __attribute__((always_inline)) {
-        if constexpr (FAST) finish_fast(pair, fw);
-        else if constexpr (TWO_PHASE) finish_two_phase(pair, fw);
-        else finish_single_pass(pair, fw);
-    };
-    auto request_fin = [&](int pair, unsigned long long (&fw)[FW], bool spread) __attribute__((always_inline)) {
-        if constexpr (FAST) {
-            unsigned long long a[3], bw[1];
-            request_n<3>(part1 + static_cast<size_t>(pair) * GW * 4, GW, 0, a, spread);
-            request_n<1>(part2 + static_cast<size_t>(pair) * GW * 4, GW, 0, bw, spread);
-            fw[0] = a[0]; fw[1 % FW] = a[1]; fw[2 % FW] = a[2]; fw[3 % FW] = bw[0];
-        } else {
-            request_n<FW>(finw + static_cast<size_t>(pair) * GW * 4, GW, 0, fw, spread);
-        }
+        if constexpr (TWO_PHASE) finish_two_phase(pair, fw); else finish_single_pass(pair, fw);
     };
 
     // ---- state of the previous pair, whose phase 2 is still to come (two-phase modes)
@@ -759,18 +683,6 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(2))) void p
             if (!ok) { A = __builtin_nanf(""); MA = A; }
             word[0] = pack2(A, Bn);
             word[1] = pack2(MA, MB);
-        } else if constexpr (FAST) {
-            // sum m log2 m with m = (p + q)/2 > 0; the halved factors are exact
-            const float hft = 0.5f * ft, hfd = 0.5f * fd;
-            float acc = 0.0f;
-#pragma unroll
-            for (int i = 0; i < NE; ++i) {
-                const float m = fmaf(et[i], hft, fmaf(ed[i], hfd, kTiny));
-                acc = fmaf(m, hw_log2(m), acc);
-            }
-            acc = wave_sumf(acc);
-            if (!ok) acc = __builtin_nanf("");
-            word[0] = pack2(acc, 0.0f);
         } else {
             float acc = 0.0f;
 #pragma unroll
@@ -814,14 +726,15 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(2))) void p
     // behind the logits that are about to be used anyway; the logits of the next pair are requested
     // as soon as phase 1 has consumed the registers; and nothing after that waits on memory unless a
     // team member is late (then the words are asked for again, behind the prefetch).
-    auto step = [&](float (&ect)[NE], float (&ecd)[NE], const float (&ept)[NE], const float (&epd)[NE], int pair,
-                    int next) __attribute__((always_inline)) {
+    auto step = [&](float (&ect)[NE], float (&ecd)[NE], const float (&ept)[NE], const float (&epd)[NE], int pair)
+                    __attribute__((always_inline)) {
         unsigned long long w[2] = {1, 1};
         unsigned long long fw[FW];
         const int fpair = fin0;
         asm volatile("" ::: "memory");
         if constexpr (TWO_PHASE)
             request_n<2>(part1 + static_cast<size_t>(prev_pair >= 0 ? prev_pair : pair) * GW * 4, GW, 0, w);
+        request_n<FW>(finw + static_cast<size_t>(fpair >= 0 ? fpair : pair) * GW * 4, GW, 0, fw, fpair >= 0);
         asm volatile("" ::: "memory");
         fill_unowned();
         // ---- phase 1: maximum, then sums of 2^(z log2e - k) with k = ceil(max log2e)
@@ -839,7 +752,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(2))) void p
         md = wave_max(md);
         const float kt = (mt == neg_inf()) ? 0.0f : ceilf(mt * kLog2e);
         const float kd = (md == neg_inf()) ? 0.0f : ceilf(md * kLog2e);
-        float st = 0.0f, sd = 0.0f, wacc = 0.0f, wdacc = 0.0f, dmax = neg_inf();
+        float st = 0.0f, sd = 0.0f, wacc = 0.0f, dmax = neg_inf();
 #pragma unroll
         for (int k = 0; k < NV; ++k) {
             float a[VE], c[VE];
@@ -847,17 +760,11 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(2))) void p
             unpack<BF16>(rb[k], c);
 #pragma unroll
             for (int e = 0; e < VE; ++e) {
-                const float ya = fmaf(a[e], kLog2e, -kt), yb = fmaf(c[e], kLog2e, -kd);
-                const float xa = hw_exp2(ya);
-                const float xb = hw_exp2(yb);
+                const float xa = hw_exp2(fmaf(a[e], kLog2e, -kt));
+                const float xb = hw_exp2(fmaf(c[e], kLog2e, -kd));
                 if constexpr (TWO_PHASE) { ect[k * VE + e] = xa; ecd[k * VE + e] = xb; }
                 st += xa;
                 sd += xb;
-                if constexpr (FAST) {
-                    // sum e y; a masked entry (y = -inf, e = 0) adds 0, a NaN stays a NaN through e
-                    wacc = fmaf(xa, fmaxf(ya, -126.0f), wacc);
-                    wdacc = fmaf(xb, fmaxf(yb, -126.0f), wdacc);
-                }
                 if constexpr (MODE == MODE_KL || MODE == MODE_KLP) {
                     const float diff = a[e] - c[e];
                     dmax = fmaxf(dmax, diff);   // +inf iff the draft masks an entry the target does not
@@ -869,10 +776,10 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(2))) void p
         // ---- the registers that held the logits are free: fetch the next pair (the request is
         // unconditional: the last step asks for one slot of its own pair, which the caches hold)
         asm volatile("" ::: "memory");
-        // (the words of a pair to finish are only looked at after phase 2, and were posted steps ago:
-        // asking for them here keeps them out of the registers while phase 1 needs those most)
-        request_fin(fpair >= 0 ? fpair : pair, fw, fpair >= 0);
-        load_item(next >= 0 ? next : pair, next >= 0);
+        {
+            const bool more = pair + nteams < P.npairs;
+            load_item(more ? pair + nteams : pair, more);
+        }
         asm volatile("" ::: "memory");
         // ---- post this wavefront's partial.  The two-phase modes need the normalisers to a relative
         // 1e-7 only (common factors of p and q); the single-pass modes take them through a logarithm.
@@ -882,11 +789,6 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(2))) void p
             st = wave_sumf(st);
             sd = wave_sumf(sd);
             mine = (lane == 0) ? w0 : pack2(st, sd);
-            if constexpr (FAST) {
-                wacc = wave_sumf(wacc);
-                wdacc = wave_sumf(wdacc);
-                if (lane == 2) mine = pack2(wacc, wdacc);
-            }
         } else {
             const double pst_ = wave_sum(static_cast<double>(st));
             const double psd_ = wave_sum(static_cast<double>(sd));
@@ -897,7 +799,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(2))) void p
             }
             mine = (lane == 0) ? w0 : (lane == 1) ? dbits(pst_) : (lane == 2) ? dbits(psd_) : dbits(pw_);
         }
-        constexpr int kPosted = FAST ? 3 : TWO_PHASE ? 2 : 4;
+        constexpr int kPosted = TWO_PHASE ? 2 : 4;
         unsigned long long* const post_at = part1 + static_cast<size_t>(pair) * GW * 4 + (lane & 3) * GW + member;
         if (lane < kPosted) post64(post_at, mine);
         PT(3);   // wave sums, prefetch issue, post
@@ -932,29 +834,23 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(2))) void p
     };
     auto finish_now = [&](int pair) __attribute__((always_inline)) {
         unsigned long long fw[FW];
-        request_fin(pair, fw, true);
+        request_n<FW>(finw + static_cast<size_t>(pair) * GW * 4, GW, 0, fw);
         finish(pair, fw);
     };
 
     float e0t[NE], e0d[NE], e1t[NE], e1d[NE];
-    int widx = team;   // position in the work list; this team takes every nteams-th
-    int pair = (widx < nwork) ? pair_at(widx) : -1;
-    auto next_pair = [&]() __attribute__((always_inline)) { return (widx + nteams < nwork) ? pair_at(widx + nteams) : -1; };
-    if (pair >= 0) load_item(pair);
+    int pair = team;
+    if (pair < P.npairs) load_item(pair);
     if constexpr (TWO_PHASE) {
 #pragma unroll
         for (int i = 0; i < NE; ++i) { e0t[i] = 0.0f; e0d[i] = 0.0f; e1t[i] = 0.0f; e1d[i] = 0.0f; }
         for (;;) {
-            if (pair < 0) break;
-            int nx = next_pair();
-            step(e0t, e0d, e1t, e1d, pair, nx);
-            widx += nteams;
-            pair = nx;
-            if (pair < 0) break;
-            nx = next_pair();
-            step(e1t, e1d, e0t, e0d, pair, nx);
-            widx += nteams;
-            pair = nx;
+            if (pair >= P.npairs) break;
+            step(e0t, e0d, e1t, e1d, pair);
+            pair += nteams;
+            if (pair >= P.npairs) break;
+            step(e1t, e1d, e0t, e0d, pair);
+            pair += nteams;
         }
         // ---- drain: phase 2 of the last pair, then the finishes still owed
         if (prev_pair >= 0) {
@@ -965,12 +861,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(2))) void p
             if (iter & 1) phase2(e0t, e0d, ft, fd, ok2); else phase2(e1t, e1d, ft, fd, ok2);
         }
     } else {
-        while (pair >= 0) {
-            const int nx = next_pair();
-            step(e0t, e0d, e1t, e1d, pair, nx);
-            widx += nteams;
-            pair = nx;
-        }
+        for (; pair < P.npairs; pair += nteams) step(e0t, e0d, e1t, e1d, pair);
     }
     if (fin0 >= 0) finish_now(fin0);
     if (fin1 >= 0) finish_now(fin1);
@@ -1140,25 +1031,16 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
         // logarithm routine by a wide margin.
         float thr = neg_inf(), rthr = neg_inf();
         // the trip count is the same for every lane: the thresholds are wavefront reductions
-        // the slot of the next trip is requested before this trip's arithmetic (lanes past the end
-        // re-read the last slot)
-        auto clamped = [&](long s) { return s < s1 ? s : s1 - 1; };
-        uint4 raw_n = make_uint4(0u, 0u, 0u, 0u), rawd_n = raw_n;
-        if (s0 < s1) {
-            raw_n = load_slot<BF16, ALIGNED>(trow, clamped(s0 + tid), P.V);
-            if (residual) rawd_n = load_slot<BF16, ALIGNED>(drow, clamped(s0 + tid), P.V);
-        }
         for (long sb = s0; sb < s1; sb += kWG) {
             const long s = sb + tid;
-            const uint4 raw = raw_n, rawd = rawd_n;
-            if (sb + kWG < s1) {
-                raw_n = load_slot<BF16, ALIGNED>(trow, clamped(s + kWG), P.V);
-                if (residual) rawd_n = load_slot<BF16, ALIGNED>(drow, clamped(s + kWG), P.V);
-            }
             if (s < s1) {
             float z[VE], zd[VE];
+            const uint4 raw = load_slot<BF16, ALIGNED>(trow, s, P.V);
             unpack<BF16>(raw, z);
-            if (residual) unpack<BF16>(rawd, zd);
+            if (residual) {
+                const uint4 rawd = load_slot<BF16, ALIGNED>(drow, s, P.V);
+                unpack<BF16>(rawd, zd);
+            }
 #pragma unroll
             for (int blk = 0; blk < VE / 4; ++blk) {
                 const long e0 = s * VE + blk * 4;
@@ -1291,7 +1173,7 @@ struct Plan {
     int VE, NV, G, spm, GS, sps;   // G = wavefronts per pair
     long nslots;
     size_t off_counters, n_counters, off_part1, off_part2, zero_bytes, off_div, off_pst, off_lse2, off_lr, off_spart,
-        off_redo, bytes;
+        bytes;
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -1338,7 +1220,6 @@ bool make_plan(int B, int rows, long V, int dtype, Plan& p) {
     p.off_lse2 = o; o = align_up(o + R * 16, 256);
     p.off_lr = o; o = align_up(o + R * 8, 256);
     p.off_spart = o; o = align_up(o + static_cast<size_t>(B) * p.GS * 32, 256);
-    p.off_redo = o; o = align_up(o + R * 4, 256);
     p.bytes = o;
     return true;
 }
@@ -1356,12 +1237,10 @@ Ws carve(void* workspace, const Plan& p, int B, int rows) {
     w.lse2 = reinterpret_cast<double*>(base + p.off_lse2);
     w.lr = reinterpret_cast<double*>(base + p.off_lr);
     w.spart = reinterpret_cast<unsigned long long*>(base + p.off_spart);
-    w.redo = reinterpret_cast<int32_t*>(base + p.off_redo);
     return w;
 }
 
 unsigned g_spin_limit = 1u << 22;
-bool g_fast_js = true;   // see fsd_debug_set_fast
 #ifdef FSD_PHASE_TIMING
 unsigned long long* g_dbg = nullptr;
 #endif
@@ -1443,14 +1322,11 @@ void launch_pair_m(int mode, bool aligned, hipStream_t st, const PairParams& P) 
         case MODE_JS: launch_pair_a<BF16, NV, MODE_JS>(aligned, st, P); break;
         case MODE_TV: launch_pair_a<BF16, NV, MODE_TV>(aligned, st, P); break;
         case MODE_KLP: launch_pair_a<BF16, NV, MODE_KLP>(aligned, st, P); break;
-        case MODE_JSF:
-            if constexpr (BF16) launch_pair_a<BF16, NV, MODE_JSF>(aligned, st, P);
-            break;
         default: launch_pair_a<BF16, NV, MODE_LSE>(aligned, st, P); break;
     }
 }
-void launch_pair(int dtype, int NV, int mode, bool aligned, hipStream_t st, const PairParams& P, bool timed) {
-    const bool prof = timed && g_prof_on && g_prof_n < kMaxProf;
+void launch_pair(int dtype, int NV, int mode, bool aligned, hipStream_t st, const PairParams& P) {
+    const bool prof = g_prof_on && g_prof_n < kMaxProf;
     if (prof) {
         if (!g_prof_made) {
             for (int i = 0; i < 2 * kMaxProf; ++i) (void)hipEventCreate(&g_prof_ev[i]);
@@ -1540,16 +1416,7 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
     pp.ws = ws;
     int k1mode = (kind == KIND_SD) ? MODE_LSE : div;
     if (k1mode == MODE_KL && dtype == FSD_F32) k1mode = MODE_KLP;
-    pp.use_list = 0;
-    if (k1mode == MODE_JS && dtype == FSD_BF16 && p.G <= 64 && g_fast_js) {
-        // bfloat16 JS: the fast kernel, then the exact one over whatever the fast one handed on
-        // (normally nothing: its wavefronts read an empty list and leave)
-        launch_pair(dtype, p.NV, MODE_JSF, aligned, st, pp, true);
-        pp.use_list = 1;
-        launch_pair(dtype, p.NV, MODE_JS, aligned, st, pp, false);
-    } else {
-        launch_pair(dtype, p.NV, k1mode, aligned, st, pp, true);
-    }
+    launch_pair(dtype, p.NV, k1mode, aligned, st, pp);
 
     SampleParams sp;
     sp.target = static_cast<const char*>(target);
@@ -1680,8 +1547,6 @@ unsigned fsd_debug_set_spin_limit(unsigned polls) {
     g_spin_limit = polls;
     return prev;
 }
-
-void fsd_debug_set_fast(int on) { g_fast_js = on != 0; }
 
 #ifdef FSD_PHASE_TIMING
 void fsd_debug_set_dbg(void* p) { g_dbg = static_cast<unsigned long long*>(p); }
