@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published peak
 
 def traffic_from_profile(workload: str):
     """HBM bytes per launch of the reduction kernel, from the committed counter summary (or None)."""
-    path = os.path.join(ROOT, "profiles", f"pair_reduce_{workload}_pmc.txt")
+    path = os.path.join(ROOT, "profiles", f"pair_kernel_{workload}_pmc.txt")
     try:
         with open(path) as f:
             for line in f:
@@ -148,7 +148,7 @@ def main() -> int:
                    "logits_dtype": cfg["dtype"], "whole_call_GBps": (alg_bytes + B * V * es) / (ms_per_step * 1e-3) / 1e9},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
-                     "traffic": traffic_from_profile(args.config), "kernel": "pair_reduce",
+                     "traffic": traffic_from_profile(args.config), "kernel": "pair_kernel",
                      "kernel_ms_mean": k1_mean_ms, "kernel_ms_min": k1_min_ms, "launches_timed": n_ev,
                      "algorithmic_bytes_per_launch": alg_bytes},
     }
@@ -171,7 +171,8 @@ def main() -> int:
         result["cpu_baseline"] = {"value": npos / dt, "unit": "positions/s", "cores": oracle.num_threads(),
                                   "kind": "oracle",
                                   "sample": f"{npos} positions of the same workload ({len(host_sets)} input sets, 3 passes), "
-                                            f"{dt:.2f} s wall"}
+                                            f"{dt:.2f} s wall on {oracle.num_threads()} threads "
+                                            f"(about {dt * oracle.num_threads():.0f} core-seconds)"}
     print(json.dumps(result), flush=True)
     return 0
 

@@ -76,8 +76,8 @@ enum {
     FSD_ROW_INTERNAL = 16   /* a bounded device-side wait expired (never expected) */
 };
 
-/* Limits: 1 <= V <= fsd_max_vocab(dtype); 1 <= K, N, max_depth <= 2048; B <= 65535;
- * B*K (B*N) < 2^24. */
+/* Limits: 1 <= V <= fsd_max_vocab(dtype) (524288 for both dtypes); 1 <= K, N,
+ * max_depth <= 2048; 1 <= B <= 65535; B*K (B*N) < 2^24. */
 int64_t fsd_max_vocab(int dtype);
 
 /* Bytes of workspace a call with these sizes needs (rows_per_seq = K or N).
@@ -160,20 +160,22 @@ int sd_verify_chain(const void* target_logits, const void* draft_logits, const i
 int fsd_profile_enable(int on);
 int fsd_profile_collect(float* mean_ms, float* min_ms);
 
-/* Test hook: number of polls a workgroup spends waiting for the other
- * workgroups that share its row pair before it gives up and flags
- * FSD_ROW_INTERNAL (default 1<<22).  Returns the previous value. */
+/* Test hook: number of polls a wavefront spends waiting for the words of the
+ * other wavefronts that share its row pair before it gives up and the call
+ * flags FSD_ROW_INTERNAL (default 1<<22).  Returns the previous value. */
 unsigned fsd_debug_set_spin_limit(unsigned polls);
 
-/* Tuning hook: workgroup shape of the vocabulary-reduction kernel, as wavefronts
- * per workgroup (4 or 8) and 16-byte slots of each row held per thread (4 or 8);
- * (0, 0) restores the library's own choice.  Results do not depend on it beyond
- * the rounding order of the partial sums. */
+/* Tuning hook: shape of the vocabulary-reduction kernel.  `wavefronts` per
+ * workgroup must be 4 (or 0 = default); `slots_per_thread` is the number of
+ * 16-byte slots of each row a lane holds: 2, 4 or 8 (bfloat16: 2 or 4), 0 =
+ * the library's own choice (32 vocabulary entries per lane and row).  A shape
+ * that would need more than 256 wavefronts per row pair is ignored.  Results
+ * do not depend on the shape beyond the rounding order of the partial sums. */
 int fsd_debug_set_shape(int wavefronts, int slots_per_thread);
 
-/* Test hook: grid size of the last vocabulary-reduction launch and the resident
- * workgroups per CU it was derived from. */
-void fsd_debug_last_launch(int* grid, int* per_cu);
+/* Test hook: grid size (workgroups) of the last vocabulary-reduction launch and
+ * the number of its workgroups the device can hold at once, which caps it. */
+void fsd_debug_last_launch(int* grid, int* resident);
 
 #ifdef __cplusplus
 }

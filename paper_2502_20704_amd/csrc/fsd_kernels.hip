@@ -296,22 +296,29 @@ __global__ void zero_counters(uint4* p, long n16) {
 // 64-bit words in the workspace.
 //
 //   phase 1   maximum of the slice (DPP reduction), integer reference exponent k = ceil(max log2e),
-//             e = 2^(z log2e - k) for every entry, their sums; posted as four words.
+//             e = 2^(z log2e - k) for every entry, their sums; posted as exchange words (two-phase
+//             modes: the two exponents in one word, the two sums as binary32 in another).
 //   exchange  (two-phase divergences) every wavefront reads the whole team's words and merges them
 //             into row-wide normalisers.
 //   phase 2   from the kept exponentials: p = e_t f_t, q = e_d f_d, the divergence's terms, one
-//             (TV: four) partial sum(s) posted.
+//             (TV: two) word(s) of partial sums posted.
 //   finish    the team's wavefronts take turns as finisher of a pair: it adds the posted partial
 //             sums in member order (fixed order: results are bit-identical run to run) and writes
 //             divergence and status.
 //
 // The kernel is persistent and software-pipelined by one pair: in a step a wavefront runs phase 1
-// of pair j and then phase 2 of pair j-1, whose team words were posted a whole step earlier and
-// requested at the top of the step, so in the normal case nothing waits; the loads of pair j+1 are
-// issued as soon as phase 1 has consumed the registers.  The single-pass modes (bfloat16 KL, the
-// normalisers of strict SD) have no phase 2.  Waiting is bounded (spin_limit polls, then
-// FSD_ROW_INTERNAL), so every wavefront reaches the end of the kernel whatever happens; all team
-// members are resident by construction (the grid never exceeds what fits on the device at once).
+// of pair j and then phase 2 of pair j-1 from a second set of exponentials.  Memory operations
+// return in the order they were issued, which fixes the order of the requests in a step (see
+// `step`): small exchange words first, the next pair's logits as soon as phase 1 has consumed the
+// registers, and nothing after that waits on memory unless a team member is late.  In practice
+// the slowest member of a team sets the pace and the others do wait for its words; that wait
+// coincides with the flight time of their own prefetch.  A step therefore costs about phase 1
+// plus one memory latency, whatever phase 2 does: this, not arithmetic or bandwidth, bounds the
+// two-phase modes at two wavefronts per SIMD (the registers of two sets of exponentials).
+// The single-pass modes (bfloat16 KL, the normalisers of strict SD) have no phase 2.  Waiting is
+// bounded (spin_limit polls, then FSD_ROW_INTERNAL), so every wavefront reaches the end of the
+// kernel whatever happens; all team members are resident by construction (the grid never exceeds
+// what fits on the device at once).
 
 // The exchange words are only ever touched with device-scope atomic loads and stores, which are
 // performed at the memory side: no cache write-back or invalidate is needed to see them.  They are
@@ -731,6 +738,9 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
         unsigned long long w[2] = {1, 1};
         unsigned long long fw[FW];
         const int fpair = fin0;
+        // Phase 1 and the request for the next pair's logits are what the whole team waits for: they
+        // run at raised priority; what follows overlaps with the memory latency and does not need it.
+        __builtin_amdgcn_s_setprio(3);
         asm volatile("" ::: "memory");
         if constexpr (TWO_PHASE)
             request_n<2>(part1 + static_cast<size_t>(prev_pair >= 0 ? prev_pair : pair) * GW * 4, GW, 0, w);
@@ -780,6 +790,7 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
             const bool more = pair + nteams < P.npairs;
             load_item(more ? pair + nteams : pair, more);
         }
+        __builtin_amdgcn_s_setprio(0);
         asm volatile("" ::: "memory");
         // ---- post this wavefront's partial.  The two-phase modes need the normalisers to a relative
         // 1e-7 only (common factors of p and q); the single-pass modes take them through a logarithm.
@@ -1537,9 +1548,9 @@ int fsd_debug_set_shape(int wavefronts, int slots_per_thread) {
     return FSD_OK;
 }
 
-void fsd_debug_last_launch(int* grid, int* per_cu) {
+void fsd_debug_last_launch(int* grid, int* resident) {
     if (grid) *grid = g_last_grid;
-    if (per_cu) *per_cu = g_last_total;
+    if (resident) *resident = g_last_total;
 }
 
 unsigned fsd_debug_set_spin_limit(unsigned polls) {
