@@ -63,6 +63,9 @@ def lib() -> ctypes.CDLL:
         L.sd_oracle_verify_chain.argtypes = [vp, vp, vp, i32, i32, i64, i32, i32, u64, u64, i32,
                                              vp, vp, vp, vp, vp, vp]
         L.sd_oracle_verify_chain.restype = c.c_int
+        L.rfsd_oracle_verify_chain.argtypes = [vp, vp, vp, i32, i32, i64, i32, i32, dbl, i32, u64, u64, i32,
+                                               vp, vp, vp, vp, vp, vp, vp]
+        L.rfsd_oracle_verify_chain.restype = c.c_int
         _lib = L
     return _lib
 
@@ -169,4 +172,22 @@ def sd_verify_chain(target, draft, cand, mode=SAMPLE, seed=0, offset=0, seq_offs
                                  offset, seq_offset, _p(out["accept_len"]), _p(out["out_tokens"]),
                                  _p(out["log_ratio"]), _p(out["margin"]), _p(out["row_status"]),
                                  _p(out["gap"]))
+    return out
+
+
+def rfsd_verify_chain(target, draft, cand, T, div, mode=SAMPLE, seed=0, offset=0, seq_offset=0):
+    """Reducible FSD (Sec. 4.2): accept iff div <= T or the strict SD test accepts."""
+    target, draft = _c(target), _c(draft)
+    cand = _c(np.asarray(cand, dtype=np.int32))
+    B, K1, V = target.shape
+    K = K1 - 1
+    assert draft.shape == (B, K, V) and cand.shape == (B, K) and draft.dtype == target.dtype
+    out = dict(accept_len=np.zeros(B, np.int32), out_tokens=np.zeros((B, K + 1), np.int32),
+               divs=np.zeros((B, K)), log_ratio=np.zeros((B, K)), margin=np.zeros((B, K)),
+               row_status=np.zeros(B, np.int32), gap=np.zeros(B))
+    lib().rfsd_oracle_verify_chain(_p(target), _p(draft), _p(cand), B, K, V, _dt(target), int(div),
+                                   float(np.float32(T)), mode, seed, offset, seq_offset,
+                                   _p(out["accept_len"]), _p(out["out_tokens"]), _p(out["divs"]),
+                                   _p(out["log_ratio"]), _p(out["margin"]), _p(out["row_status"]),
+                                   _p(out["gap"]))
     return out

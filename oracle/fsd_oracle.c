@@ -430,3 +430,76 @@ int sd_oracle_verify_chain(const void* target, const void* draft, const int32_t*
     }
     return 0;
 }
+
+/* ------------------------------------------------- reducible FSD (rFSD) */
+
+/* Sec. 4.2 ("Reducing FSD to standard SD"): position i is accepted iff the
+ * divergence of its two distributions is within T (the FSD rule, with the same
+ * "<=" reading as fsd_oracle_verify_chain) OR the strict SD test of Sec. 3
+ * eq. 1-2 accepts the candidate token (same uniforms as sd_oracle_verify_chain).
+ * At the first rejection the token is resampled from the normalised positive
+ * part of p - q (Sec. 3 eq. 3), otherwise from the row after the last candidate.
+ * Outputs as sd_oracle_verify_chain plus divs [B,K]. */
+int rfsd_oracle_verify_chain(const void* target, const void* draft, const int32_t* cand, int B, int K,
+                             long V, int dt, int div_kind, double T, int mode, uint64_t seed,
+                             uint64_t offset, int seq_offset, int32_t* accept_len, int32_t* out_tokens,
+                             double* divs, double* log_ratio, double* margin, int32_t* row_status,
+                             double* gap) {
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        int status = 0;
+        int n = K;
+        double lse_n[2] = {NAN, NAN};
+        for (int i = 0; i < K; ++i) {
+            size_t toff = ((size_t)b * (size_t)(K + 1) + (size_t)i) * (size_t)V;
+            size_t doff = ((size_t)b * (size_t)K + (size_t)i) * (size_t)V;
+            double d3[3], lse2[2];
+            int pst = fsd_oracle_pair(target, toff, draft, doff, V, dt, d3, lse2);
+            status |= pst;
+            double d = d3[div_kind];
+            divs[(size_t)b * K + i] = d;
+            int32_t x = cand[(size_t)b * K + i];
+            double ratio = NAN, mar = NAN;
+            int sd_ok = 0;
+            if (x < 0 || x >= V) status |= ST_BAD_TOKEN;
+            if (!pst && x >= 0 && x < V) {
+                double lp = (double)load_f(target, toff + (size_t)x, dt) - lse2[0];
+                double lq = (double)load_f(draft, doff + (size_t)x, dt) - lse2[1];
+                ratio = (lp == -INFINITY) ? -INFINITY : lp - lq;
+                double u = (double)fsd_oracle_word_to_uniform(
+                    fsd_oracle_random_word(seed, offset, 1u, (uint32_t)(b + seq_offset), (uint32_t)i));
+                double thr = ratio < 0.0 ? ratio : 0.0;
+                mar = thr - log(u);
+                sd_ok = (mar > 0.0);
+            }
+            log_ratio[(size_t)b * K + i] = ratio;
+            margin[(size_t)b * K + i] = mar;
+            int ok = (d <= T) || sd_ok;
+            if (!ok && i < n) { n = i; lse_n[0] = lse2[0]; lse_n[1] = lse2[1]; }
+        }
+        size_t soff = ((size_t)b * (size_t)(K + 1) + (size_t)n) * (size_t)V;
+        if (!status && row_is_bad(target, soff, V, dt)) status |= ST_NONFINITE;
+        for (int i = 0; i <= K; ++i) out_tokens[(size_t)b * (K + 1) + i] = -1;
+        if (gap) gap[b] = INFINITY;
+        if (status) {
+            accept_len[b] = 0;
+        } else {
+            accept_len[b] = n;
+            for (int i = 0; i < n; ++i) out_tokens[(size_t)b * (K + 1) + i] = cand[(size_t)b * K + i];
+            int32_t y = -1;
+            if (n < K) {
+                size_t doff = ((size_t)b * (size_t)K + (size_t)n) * (size_t)V;
+                y = sample_residual(target, soff, draft, doff, V, dt, mode, seed, offset, (uint32_t)(b + seq_offset),
+                                    lse_n[0], lse_n[1], gap ? &gap[b] : NULL);
+            }
+            if (y < 0) {
+                float g32;
+                y = sample_row(target, soff, V, dt, mode, seed, offset, (uint32_t)(b + seq_offset), &g32);
+                if (gap) gap[b] = (double)g32;
+            }
+            out_tokens[(size_t)b * (K + 1) + n] = y;
+        }
+        row_status[b] = status;
+    }
+    return 0;
+}

@@ -457,3 +457,64 @@ def test_sd_identical_models_accept_everything(oracle):
     out = oracle.sd_verify_chain(t, t[:, :5].copy(), cand, seed=2)
     assert (out["accept_len"] == 5).all() and (out["log_ratio"] == 0).all()
     assert (out["out_tokens"][:, 5] >= 0).all()
+
+
+# ---- reducible FSD (Sec. 4.2): "div <= T or the strict SD test"
+
+def test_rfsd_reduces_to_sd_and_to_fsd(oracle):
+    t, d, cand = _small_chain(21, B=60, K=6)
+    for div in (0, 1, 2):
+        sd = oracle.sd_verify_chain(t, d, cand, seed=5, offset=3)
+        # no divergence of distinct rows is <= 0, and nothing is <= -1: the SD rule alone decides
+        for T in (0.0, -1.0):
+            r = oracle.rfsd_verify_chain(t, d, cand, T, div, seed=5, offset=3)
+            assert (r["accept_len"] == sd["accept_len"]).all()
+            assert (r["out_tokens"] == sd["out_tokens"]).all()
+            assert np.array_equal(r["log_ratio"], sd["log_ratio"])
+        # a threshold nothing exceeds: everything accepted, token from the row after the candidates
+        f = oracle.verify_chain(t, d, cand, 1e9, div, seed=5, offset=3)
+        r = oracle.rfsd_verify_chain(t, d, cand, 1e9, div, seed=5, offset=3)
+        assert (r["accept_len"] == 6).all() and (r["out_tokens"] == f["out_tokens"]).all()
+        assert np.array_equal(r["divs"], f["divs"])
+
+
+@pytest.mark.parametrize("div", [0, 1, 2])
+def test_rfsd_prefix_is_the_or_of_both_rules(oracle, div):
+    t, d, cand = _small_chain(22, B=80, K=7)
+    f = oracle.verify_chain(t, d, cand, 1e9, div, seed=9)
+    sd = oracle.sd_verify_chain(t, d, cand, seed=9)
+    T = float(np.median(f["divs"]))
+    r = oracle.rfsd_verify_chain(t, d, cand, T, div, seed=9)
+    ok = (f["divs"] <= np.float32(T)) | (sd["margin"] > 0)
+    want = np.array([int(np.argmin(row)) if not row.all() else 7 for row in ok])
+    assert (r["accept_len"] == want).all()
+    fT = oracle.verify_chain(t, d, cand, T, div, seed=9)
+    assert (r["accept_len"] >= np.maximum(fT["accept_len"], sd["accept_len"])).all()
+    assert 0 < (r["accept_len"] > sd["accept_len"]).sum()   # the threshold does add acceptances here
+    # accepted candidates are copied, the rest is padding
+    for b in range(80):
+        n = r["accept_len"][b]
+        assert (r["out_tokens"][b, :n] == cand[b, :n]).all() and (r["out_tokens"][b, n + 1:] == -1).all()
+
+
+def test_rfsd_rejections_resample_from_the_residual(oracle):
+    # one position, V = 8: a rejection needs div > T and the SD test failing; the token then follows
+    # norm(max(0, p - q)) exactly as in strict SD
+    rng = np.random.default_rng(3)
+    V, B = 8, 40000
+    zt = rng.standard_normal(V).astype(np.float32) * 1.5
+    zd = rng.standard_normal(V).astype(np.float32) * 1.5
+    p = np.exp(zt.astype(np.float64)); p /= p.sum()
+    q = np.exp(zd.astype(np.float64)); q /= q.sum()
+    cand = rng.choice(V, size=(B, 1), p=q).astype(np.int32)
+    t = np.broadcast_to(zt, (B, 2, V)).copy()
+    d = np.broadcast_to(zd, (B, 1, V)).copy()
+    r = oracle.rfsd_verify_chain(t, d, cand, 1e-6, 2, seed=77)      # TV(p, q) is far above 1e-6
+    sd = oracle.sd_verify_chain(t, d, cand, seed=77)
+    assert (r["accept_len"] == sd["accept_len"]).all() and (r["out_tokens"] == sd["out_tokens"]).all()
+    rej = r["accept_len"] == 0
+    res = np.maximum(p - q, 0); res /= res.sum()
+    obs = np.bincount(r["out_tokens"][rej, 0], minlength=V)
+    assert (obs[res == 0] == 0).all()
+    m = res > 0
+    assert (((obs[m] - obs.sum() * res[m]) ** 2 / (obs.sum() * res[m])).sum()) < 29.9
