@@ -150,6 +150,23 @@ int sd_verify_chain(const void* target_logits, const void* draft_logits, const i
                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Reducible FSD (paper Sec. 4.2, "Reducing FSD to standard SD"): position i is
+ * accepted iff div(p_i, q_i) <= T (the rule of fsd_verify_chain) OR the strict
+ * SD test of sd_verify_chain accepts the candidate token, with the same uniform
+ * numbers; at the first rejection the token is drawn from the normalised
+ * positive part of p - q, otherwise from the row after the last candidate.
+ * With T <= 0 and no bit-identical rows the outputs equal sd_verify_chain's.
+ * Tensors and outputs as in fsd_verify_chain, plus
+ *
+ *   log_ratio [B, K] out  optional, ln p_i(x_i) - ln q_i(x_i)
+ */
+int rfsd_verify_chain(const void* target_logits, const void* draft_logits, const int32_t* cand_tokens,
+                      int B, int K, int V, int dtype, int div, float T, int mode, uint64_t seed,
+                      uint64_t offset, int32_t* accept_len, int32_t* out_tokens, float* divergences,
+                      float* log_ratio, int32_t* row_status, void* workspace, size_t workspace_bytes,
+                      void* hip_stream);
+
+/*
  * Timing of the vocabulary-reduction kernel, for benchmarks.  After
  * fsd_profile_enable(1) every verify call brackets that kernel with a pair of
  * events on the call's stream (up to 4096 pairs are kept; later calls are

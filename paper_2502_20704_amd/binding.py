@@ -51,6 +51,9 @@ def library() -> ctypes.CDLL:
         L.sd_verify_chain.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, u64, u64,
                                       vp, vp, vp, vp, vp, sz, vp]
         L.sd_verify_chain.restype = i32
+        L.rfsd_verify_chain.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, f32, i32, u64, u64,
+                                        vp, vp, vp, vp, vp, vp, sz, vp]
+        L.rfsd_verify_chain.restype = i32
         L.fsd_profile_enable.argtypes = [i32]
         L.fsd_profile_enable.restype = i32
         L.fsd_profile_collect.argtypes = [vp, vp]
@@ -196,6 +199,36 @@ def sd_verify_chain(target, draft, cand, mode=SAMPLE, seed=0, offset=0, *, out=N
                                    _ptr(out.get("row_status")), wptr, wbytes, _stream(stream))
     if st != 0:
         raise FsdError(st, "sd_verify_chain")
+    out["_workspace"] = workspace
+    return out
+
+
+def rfsd_verify_chain(target, draft, cand, T, div=DIV_JS, mode=SAMPLE, seed=0, offset=0, *, out=None,
+                      workspace=None, stream=None):
+    """reducible FSD on the chain tensors -> accept_len, out_tokens, divergences, log_ratio, row_status."""
+    import torch
+
+    B, K1, V = target.shape
+    K = K1 - 1
+    dt = _dtype_code(target)
+    _check(target, "target")
+    _check(draft, "draft", (B, K, V), target.dtype)
+    _check(cand, "cand", (B, K), torch.int32)
+    dev = target.device
+    if out is None:
+        out = dict(accept_len=torch.empty(B, dtype=torch.int32, device=dev),
+                   out_tokens=torch.empty((B, K + 1), dtype=torch.int32, device=dev),
+                   divergences=torch.empty((B, K), dtype=torch.float32, device=dev),
+                   log_ratio=torch.empty((B, K), dtype=torch.float32, device=dev),
+                   row_status=torch.empty(B, dtype=torch.int32, device=dev))
+    need = fsd_workspace_bytes(B, K, V, dt)
+    workspace, wptr, wbytes = _workspace(workspace, need, dev)
+    st = library().rfsd_verify_chain(_ptr(target), _ptr(draft), _ptr(cand), B, K, V, dt, int(div), float(T), mode,
+                                     seed, offset, _ptr(out["accept_len"]), _ptr(out["out_tokens"]),
+                                     _ptr(out.get("divergences")), _ptr(out.get("log_ratio")),
+                                     _ptr(out.get("row_status")), wptr, wbytes, _stream(stream))
+    if st != 0:
+        raise FsdError(st, "rfsd_verify_chain")
     out["_workspace"] = workspace
     return out
 

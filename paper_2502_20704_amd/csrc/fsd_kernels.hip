@@ -32,7 +32,7 @@ constexpr double kLn2 = 0.69314718055994530942;
 // MODE_KL: single-pass KL (absolute error ~1e-7, enough for bfloat16 inputs); MODE_KLP: two-phase,
 // pointwise non-negative KL for binary32 inputs; MODE_LSE: normalisers only (strict SD)
 enum { MODE_KL = 0, MODE_JS = 1, MODE_TV = 2, MODE_LSE = 3, MODE_KLP = 4 };
-enum { KIND_CHAIN = 0, KIND_TREE = 1, KIND_SD = 2 };
+enum { KIND_CHAIN = 0, KIND_TREE = 1, KIND_SD = 2, KIND_RFSD = 3 };
 
 #define AGENT __HIP_MEMORY_SCOPE_AGENT
 
@@ -276,6 +276,8 @@ struct PairParams {
     unsigned long long* dbg;   // [grid][4 wavefronts][10]
 #endif
     float* user_div;        // optional [R]
+    float* user_ratio;      // optional [R], reducible FSD only
+    int want_ratio;         // 1: the finisher also writes ln p(x) - ln q(x) at the candidate token (reducible FSD)
     Ws ws;
 };
 
@@ -523,6 +525,26 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
         }
     };
 
+    // strict SD's ln p(x) - ln q(x) at the candidate token (Sec. 3, eq. 1) from the rows' log2-sum-exp2;
+    // lane 0 only.  Returns the status bits it adds.
+    auto write_ratio = [&](int pair, double lse2_t, double lse2_d, int status, float* user) __attribute__((always_inline)) -> int {
+        const int x = P.cand[pair];
+        double ratio = __builtin_nan("");
+        int add = 0;
+        if (x < 0 || x >= P.V) {
+            add = FSD_ROW_BAD_TOKEN;
+        } else if (!(status & FSD_ROW_NONFINITE)) {
+            const char *tptr, *dptr;
+            row_ptrs(pair, tptr, dptr);
+            const double lp = static_cast<double>(load_elem<BF16>(tptr, x)) - lse2_t * kLn2;
+            const double lq = static_cast<double>(load_elem<BF16>(dptr, x)) - lse2_d * kLn2;
+            ratio = (lp == -__builtin_inf()) ? -__builtin_inf() : lp - lq;
+        }
+        P.ws.lr[pair] = ratio;
+        if (user) user[pair] = static_cast<float>(ratio);
+        return add;
+    };
+
     // ---- finishing a pair: add what the team posted for it, in member order.  fw holds the words of
     // the first 64 members, requested earlier.
     auto finish_two_phase = [&](int pair, unsigned long long (&fw)[FW]) __attribute__((always_inline)) {
@@ -553,10 +575,36 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
         if (!s.ok) status |= FSD_ROW_INTERNAL;
         if (value < 0.0) value = 0.0;
         if (status) value = __builtin_nan("");
+        double lse2_t = 0.0, lse2_d = 0.0;
+        if (P.want_ratio) {
+            // reducible FSD also needs the rows' normalisers: the team's phase-1 words once more, this
+            // time merged in float64 (they were all posted before the divergence words read above)
+            const unsigned long long* p1 = part1 + static_cast<size_t>(pair) * GW * 4;
+            float Kt = neg_inf(), Kd = neg_inf();
+            double Zt = 0.0, Zd = 0.0;
+            bool ok = true;
+            for (int base = 0; base < GW; base += 64) {
+                const WordsN<2> r = repoll_n<2>(p1, GW, base, P.spin_limit);
+                ok &= r.ok;
+                const bool in = base + lane < GW;
+                const float kt = lo_f(r.w[0]), kd = hi_f(r.w[0]);
+                const double St = in ? static_cast<double>(lo_f(r.w[1])) : 0.0, Sd = in ? static_cast<double>(hi_f(r.w[1])) : 0.0;
+                const float nKt = fmaxf(Kt, wave_max((St > 0.0) ? kt : neg_inf()));
+                const float nKd = fmaxf(Kd, wave_max((Sd > 0.0) ? kd : neg_inf()));
+                Zt = ((Zt > 0.0) ? ldexp(Zt, kdiff(Kt, nKt)) : Zt) + wave_sum((St > 0.0) ? ldexp(St, kdiff(kt, nKt)) : 0.0);
+                Zd = ((Zd > 0.0) ? ldexp(Zd, kdiff(Kd, nKd)) : Zd) + wave_sum((Sd > 0.0) ? ldexp(Sd, kdiff(kd, nKd)) : 0.0);
+                Kt = nKt;
+                Kd = nKd;
+            }
+            if (!ok) status |= FSD_ROW_INTERNAL;
+            lse2_t = static_cast<double>(Kt) + log2(Zt);
+            lse2_d = static_cast<double>(Kd) + log2(Zd);
+        }
         if (lane == 0) {
+            if (P.want_ratio) status |= write_ratio(pair, lse2_t, lse2_d, status, P.user_ratio);
             P.ws.div[pair] = static_cast<float>(value);
-            P.ws.lse2[2 * pair] = 0.0;
-            P.ws.lse2[2 * pair + 1] = 0.0;
+            P.ws.lse2[2 * pair] = lse2_t;
+            P.ws.lse2[2 * pair + 1] = lse2_d;
             if (P.user_div) P.user_div[pair] = static_cast<float>(value);
             P.ws.pst[pair] = status;
         }
@@ -615,20 +663,9 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
             P.ws.lse2[2 * pair + 1] = lse2_d;
             if (P.user_div) P.user_div[pair] = static_cast<float>(value);
             if constexpr (MODE == MODE_LSE) {
-                // strict SD: ln p(x) - ln q(x) at the candidate token (Sec. 3, eq. 1)
-                const int x = P.cand[pair];
-                double ratio = __builtin_nan("");
-                if (x < 0 || x >= P.V) {
-                    status |= FSD_ROW_BAD_TOKEN;
-                } else if (!(status & FSD_ROW_NONFINITE)) {
-                    const char *tptr, *dptr;
-                    row_ptrs(pair, tptr, dptr);
-                    const double lp = static_cast<double>(load_elem<BF16>(tptr, x)) - lse2_t * kLn2;
-                    const double lq = static_cast<double>(load_elem<BF16>(dptr, x)) - lse2_d * kLn2;
-                    ratio = (lp == -__builtin_inf()) ? -__builtin_inf() : lp - lq;
-                }
-                P.ws.lr[pair] = ratio;
-                if (P.user_div) P.user_div[pair] = static_cast<float>(ratio);
+                status |= write_ratio(pair, lse2_t, lse2_d, status, P.user_div);
+            } else {
+                if (P.want_ratio) status |= write_ratio(pair, lse2_t, lse2_d, status, P.user_ratio);
             }
             P.ws.pst[pair] = status;
         }
@@ -946,14 +983,15 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
     int n = 0;         // accepted prefix length / path depth
     int sample_row = 0;
     int winner = -1;
-    if constexpr (KIND == KIND_CHAIN || KIND == KIND_SD) {
+    if constexpr (KIND == KIND_CHAIN || KIND == KIND_SD || KIND == KIND_RFSD) {
         for (int i = tid; i < rows; i += kWG) {
             const int pr = b * rows + i;
             const int st = P.ws.pst[pr];
-            bool ok;
-            if constexpr (KIND == KIND_CHAIN) {
+            bool ok = false;
+            if constexpr (KIND == KIND_CHAIN || KIND == KIND_RFSD) {
                 ok = (P.ws.div[pr] <= P.T);   // Sec. 4 eq. 4 (NaN compares false)
-            } else {
+            }
+            if constexpr (KIND == KIND_SD || KIND == KIND_RFSD) {   // reducible FSD (Sec. 4.2): either rule accepts
                 // Sec. 3 eq. 1-2 in the log domain: min(1, p/q) > u  <=>  min(0, ln p - ln q) - ln u > 0
                 const double ratio = P.ws.lr[pr];
                 const U4 r = philox4x32_10((static_cast<unsigned>(i) >> 2) | (1u << 30), static_cast<unsigned>(b),
@@ -961,7 +999,7 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
                 const unsigned wsel = (i & 3) == 0 ? r.x : (i & 3) == 1 ? r.y : (i & 3) == 2 ? r.z : r.w;
                 const double u = static_cast<double>(word_to_uniform(wsel));
                 const double thr = ratio < 0.0 ? ratio : 0.0;
-                ok = (thr - log(u) > 0.0);
+                ok = ok || (thr - log(u) > 0.0);
             }
             if (st) atomicOr(&s_st, st);
             if (!ok) atomicMin(&s_n, i);
@@ -1022,7 +1060,7 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
     bool residual = false;
     const char* drow = nullptr;
     float lt = 0.0f, ld = 0.0f;
-    if constexpr (KIND == KIND_SD) {
+    if constexpr (KIND == KIND_SD || KIND == KIND_RFSD) {
         if (n < rows) {   // rejected at n: the residual of Sec. 3 eq. 3 needs the draft row as well
             residual = true;
             drow = P.draft + (static_cast<size_t>(b) * rows + n) * static_cast<size_t>(P.V) * ES;
@@ -1364,6 +1402,7 @@ void launch_sample_k(int kind, dim3 grid, size_t lds, hipStream_t st, const Samp
     switch (kind) {
         case KIND_CHAIN: hipLaunchKernelGGL((accept_sample<BF16, ALIGNED, KIND_CHAIN>), grid, dim3(kWG), lds, st, P); break;
         case KIND_TREE: hipLaunchKernelGGL((accept_sample<BF16, ALIGNED, KIND_TREE>), grid, dim3(kWG), lds, st, P); break;
+        case KIND_RFSD: hipLaunchKernelGGL((accept_sample<BF16, ALIGNED, KIND_RFSD>), grid, dim3(kWG), lds, st, P); break;
         default: hipLaunchKernelGGL((accept_sample<BF16, ALIGNED, KIND_SD>), grid, dim3(kWG), lds, st, P); break;
     }
 }
@@ -1385,8 +1424,8 @@ bool is_aligned(const void* a, const void* b, long V, int VE) {
 // the common body of the three entry points
 int run(int kind, const void* target, const void* draft, const int32_t* tokens, const int32_t* parent, int B,
         int rows, int max_depth, int V, int dtype, int div, float T, int mode, uint64_t seed, uint64_t offset,
-        int32_t* out_len, int32_t* path_nodes, int32_t* out_tokens, float* user_vals, int32_t* row_status,
-        void* workspace, size_t workspace_bytes, void* hip_stream) {
+        int32_t* out_len, int32_t* path_nodes, int32_t* out_tokens, float* user_vals, float* user_ratio,
+        int32_t* row_status, void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!target || !draft || !tokens || !out_len || !out_tokens) return FSD_ERR_NULL;
     if (kind == KIND_TREE && (!parent || !path_nodes)) return FSD_ERR_NULL;
     if (dtype != FSD_F32 && dtype != FSD_BF16) return FSD_ERR_DTYPE;
@@ -1424,6 +1463,8 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
     pp.dbg = g_dbg;
 #endif
     pp.user_div = user_vals;
+    pp.user_ratio = user_ratio;
+    pp.want_ratio = (kind == KIND_RFSD) ? 1 : 0;
     pp.ws = ws;
     int k1mode = (kind == KIND_SD) ? MODE_LSE : div;
     if (k1mode == MODE_KL && dtype == FSD_F32) k1mode = MODE_KLP;
@@ -1495,7 +1536,7 @@ int fsd_verify_chain(const void* target_logits, const void* draft_logits, const 
                      int32_t* accept_len, int32_t* out_tokens, float* divergences, int32_t* row_status,
                      void* workspace, size_t workspace_bytes, void* hip_stream) {
     return run(KIND_CHAIN, target_logits, draft_logits, cand_tokens, nullptr, B, K, 0, V, dtype, div, T, mode, seed,
-               offset, accept_len, nullptr, out_tokens, divergences, row_status, workspace, workspace_bytes,
+               offset, accept_len, nullptr, out_tokens, divergences, nullptr, row_status, workspace, workspace_bytes,
                hip_stream);
 }
 
@@ -1505,7 +1546,7 @@ int fsd_verify_tree(const void* target_logits, const void* draft_logits, const i
                     int32_t* out_tokens, float* divergences, int32_t* row_status, void* workspace,
                     size_t workspace_bytes, void* hip_stream) {
     return run(KIND_TREE, target_logits, draft_logits, node_tokens, parent, B, N, max_depth, V, dtype, div, T, mode,
-               seed, offset, path_len, path_nodes, out_tokens, divergences, row_status, workspace,
+               seed, offset, path_len, path_nodes, out_tokens, divergences, nullptr, row_status, workspace,
                workspace_bytes, hip_stream);
 }
 
@@ -1514,8 +1555,17 @@ int sd_verify_chain(const void* target_logits, const void* draft_logits, const i
                     int32_t* out_tokens, float* log_ratio, int32_t* row_status, void* workspace,
                     size_t workspace_bytes, void* hip_stream) {
     return run(KIND_SD, target_logits, draft_logits, cand_tokens, nullptr, B, K, 0, V, dtype, FSD_DIV_KL, 0.0f, mode,
-               seed, offset, accept_len, nullptr, out_tokens, log_ratio, row_status, workspace, workspace_bytes,
+               seed, offset, accept_len, nullptr, out_tokens, log_ratio, nullptr, row_status, workspace, workspace_bytes,
                hip_stream);
+}
+
+int rfsd_verify_chain(const void* target_logits, const void* draft_logits, const int32_t* cand_tokens, int B, int K,
+                      int V, int dtype, int div, float T, int mode, uint64_t seed, uint64_t offset,
+                      int32_t* accept_len, int32_t* out_tokens, float* divergences, float* log_ratio,
+                      int32_t* row_status, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return run(KIND_RFSD, target_logits, draft_logits, cand_tokens, nullptr, B, K, 0, V, dtype, div, T, mode, seed,
+               offset, accept_len, nullptr, out_tokens, divergences, log_ratio, row_status, workspace,
+               workspace_bytes, hip_stream);
 }
 
 int fsd_profile_enable(int on) {

@@ -204,6 +204,78 @@ def test_strict_sd_small(torch_cuda, oracle):
             check_sd(g, o, f"SD B={B} K={K} V={V} {dtype} mode={mode}")
 
 
+def check_rfsd(g, o, T, tol, what):
+    """reducible FSD: a position is decided by div <= T or by the SD margin; a sequence may differ
+    from the oracle only where the deciding quantity sits on its threshold."""
+    assert (g["row_status"] == o["row_status"]).all(), what
+    pu.check_divs(g["divergences"], o["divs"], tol, what)
+    fin = np.isfinite(o["log_ratio"])
+    assert (np.isfinite(g["log_ratio"]) == fin).all()
+    assert np.allclose(g["log_ratio"][fin], o["log_ratio"][fin], rtol=2e-5, atol=2e-5), what
+    near = pu.near_threshold(o["divs"], T) | (np.abs(o["margin"]) <= 1e-5)
+    n_near = n_tie = 0
+    for b in range(o["accept_len"].shape[0]):
+        ng, no = int(g["accept_len"][b]), int(o["accept_len"][b])
+        if ng != no:
+            assert near[b, min(ng, no)], f"{what}: accept_len[{b}] gpu {ng} oracle {no}"
+            n_near += 1
+            continue
+        if not (g["out_tokens"][b] == o["out_tokens"][b]).all():
+            assert o["gap"][b] < 1e-4, f"{what}: tokens[{b}] gpu {g['out_tokens'][b]} oracle {o['out_tokens'][b]} gap {o['gap'][b]}"
+            n_tie += 1
+    assert n_near + n_tie <= max(2, o["accept_len"].shape[0] // 20), what
+    return dict(near=n_near, ties=n_tie)
+
+
+def run_rfsd(torch_cuda, inp, T, div, mode=None, seed=0, offset=0):
+    d = pu.to_dev(inp, ("target", "draft", "cand"))
+    out = fsd.rfsd_verify_chain(d["target"], d["draft"], d["cand"], T, div, fsd.SAMPLE if mode is None else mode,
+                                seed, offset)
+    torch_cuda.cuda.synchronize()
+    return pu.host(out, pu.RFSD_KEYS)
+
+
+def test_rfsd_small(torch_cuda, oracle):
+    for (B, K, V, dtype, kind, sigma) in SMALL[:7]:
+        inp = synth.chain_inputs(B, K, V, dtype, kind, sigma, seed=31)
+        tol = pu.rel_tol(dtype)
+        for div in (fsd.DIV_KL, fsd.DIV_JS, fsd.DIV_TV):
+            base = oracle.verify_chain(inp["target"], inp["draft"], inp["cand"], 1e9, div)
+            T = float(np.float32(np.median(base["divs"])))
+            for mode in (fsd.SAMPLE, fsd.GREEDY):
+                g = run_rfsd(torch_cuda, inp, T, div, mode, seed=8, offset=2)
+                o = oracle.rfsd_verify_chain(inp["target"], inp["draft"], inp["cand"], T, div, mode, seed=8, offset=2)
+                check_rfsd(g, o, T, tol, f"rFSD B={B} K={K} V={V} {dtype} div={div} mode={mode}")
+
+
+def test_rfsd_reduces_to_strict_sd_and_to_fsd(torch_cuda, oracle):
+    """Sec. 4.2: with T = 0 the rule is strict SD's (bit-identical outputs); with a threshold nothing
+    exceeds it is FSD's."""
+    inp = synth.chain_inputs(16, 6, 32000, "bf16", "peaked", (0.25, 4.0), seed=33)
+    d = pu.to_dev(inp, ("target", "draft", "cand"))
+    sd = fsd.sd_verify_chain(d["target"], d["draft"], d["cand"], seed=12, offset=5)
+    torch_cuda.cuda.synchronize()
+    sd = pu.host(sd, pu.SD_KEYS)
+    for div in (fsd.DIV_KL, fsd.DIV_JS, fsd.DIV_TV):
+        g = run_rfsd(torch_cuda, inp, 0.0, div, seed=12, offset=5)
+        assert (g["accept_len"] == sd["accept_len"]).all() and (g["out_tokens"] == sd["out_tokens"]).all()
+        f = run_chain(torch_cuda, inp, 1e9, div, seed=12, offset=5)
+        g = run_rfsd(torch_cuda, inp, 1e9, div, seed=12, offset=5)
+        assert (g["accept_len"] == 6).all() and (g["out_tokens"] == f["out_tokens"]).all()
+        assert np.array_equal(g["divergences"], f["divergences"])
+
+
+def test_config_c2_rfsd(torch_cuda, oracle):
+    inp = synth.config_inputs("C2", seed=0)
+    for div in (fsd.DIV_JS, fsd.DIV_KL):
+        g = run_rfsd(torch_cuda, inp, 0.1, div, seed=4, offset=1)
+        o = oracle.rfsd_verify_chain(inp["target"], inp["draft"], inp["cand"], 0.1, div, seed=4, offset=1)
+        r = check_rfsd(g, o, 0.1, 2e-3, f"C2 rFSD div={div}")
+        sd = oracle.sd_verify_chain(inp["target"], inp["draft"], inp["cand"], seed=4, offset=1)
+        print("C2 rFSD", div, r, "accept_len histogram", np.bincount(o["accept_len"], minlength=9),
+              "strict SD", np.bincount(sd["accept_len"], minlength=9), flush=True)
+
+
 def test_config_c3_sampled(torch_cuda, oracle):
     """full-size C3 on the GPU; the oracle checks a sample of its sequences one by one."""
     c = synth.CONFIGS["C3"]
