@@ -191,3 +191,32 @@ def rfsd_verify_chain(target, draft, cand, T, div, mode=SAMPLE, seed=0, offset=0
                                    _p(out["log_ratio"]), _p(out["margin"]), _p(out["row_status"]),
                                    _p(out["gap"]))
     return out
+
+
+def accepted_fraction(divs, T):
+    """Share of all candidate positions the chain rule accepts at threshold T (Sec. 4 eq. 4 with the
+    "<=" reading): per sequence, the positions before the first one whose divergence exceeds T."""
+    divs = np.asarray(divs, dtype=np.float64)
+    B, K = divs.shape
+    acc = 0
+    for b in range(B):
+        for i in range(K):
+            if not (divs[b, i] <= T):   # NaN rejects
+                break
+            acc += 1
+    return acc / float(B * K)
+
+
+def calibrate_threshold(divs, fraction):
+    """Threshold tuning on a dev set (Sec. 5.3 "Tuning T on small dev set"; App. A: the T that accepts
+    about the same share of candidate tokens as strict SD): the smallest T, among the divergences that
+    occur (and +inf), at which the chain rule accepts at least `fraction` of all candidate positions.
+    Plain search over every candidate value; returns (T, accepted fraction at T).  0 < fraction <= 1."""
+    assert 0.0 < fraction <= 1.0
+    divs = np.asarray(divs, dtype=np.float64)
+    values = np.unique(np.concatenate([divs[np.isfinite(divs)].ravel(), [np.inf]]))
+    for T in values:            # ascending
+        f = accepted_fraction(divs, T)
+        if f >= fraction:
+            return float(T), f
+    return float("inf"), accepted_fraction(divs, np.inf)

@@ -518,3 +518,42 @@ def test_rfsd_rejections_resample_from_the_residual(oracle):
     assert (obs[res == 0] == 0).all()
     m = res > 0
     assert (((obs[m] - obs.sum() * res[m]) ** 2 / (obs.sum() * res[m])).sum()) < 29.9
+
+
+# ---- threshold tuning on a dev set
+
+def test_calibration_matches_order_statistic_of_prefix_maxima(oracle):
+    # a position is accepted iff every divergence up to it is <= T, i.e. iff the running maximum is:
+    # the tuned threshold is therefore an order statistic of the running maxima (independent route)
+    rng = np.random.default_rng(5)
+    for B, K in ((1, 1), (3, 4), (17, 8), (40, 5)):
+        divs = rng.gamma(0.7, 0.2, size=(B, K)).astype(np.float32)
+        divs[rng.random((B, K)) < 0.1] = 0.0
+        run_max = np.maximum.accumulate(divs.astype(np.float64), axis=1).ravel()
+        srt = np.sort(run_max)
+        n = B * K
+        for frac in (1e-9, 0.25, 0.5, 0.731, 1.0):
+            T, got = oracle.calibrate_threshold(divs, frac)
+            k = int(math.ceil(frac * n - 1e-12))
+            assert T == srt[k - 1]
+            assert got == (run_max <= T).mean() >= frac
+            # minimal: the next smaller value that occurs does not reach the target
+            smaller = srt[srt < T]
+            if smaller.size:
+                assert oracle.accepted_fraction(divs, smaller[-1]) < frac
+
+
+def test_calibration_agrees_with_the_verifier(oracle):
+    # the fraction the tuned threshold promises is what verify_chain then accepts
+    t, d, cand = _small_chain(41, B=30, K=6, sigma=1.5)
+    base = oracle.verify_chain(t, d, cand, 1e9, 1)
+    sd = oracle.sd_verify_chain(t, d, cand, seed=3)
+    target = sd["accept_len"].sum() / sd["accept_len"].size / 6.0      # strict SD's share (App. A)
+    T, frac = oracle.calibrate_threshold(base["divs"].astype(np.float32), target)
+    out = oracle.verify_chain(t, d, cand, T, 1)
+    assert out["accept_len"].sum() / (30 * 6.0) == frac >= target
+    # NaN divergences (unusable rows) are never accepted and +inf is the last resort
+    divs = np.array([[0.1, np.nan, 0.0], [0.2, 0.3, 0.05]], dtype=np.float32)
+    assert oracle.calibrate_threshold(divs, 0.5) == (float(np.float32(0.3)), 4 / 6)   # 0.2 accepts 2 of 6 only
+    assert oracle.calibrate_threshold(divs, 0.9)[0] == float("inf")
+    assert oracle.calibrate_threshold(divs, 0.9)[1] == 4 / 6
