@@ -167,6 +167,28 @@ int rfsd_verify_chain(const void* target_logits, const void* draft_logits, const
                       void* hip_stream);
 
 /*
+ * Threshold tuning on a dev set (paper Sec. 5.3 "Tuning T on small dev set";
+ * App. A: the threshold that accepts about the same share of candidate tokens
+ * as strict SD).  From the divergences of a batch of candidate sequences (the
+ * `divergences` output of fsd_verify_chain, any T) it finds the smallest
+ * threshold, among the values that occur, at which the chain rule accepts at
+ * least `target_fraction` of all B*K candidate positions; +inf if no threshold
+ * does (NaN divergences are never accepted).  Exact: the result is one of the
+ * input values.
+ *
+ *   divergences  [B, K] device, binary32, >= 0 or NaN
+ *   target_fraction      0 < f <= 1 (e.g. sum(accept_len of strict SD) / (B*K))
+ *   T_out        [1] device out   the threshold
+ *   fraction_out [1] device out   optional, the share accepted at T_out
+ *   workspace    device, 256-byte aligned, fsd_calibrate_workspace_bytes(B, K)
+ *
+ * Asynchronous on hip_stream like the verify calls; limits as there.
+ */
+size_t fsd_calibrate_workspace_bytes(int B, int K);
+int fsd_calibrate_threshold(const float* divergences, int B, int K, float target_fraction, float* T_out,
+                            float* fraction_out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Timing of the vocabulary-reduction kernel, for benchmarks.  After
  * fsd_profile_enable(1) every verify call brackets that kernel with a pair of
  * events on the call's stream (up to 4096 pairs are kept; later calls are

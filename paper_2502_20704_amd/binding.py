@@ -54,6 +54,10 @@ def library() -> ctypes.CDLL:
         L.rfsd_verify_chain.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, f32, i32, u64, u64,
                                         vp, vp, vp, vp, vp, vp, sz, vp]
         L.rfsd_verify_chain.restype = i32
+        L.fsd_calibrate_workspace_bytes.argtypes = [i32, i32]
+        L.fsd_calibrate_workspace_bytes.restype = sz
+        L.fsd_calibrate_threshold.argtypes = [vp, i32, i32, f32, vp, vp, vp, sz, vp]
+        L.fsd_calibrate_threshold.restype = i32
         L.fsd_profile_enable.argtypes = [i32]
         L.fsd_profile_enable.restype = i32
         L.fsd_profile_collect.argtypes = [vp, vp]
@@ -231,6 +235,29 @@ def rfsd_verify_chain(target, draft, cand, T, div=DIV_JS, mode=SAMPLE, seed=0, o
         raise FsdError(st, "rfsd_verify_chain")
     out["_workspace"] = workspace
     return out
+
+
+def fsd_calibrate_threshold(divergences, target_fraction: float, *, stream=None):
+    """(T, accepted fraction) as 1-element device tensors: the smallest occurring threshold at which
+    the chain rule accepts at least `target_fraction` of the candidate positions of `divergences`."""
+    import torch
+
+    _check(divergences, "divergences", None, torch.float32)
+    B, K = divergences.shape
+    dev = divergences.device
+    need = int(library().fsd_calibrate_workspace_bytes(B, K))
+    if need == 0:
+        raise FsdError(-2, "fsd_calibrate_workspace_bytes")
+    ws = torch.empty(need + 256, dtype=torch.uint8, device=dev)
+    off = (-ws.data_ptr()) % 256
+    T = torch.empty(1, dtype=torch.float32, device=dev)
+    frac = torch.empty(1, dtype=torch.float32, device=dev)
+    st = library().fsd_calibrate_threshold(_ptr(divergences), B, K, float(target_fraction), _ptr(T), _ptr(frac),
+                                           ctypes.c_void_p(ws.data_ptr() + off), need, _stream(stream))
+    if st != 0:
+        raise FsdError(st, "fsd_calibrate_threshold")
+    T._workspace = ws   # keep the workspace alive until the stream has used it
+    return T, frac
 
 
 def profile_enable(on: bool) -> None:

@@ -1216,6 +1216,82 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
 }
 
 // ------------------------------------------------------------------------------------------
+// threshold tuning on a dev set (Sec. 5.3, App. A): the smallest occurring T at which the chain rule
+// accepts a given share of all candidate positions.  A position is accepted iff every divergence up
+// to it is <= T, i.e. iff the running maximum of its sequence is: T is the ceil(fraction n)-th
+// smallest running maximum.  Non-negative binary32 values order like their bit patterns, so the
+// order statistic is found exactly by a radix select over four 8-bit digits.
+
+struct CalibState { unsigned prefix, mask, rank, count_le; unsigned hist[256]; };
+constexpr unsigned kCalibInf = 0x7F800000u, kCalibNever = 0x7FFFFFFFu;
+
+__global__ void calib_keys(const float* div, int B, int K, unsigned* keys) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    float m = 0.0f;
+    bool dead = false;
+    for (int i = 0; i < K; ++i) {
+        const float d = div[static_cast<size_t>(b) * K + i];
+        // an unusable position (NaN) is never accepted, nor is anything after it: a key above +inf
+        dead |= (d != d);
+        m = fmaxf(m, d);
+        keys[static_cast<size_t>(b) * K + i] = dead ? kCalibNever : __float_as_uint(m);
+    }
+}
+__global__ void calib_init(CalibState* st, unsigned rank) {
+    const int t = threadIdx.x;
+    if (t == 0) { st->prefix = 0u; st->mask = 0u; st->rank = rank; st->count_le = 0u; }
+    st->hist[t] = 0u;
+}
+__global__ void calib_hist(const unsigned* keys, long n, int shift, CalibState* st) {
+    __shared__ unsigned h[256];
+    h[threadIdx.x] = 0u;
+    __syncthreads();
+    const unsigned prefix = st->prefix, mask = st->mask;
+    for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < n; i += static_cast<long>(gridDim.x) * blockDim.x) {
+        const unsigned k = keys[i];
+        if ((k & mask) == prefix) atomicAdd(&h[(k >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (h[threadIdx.x]) atomicAdd(&st->hist[threadIdx.x], h[threadIdx.x]);
+}
+// one workgroup of 256: the digit whose cumulative count reaches the rank; clears the histogram
+__global__ void calib_pick(CalibState* st, int shift) {
+    __shared__ unsigned h[256];
+    const int t = threadIdx.x;
+    h[t] = st->hist[t];
+    st->hist[t] = 0u;
+    __syncthreads();
+    if (t == 0) {
+        unsigned rank = st->rank, below = 0u;
+        int d = 0;
+        for (; d < 255; ++d) {
+            if (below + h[d] >= rank) break;
+            below += h[d];
+        }
+        st->prefix |= static_cast<unsigned>(d) << shift;
+        st->mask |= 255u << shift;
+        st->rank = rank - below;
+    }
+}
+__global__ void calib_count(const unsigned* keys, long n, CalibState* st) {
+    __shared__ unsigned c;
+    if (threadIdx.x == 0) c = 0u;
+    __syncthreads();
+    const unsigned key = st->prefix < kCalibInf ? st->prefix : kCalibInf;   // no threshold reaches the target: +inf
+    unsigned mine = 0u;
+    for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < n; i += static_cast<long>(gridDim.x) * blockDim.x)
+        mine += (keys[i] <= key) ? 1u : 0u;
+    if (mine) atomicAdd(&c, mine);
+    __syncthreads();
+    if (threadIdx.x == 0 && c) atomicAdd(&st->count_le, c);
+}
+__global__ void calib_result(const CalibState* st, long n, float* T_out, float* fraction_out) {
+    *T_out = __uint_as_float(st->prefix < kCalibInf ? st->prefix : kCalibInf);
+    if (fraction_out) *fraction_out = static_cast<float>(static_cast<double>(st->count_le) / static_cast<double>(n));
+}
+
+// ------------------------------------------------------------------------------------------
 // host side: planning, workspace, launches
 
 struct Plan {
@@ -1515,6 +1591,39 @@ size_t fsd_workspace_bytes(int B, int rows_per_seq, int V, int dtype) {
     Plan p;
     if (!make_plan(B, rows_per_seq, V, dtype, p)) return 0;
     return p.bytes;
+}
+
+size_t fsd_calibrate_workspace_bytes(int B, int K) {
+    if (B < 1 || K < 1 || K > kMaxRows || static_cast<long>(B) * K >= (1L << 24)) return 0;
+    return align_up(sizeof(CalibState), 256) + align_up(static_cast<size_t>(B) * K * 4, 256);
+}
+
+int fsd_calibrate_threshold(const float* divergences, int B, int K, float target_fraction, float* T_out,
+                            float* fraction_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!divergences || !T_out) return FSD_ERR_NULL;
+    const size_t need = fsd_calibrate_workspace_bytes(B, K);
+    if (need == 0 || !(target_fraction > 0.0f) || !(target_fraction <= 1.0f)) return FSD_ERR_SHAPE;
+    if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 != 0 || workspace_bytes < need) return FSD_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    CalibState* state = static_cast<CalibState*>(workspace);
+    unsigned* keys = reinterpret_cast<unsigned*>(static_cast<char*>(workspace) + align_up(sizeof(CalibState), 256));
+    const long n = static_cast<long>(B) * K;
+    // rank = ceil(fraction n), in exact arithmetic on the binary32 fraction
+    const double want = static_cast<double>(target_fraction) * static_cast<double>(n);
+    long rank = static_cast<long>(want);
+    if (static_cast<double>(rank) < want) ++rank;
+    if (rank < 1) rank = 1;
+    if (rank > n) rank = n;
+    const unsigned blocks = static_cast<unsigned>(n / 4096 + 1 > 1024 ? 1024 : n / 4096 + 1);
+    hipLaunchKernelGGL(calib_keys, dim3((B + 255) / 256), dim3(256), 0, st, divergences, B, K, keys);
+    hipLaunchKernelGGL(calib_init, dim3(1), dim3(256), 0, st, state, static_cast<unsigned>(rank));
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        hipLaunchKernelGGL(calib_hist, dim3(blocks), dim3(256), 0, st, keys, n, shift, state);
+        hipLaunchKernelGGL(calib_pick, dim3(1), dim3(256), 0, st, state, shift);
+    }
+    hipLaunchKernelGGL(calib_count, dim3(blocks), dim3(256), 0, st, keys, n, state);
+    hipLaunchKernelGGL(calib_result, dim3(1), dim3(1), 0, st, state, n, T_out, fraction_out);
+    return (hipGetLastError() == hipSuccess) ? FSD_OK : FSD_ERR_LAUNCH;
 }
 
 const char* fsd_status_string(int status) {

@@ -86,6 +86,31 @@ def test_tree_and_sd_argument_errors():
     assert st == -5
 
 
+def test_rfsd_and_calibration_argument_errors():
+    L = fsd.library()
+    big = 1 << 30
+    st = L.rfsd_verify_chain(FAKE, FAKE, None, 1, 4, 100, fsd.F32, fsd.DIV_JS, 0.1, 0, 0, 0, FAKE, FAKE, None, None,
+                             None, FAKE, big, None)
+    assert st == -1                                           # candidate tokens missing
+    st = L.rfsd_verify_chain(FAKE, FAKE, FAKE, 1, 4, 100, fsd.F32, 7, 0.1, 0, 0, 0, FAKE, FAKE, None, None,
+                             None, FAKE, big, None)
+    assert st == -4
+    st = L.rfsd_verify_chain(FAKE, FAKE, FAKE, 1, 4, 100, fsd.F32, fsd.DIV_TV, float("nan"), 0, 0, 0, FAKE, FAKE,
+                             None, None, None, FAKE, big, None)
+    assert st == -2
+    need = L.fsd_calibrate_workspace_bytes(64, 8)
+    assert need >= 64 * 8 * 4 and need % 256 == 0
+    assert L.fsd_calibrate_workspace_bytes(0, 8) == 0 and L.fsd_calibrate_workspace_bytes(8, 0) == 0
+    assert L.fsd_calibrate_threshold(None, 64, 8, 0.5, FAKE, None, FAKE, need, None) == -1
+    assert L.fsd_calibrate_threshold(FAKE, 64, 8, 0.5, None, None, FAKE, need, None) == -1
+    assert L.fsd_calibrate_threshold(FAKE, 64, 8, 0.0, FAKE, None, FAKE, need, None) == -2
+    assert L.fsd_calibrate_threshold(FAKE, 64, 8, 1.5, FAKE, None, FAKE, need, None) == -2
+    assert L.fsd_calibrate_threshold(FAKE, 64, 8, float("nan"), FAKE, None, FAKE, need, None) == -2
+    assert L.fsd_calibrate_threshold(FAKE, 0, 8, 0.5, FAKE, None, FAKE, need, None) == -2
+    assert L.fsd_calibrate_threshold(FAKE, 64, 8, 0.5, FAKE, None, FAKE, need - 1, None) == -5
+    assert L.fsd_calibrate_threshold(FAKE, 64, 8, 0.5, FAKE, None, None, need, None) == -5
+
+
 def test_status_strings():
     L = fsd.library()
     seen = {L.fsd_status_string(s) for s in range(-7, 1)}

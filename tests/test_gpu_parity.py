@@ -276,6 +276,46 @@ def test_config_c2_rfsd(torch_cuda, oracle):
               "strict SD", np.bincount(sd["accept_len"], minlength=9), flush=True)
 
 
+def test_threshold_calibration(torch_cuda, oracle):
+    """fsd_calibrate_threshold against the oracle's plain search: bit-exact T, same accepted share."""
+    torch = torch_cuda
+    rng = np.random.default_rng(7)
+    for (B, K) in ((1, 1), (3, 4), (64, 8), (257, 16), (3000, 5)):
+        divs = rng.gamma(0.7, 0.2, size=(B, K)).astype(np.float32)
+        divs[rng.random((B, K)) < 0.1] = 0.0
+        divs[rng.random((B, K)) < 0.02] = np.nan
+        if B * K > 100:
+            divs[1, 2] = divs[0, 0]          # duplicates
+        dev = torch.from_numpy(divs).cuda()
+        fr = (1.0 / (B * K), 0.1, 0.5, 0.9, 1.0) if B * K <= 2000 else (0.37,)
+        for frac in fr:
+            T, got = fsd.fsd_calibrate_threshold(dev, frac)
+            torch.cuda.synchronize()
+            oT, ofrac = oracle.calibrate_threshold(divs, float(np.float32(frac)))
+            assert float(T.item()) == oT, (B, K, frac, float(T.item()), oT)
+            assert abs(float(got.item()) - ofrac) < 1e-6
+
+
+def test_calibrated_threshold_matches_strict_sd_share(torch_cuda, oracle):
+    """App. A's recipe on the GPU: divergences of a dev batch, strict SD's accepted share, the
+    threshold that reaches it, and the FSD call at that threshold accepts exactly the promised share."""
+    torch = torch_cuda
+    inp = synth.chain_inputs(32, 8, 32000, "bf16", "peaked", (0.25, 4.0), seed=51)
+    d = pu.to_dev(inp, ("target", "draft", "cand"))
+    base = fsd.fsd_verify_chain(d["target"], d["draft"], d["cand"], 1e9, fsd.DIV_JS)
+    sd = fsd.sd_verify_chain(d["target"], d["draft"], d["cand"], seed=3)
+    share = float(sd["accept_len"].sum().item()) / (32 * 8)
+    T, frac = fsd.fsd_calibrate_threshold(base["divergences"], share)
+    torch.cuda.synchronize()
+    out = fsd.fsd_verify_chain(d["target"], d["draft"], d["cand"], float(T.item()), fsd.DIV_JS)
+    torch.cuda.synchronize()
+    got = float(out["accept_len"].sum().item()) / (32 * 8)
+    assert got >= share and abs(got - float(frac.item())) < 1e-6
+    oT, ofrac = oracle.calibrate_threshold(base["divergences"].cpu().numpy(), float(np.float32(share)))
+    assert float(T.item()) == oT and abs(ofrac - got) < 1e-9
+    print("strict SD share", share, "-> T", float(T.item()), "FSD share", got, flush=True)
+
+
 def test_config_c3_sampled(torch_cuda, oracle):
     """full-size C3 on the GPU; the oracle checks a sample of its sequences one by one."""
     c = synth.CONFIGS["C3"]
