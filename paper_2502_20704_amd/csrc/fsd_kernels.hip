@@ -1082,10 +1082,20 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
         // the trip count is the same for every lane: the thresholds are wavefront reductions
         for (long sb = s0; sb < s1; sb += kWG) {
             const long s = sb + tid;
-            if (s < s1) {
+            const bool live = s < s1;
             float z[VE], zd[VE];
-            const uint4 raw = load_slot<BF16, ALIGNED>(trow, s, P.V);
+            const uint4 raw = load_slot<BF16, ALIGNED>(trow, live ? s : s1 - 1, P.V);
             unpack<BF16>(raw, z);
+            if (P.mode == FSD_SAMPLE) {
+                // No variate is below -ln(24 ln 2) = -2.8116 (u >= 2^-24), so the largest logit seen minus
+                // 2.82 is already a score the winner must reach: most entries are ruled out before any
+                // variate has been evaluated at all.
+                float zm = neg_inf();
+#pragma unroll
+                for (int e = 0; e < VE; ++e) zm = fmaxf(zm, z[e]);
+                thr = fmaxf(thr, wave_max(live ? zm : neg_inf()) - 2.82f);
+            }
+            if (live) {
             if (residual) {
                 const uint4 rawd = load_slot<BF16, ALIGNED>(drow, s, P.V);
                 unpack<BF16>(rawd, zd);
@@ -1132,7 +1142,7 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
             }
             }
             if (P.mode == FSD_SAMPLE) {
-                thr = wave_max(best.score);
+                thr = fmaxf(thr, wave_max(best.score));
                 if (residual) rthr = wave_max(rbest.score);
             }
         }

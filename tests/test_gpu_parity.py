@@ -59,6 +59,37 @@ def test_chain_small(torch_cuda, oracle, B, K, V, dtype, kind, sigma, div):
         pu.check_chain(g, o, T, pu.rel_tol(dtype), f"B={B} K={K} V={V} {dtype} div={div} T={T}")
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_maximum_vocabulary(torch_cuda, oracle, dtype):
+    """V = fsd_max_vocab: 256 wavefronts per row pair, merged in four rounds of 64; one more entry is refused."""
+    vmax = int(fsd.library().fsd_max_vocab(fsd.BF16 if dtype == "bf16" else fsd.F32))
+    assert vmax == 524288
+    inp = synth.chain_inputs(1, 2, vmax, dtype, "zipf", 1.0, seed=61)
+    for div in (fsd.DIV_JS, fsd.DIV_KL, fsd.DIV_TV):
+        g = run_chain(torch_cuda, inp, 0.2, div, seed=2)
+        o = oracle.verify_chain(inp["target"], inp["draft"], inp["cand"], 0.2, div, seed=2)
+        pu.check_chain(g, o, 0.2, pu.rel_tol(dtype), f"max vocab {dtype} div={div}")
+    assert fsd.fsd_workspace_bytes(1, 2, vmax + 1, fsd.BF16 if dtype == "bf16" else fsd.F32) == 0
+
+
+def test_third_model_family_vocabulary(torch_cuda, oracle):
+    """V = 256 000 (the largest vocabulary among the paper's model pairs), 125 wavefronts per pair."""
+    inp = synth.chain_inputs(4, 4, 256000, "bf16", "peaked", (0.25, 4.0), seed=62)
+    for div in (fsd.DIV_JS, fsd.DIV_KL, fsd.DIV_TV):
+        g = run_chain(torch_cuda, inp, 0.1, div, seed=2)
+        o = oracle.verify_chain(inp["target"], inp["draft"], inp["cand"], 0.1, div, seed=2)
+        pu.check_chain(g, o, 0.1, 2e-3, f"V=256000 div={div}")
+
+
+def test_many_short_sequences(torch_cuda, oracle):
+    """far more row pairs than resident teams, smallest team size"""
+    inp = synth.chain_inputs(700, 5, 1000, "bf16", "gauss2", (0.25, 2.0), seed=63)
+    for div in (fsd.DIV_JS, fsd.DIV_KL):
+        g = run_chain(torch_cuda, inp, 0.05, div, seed=2)
+        o = oracle.verify_chain(inp["target"], inp["draft"], inp["cand"], 0.05, div, seed=2)
+        pu.check_chain(g, o, 0.05, 2e-3, f"B=700 div={div}")
+
+
 def test_chain_greedy_and_determinism(torch_cuda, oracle):
     inp = synth.chain_inputs(6, 5, 12345, "bf16", "peaked", 1.0, seed=3)
     g = run_chain(torch_cuda, inp, 0.05, fsd.DIV_JS, mode=fsd.GREEDY)
