@@ -356,10 +356,10 @@ __device__ __forceinline__ unsigned long long pack2(float lo, float hi) {
 __device__ __forceinline__ float lo_f(unsigned long long w) { return __uint_as_float(static_cast<unsigned>(w)); }
 __device__ __forceinline__ float hi_f(unsigned long long w) { return __uint_as_float(static_cast<unsigned>(w >> 32)); }
 
-// A pair owns 4 GW words of an exchange array: word k of member m sits at [k GW + m], so that the
-// 64 lanes of a request touch consecutive words.  Lane l reads the first N words of member
-// (base + l); lanes beyond the team re-read the last member's (no branch around the loads, see
-// load_item).  Nothing looks at the values here, so the loads stay in flight until they are
+// A pair owns 4 GW words of an exchange array, of which a mode uses N per member: word k of member
+// m sits at [m N + k], so that a member's post is one contiguous store and the 64 lanes of a
+// request touch consecutive words.  Lane l reads the N words of member (base + l); lanes beyond
+// the team re-read the last member's (no branch around the loads, see load_item).  Nothing looks at the values here, so the loads stay in flight until they are
 // awaited.  With spread == false every lane reads member 0 (a request whose result is not needed
 // costs one cache line).
 template <int N>
@@ -368,7 +368,7 @@ __device__ __forceinline__ void request_n(const unsigned long long* p, int GW, i
     const int m = base + static_cast<int>(threadIdx.x & 63);
     const int mm = spread ? ((m < GW) ? m : GW - 1) : 0;
 #pragma unroll
-    for (int k = 0; k < N; ++k) w[k] = read64(p + k * GW + mm);
+    for (int k = 0; k < N; ++k) w[k] = read64(p + mm * N + k);
 }
 // The words are normally there when they are looked at.  Everything that loops over memory (asking
 // again, further rounds of 64 members) lives in functions that are NOT inlined: the compiler's
@@ -759,7 +759,7 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
             unsigned long long mine = word[0];
 #pragma unroll
             for (int k = 1; k < PW; ++k) mine = (lane == k) ? word[k] : mine;
-            post64(part2 + static_cast<size_t>(prev_pair) * GW * 4 + lane * GW + member, mine);
+            post64(part2 + static_cast<size_t>(prev_pair) * GW * 4 + member * PW + lane, mine);
         }
     };
 
@@ -848,7 +848,7 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
             mine = (lane == 0) ? w0 : (lane == 1) ? dbits(pst_) : (lane == 2) ? dbits(psd_) : dbits(pw_);
         }
         constexpr int kPosted = TWO_PHASE ? 2 : 4;
-        unsigned long long* const post_at = part1 + static_cast<size_t>(pair) * GW * 4 + (lane & 3) * GW + member;
+        unsigned long long* const post_at = part1 + static_cast<size_t>(pair) * GW * 4 + member * kPosted + (lane & 3);
         if (lane < kPosted) post64(post_at, mine);
         PT(3);   // wave sums, prefetch issue, post
         if constexpr (TWO_PHASE) {
