@@ -66,6 +66,9 @@ def lib() -> ctypes.CDLL:
         L.rfsd_oracle_verify_chain.argtypes = [vp, vp, vp, i32, i32, i64, i32, i32, dbl, i32, u64, u64, i32,
                                                vp, vp, vp, vp, vp, vp, vp]
         L.rfsd_oracle_verify_chain.restype = c.c_int
+        L.fsd_oracle_verify_chain_warped.argtypes = [vp, vp, vp, i32, i32, i64, i32, i32, dbl, i32, u64, u64, i32,
+                                                     c.c_float, i32, dbl, vp, vp, vp, vp, vp, vp, vp]
+        L.fsd_oracle_verify_chain_warped.restype = c.c_int
         _lib = L
     return _lib
 
@@ -220,3 +223,24 @@ def calibrate_threshold(divs, fraction):
         if f >= fraction:
             return float(T), f
     return float("inf"), accepted_fraction(divs, np.inf)
+
+
+def verify_chain_warped(target, draft, cand, T, div=DIV_JS, mode=SAMPLE, seed=0, offset=0, seq_offset=0,
+                        temperature=1.0, top_k=0, top_p=1.0):
+    """verify_chain with temperature / top-k / top-p applied where the token is drawn."""
+    target, draft = _c(target), _c(draft)
+    cand = _c(np.asarray(cand, dtype=np.int32))
+    B, K1, V = target.shape
+    K = K1 - 1
+    assert draft.shape == (B, K, V) and cand.shape == (B, K) and draft.dtype == target.dtype
+    assert temperature > 0 and top_k >= 0 and 0 < top_p <= 1
+    inv_temp = float(np.float32(1.0 / float(temperature)))
+    out = dict(accept_len=np.zeros(B, np.int32), out_tokens=np.zeros((B, K + 1), np.int32),
+               divs=np.zeros((B, K)), row_status=np.zeros(B, np.int32), gap=np.zeros(B, np.float32),
+               threshold=np.zeros(B, np.float32), slack=np.zeros(B))
+    lib().fsd_oracle_verify_chain_warped(_p(target), _p(draft), _p(cand), B, K, V, _dt(target), div,
+                                         float(np.float32(T)), mode, seed, offset, seq_offset, inv_temp,
+                                         int(top_k), float(np.float32(top_p)), _p(out["accept_len"]),
+                                         _p(out["out_tokens"]), _p(out["divs"]), _p(out["row_status"]),
+                                         _p(out["gap"]), _p(out["threshold"]), _p(out["slack"]))
+    return out

@@ -503,3 +503,122 @@ int rfsd_oracle_verify_chain(const void* target, const void* draft, const int32_
     }
     return 0;
 }
+
+/* ------------------------------------------ sampling-method warpers (chain) */
+
+static int cmp_float_desc(const void* a, const void* b) {
+    float x = *(const float*)a, y = *(const float*)b;
+    return (x < y) - (x > y);
+}
+
+/* The token of softmax-sampling with the usual warpers, applied in this order to the row's logits
+ * (Sec. 4: the token is drawn with "whatever sampling method the user sets"):
+ *   temperature  s_v = z_v * inv_temp, one binary32 multiply (inv_temp = binary32(1/temperature));
+ *   top-k        keep the entries with s_v >= the top_k-th largest s (ties at it are all kept);
+ *   top-p        with q = softmax of the kept s, keep s_v >= t, t the largest value with
+ *                sum_{s_v >= t} q_v >= top_p (ties kept);
+ * then Gumbel-max over the kept entries on s_v + G_v, the random stream of sample_row.
+ * threshold (out) = the smallest kept s; slack (out) = how far the nucleus mass at the decision
+ * was from top_p on the nearer side (tiny = a binary32 evaluation may keep one value more or less). */
+static int32_t sample_row_warped(const void* base, size_t off, long V, int dt, int mode, uint64_t seed,
+                                 uint64_t offset, uint32_t b, float inv_temp, int top_k, double top_p,
+                                 float* gap, float* threshold, double* slack) {
+    float* sv = (float*)malloc(sizeof(float) * (size_t)V);
+    float* srt = (float*)malloc(sizeof(float) * (size_t)V);
+    for (long v = 0; v < V; ++v) {
+        float z = load_f(base, off + (size_t)v, dt);
+        sv[v] = z * inv_temp;
+        srt[v] = sv[v];
+    }
+    qsort(srt, (size_t)V, sizeof(float), cmp_float_desc);
+    float t = -INFINITY;
+    long nk = V;
+    if (top_k > 0 && top_k < V) {
+        t = srt[top_k - 1];
+        nk = top_k;
+        while (nk < V && srt[nk] == t) ++nk; /* ties */
+    }
+    *slack = INFINITY;
+    if (top_p < 1.0) {
+        double m = (double)srt[0], Z = 0.0;
+        for (long i = 0; i < nk; ++i) Z += exp((double)srt[i] - m);
+        double cum = 0.0;
+        long i = 0;
+        float tp = srt[nk - 1];
+        while (i < nk) {
+            long j = i;
+            double blk = 0.0;
+            while (j < nk && srt[j] == srt[i]) { blk += exp((double)srt[j] - m); ++j; }
+            double before = cum / Z;
+            cum += blk;
+            double after = cum / Z;
+            if (fabs(before - top_p) < *slack && i > 0) *slack = fabs(before - top_p);
+            if (fabs(after - top_p) < *slack) *slack = fabs(after - top_p);
+            if (after >= top_p) { tp = srt[i]; break; }
+            i = j;
+        }
+        if (tp > t) t = tp;
+    }
+    *threshold = t;
+    float best = -INFINITY, second = -INFINITY;
+    int32_t arg = -1;
+    for (long v = 0; v < V; ++v) {
+        if (!(sv[v] >= t)) continue;
+        float score = sv[v];
+        if (mode == ORACLE_SAMPLE) {
+            float g = fsd_oracle_gumbel(fsd_oracle_random_word(seed, offset, 0u, b, (uint32_t)v));
+            score = sv[v] + g;
+        }
+        if (score > best || arg < 0) {
+            if (arg >= 0) second = best;
+            best = score; arg = (int32_t)v;
+        } else if (score > second) {
+            second = score;
+        }
+    }
+    if (gap) *gap = best - second;
+    free(sv);
+    free(srt);
+    return arg;
+}
+
+/* fsd_oracle_verify_chain with the warpers above applied where the token is drawn.
+ * Extra outputs: threshold [B] (smallest kept scaled logit), slack [B]. */
+int fsd_oracle_verify_chain_warped(const void* target, const void* draft, const int32_t* cand, int B, int K,
+                                   long V, int dt, int div_kind, double T, int mode, uint64_t seed,
+                                   uint64_t offset, int seq_offset, float inv_temp, int top_k, double top_p,
+                                   int32_t* accept_len, int32_t* out_tokens, double* divs,
+                                   int32_t* row_status, float* gap, float* threshold, double* slack) {
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        int status = 0;
+        int n = K;
+        for (int i = 0; i < K; ++i) {
+            double d3[3];
+            size_t toff = ((size_t)b * (size_t)(K + 1) + (size_t)i) * (size_t)V;
+            size_t doff = ((size_t)b * (size_t)K + (size_t)i) * (size_t)V;
+            status |= fsd_oracle_pair(target, toff, draft, doff, V, dt, d3, NULL);
+            double d = d3[div_kind];
+            divs[(size_t)b * K + i] = d;
+            int ok = (d <= T);
+            if (!ok && i < n) n = i;
+        }
+        size_t soff = ((size_t)b * (size_t)(K + 1) + (size_t)n) * (size_t)V;
+        if (!status && row_is_bad(target, soff, V, dt)) status |= ST_NONFINITE;
+        for (int i = 0; i <= K; ++i) out_tokens[(size_t)b * (K + 1) + i] = -1;
+        gap[b] = INFINITY;
+        threshold[b] = NAN;
+        slack[b] = INFINITY;
+        if (status) {
+            accept_len[b] = 0;
+        } else {
+            accept_len[b] = n;
+            for (int i = 0; i < n; ++i) out_tokens[(size_t)b * (K + 1) + i] = cand[(size_t)b * K + i];
+            out_tokens[(size_t)b * (K + 1) + n] =
+                sample_row_warped(target, soff, V, dt, mode, seed, offset, (uint32_t)(b + seq_offset), inv_temp, top_k,
+                                  top_p, &gap[b], &threshold[b], &slack[b]);
+        }
+        row_status[b] = status;
+    }
+    return 0;
+}

@@ -557,3 +557,85 @@ def test_calibration_agrees_with_the_verifier(oracle):
     assert oracle.calibrate_threshold(divs, 0.5) == (float(np.float32(0.3)), 4 / 6)   # 0.2 accepts 2 of 6 only
     assert oracle.calibrate_threshold(divs, 0.9)[0] == float("inf")
     assert oracle.calibrate_threshold(divs, 0.9)[1] == 4 / 6
+
+
+# ---- sampling-method warpers: temperature, top-k, top-p
+
+def _warped_reference(z, temperature, top_k, top_p):
+    """independent numpy statement of the warped distribution (float64, ties kept)"""
+    s = (z.astype(np.float32) * np.float32(1.0 / temperature)).astype(np.float64)
+    keep = np.ones(s.size, bool)
+    if 0 < top_k < s.size:
+        keep = s >= np.sort(s)[::-1][top_k - 1]
+    q = np.where(keep, np.exp(s - s.max()), 0.0)
+    q /= q.sum()
+    if top_p < 1.0:
+        for t in np.sort(np.unique(s[keep]))[::-1]:
+            if q[s >= t].sum() >= np.float32(top_p):
+                keep &= s >= t
+                break
+    q = np.where(keep, q, 0.0)
+    return q / q.sum()
+
+
+def test_warpers_off_is_the_plain_sampler(oracle):
+    t, d, cand = _small_chain(31, B=40, K=4)
+    for mode in (0, 1):
+        a = oracle.verify_chain(t, d, cand, 0.05, 1, mode, seed=11, offset=2)
+        b = oracle.verify_chain_warped(t, d, cand, 0.05, 1, mode, seed=11, offset=2)
+        for k in ("accept_len", "out_tokens", "divs", "row_status", "gap"):
+            assert np.array_equal(a[k], b[k]), k
+
+
+def test_top_k_one_is_greedy_and_token_is_always_kept(oracle):
+    t, d, cand = _small_chain(32, B=60, K=3, V=50)
+    g = oracle.verify_chain(t, d, cand, 0.05, 1, 1, seed=1)
+    w = oracle.verify_chain_warped(t, d, cand, 0.05, 1, 0, seed=1, top_k=1)
+    assert np.array_equal(g["out_tokens"], w["out_tokens"])
+    prev = None
+    for top_k, top_p in ((0, 1.0), (20, 1.0), (20, 0.9), (5, 0.9), (5, 0.5)):
+        w = oracle.verify_chain_warped(t, d, cand, 0.05, 1, 0, seed=1, temperature=0.8, top_k=top_k, top_p=top_p)
+        for b in range(60):
+            n = w["accept_len"][b]
+            s = t[b, n] * np.float32(1.0 / 0.8)
+            assert s[w["out_tokens"][b, n]] >= w["threshold"][b]
+            ref = _warped_reference(t[b, n], 0.8, top_k, top_p)
+            assert np.array_equal(ref > 0, s >= w["threshold"][b])      # the kept set itself
+        if prev is not None:
+            assert (w["threshold"] >= prev).all()                      # each setting keeps a subset of the one before
+        prev = w["threshold"]
+
+
+def test_nucleus_boundary_on_known_masses(oracle):
+    p = np.array([0.05, 0.5, 0.15, 0.3])
+    z = np.log(p).astype(np.float32)
+    t = np.broadcast_to(z, (1, 2, 4)).copy()
+    d = t[:, :1].copy()
+    cand = np.zeros((1, 1), np.int32)
+    for top_p, kept in ((0.3, 1), (0.5, 1), (0.51, 2), (0.79, 2), (0.81, 3), (0.96, 4)):
+        w = oracle.verify_chain_warped(t, d, cand, 1e9, 1, seed=0, top_p=top_p)
+        assert (z >= w["threshold"][0]).sum() == kept, (top_p, kept)
+    # ties at the boundary are kept together
+    z = np.log(np.array([0.4, 0.2, 0.2, 0.2])).astype(np.float32)
+    t = np.broadcast_to(z, (1, 2, 4)).copy()
+    w = oracle.verify_chain_warped(t, t[:, :1].copy(), cand, 1e9, 1, seed=0, top_p=0.5)
+    assert (z >= w["threshold"][0]).sum() == 4
+    w = oracle.verify_chain_warped(t, t[:, :1].copy(), cand, 1e9, 1, seed=0, top_k=2)
+    assert (z >= w["threshold"][0]).sum() == 4
+
+
+def test_warped_sampler_chi_square_v8(oracle):
+    rng = np.random.default_rng(8)
+    V, B = 8, 60000
+    z = (rng.standard_normal(V) * 1.5).astype(np.float32)
+    t = np.broadcast_to(z, (B, 2, V)).copy()
+    d = t[:, :1].copy()
+    cand = np.zeros((B, 1), np.int32)
+    for temperature, top_k, top_p in ((0.7, 0, 1.0), (1.3, 5, 1.0), (1.0, 0, 0.8), (0.9, 6, 0.7)):
+        w = oracle.verify_chain_warped(t, d, cand, 1e9, 1, seed=99, temperature=temperature, top_k=top_k, top_p=top_p)
+        ref = _warped_reference(z, temperature, top_k, top_p)
+        obs = np.bincount(w["out_tokens"][:, 1], minlength=V)
+        assert (obs[ref == 0] == 0).all()
+        m = ref > 0
+        chi = (((obs[m] - B * ref[m]) ** 2) / (B * ref[m])).sum()
+        assert chi < 29.9, (temperature, top_k, top_p, chi)
