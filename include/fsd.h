@@ -150,6 +150,26 @@ int sd_verify_chain(const void* target_logits, const void* draft_logits, const i
                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * fsd_verify_chain with the usual sampling-method warpers applied where the
+ * token is drawn (paper Sec. 4: "whatever sampling method the user sets"), in
+ * this order, on the target row the token comes from:
+ *   temperature  s_v = z_v * binary32(1 / temperature), 1e-3 <= temperature <= 1e3;
+ *   top_k        keep the entries with s_v >= the top_k-th largest s (ties at it
+ *                are all kept); 0 or >= V switches it off;
+ *   top_p        with q = softmax of the kept s, keep s_v >= t, t the largest
+ *                value with sum_{s_v >= t} q_v >= top_p (ties kept); 1 = off;
+ * then the Gumbel-max draw of fsd_verify_chain over the kept entries, on
+ * s_v + G_v with the same random stream.  FSD_GREEDY ignores the warpers (the
+ * argmax is always kept).  Acceptance does not depend on them.  With
+ * temperature 1, top_k 0 and top_p 1 the call is fsd_verify_chain.
+ */
+int fsd_verify_chain_warped(const void* target_logits, const void* draft_logits, const int32_t* cand_tokens,
+                            int B, int K, int V, int dtype, int div, float T, int mode, uint64_t seed,
+                            uint64_t offset, float temperature, int top_k, float top_p, int32_t* accept_len,
+                            int32_t* out_tokens, float* divergences, int32_t* row_status, void* workspace,
+                            size_t workspace_bytes, void* hip_stream);
+
+/*
  * Reducible FSD (paper Sec. 4.2, "Reducing FSD to standard SD"): position i is
  * accepted iff div(p_i, q_i) <= T (the rule of fsd_verify_chain) OR the strict
  * SD test of sd_verify_chain accepts the candidate token, with the same uniform

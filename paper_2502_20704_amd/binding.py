@@ -45,6 +45,9 @@ def library() -> ctypes.CDLL:
         L.fsd_verify_chain.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, f32, i32, u64, u64,
                                        vp, vp, vp, vp, vp, sz, vp]
         L.fsd_verify_chain.restype = i32
+        L.fsd_verify_chain_warped.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, f32, i32, u64, u64, f32, i32, f32,
+                                              vp, vp, vp, vp, vp, sz, vp]
+        L.fsd_verify_chain_warped.restype = i32
         L.fsd_verify_tree.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, f32, i32, u64, u64,
                                       vp, vp, vp, vp, vp, vp, sz, vp]
         L.fsd_verify_tree.restype = i32
@@ -142,6 +145,36 @@ def fsd_verify_chain(target, draft, cand, T, div=DIV_JS, mode=SAMPLE, seed=0, of
                                     _stream(stream))
     if st != 0:
         raise FsdError(st, "fsd_verify_chain")
+    out["_workspace"] = workspace
+    return out
+
+
+def fsd_verify_chain_warped(target, draft, cand, T, div=DIV_JS, mode=SAMPLE, seed=0, offset=0, *,
+                            temperature=1.0, top_k=0, top_p=1.0, out=None, workspace=None, stream=None):
+    """fsd_verify_chain with temperature / top-k / top-p applied where the token is drawn."""
+    import torch
+
+    B, K1, V = target.shape
+    K = K1 - 1
+    dt = _dtype_code(target)
+    _check(target, "target")
+    _check(draft, "draft", (B, K, V), target.dtype)
+    _check(cand, "cand", (B, K), torch.int32)
+    dev = target.device
+    if out is None:
+        out = dict(accept_len=torch.empty(B, dtype=torch.int32, device=dev),
+                   out_tokens=torch.empty((B, K + 1), dtype=torch.int32, device=dev),
+                   divergences=torch.empty((B, K), dtype=torch.float32, device=dev),
+                   row_status=torch.empty(B, dtype=torch.int32, device=dev))
+    need = fsd_workspace_bytes(B, K, V, dt)
+    workspace, wptr, wbytes = _workspace(workspace, need, dev)
+    st = library().fsd_verify_chain_warped(_ptr(target), _ptr(draft), _ptr(cand), B, K, V, dt, div, float(T), mode,
+                                           seed, offset, float(temperature), int(top_k), float(top_p),
+                                           _ptr(out["accept_len"]), _ptr(out["out_tokens"]),
+                                           _ptr(out.get("divergences")), _ptr(out.get("row_status")), wptr, wbytes,
+                                           _stream(stream))
+    if st != 0:
+        raise FsdError(st, "fsd_verify_chain_warped")
     out["_workspace"] = workspace
     return out
 

@@ -258,6 +258,7 @@ struct Ws {
     double* lse2;        // [R][2] log2-sum-exp2 of the target / draft row of the pair
     double* lr;          // [R] strict SD: ln p(x) - ln q(x)
     unsigned long long* spart;  // [B][GS][4]
+    float* thr;          // [B] warpers: smallest kept scaled logit of the sampled row
 };
 
 struct PairParams {
@@ -946,6 +947,8 @@ struct SampleParams {
     int32_t* out_tokens;
     int32_t* path_nodes;      // tree only
     int32_t* row_status;      // optional
+    const float* thr;         // optional [B]: warpers, smallest kept scaled logit of the sampled row
+    float inv_temp;           // warpers: binary32(1 / temperature), 1 otherwise
     Ws ws;
 };
 
@@ -1079,6 +1082,7 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
         // G <= ln2 (24 - floor(log2 m)) = ln2 (clz(m) - 7); 1e-3 covers the rounding of the
         // logarithm routine by a wide margin.
         float thr = neg_inf(), rthr = neg_inf();
+        const float thr_b = P.thr ? P.thr[b] : neg_inf();
         // the trip count is the same for every lane: the thresholds are wavefront reductions
         for (long sb = s0; sb < s1; sb += kWG) {
             const long s = sb + tid;
@@ -1086,6 +1090,15 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
             float z[VE], zd[VE];
             const uint4 raw = load_slot<BF16, ALIGNED>(trow, live ? s : s1 - 1, P.V);
             unpack<BF16>(raw, z);
+            if (P.thr && P.mode == FSD_SAMPLE) {
+                // temperature, then the kept set of top-k / top-p: everything else leaves the draw
+#pragma unroll
+                for (int e = 0; e < VE; ++e) {
+                    bad |= !(z[e] < __builtin_inff());
+                    const float sv = __fmul_rn(z[e], P.inv_temp);
+                    z[e] = (sv >= thr_b) ? sv : neg_inf();
+                }
+            }
             if (P.mode == FSD_SAMPLE) {
                 // No variate is below -ln(24 ln 2) = -2.8116 (u >= 2^-24), so the largest logit seen minus
                 // 2.82 is already a score the winner must reach: most entries are ruled out before any
@@ -1226,6 +1239,174 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
 }
 
 // ------------------------------------------------------------------------------------------
+// sampling-method warpers (Sec. 4: the token is drawn with "whatever sampling method the user
+// sets"): temperature, then top-k, then top-p, in that order, on the row the token is drawn from.
+// One workgroup per sequence finds the smallest kept scaled logit s = z inv_temp:
+//   top-k   the k-th largest s, by a radix select over the order-preserving 32-bit image of s
+//           (four 8-bit digits, counted from the top);
+//   top-p   the largest t with sum_{s >= t} e^(s - max) >= top_p sum_{kept} e^(s - max), by the same
+//           select on weights; the weights are 2^40 fixed-point integers, so that the sums do not
+//           depend on the order of the atomic additions (results are the same run to run).
+// Ties at either threshold are kept.  accept_sample then drops every entry below the threshold.
+// Correct first: a row is passed over once per digit by a single workgroup, which costs far more
+// than the draw itself when top-k or top-p is on.
+
+__device__ __forceinline__ unsigned ordered_key(float x) {
+    const unsigned u = __float_as_uint(x);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float key_value(unsigned k) {
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
+}
+
+struct WarpParams {
+    const char* target;
+    int rows;             // K
+    long V;
+    long nslots;
+    float T;
+    float inv_temp;
+    int top_k;            // 0 = off
+    float top_p;          // 1 = off
+    float* thr;           // [B] out
+    Ws ws;
+};
+
+constexpr int kWarpWG = 1024;
+
+template <bool BF16, bool ALIGNED>
+__global__ __launch_bounds__(kWarpWG) void warp_select(WarpParams P) {
+    constexpr int VE = Slot<BF16>::VE;
+    constexpr int ES = BF16 ? 2 : 4;
+    __shared__ unsigned long long s_hist[256];
+    __shared__ float s_red[kWarpWG / 64];
+    __shared__ int s_n, s_st;
+    __shared__ unsigned s_prefix, s_mask;
+    __shared__ unsigned long long s_need;
+    __shared__ float s_max;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b = blockIdx.x;
+
+    // ---- the row the token will be drawn from: the first rejected position, or the row after the last
+    if (tid == 0) { s_n = P.rows; s_st = 0; }
+    __syncthreads();
+    for (int i = tid; i < P.rows; i += kWarpWG) {
+        const int pr = b * P.rows + i;
+        if (P.ws.pst[pr]) atomicOr(&s_st, 1);
+        if (!(P.ws.div[pr] <= P.T)) atomicMin(&s_n, i);
+    }
+    __syncthreads();
+    if (s_st || P.ws.counters[1]) {   // nothing will be drawn for this sequence
+        if (tid == 0) P.thr[b] = neg_inf();
+        return;
+    }
+    const char* row = P.target + (static_cast<size_t>(b) * (P.rows + 1) + s_n) * static_cast<size_t>(P.V) * ES;
+
+    // one pass over the row: f(scaled logit, key) for every entry
+    auto for_each = [&](auto&& f) __attribute__((always_inline)) {
+        for (long sl = tid; sl < P.nslots; sl += kWarpWG) {
+            float z[VE];
+            const uint4 raw = load_slot<BF16, ALIGNED>(row, sl, P.V);
+            unpack<BF16>(raw, z);
+#pragma unroll
+            for (int e = 0; e < VE; ++e) {
+                if (sl * VE + e < P.V) {
+                    const float sv = __fmul_rn(z[e], P.inv_temp);
+                    f(sv, ordered_key(sv));
+                }
+            }
+        }
+    };
+    // from the top: the digit at which the accumulated histogram reaches `need`; updates prefix/need
+    auto pick_from_top = [&](int shift) __attribute__((always_inline)) {
+        __syncthreads();
+        if (tid == 0) {
+            unsigned long long above = 0, need = s_need;
+            int d = 255;
+            for (; d > 0; --d) {
+                if (above + s_hist[d] >= need) break;
+                above += s_hist[d];
+            }
+            s_prefix |= static_cast<unsigned>(d) << shift;
+            s_mask |= 255u << shift;
+            s_need = need - above;
+        }
+        __syncthreads();
+    };
+
+    float t_k = neg_inf();
+    // ---- maximum of the scaled row (top-p's weights are relative to it)
+    {
+        float m = neg_inf();
+        for_each([&](float sv, unsigned) { m = fmaxf(m, sv); });
+        m = wave_max(m);
+        if (lane == 0) s_red[wave] = m;
+        __syncthreads();
+        if (tid == 0) {
+            float mm = s_red[0];
+            for (int w = 1; w < kWarpWG / 64; ++w) mm = fmaxf(mm, s_red[w]);
+            s_max = mm;
+        }
+        __syncthreads();
+    }
+    const float smax = s_max;
+
+    // ---- top-k: the k-th largest scaled logit
+    if (P.top_k > 0 && P.top_k < P.V) {
+        if (tid == 0) { s_prefix = 0u; s_mask = 0u; s_need = static_cast<unsigned long long>(P.top_k); }
+        for (int shift = 24; shift >= 0; shift -= 8) {
+            if (tid < 256) s_hist[tid] = 0ull;
+            __syncthreads();
+            const unsigned prefix = s_prefix, mask = s_mask;
+            for_each([&](float, unsigned key) {
+                if ((key & mask) == prefix) atomicAdd(&s_hist[(key >> shift) & 255u], 1ull);
+            });
+            pick_from_top(shift);
+        }
+        t_k = key_value(s_prefix);
+        __syncthreads();
+    }
+
+    // ---- top-p over what top-k kept
+    float t_p = neg_inf();
+    if (P.top_p < 1.0f) {
+        const float c = smax * kLog2e;
+        auto weight = [&](float sv) __attribute__((always_inline)) -> unsigned long long {
+            // e^(s - max) in 2^-40 units; entries at -inf weigh nothing
+            const float w = hw_exp2(fmaf(sv, kLog2e, -c));
+            return static_cast<unsigned long long>(static_cast<double>(w) * 1099511627776.0 + 0.5);
+        };
+        if (tid == 0) { s_prefix = 0u; s_mask = 0u; s_need = 0ull; }
+        for (int shift = 24; shift >= 0; shift -= 8) {
+            if (tid < 256) s_hist[tid] = 0ull;
+            __syncthreads();
+            const unsigned prefix = s_prefix, mask = s_mask;
+            for_each([&](float sv, unsigned key) {
+                if (sv >= t_k && (key & mask) == prefix) {
+                    const unsigned long long w = weight(sv);
+                    if (w) atomicAdd(&s_hist[(key >> shift) & 255u], w);
+                }
+            });
+            if (shift == 24) {
+                // the first histogram holds every kept entry: its total is the normaliser
+                __syncthreads();
+                if (tid == 0) {
+                    unsigned long long Z = 0;
+                    for (int d = 0; d < 256; ++d) Z += s_hist[d];
+                    double need = static_cast<double>(P.top_p) * static_cast<double>(Z);
+                    unsigned long long n = static_cast<unsigned long long>(need);
+                    if (static_cast<double>(n) < need) ++n;
+                    s_need = n ? n : 1ull;
+                }
+            }
+            pick_from_top(shift);
+        }
+        t_p = key_value(s_prefix);
+    }
+    if (tid == 0) P.thr[b] = fmaxf(t_k, t_p);
+}
+
+// ------------------------------------------------------------------------------------------
 // threshold tuning on a dev set (Sec. 5.3, App. A): the smallest occurring T at which the chain rule
 // accepts a given share of all candidate positions.  A position is accepted iff every divergence up
 // to it is <= T, i.e. iff the running maximum of its sequence is: T is the ceil(fraction n)-th
@@ -1308,7 +1489,7 @@ struct Plan {
     int VE, NV, G, spm, GS, sps;   // G = wavefronts per pair
     long nslots;
     size_t off_counters, n_counters, off_part1, off_part2, zero_bytes, off_div, off_pst, off_lse2, off_lr, off_spart,
-        bytes;
+        off_thr, bytes;
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -1355,6 +1536,7 @@ bool make_plan(int B, int rows, long V, int dtype, Plan& p) {
     p.off_lse2 = o; o = align_up(o + R * 16, 256);
     p.off_lr = o; o = align_up(o + R * 8, 256);
     p.off_spart = o; o = align_up(o + static_cast<size_t>(B) * p.GS * 32, 256);
+    p.off_thr = o; o = align_up(o + static_cast<size_t>(B) * 4, 256);
     p.bytes = o;
     return true;
 }
@@ -1372,6 +1554,7 @@ Ws carve(void* workspace, const Plan& p, int B, int rows) {
     w.lse2 = reinterpret_cast<double*>(base + p.off_lse2);
     w.lr = reinterpret_cast<double*>(base + p.off_lr);
     w.spart = reinterpret_cast<unsigned long long*>(base + p.off_spart);
+    w.thr = reinterpret_cast<float*>(base + p.off_thr);
     return w;
 }
 
@@ -1511,7 +1694,8 @@ bool is_aligned(const void* a, const void* b, long V, int VE) {
 int run(int kind, const void* target, const void* draft, const int32_t* tokens, const int32_t* parent, int B,
         int rows, int max_depth, int V, int dtype, int div, float T, int mode, uint64_t seed, uint64_t offset,
         int32_t* out_len, int32_t* path_nodes, int32_t* out_tokens, float* user_vals, float* user_ratio,
-        int32_t* row_status, void* workspace, size_t workspace_bytes, void* hip_stream) {
+        int32_t* row_status, void* workspace, size_t workspace_bytes, void* hip_stream,
+        float temperature = 1.0f, int top_k = 0, float top_p = 1.0f) {
     if (!target || !draft || !tokens || !out_len || !out_tokens) return FSD_ERR_NULL;
     if (kind == KIND_TREE && (!parent || !path_nodes)) return FSD_ERR_NULL;
     if (dtype != FSD_F32 && dtype != FSD_BF16) return FSD_ERR_DTYPE;
@@ -1519,6 +1703,7 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
     if (mode != FSD_SAMPLE && mode != FSD_GREEDY) return FSD_ERR_MODE;
     if (T != T) return FSD_ERR_SHAPE;
     if (kind == KIND_TREE && (max_depth < 1 || max_depth > kMaxRows)) return FSD_ERR_SHAPE;
+    if (!(temperature >= 1e-3f && temperature <= 1e3f) || top_k < 0 || !(top_p > 0.0f && top_p <= 1.0f)) return FSD_ERR_SHAPE;
     Plan p;
     if (!make_plan(B, rows, V, dtype, p)) return FSD_ERR_SHAPE;
     if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 != 0 || workspace_bytes < p.bytes)
@@ -1578,6 +1763,32 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
     sp.path_nodes = path_nodes;
     sp.row_status = row_status;
     sp.ws = ws;
+    sp.thr = nullptr;
+    sp.inv_temp = 1.0f;
+    const bool warped = (temperature != 1.0f) || (top_k > 0 && top_k < V) || (top_p < 1.0f);
+    if (warped && mode == FSD_SAMPLE) {
+        // warpers: one more kernel finds, per sequence, the smallest kept scaled logit
+        WarpParams wp;
+        wp.target = static_cast<const char*>(target);
+        wp.rows = rows;
+        wp.V = V;
+        wp.nslots = p.nslots;
+        wp.T = T;
+        wp.inv_temp = static_cast<float>(1.0 / static_cast<double>(temperature));
+        wp.top_k = top_k;
+        wp.top_p = top_p;
+        wp.thr = ws.thr;
+        wp.ws = ws;
+        if (dtype == FSD_BF16) {
+            if (aligned) hipLaunchKernelGGL((warp_select<true, true>), dim3(B), dim3(kWarpWG), 0, st, wp);
+            else hipLaunchKernelGGL((warp_select<true, false>), dim3(B), dim3(kWarpWG), 0, st, wp);
+        } else {
+            if (aligned) hipLaunchKernelGGL((warp_select<false, true>), dim3(B), dim3(kWarpWG), 0, st, wp);
+            else hipLaunchKernelGGL((warp_select<false, false>), dim3(B), dim3(kWarpWG), 0, st, wp);
+        }
+        sp.thr = ws.thr;
+        sp.inv_temp = wp.inv_temp;
+    }
     const size_t lds = (kind == KIND_TREE) ? static_cast<size_t>(rows) * 16 : 0;
     launch_sample(dtype, aligned, kind, dim3(p.GS, B), lds, st, sp);
 
@@ -1676,6 +1887,16 @@ int sd_verify_chain(const void* target_logits, const void* draft_logits, const i
     return run(KIND_SD, target_logits, draft_logits, cand_tokens, nullptr, B, K, 0, V, dtype, FSD_DIV_KL, 0.0f, mode,
                seed, offset, accept_len, nullptr, out_tokens, log_ratio, nullptr, row_status, workspace, workspace_bytes,
                hip_stream);
+}
+
+int fsd_verify_chain_warped(const void* target_logits, const void* draft_logits, const int32_t* cand_tokens, int B,
+                            int K, int V, int dtype, int div, float T, int mode, uint64_t seed, uint64_t offset,
+                            float temperature, int top_k, float top_p, int32_t* accept_len, int32_t* out_tokens,
+                            float* divergences, int32_t* row_status, void* workspace, size_t workspace_bytes,
+                            void* hip_stream) {
+    return run(KIND_CHAIN, target_logits, draft_logits, cand_tokens, nullptr, B, K, 0, V, dtype, div, T, mode, seed,
+               offset, accept_len, nullptr, out_tokens, divergences, nullptr, row_status, workspace, workspace_bytes,
+               hip_stream, temperature, top_k, top_p);
 }
 
 int rfsd_verify_chain(const void* target_logits, const void* draft_logits, const int32_t* cand_tokens, int B, int K,

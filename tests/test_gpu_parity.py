@@ -307,6 +307,65 @@ def test_config_c2_rfsd(torch_cuda, oracle):
               "strict SD", np.bincount(sd["accept_len"], minlength=9), flush=True)
 
 
+def run_warped(torch_cuda, inp, T, div, mode, seed, offset, **kw):
+    d = pu.to_dev(inp, ("target", "draft", "cand"))
+    out = fsd.fsd_verify_chain_warped(d["target"], d["draft"], d["cand"], T, div, mode, seed, offset, **kw)
+    torch_cuda.cuda.synchronize()
+    return pu.host(out, pu.CHAIN_KEYS)
+
+
+def check_warped(g, o, T, tol, what):
+    """as check_chain; a token may differ where the nucleus mass sat on top_p (the kept set then
+    differs by one value) or where two scores tie to 1e-6"""
+    assert (g["row_status"] == o["row_status"]).all(), what
+    pu.check_divs(g["divergences"], o["divs"], tol, what)
+    assert (g["accept_len"] == o["accept_len"]).all() or pu.near_threshold(o["divs"], T).any(), what
+    n_soft = 0
+    for b in range(o["accept_len"].shape[0]):
+        if g["accept_len"][b] != o["accept_len"][b]:
+            n_soft += 1
+            continue
+        if not (g["out_tokens"][b] == o["out_tokens"][b]).all():
+            assert o["slack"][b] < 1e-5 or o["gap"][b] < 1e-6, \
+                f"{what}: tokens[{b}] gpu {g['out_tokens'][b]} oracle {o['out_tokens'][b]} slack {o['slack'][b]} gap {o['gap'][b]}"
+            n_soft += 1
+    assert n_soft <= max(1, o["accept_len"].shape[0] // 20), what
+    return n_soft
+
+
+WARPS = [dict(temperature=0.7), dict(top_k=1), dict(top_k=40), dict(top_p=0.9), dict(top_p=0.3),
+         dict(temperature=1.3, top_k=50, top_p=0.8), dict(temperature=0.5, top_k=100000, top_p=0.95)]
+
+
+def test_warpers_small(torch_cuda, oracle):
+    for (B, K, V, dtype, kind, sigma) in SMALL[:7]:
+        inp = synth.chain_inputs(B, K, V, dtype, kind, sigma, seed=71)
+        tol = pu.rel_tol(dtype)
+        for kw in WARPS:
+            g = run_warped(torch_cuda, inp, 0.1, fsd.DIV_JS, fsd.SAMPLE, 5, 2, **kw)
+            o = oracle.verify_chain_warped(inp["target"], inp["draft"], inp["cand"], 0.1, fsd.DIV_JS, fsd.SAMPLE, 5, 2, **kw)
+            check_warped(g, o, 0.1, tol, f"warped B={B} K={K} V={V} {dtype} {kw}")
+    # warpers off: the plain call, bit for bit; greedy ignores them
+    inp = synth.chain_inputs(5, 9, 32000, "bf16", "zipf", (0.25, 4.0), seed=72)
+    a = run_chain(torch_cuda, inp, 0.1, fsd.DIV_JS, seed=5, offset=2)
+    b = run_warped(torch_cuda, inp, 0.1, fsd.DIV_JS, fsd.SAMPLE, 5, 2)
+    c = run_warped(torch_cuda, inp, 0.1, fsd.DIV_JS, fsd.GREEDY, 5, 2, temperature=0.6, top_k=7, top_p=0.5)
+    gr = run_chain(torch_cuda, inp, 0.1, fsd.DIV_JS, mode=fsd.GREEDY, seed=5, offset=2)
+    for k in pu.CHAIN_KEYS:
+        assert np.array_equal(a[k], b[k]) and np.array_equal(c[k], gr[k]), k
+
+
+def test_config_c2_warped(torch_cuda, oracle):
+    inp = synth.config_inputs("C2", seed=0)
+    for kw in (dict(temperature=0.8, top_k=50, top_p=0.9), dict(top_p=0.6)):
+        g = run_warped(torch_cuda, inp, 0.1, fsd.DIV_JS, fsd.SAMPLE, 3, 11, **kw)
+        o = oracle.verify_chain_warped(inp["target"], inp["draft"], inp["cand"], 0.1, fsd.DIV_JS, fsd.SAMPLE, 3, 11, **kw)
+        n = check_warped(g, o, 0.1, 2e-3, f"C2 warped {kw}")
+        kept = [(pu.synth.bf16_bits_to_f32(inp["target"][b, o["accept_len"][b]]) * np.float32(1 / kw.get("temperature", 1.0))
+                 >= o["threshold"][b]).sum() for b in range(4)]
+        print("C2 warped", kw, "soft rows", n, "kept entries of the first rows", kept, flush=True)
+
+
 def test_threshold_calibration(torch_cuda, oracle):
     """fsd_calibrate_threshold against the oracle's plain search: bit-exact T, same accepted share."""
     torch = torch_cuda
