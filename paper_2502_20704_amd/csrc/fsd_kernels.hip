@@ -458,6 +458,9 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
     constexpr int NE = TWO_PHASE ? NV * VE : 1;   // exponentials kept per row and lane
     constexpr int PW = (MODE == MODE_TV) ? 2 : 1;   // divergence words a member posts (two sums each)
     constexpr int FW = TWO_PHASE ? PW : 4;          // words per member the finisher reads
+    // binary32 logits: the two-phase kernels hold 8 slots of each row per lane and one wavefront per
+    // SIMD anyway, which leaves registers for a second set of logits
+    constexpr bool DEEP = !BF16 && TWO_PHASE && NV == 8;
     constexpr float kTiny = 2e-38f;   // keeps p + q > 0 without changing any result
     constexpr int kWavesPerWG = kWG / 64;
 
@@ -495,7 +498,6 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
     // Every lane always loads (a lane without a slot of its own re-reads a valid one and the value is
     // replaced by -inf afterwards): loads that sit inside branches would make the compiler wait for
     // all outstanding memory operations at every later use, and the prefetch would no longer overlap.
-    uint4 ra[NV], rb[NV];
     long slot_of[NV];
     bool own[NV];
     bool all_own = true;
@@ -507,7 +509,7 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
         slot_of[k] = own[k] ? s : ((s1 > s0) ? s1 - 1 : 0);
     }
     const bool fill_needed = __any(!all_own) != 0;   // wavefront-uniform
-    auto load_item = [&](int pair, bool wanted = true) __attribute__((always_inline)) {
+    auto load_item = [&](uint4 (&ra)[NV], uint4 (&rb)[NV], int pair, bool wanted = true) __attribute__((always_inline)) {
         const char *tptr, *dptr;
         row_ptrs(pair, tptr, dptr);
 #pragma unroll
@@ -517,7 +519,7 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
             rb[k] = load_slot<BF16, ALIGNED>(dptr, sl, P.V);
         }
     };
-    auto fill_unowned = [&]() __attribute__((always_inline)) {
+    auto fill_unowned = [&](uint4 (&ra)[NV], uint4 (&rb)[NV]) __attribute__((always_inline)) {
         if (fill_needed) {
 #pragma unroll
             for (int k = 0; k < NV; ++k) {
@@ -771,7 +773,11 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
     // behind the logits that are about to be used anyway; the logits of the next pair are requested
     // as soon as phase 1 has consumed the registers; and nothing after that waits on memory unless a
     // team member is late (then the words are asked for again, behind the prefetch).
-    auto step = [&](float (&ect)[NE], float (&ecd)[NE], const float (&ept)[NE], const float (&epd)[NE], int pair)
+    // (ra, rb) hold the logits of `pair`, the next pair's go to (rna, rnb).  Where registers allow
+    // (DEEP) these are two sets and the next pair is requested at the top of the step, a whole step
+    // ahead; otherwise both names are the same set and the request follows phase 1.
+    auto step = [&](float (&ect)[NE], float (&ecd)[NE], const float (&ept)[NE], const float (&epd)[NE],
+                    uint4 (&ra)[NV], uint4 (&rb)[NV], uint4 (&rna)[NV], uint4 (&rnb)[NV], int pair)
                     __attribute__((always_inline)) {
         unsigned long long w[2] = {1, 1};
         unsigned long long fw[FW];
@@ -783,8 +789,12 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
         if constexpr (TWO_PHASE)
             request_n<2>(part1 + static_cast<size_t>(prev_pair >= 0 ? prev_pair : pair) * GW * 4, GW, 0, w);
         request_n<FW>(finw + static_cast<size_t>(fpair >= 0 ? fpair : pair) * GW * 4, GW, 0, fw, fpair >= 0);
+        if constexpr (DEEP) {
+            const bool more = pair + nteams < P.npairs;
+            load_item(rna, rnb, more ? pair + nteams : pair, more);
+        }
         asm volatile("" ::: "memory");
-        fill_unowned();
+        fill_unowned(ra, rb);
         // ---- phase 1: maximum, then sums of 2^(z log2e - k) with k = ceil(max log2e)
         float mt = neg_inf(), md = neg_inf();
 #pragma unroll
@@ -824,9 +834,9 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
         // ---- the registers that held the logits are free: fetch the next pair (the request is
         // unconditional: the last step asks for one slot of its own pair, which the caches hold)
         asm volatile("" ::: "memory");
-        {
+        if constexpr (!DEEP) {
             const bool more = pair + nteams < P.npairs;
-            load_item(more ? pair + nteams : pair, more);
+            load_item(rna, rnb, more ? pair + nteams : pair, more);
         }
         __builtin_amdgcn_s_setprio(0);
         asm volatile("" ::: "memory");
@@ -888,17 +898,20 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
     };
 
     float e0t[NE], e0d[NE], e1t[NE], e1d[NE];
+    uint4 r0a[NV], r0b[NV], r1a[DEEP ? NV : 1], r1b[DEEP ? NV : 1];
     int pair = team;
-    if (pair < P.npairs) load_item(pair);
+    if (pair < P.npairs) load_item(r0a, r0b, pair);
     if constexpr (TWO_PHASE) {
 #pragma unroll
         for (int i = 0; i < NE; ++i) { e0t[i] = 0.0f; e0d[i] = 0.0f; e1t[i] = 0.0f; e1d[i] = 0.0f; }
         for (;;) {
             if (pair >= P.npairs) break;
-            step(e0t, e0d, e1t, e1d, pair);
+            if constexpr (DEEP) step(e0t, e0d, e1t, e1d, r0a, r0b, r1a, r1b, pair);
+            else step(e0t, e0d, e1t, e1d, r0a, r0b, r0a, r0b, pair);
             pair += nteams;
             if (pair >= P.npairs) break;
-            step(e1t, e1d, e0t, e0d, pair);
+            if constexpr (DEEP) step(e1t, e1d, e0t, e0d, r1a, r1b, r0a, r0b, pair);
+            else step(e1t, e1d, e0t, e0d, r0a, r0b, r0a, r0b, pair);
             pair += nteams;
         }
         // ---- drain: phase 2 of the last pair, then the finishes still owed
@@ -910,7 +923,7 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
             if (iter & 1) phase2(e0t, e0d, ft, fd, ok2); else phase2(e1t, e1d, ft, fd, ok2);
         }
     } else {
-        for (; pair < P.npairs; pair += nteams) step(e0t, e0d, e1t, e1d, pair);
+        for (; pair < P.npairs; pair += nteams) step(e0t, e0d, e1t, e1d, r0a, r0b, r0a, r0b, pair);
     }
     if (fin0 >= 0) finish_now(fin0);
     if (fin1 >= 0) finish_now(fin1);
