@@ -789,10 +789,6 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
         if constexpr (TWO_PHASE)
             request_n<2>(part1 + static_cast<size_t>(prev_pair >= 0 ? prev_pair : pair) * GW * 4, GW, 0, w);
         request_n<FW>(finw + static_cast<size_t>(fpair >= 0 ? fpair : pair) * GW * 4, GW, 0, fw, fpair >= 0);
-        if constexpr (DEEP) {
-            const bool more = pair + nteams < P.npairs;
-            load_item(rna, rnb, more ? pair + nteams : pair, more);
-        }
         asm volatile("" ::: "memory");
         fill_unowned(ra, rb);
         // ---- phase 1: maximum, then sums of 2^(z log2e - k) with k = ceil(max log2e)
@@ -863,14 +859,21 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
         if (lane < kPosted) post64(post_at, mine);
         PT(3);   // wave sums, prefetch issue, post
         if constexpr (TWO_PHASE) {
-            if (prev_pair >= 0) {
-                // ---- the previous pair's normalisers, then its phase 2
-                float ft, fd;
-                const bool ok2 = merge_team(w, ft, fd);
-                PT(2);   // team merge (wait for the team's words)
-                phase2(ept, epd, ft, fd, ok2);
-                PT(4);   // phase 2
+            // ---- the previous pair's normalisers, then its phase 2
+            float ft = 0.0f, fd = 0.0f;
+            bool ok2 = false;
+            if (prev_pair >= 0) ok2 = merge_team(w, ft, fd);
+            PT(2);   // team merge (wait for the team's words)
+            if constexpr (DEEP) {
+                // requested only now: a poll that had to be repeated would otherwise wait for these
+                // loads as well (memory operations return in the order of issue)
+                asm volatile("" ::: "memory");
+                const bool more = pair + nteams < P.npairs;
+                load_item(rna, rnb, more ? pair + nteams : pair, more);
+                asm volatile("" ::: "memory");
             }
+            if (prev_pair >= 0) phase2(ept, epd, ft, fd, ok2);
+            PT(4);   // phase 2
             // the posted value and its address stay in their registers until here: reusing them
             // earlier would make phase 2 wait for the store, and with it for the prefetch
             asm volatile("" ::"v"(mine), "v"(post_at));
