@@ -424,7 +424,7 @@ __device__ __forceinline__ void merge_round(const unsigned long long (&w)[2], bo
 }
 // teams of more than 64 wavefronts: the members beyond the first round
 __device__ __noinline__ TeamNorm merge_more_rounds(const unsigned long long* p1, int GW, unsigned limit, TeamNorm n) {
-    for (int base = 64; base < GW; base += 64) {
+    for (int base = 128; base < GW; base += 64) {
         const WordsN<2> r = repoll_n<2>(p1, GW, base, limit);
         if (!r.ok) n.ok = false;
         merge_round(r.w, base + static_cast<int>(threadIdx.x & 63) < GW, n);
@@ -460,7 +460,13 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
     constexpr int FW = TWO_PHASE ? PW : 4;          // words per member the finisher reads
     // binary32 logits: the two-phase kernels hold 8 slots of each row per lane and one wavefront per
     // SIMD anyway, which leaves registers for a second set of logits
-    constexpr bool DEEP = !BF16 && TWO_PHASE && NV == 8;
+    constexpr bool DEEP = false;
+    // Phase 2 of a pair runs LAG steps after its phase 1.  One step hides the exchange only while
+    // another wavefront on the SIMD has work; the binary32 kernels run one wavefront per SIMD and
+    // have the registers for a third set of exponentials, so they wait two steps: by then every
+    // member's words have long been posted.
+    constexpr int LAG = (!BF16 && TWO_PHASE && NV == 8) ? 2 : 1;
+    constexpr int NB = LAG + 1;                      // sets of kept exponentials
     constexpr float kTiny = 2e-38f;   // keeps p + q > 0 without changing any result
     constexpr int kWavesPerWG = kWG / 64;
 
@@ -678,34 +684,43 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
     };
 
     // ---- state of the previous pair, whose phase 2 is still to come (two-phase modes)
-    float pkt = 0.0f, pkd = 0.0f;
-    bool pmass_t = false, pmass_d = false, pmask = false;
-    int prev_pair = -1;
-    // pairs this wavefront has to finish: now / one / two steps from now
-    int fin0 = -1, fin1 = -1, fin2 = -1;
+    struct Pend { int pair; float kt, kd; bool mass_t, mass_d, mask; };
+    Pend pend[LAG];   // [0] the last step's pair ... [LAG-1] the one whose phase 2 is due
+#pragma unroll
+    for (int i = 0; i < LAG; ++i) pend[i] = Pend{-1, 0.0f, 0.0f, false, false, false};
+    // pairs this wavefront has to finish: fin[0] now, fin[i] i steps from now
+    constexpr int NF = LAG + 2;
+    int fin[NF];
+#pragma unroll
+    for (int i = 0; i < NF; ++i) fin[i] = -1;
     int iter = 0;
 
     // the previous pair's row-wide normalisers from the team's words (w holds the first 64 members'):
     // factors ft, fd with p = e_t ft, q = e_d fd
-    auto merge_team = [&](unsigned long long (&w)[2], float& ft, float& fd) __attribute__((always_inline)) -> bool {
-        const unsigned long long* p1 = part1 + static_cast<size_t>(prev_pair) * GW * 4;
+    auto merge_team = [&](const Pend& pp, unsigned long long (&w)[2], unsigned long long (&w2)[2], float& ft, float& fd) __attribute__((always_inline)) -> bool {
+        const unsigned long long* p1 = part1 + static_cast<size_t>(pp.pair) * GW * 4;
         // binary32 is enough: the normalisers enter p and q as common factors
         TeamNorm n{neg_inf(), neg_inf(), 0.0f, 0.0f, true};
         n.ok = await_n<2>(p1, GW, 0, P.spin_limit, w);
         merge_round(w, lane < GW, n);
-        if (GW > 64) n = merge_more_rounds(p1, GW, P.spin_limit, n);
+        if (GW > 64) {
+            // members 64..127 were requested with the first 64; larger teams ask for the rest here
+            if (!await_n<2>(p1, GW, 64, P.spin_limit, w2)) n.ok = false;
+            merge_round(w2, 64 + lane < GW, n);
+            if (GW > 128) n = merge_more_rounds(p1, GW, P.spin_limit, n);
+        }
         const float Kt = n.Kt, Kd = n.Kd, zt = n.zt, zd = n.zd;
         const bool ok = n.ok;
         const float rzt = 1.0f / zt, rzd = 1.0f / zd;   // inf for a row without mass, NaN for a bad one
         // ft = 2^(k_wave - K) / S: an exact power of two times one rounded reciprocal.  A wavefront
         // without mass has only zeros in e; its factor is 0 (NaN if the row is unusable).
-        ft = pmass_t ? ldexpf(rzt, kdiff(pkt, Kt)) : rzt * 0.0f;
-        fd = pmass_d ? ldexpf(rzd, kdiff(pkd, Kd)) : rzd * 0.0f;
+        ft = pp.mass_t ? ldexpf(rzt, kdiff(pp.kt, Kt)) : rzt * 0.0f;
+        fd = pp.mass_d ? ldexpf(rzd, kdiff(pp.kd, Kd)) : rzd * 0.0f;
         return ok;
     };
 
     // phase 2 of the previous pair from its kept exponentials
-    auto phase2 = [&](const float (&et)[NE], const float (&ed)[NE], float ft, float fd, bool ok) __attribute__((always_inline)) {
+    auto phase2 = [&](const Pend& pp, const float (&et)[NE], const float (&ed)[NE], float ft, float fd, bool ok) __attribute__((always_inline)) {
         // Only relative errors enter p and q, and the divergences below are functions of (p, q)
         // alone, second order in r = (p - q)/(p + q): the result is the divergence of a slightly
         // perturbed input.  u = 1 + r = 2p/s and v = 2 - u = 2q/s (exact subtraction).
@@ -752,7 +767,7 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
             }
             acc = wave_sumf(acc);
             if constexpr (MODE == MODE_KLP) {
-                if (__any(pmask)) acc += __builtin_inff();   // draft masks an entry the target keeps; NaN stays NaN
+                if (__any(pp.mask)) acc += __builtin_inff();   // draft masks an entry the target keeps; NaN stays NaN
             }
             if (!ok) acc = __builtin_nanf("");
             word[0] = pack2(acc, 0.0f);
@@ -762,7 +777,7 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
             unsigned long long mine = word[0];
 #pragma unroll
             for (int k = 1; k < PW; ++k) mine = (lane == k) ? word[k] : mine;
-            post64(part2 + static_cast<size_t>(prev_pair) * GW * 4 + member * PW + lane, mine);
+            post64(part2 + static_cast<size_t>(pp.pair) * GW * 4 + member * PW + lane, mine);
         }
     };
 
@@ -779,15 +794,20 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
     auto step = [&](float (&ect)[NE], float (&ecd)[NE], const float (&ept)[NE], const float (&epd)[NE],
                     uint4 (&ra)[NV], uint4 (&rb)[NV], uint4 (&rna)[NV], uint4 (&rnb)[NV], int pair)
                     __attribute__((always_inline)) {
-        unsigned long long w[2] = {1, 1};
+        unsigned long long w[2] = {1, 1}, w2[2] = {1, 1};
         unsigned long long fw[FW];
-        const int fpair = fin0;
+        const int fpair = fin[0];
+        const Pend due = pend[LAG - 1];
         // Phase 1 and the request for the next pair's logits are what the whole team waits for: they
         // run at raised priority; what follows overlaps with the memory latency and does not need it.
         __builtin_amdgcn_s_setprio(3);
         asm volatile("" ::: "memory");
         if constexpr (TWO_PHASE)
-            request_n<2>(part1 + static_cast<size_t>(prev_pair >= 0 ? prev_pair : pair) * GW * 4, GW, 0, w);
+        {
+            const unsigned long long* const p1 = part1 + static_cast<size_t>(due.pair >= 0 ? due.pair : pair) * GW * 4;
+            request_n<2>(p1, GW, 0, w);
+            request_n<2>(p1, GW, 64, w2, GW > 64);
+        }
         request_n<FW>(finw + static_cast<size_t>(fpair >= 0 ? fpair : pair) * GW * 4, GW, 0, fw, fpair >= 0);
         asm volatile("" ::: "memory");
         fill_unowned(ra, rb);
@@ -862,7 +882,7 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
             // ---- the previous pair's normalisers, then its phase 2
             float ft = 0.0f, fd = 0.0f;
             bool ok2 = false;
-            if (prev_pair >= 0) ok2 = merge_team(w, ft, fd);
+            if (due.pair >= 0) ok2 = merge_team(due, w, w2, ft, fd);
             PT(2);   // team merge (wait for the team's words)
             if constexpr (DEEP) {
                 // requested only now: a poll that had to be repeated would otherwise wait for these
@@ -872,26 +892,26 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
                 load_item(rna, rnb, more ? pair + nteams : pair, more);
                 asm volatile("" ::: "memory");
             }
-            if (prev_pair >= 0) phase2(ept, epd, ft, fd, ok2);
+            if (due.pair >= 0) phase2(due, ept, epd, ft, fd, ok2);
             PT(4);   // phase 2
             // the posted value and its address stay in their registers until here: reusing them
             // earlier would make phase 2 wait for the store, and with it for the prefetch
             asm volatile("" ::"v"(mine), "v"(post_at));
-            pkt = kt; pkd = kd;
-            pmass_t = (st > 0.0f) || (st != st);
-            pmass_d = (sd > 0.0f) || (sd != sd);
-            pmask = (dmax == __builtin_inff());
+#pragma unroll
+            for (int i = LAG - 1; i > 0; --i) pend[i] = pend[i - 1];
+            pend[0] = Pend{pair, kt, kd, (st > 0.0f) || (st != st), (sd > 0.0f) || (sd != sd), dmax == __builtin_inff()};
         }
         // ---- finishing duties: the pair whose turn has come, then note this pair if it is ours
         if (fpair >= 0) finish(fpair, fw);
         PT(5);   // finishing duty
-        fin0 = fin1; fin1 = fin2; fin2 = -1;
+#pragma unroll
+        for (int i = 0; i + 1 < NF; ++i) fin[i] = fin[i + 1];
+        fin[NF - 1] = -1;
         if (iter % GW == member) {
-            // two-phase: the divergence words of this pair are posted in the next step and read two
-            // steps after that; single-pass: the phase-1 words are all that is needed, read next step
-            if constexpr (TWO_PHASE) fin2 = pair; else fin0 = pair;
+            // two-phase: the divergence words of this pair are posted LAG steps from now and read
+            // the step after that; single-pass: the phase-1 words are all that is needed, read next step
+            if constexpr (TWO_PHASE) fin[NF - 1] = pair; else fin[0] = pair;
         }
-        prev_pair = pair;
         ++iter;
     };
     auto finish_now = [&](int pair) __attribute__((always_inline)) {
@@ -900,37 +920,52 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
         finish(pair, fw);
     };
 
-    float e0t[NE], e0d[NE], e1t[NE], e1d[NE];
-    uint4 r0a[NV], r0b[NV], r1a[DEEP ? NV : 1], r1b[DEEP ? NV : 1];
+    float et[NB][NE], ed[NB][NE];
+    uint4 r0a[NV], r0b[NV];
     int pair = team;
     if (pair < P.npairs) load_item(r0a, r0b, pair);
     if constexpr (TWO_PHASE) {
 #pragma unroll
-        for (int i = 0; i < NE; ++i) { e0t[i] = 0.0f; e0d[i] = 0.0f; e1t[i] = 0.0f; e1d[i] = 0.0f; }
-        for (;;) {
-            if (pair >= P.npairs) break;
-            if constexpr (DEEP) step(e0t, e0d, e1t, e1d, r0a, r0b, r1a, r1b, pair);
-            else step(e0t, e0d, e1t, e1d, r0a, r0b, r0a, r0b, pair);
-            pair += nteams;
-            if (pair >= P.npairs) break;
-            if constexpr (DEEP) step(e1t, e1d, e0t, e0d, r1a, r1b, r0a, r0b, pair);
-            else step(e1t, e1d, e0t, e0d, r0a, r0b, r0a, r0b, pair);
-            pair += nteams;
+        for (int b = 0; b < NB; ++b) {
+#pragma unroll
+            for (int i = 0; i < NE; ++i) { et[b][i] = 0.0f; ed[b][i] = 0.0f; }
         }
-        // ---- drain: phase 2 of the last pair, then the finishes still owed
-        if (prev_pair >= 0) {
-            unsigned long long w[2];
-            float ft, fd;
-            request_n<2>(part1 + static_cast<size_t>(prev_pair) * GW * 4, GW, 0, w);
-            const bool ok2 = merge_team(w, ft, fd);
-            if (iter & 1) phase2(e0t, e0d, ft, fd, ok2); else phase2(e1t, e1d, ft, fd, ok2);
+        // step i keeps its exponentials in set i % NB and reads the set written LAG steps earlier
+        bool live = pair < P.npairs;
+        while (live) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                if (live) {
+                    step(et[b], ed[b], et[(b + 1) % NB], ed[(b + 1) % NB], r0a, r0b, r0a, r0b, pair);
+                    pair += nteams;
+                    live = pair < P.npairs;
+                }
+            }
+        }
+        // ---- drain: phase 2 of the pairs still pending, oldest first, then the finishes still owed
+#pragma unroll
+        for (int d = LAG; d >= 1; --d) {
+            const Pend pp = pend[d - 1];
+            if (pp.pair >= 0) {
+                unsigned long long w[2], w2[2];
+                float ft, fd;
+                request_n<2>(part1 + static_cast<size_t>(pp.pair) * GW * 4, GW, 0, w);
+                request_n<2>(part1 + static_cast<size_t>(pp.pair) * GW * 4, GW, 64, w2, GW > 64);
+                const bool ok2 = merge_team(pp, w, w2, ft, fd);
+                const int b = (iter + NB - d) % NB;   // written at step iter - d
+#pragma unroll
+                for (int c = 0; c < NB; ++c) {
+                    if (b == c) phase2(pp, et[c], ed[c], ft, fd, ok2);
+                }
+            }
         }
     } else {
-        for (; pair < P.npairs; pair += nteams) step(e0t, e0d, e1t, e1d, r0a, r0b, r0a, r0b, pair);
+        for (; pair < P.npairs; pair += nteams) step(et[0], ed[0], et[1], ed[1], r0a, r0b, r0a, r0b, pair);
     }
-    if (fin0 >= 0) finish_now(fin0);
-    if (fin1 >= 0) finish_now(fin1);
-    if (fin2 >= 0) finish_now(fin2);
+#pragma unroll
+    for (int i = 0; i < NF; ++i) {
+        if (fin[i] >= 0) finish_now(fin[i]);
+    }
 #ifdef FSD_PHASE_TIMING
     PT(6);   // drain
     if (P.dbg && lane == 0) {
