@@ -149,7 +149,8 @@ __device__ __forceinline__ uint4 slot_neg_inf() {
 template <bool BF16, bool ALIGNED>
 __device__ __forceinline__ uint4 load_slot(const char* row, long slot, long V) {
     if constexpr (ALIGNED) {
-        return *reinterpret_cast<const uint4*>(row + slot * 16);
+        // a 32-bit offset from the row (rows are at most 2 MiB): the row pointer stays scalar
+        return *reinterpret_cast<const uint4*>(row + static_cast<size_t>(static_cast<unsigned>(slot) * 16u));
     } else if constexpr (BF16) {
         const unsigned short* p = reinterpret_cast<const unsigned short*>(row);
         unsigned w[4];
@@ -450,6 +451,8 @@ __device__ __noinline__ Sums<N> sum_more_rounds(const unsigned long long* p2, in
     return s;
 }
 
+template <int I> struct SetId { static constexpr int value = I; };
+
 template <bool BF16, int NV, int MODE, bool ALIGNED>
 __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
     constexpr int VE = Slot<BF16>::VE;
@@ -460,22 +463,46 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
     constexpr int FW = TWO_PHASE ? PW : 4;          // words per member the finisher reads
     // binary32 logits: the two-phase kernels hold 8 slots of each row per lane and one wavefront per
     // SIMD anyway, which leaves registers for a second set of logits
-    constexpr bool DEEP = false;
-    // Phase 2 of a pair runs LAG steps after its phase 1.  One step hides the exchange only while
-    // another wavefront on the SIMD has work; the binary32 kernels run one wavefront per SIMD and
-    // have the registers for a third set of exponentials, so they wait two steps: by then every
-    // member's words have long been posted.
-    constexpr int LAG = (!BF16 && TWO_PHASE && NV == 8) ? 2 : 1;
+    constexpr bool DEEP = !BF16 && TWO_PHASE && NV == 8;
+    // Phase 2 of a pair runs LAG steps after its phase 1.  With one step, a wavefront's own chain
+    // from one phase 1 to the next still holds the whole latency of the exchange (post, then the
+    // slowest member's words), which only another wavefront on the same SIMD can fill; with two,
+    // every member's words have long been posted when they are looked at.  That takes a third set
+    // of kept exponentials: the binary32 kernels with 8 slots per lane run one wavefront per SIMD
+    // and have the registers.  (The bfloat16 kernels run two per SIMD and are bound by vector-ALU
+    // issue: a third set kept in LDS removed their waits and left their time unchanged.)
+    constexpr int LAG = (TWO_PHASE && !BF16 && NV == 8) ? 2 : 1;
     constexpr int NB = LAG + 1;                      // sets of kept exponentials
+    constexpr int NC = (NE + 3) / 4;                 // chunks of four per row
     constexpr float kTiny = 2e-38f;   // keeps p + q > 0 without changing any result
     constexpr int kWavesPerWG = kWG / 64;
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // the wavefront's number as a scalar: everything derived from it (member, slot range, exchange
+    // addresses) then lives in scalar registers
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
+    // NB sets of kept exponentials, named by SetId<> so that every index is a constant and the
+    // arrays stay in registers; accessed four at a time
+    float et[NB][NE], ed[NB][NE];
+    auto put4 = [&](auto S, int c, const float (&t4)[4], const float (&d4)[4]) __attribute__((always_inline)) {
+        constexpr int s_ = decltype(S)::value;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { et[s_][4 * c + i] = t4[i]; ed[s_][4 * c + i] = d4[i]; }
+    };
+    auto get4 = [&](auto S, int c, float (&t4)[4], float (&d4)[4]) __attribute__((always_inline)) {
+        constexpr int s_ = decltype(S)::value;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { t4[i] = et[s_][4 * c + i]; d4[i] = ed[s_][4 * c + i]; }
+    };
     const int GW = P.G;                                   // wavefronts per pair
     const int wgs_per_team = GW / kWavesPerWG;
-    const int team = static_cast<int>(blockIdx.x) / wgs_per_team;
+    // A team is a run of consecutive workgroups, which the dispatcher spreads over the XCDs.  (Two
+    // other deals were measured at C2 and dropped: teams whose workgroups all sit on one XCD ran a
+    // third slower, and teams made half of early and half of late arrivals on the compute units
+    // ended together but no sooner: the kernel is bound by vector-ALU issue either way.)
     const int nteams = static_cast<int>(gridDim.x) / wgs_per_team;
-    const int member = (static_cast<int>(blockIdx.x) % wgs_per_team) * kWavesPerWG + wave;
+    const int team = static_cast<int>(blockIdx.x) / wgs_per_team;
+    const int wg_in_team = static_cast<int>(blockIdx.x) % wgs_per_team;
+    const int member = wg_in_team * kWavesPerWG + wave;
     const long s0 = static_cast<long>(member) * P.spm;
     const long s1 = (s0 + P.spm < P.nslots) ? s0 + P.spm : P.nslots;
     unsigned long long* const part1 = P.ws.part1;
@@ -504,23 +531,19 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
     // Every lane always loads (a lane without a slot of its own re-reads a valid one and the value is
     // replaced by -inf afterwards): loads that sit inside branches would make the compiler wait for
     // all outstanding memory operations at every later use, and the prefetch would no longer overlap.
-    long slot_of[NV];
-    bool own[NV];
-    bool all_own = true;
-#pragma unroll
-    for (int k = 0; k < NV; ++k) {
-        const long s = s0 + k * 64 + lane;
-        own[k] = s < s1;
-        all_own &= own[k];
-        slot_of[k] = own[k] ? s : ((s1 > s0) ? s1 - 1 : 0);
-    }
-    const bool fill_needed = __any(!all_own) != 0;   // wavefront-uniform
+    // Slot k of this lane is sl0 + 64 k; it is the lane's own while below s1 (computed where needed:
+    // kept per slot, these would cost registers the two-phase kernels do not have).
+    const int sl0 = static_cast<int>(s0) + lane;
+    const int sl_last = (s1 > s0) ? static_cast<int>(s1) - 1 : 0;
+    const int sl_end = static_cast<int>(s1);
+    const bool fill_needed = s0 + NV * 64 > s1;   // wavefront-uniform: some lane lacks a slot
     auto load_item = [&](uint4 (&ra)[NV], uint4 (&rb)[NV], int pair, bool wanted = true) __attribute__((always_inline)) {
         const char *tptr, *dptr;
         row_ptrs(pair, tptr, dptr);
 #pragma unroll
         for (int k = 0; k < NV; ++k) {
-            const long sl = wanted ? slot_of[k] : 0;   // not wanted: one cached slot for all lanes
+            const int sk = sl0 + 64 * k;
+            const long sl = wanted ? (sk < sl_end ? sk : sl_last) : 0;   // not wanted: one cached slot for all lanes
             ra[k] = load_slot<BF16, ALIGNED>(tptr, sl, P.V);
             rb[k] = load_slot<BF16, ALIGNED>(dptr, sl, P.V);
         }
@@ -529,7 +552,7 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
         if (fill_needed) {
 #pragma unroll
             for (int k = 0; k < NV; ++k) {
-                if (!own[k]) { ra[k] = slot_neg_inf<BF16>(); rb[k] = slot_neg_inf<BF16>(); }
+                if (sl0 + 64 * k >= sl_end) { ra[k] = slot_neg_inf<BF16>(); rb[k] = slot_neg_inf<BF16>(); }
             }
         }
     };
@@ -688,8 +711,11 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
     Pend pend[LAG];   // [0] the last step's pair ... [LAG-1] the one whose phase 2 is due
 #pragma unroll
     for (int i = 0; i < LAG; ++i) pend[i] = Pend{-1, 0.0f, 0.0f, false, false, false};
-    // pairs this wavefront has to finish: fin[0] now, fin[i] i steps from now
-    constexpr int NF = LAG + 2;
+    // pairs this wavefront has to finish: fin[0] now, fin[i] i steps from now.  A two-phase pair
+    // is finished NF steps after its phase 1.  Whoever starts step n has merged the team words of
+    // step n - 1, so every member has ended step n - 2 - LAG and with it phase 2 of the pair of step
+    // n - 2 - 2 LAG: the finisher's words are there when it asks, however far the team has spread.
+    constexpr int NF = TWO_PHASE ? 2 * LAG + 2 : 1;
     int fin[NF];
 #pragma unroll
     for (int i = 0; i < NF; ++i) fin[i] = -1;
@@ -720,7 +746,7 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
     };
 
     // phase 2 of the previous pair from its kept exponentials
-    auto phase2 = [&](const Pend& pp, const float (&et)[NE], const float (&ed)[NE], float ft, float fd, bool ok) __attribute__((always_inline)) {
+    auto phase2 = [&](const Pend& pp, auto S, float ft, float fd, bool ok) __attribute__((always_inline)) {
         // Only relative errors enter p and q, and the divergences below are functions of (p, q)
         // alone, second order in r = (p - q)/(p + q): the result is the divergence of a slightly
         // perturbed input.  u = 1 + r = 2p/s and v = 2 - u = 2q/s (exact subtraction).
@@ -728,13 +754,18 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
         if constexpr (MODE == MODE_TV) {
             float A = 0.0f, Bn = 0.0f, MA = 0.0f, MB = 0.0f;
 #pragma unroll
-            for (int i = 0; i < NE; ++i) {
-                const float p = et[i] * ft, q = ed[i] * fd;   // separately rounded: p == q for equal rows
-                const float d = p - q, sum = p + q;
-                A += fmaxf(d, 0.0f);
-                Bn += fmaxf(-d, 0.0f);
-                MA += (d > 0.0f) ? sum : 0.0f;
-                MB += (d < 0.0f) ? sum : 0.0f;
+            for (int c = 0; c < NC; ++c) {
+                float t4[4], d4[4];
+                get4(S, c, t4, d4);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float p = t4[i] * ft, q = d4[i] * fd;   // separately rounded: p == q for equal rows
+                    const float d = p - q, sum = p + q;
+                    A += fmaxf(d, 0.0f);
+                    Bn += fmaxf(-d, 0.0f);
+                    MA += (d > 0.0f) ? sum : 0.0f;
+                    MB += (d < 0.0f) ? sum : 0.0f;
+                }
             }
             // max() drops NaN: an unusable row (NaN factor) is made to reach the side selection
             if (ft != ft || fd != fd) { A = ft + fd; Bn = A; MA = A; MB = A; }
@@ -748,8 +779,12 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
         } else {
             float acc = 0.0f;
 #pragma unroll
-            for (int i = 0; i < NE; ++i) {
-                const float p = fmaf(et[i], ft, kTiny), q = fmaf(ed[i], fd, kTiny);
+            for (int c = 0; c < NC; ++c) {
+              float t4[4], d4[4];
+              get4(S, c, t4, d4);
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                const float p = fmaf(t4[i], ft, kTiny), q = fmaf(d4[i], fd, kTiny);
                 const float d = p - q, sum = p + q;
                 const float inv = __builtin_amdgcn_rcpf(sum);
                 const float u = fmaxf(fmaf(d, inv, 1.0f), kTiny), v = fmaxf(2.0f - u, kTiny);
@@ -764,6 +799,7 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
                     // two parts; p ln(u/v) - (p - q) would keep it to first order.
                     acc = fmaf(sum, fmaf(u, hw_log2(u) - hw_log2(v), (v - u) * kLog2e), acc);
                 }
+              }
             }
             acc = wave_sumf(acc);
             if constexpr (MODE == MODE_KLP) {
@@ -777,9 +813,28 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
             unsigned long long mine = word[0];
 #pragma unroll
             for (int k = 1; k < PW; ++k) mine = (lane == k) ? word[k] : mine;
-            post64(part2 + static_cast<size_t>(pp.pair) * GW * 4 + member * PW + lane, mine);
+            // the lane's offset is recomputed here (hidden from loop-invariant hoisting): kept across
+            // the loop it would be spilled, and the reload would wait for every load in flight
+            int l = lane;
+            asm volatile("" : "+v"(l));
+            post64(part2 + static_cast<size_t>(pp.pair) * GW * 4 + member * PW + l, mine);
         }
     };
+
+    auto finish_now = [&](int pair) __attribute__((always_inline)) {
+        unsigned long long fw[FW];
+        request_n<FW>(finw + static_cast<size_t>(pair) * GW * 4, GW, 0, fw);
+        finish(pair, fw);
+    };
+    // Single-pass modes: nothing makes the members of a team wait for each other, so they drift
+    // apart, and a finisher that looked for the words one step after its own post would wait for
+    // the slowest member (measured: a third of the kernel's time was this tail).  The finisher of
+    // a pair therefore looks kSpDelay steps later, or after its last step, whichever comes first:
+    // by then the words are there, and what little waiting is left falls where the kernel has to
+    // wait for its slowest wavefront anyway.  A member is named every GW steps, so one pending
+    // pair is all there is to remember.
+    const int sp_delay = (GW - 1 < 16) ? GW - 1 : 16;
+    int sp_pair = -1, sp_due = 0;
 
     // One step: phase 1 of `pair` into (ect, ecd), then phase 2 of the previous pair from (ept, epd).
     // Memory operations return in the order they were issued, so the order of the requests decides
@@ -791,12 +846,12 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
     // (ra, rb) hold the logits of `pair`, the next pair's go to (rna, rnb).  Where registers allow
     // (DEEP) these are two sets and the next pair is requested at the top of the step, a whole step
     // ahead; otherwise both names are the same set and the request follows phase 1.
-    auto step = [&](float (&ect)[NE], float (&ecd)[NE], const float (&ept)[NE], const float (&epd)[NE],
-                    uint4 (&ra)[NV], uint4 (&rb)[NV], uint4 (&rna)[NV], uint4 (&rnb)[NV], int pair)
+    // SC names the set that takes this pair's exponentials, SP the one written LAG steps ago.
+    auto step = [&](auto SC, auto SP, uint4 (&ra)[NV], uint4 (&rb)[NV], uint4 (&rna)[NV], uint4 (&rnb)[NV], int pair)
                     __attribute__((always_inline)) {
         unsigned long long w[2] = {1, 1}, w2[2] = {1, 1};
         unsigned long long fw[FW];
-        const int fpair = fin[0];
+        const int fpair = TWO_PHASE ? fin[0] : ((sp_pair >= 0 && iter >= sp_due) ? sp_pair : -1);
         const Pend due = pend[LAG - 1];
         // Phase 1 and the request for the next pair's logits are what the whole team waits for: they
         // run at raised priority; what follows overlaps with the memory latency and does not need it.
@@ -809,6 +864,14 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
             request_n<2>(p1, GW, 64, w2, GW > 64);
         }
         request_n<FW>(finw + static_cast<size_t>(fpair >= 0 ? fpair : pair) * GW * 4, GW, 0, fw, fpair >= 0);
+        if constexpr (DEEP) {
+            // this pair's logits arrived in the second set a step ago; move them and ask for the next pair's
+#pragma unroll
+            for (int k = 0; k < NV; ++k) { ra[k] = rna[k]; rb[k] = rnb[k]; }
+            asm volatile("" ::: "memory");
+            const bool more = pair + nteams < P.npairs;
+            load_item(rna, rnb, more ? pair + nteams : pair, more);
+        }
         asm volatile("" ::: "memory");
         fill_unowned(ra, rb);
         // ---- phase 1: maximum, then sums of 2^(z log2e - k) with k = ceil(max log2e)
@@ -832,17 +895,27 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
             float a[VE], c[VE];
             unpack<BF16>(ra[k], a);
             unpack<BF16>(rb[k], c);
+            float xa_[VE], xb_[VE];
 #pragma unroll
             for (int e = 0; e < VE; ++e) {
                 const float xa = hw_exp2(fmaf(a[e], kLog2e, -kt));
                 const float xb = hw_exp2(fmaf(c[e], kLog2e, -kd));
-                if constexpr (TWO_PHASE) { ect[k * VE + e] = xa; ecd[k * VE + e] = xb; }
+                xa_[e] = xa;
+                xb_[e] = xb;
                 st += xa;
                 sd += xb;
                 if constexpr (MODE == MODE_KL || MODE == MODE_KLP) {
                     const float diff = a[e] - c[e];
                     dmax = fmaxf(dmax, diff);   // +inf iff the draft masks an entry the target does not
                     if constexpr (MODE == MODE_KL) wacc = fmaf(xa, fminf(fmaxf(diff, -FLT_MAX), FLT_MAX), wacc);
+                }
+            }
+            if constexpr (TWO_PHASE) {
+#pragma unroll
+                for (int h = 0; h < VE / 4; ++h) {
+                    const float t4[4] = {xa_[4 * h], xa_[4 * h + 1], xa_[4 * h + 2], xa_[4 * h + 3]};
+                    const float d4[4] = {xb_[4 * h], xb_[4 * h + 1], xb_[4 * h + 2], xb_[4 * h + 3]};
+                    put4(SC, k * (VE / 4) + h, t4, d4);
                 }
             }
         }
@@ -884,15 +957,7 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
             bool ok2 = false;
             if (due.pair >= 0) ok2 = merge_team(due, w, w2, ft, fd);
             PT(2);   // team merge (wait for the team's words)
-            if constexpr (DEEP) {
-                // requested only now: a poll that had to be repeated would otherwise wait for these
-                // loads as well (memory operations return in the order of issue)
-                asm volatile("" ::: "memory");
-                const bool more = pair + nteams < P.npairs;
-                load_item(rna, rnb, more ? pair + nteams : pair, more);
-                asm volatile("" ::: "memory");
-            }
-            if (due.pair >= 0) phase2(due, ept, epd, ft, fd, ok2);
+            if (due.pair >= 0) phase2(due, SP, ft, fd, ok2);
             PT(4);   // phase 2
             // the posted value and its address stay in their registers until here: reusing them
             // earlier would make phase 2 wait for the store, and with it for the prefetch
@@ -903,40 +968,42 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
         }
         // ---- finishing duties: the pair whose turn has come, then note this pair if it is ours
         if (fpair >= 0) finish(fpair, fw);
-        PT(5);   // finishing duty
+        if constexpr (TWO_PHASE) {
 #pragma unroll
-        for (int i = 0; i + 1 < NF; ++i) fin[i] = fin[i + 1];
-        fin[NF - 1] = -1;
-        if (iter % GW == member) {
-            // two-phase: the divergence words of this pair are posted LAG steps from now and read
-            // the step after that; single-pass: the phase-1 words are all that is needed, read next step
-            if constexpr (TWO_PHASE) fin[NF - 1] = pair; else fin[0] = pair;
+            for (int i = 0; i + 1 < NF; ++i) fin[i] = fin[i + 1];
+            fin[NF - 1] = (iter % GW == member) ? pair : -1;   // the members take turns
+        } else {
+            if (fpair >= 0) sp_pair = -1;
+            if (iter % GW == member) { sp_pair = pair; sp_due = iter + sp_delay; }
         }
+        PT(5);   // finishing duty
         ++iter;
     };
-    auto finish_now = [&](int pair) __attribute__((always_inline)) {
-        unsigned long long fw[FW];
-        request_n<FW>(finw + static_cast<size_t>(pair) * GW * 4, GW, 0, fw);
-        finish(pair, fw);
-    };
 
-    float et[NB][NE], ed[NB][NE];
-    uint4 r0a[NV], r0b[NV];
+    uint4 r0a[NV], r0b[NV], r1a[DEEP ? NV : 1], r1b[DEEP ? NV : 1];
     int pair = team;
-    if (pair < P.npairs) load_item(r0a, r0b, pair);
+    if (pair < P.npairs) {
+        if constexpr (DEEP) load_item(r1a, r1b, pair); else load_item(r0a, r0b, pair);
+    }
+    auto one_step = [&](auto SC, auto SP, int pr) __attribute__((always_inline)) {
+        if constexpr (DEEP) step(SC, SP, r0a, r0b, r1a, r1b, pr);
+        else step(SC, SP, r0a, r0b, r0a, r0b, pr);
+    };
     if constexpr (TWO_PHASE) {
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-#pragma unroll
-            for (int i = 0; i < NE; ++i) { et[b][i] = 0.0f; ed[b][i] = 0.0f; }
-        }
         // step i keeps its exponentials in set i % NB and reads the set written LAG steps earlier
         bool live = pair < P.npairs;
         while (live) {
-#pragma unroll
-            for (int b = 0; b < NB; ++b) {
+            one_step(SetId<0>{}, SetId<1 % NB>{}, pair);
+            pair += nteams;
+            live = pair < P.npairs;
+            if (live) {
+                one_step(SetId<1>{}, SetId<2 % NB>{}, pair);
+                pair += nteams;
+                live = pair < P.npairs;
+            }
+            if constexpr (NB == 3) {
                 if (live) {
-                    step(et[b], ed[b], et[(b + 1) % NB], ed[(b + 1) % NB], r0a, r0b, r0a, r0b, pair);
+                    one_step(SetId<2>{}, SetId<0>{}, pair);
                     pair += nteams;
                     live = pair < P.npairs;
                 }
@@ -953,18 +1020,18 @@ __global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
                 request_n<2>(part1 + static_cast<size_t>(pp.pair) * GW * 4, GW, 64, w2, GW > 64);
                 const bool ok2 = merge_team(pp, w, w2, ft, fd);
                 const int b = (iter + NB - d) % NB;   // written at step iter - d
-#pragma unroll
-                for (int c = 0; c < NB; ++c) {
-                    if (b == c) phase2(pp, et[c], ed[c], ft, fd, ok2);
-                }
+                if (b == 0) phase2(pp, SetId<0>{}, ft, fd, ok2);
+                else if (b == 1) phase2(pp, SetId<1>{}, ft, fd, ok2);
+                else phase2(pp, SetId<NB - 1>{}, ft, fd, ok2);
             }
         }
-    } else {
-        for (; pair < P.npairs; pair += nteams) step(et[0], ed[0], et[1], ed[1], r0a, r0b, r0a, r0b, pair);
-    }
 #pragma unroll
-    for (int i = 0; i < NF; ++i) {
-        if (fin[i] >= 0) finish_now(fin[i]);
+        for (int i = 0; i < NF; ++i) {
+            if (fin[i] >= 0) finish_now(fin[i]);
+        }
+    } else {
+        for (; pair < P.npairs; pair += nteams) one_step(SetId<0>{}, SetId<1>{}, pair);
+        if (sp_pair >= 0) finish_now(sp_pair);
     }
 #ifdef FSD_PHASE_TIMING
     PT(6);   // drain
