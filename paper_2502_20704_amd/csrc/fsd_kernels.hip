@@ -1,12 +1,12 @@
 // HIP kernels and C ABI of the FSD candidate-verification step for gfx950 (MI355X).
 //
 // Three launches per call:
-//   zero_counters   clears the few counters the next two kernels use
-//   pair_reduce     the vocabulary reduction: one (target row, draft row) pair is split over a
-//                   team of G workgroups; every workgroup loads its slice of both rows ONCE into
+//   zero_counters   clears the counters and exchange words the next two kernels use
+//   pair_kernel     the vocabulary reduction: one (target row, draft row) pair is split over a
+//                   team of G wavefronts; every wavefront loads its slice of both rows ONCE into
 //                   registers with 128-bit loads, the team exchanges the softmax normalisers
-//                   through device-scope atomics, and the divergence (paper App. C.1-C.3) is
-//                   accumulated from the registers.  The last workgroup of a team to finish adds
+//                   through 64-bit words in the workspace, and the divergence (paper App. C.1-C.3)
+//                   is accumulated from the registers.  One member per pair (they take turns) adds
 //                   the team's partial sums in a fixed order, so results are run-to-run identical.
 //   accept_sample   per sequence: the accepted prefix (Sec. 4, eq. 4) or accepted tree path
 //                   (Sec. 6.4) or the strict-SD acceptance (Sec. 3, eq. 1-2), then the extra token
