@@ -63,6 +63,9 @@ def lib() -> ctypes.CDLL:
         L.sd_oracle_verify_chain.argtypes = [vp, vp, vp, i32, i32, i64, i32, i32, u64, u64, i32,
                                              vp, vp, vp, vp, vp, vp]
         L.sd_oracle_verify_chain.restype = c.c_int
+        L.sd_oracle_verify_tree.argtypes = [vp, vp, vp, vp, i32, i32, i32, i64, i32, i32, u64, u64, i32,
+                                            vp, vp, vp, vp, vp, vp, vp]
+        L.sd_oracle_verify_tree.restype = c.c_int
         L.rfsd_oracle_verify_chain.argtypes = [vp, vp, vp, i32, i32, i64, i32, i32, dbl, i32, u64, u64, i32,
                                                vp, vp, vp, vp, vp, vp, vp]
         L.rfsd_oracle_verify_chain.restype = c.c_int
@@ -175,6 +178,25 @@ def sd_verify_chain(target, draft, cand, mode=SAMPLE, seed=0, offset=0, seq_offs
                                  offset, seq_offset, _p(out["accept_len"]), _p(out["out_tokens"]),
                                  _p(out["log_ratio"]), _p(out["margin"]), _p(out["row_status"]),
                                  _p(out["gap"]))
+    return out
+
+
+def sd_verify_tree(target, draft, node_tokens, parent, max_depth, mode=SAMPLE, seed=0, offset=0, seq_offset=0):
+    """Strict SD over a token tree: children in index order, residual update after every rejection."""
+    target, draft = _c(target), _c(draft)
+    node_tokens = _c(np.asarray(node_tokens, dtype=np.int32))
+    parent = _c(np.asarray(parent, dtype=np.int32))
+    B, N1, V = target.shape
+    N = N1 - 1
+    assert draft.shape == (B, N, V) and node_tokens.shape == (B, N) and parent.shape == (B, N)
+    assert draft.dtype == target.dtype
+    out = dict(path_len=np.zeros(B, np.int32), path_nodes=np.zeros((B, max_depth), np.int32),
+               out_tokens=np.zeros((B, max_depth + 1), np.int32), log_ratio=np.zeros((B, N)),
+               margin=np.zeros((B, N)), row_status=np.zeros(B, np.int32), gap=np.zeros(B))
+    lib().sd_oracle_verify_tree(_p(target), _p(draft), _p(node_tokens), _p(parent), B, N, max_depth, V,
+                                _dt(target), mode, seed, offset, seq_offset, _p(out["path_len"]),
+                                _p(out["path_nodes"]), _p(out["out_tokens"]), _p(out["log_ratio"]),
+                                _p(out["margin"]), _p(out["row_status"]), _p(out["gap"]))
     return out
 
 

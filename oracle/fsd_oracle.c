@@ -19,6 +19,8 @@
  *   - strict SD: accept iff min(1, p/q) > y, y ~ U(0,1) (Sec. 3, eq. 1-2);
  *     on rejection resample from the positive part of p - q, normalised
  *     (Sec. 3, eq. 3, read as the rule of the works cited there)
+ *   - strict SD over a token tree (the family Sec. 2 cites): children tried in
+ *     index order with the residual update of eq. 3 after every rejection
  *   - token trees (Sec. 6.4): a node carries the acceptance bit of
  *     (target row of its parent context, its own draft row); the deepest node
  *     whose ancestors are all accepted wins, lowest index on ties.
@@ -427,6 +429,147 @@ int sd_oracle_verify_chain(const void* target, const void* draft, const int32_t*
             out_tokens[(size_t)b * (K + 1) + n] = y;
         }
         row_status[b] = status;
+    }
+    return 0;
+}
+
+/* ------------------------------------- strict SD over a token tree */
+
+/* Strict (distribution-preserving) verification of a token tree: the tree
+ * analogue of sd_oracle_verify_chain.  The paper only names this family of
+ * methods (Sec. 2, "verifying more tokens with tree-structured proposals");
+ * the procedure here is the published multi-round rejection rule of that
+ * family, stated for this library's tree layout:
+ *
+ *   at the current context with target distribution p, the children are tried
+ *   in index order; child j (token x_j, proposed from its own draft
+ *   distribution q_j) is accepted iff min(1, p(x_j)/q_j(x_j)) > y_j (Sec. 3,
+ *   eq. 1-2, y_j = the SD uniform of index j); on acceptance the walk moves to
+ *   the context after node j; on rejection p is replaced by the normalised
+ *   positive part of p - q_j (Sec. 3, eq. 3) before the next child is tried.
+ *   When no child is accepted the token is drawn from the current p: the
+ *   target row itself at a node without children, else the residual of the
+ *   last rejection.
+ *
+ * With one child per node this is sd_oracle_verify_chain, bit for bit.
+ * log_ratio [B,N] = ln p(x_j) - ln q_j(x_j) with the p in force when node j was
+ * tried, margin [B,N] as in the chain (NaN for nodes never tried). */
+int sd_oracle_verify_tree(const void* target, const void* draft, const int32_t* node_tokens,
+                          const int32_t* parent, int B, int N, int max_depth, long V, int dt, int mode,
+                          uint64_t seed, uint64_t offset, int seq_offset, int32_t* path_len,
+                          int32_t* path_nodes, int32_t* out_tokens, double* log_ratio, double* margin,
+                          int32_t* row_status, double* gap) {
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        int status = 0;
+        const int32_t* par = parent + (size_t)b * N;
+        const int32_t* tok = node_tokens + (size_t)b * N;
+        int* depth = (int*)malloc(sizeof(int) * (size_t)(N > 0 ? N : 1));
+        double* lse_d = (double*)malloc(sizeof(double) * (size_t)(N > 0 ? N : 1));
+        double* p = (double*)malloc(sizeof(double) * (size_t)V);   /* the distribution in force */
+        double* r = (double*)malloc(sizeof(double) * (size_t)V);   /* positive part of p - q, not normalised */
+        for (int j = 0; j < N; ++j) {
+            log_ratio[(size_t)b * N + j] = NAN;
+            margin[(size_t)b * N + j] = NAN;
+            if (par[j] < -1 || par[j] >= j) status |= ST_BAD_PARENT;
+            if (tok[j] < 0 || tok[j] >= V) status |= ST_BAD_TOKEN;
+        }
+        if (!(status & ST_BAD_PARENT)) {
+            for (int j = 0; j < N; ++j) {
+                depth[j] = par[j] < 0 ? 1 : depth[par[j]] + 1;
+                if (depth[j] > max_depth) status |= ST_TOO_DEEP;
+                int bad = 0;
+                (void)row_lse(target, ((size_t)b * (size_t)(N + 1) + (size_t)(par[j] + 1)) * (size_t)V, V, dt, &bad);
+                lse_d[j] = row_lse(draft, ((size_t)b * (size_t)N + (size_t)j) * (size_t)V, V, dt, &bad);
+                if (bad) status |= ST_NONFINITE;
+            }
+        }
+        for (int i = 0; i < max_depth; ++i) path_nodes[(size_t)b * max_depth + i] = -1;
+        for (int i = 0; i <= max_depth; ++i) out_tokens[(size_t)b * (max_depth + 1) + i] = -1;
+        if (gap) gap[b] = INFINITY;
+        path_len[b] = 0;
+        if (!status) {
+            int cur = -1, n = 0;
+            int32_t y = -1;
+            for (;;) {
+                const size_t toff = ((size_t)b * (size_t)(N + 1) + (size_t)(cur + 1)) * (size_t)V;
+                int bad = 0;
+                const double lt = row_lse(target, toff, V, dt, &bad);
+                if (bad) { status |= ST_NONFINITE; break; }
+                int nrej = 0, next = -1;
+                for (int j = cur + 1; j < N && next < 0; ++j) {
+                    if (par[j] != cur) continue;
+                    const size_t doff = ((size_t)b * (size_t)N + (size_t)j) * (size_t)V;
+                    const int32_t x = tok[j];
+                    const double lq = (double)load_f(draft, doff + (size_t)x, dt) - lse_d[j];
+                    double lp;
+                    if (nrej == 0) lp = (double)load_f(target, toff + (size_t)x, dt) - lt;
+                    else lp = p[x] > 0.0 ? log(p[x]) : -INFINITY;
+                    const double ratio = (lp == -INFINITY) ? -INFINITY : lp - lq;
+                    const double u = (double)fsd_oracle_word_to_uniform(
+                        fsd_oracle_random_word(seed, offset, 1u, (uint32_t)(b + seq_offset), (uint32_t)j));
+                    const double thr = ratio < 0.0 ? ratio : 0.0;
+                    const double mar = thr - log(u);
+                    log_ratio[(size_t)b * N + j] = ratio;
+                    margin[(size_t)b * N + j] = mar;
+                    if (mar > 0.0) { next = j; break; }
+                    /* rejected: p <- positive part of p - q_j, normalised (kept as it is if that part is empty) */
+                    double Z = 0.0;
+                    for (long v = 0; v < V; ++v) {
+                        const double pv = (nrej == 0) ? exp((double)load_f(target, toff + (size_t)v, dt) - lt) : p[v];
+                        const double qv = exp((double)load_f(draft, doff + (size_t)v, dt) - lse_d[j]);
+                        const double d = pv - qv;
+                        if (nrej == 0) p[v] = pv;
+                        r[v] = d > 0.0 ? d : 0.0;
+                        Z += r[v];
+                    }
+                    if (Z > 0.0) {
+                        for (long v = 0; v < V; ++v) p[v] = r[v] / Z;
+                        ++nrej;
+                    }
+                }
+                if (next >= 0) {
+                    path_nodes[(size_t)b * max_depth + n] = next;
+                    out_tokens[(size_t)b * (max_depth + 1) + n] = tok[next];
+                    ++n;
+                    cur = next;
+                    continue;
+                }
+                /* nobody accepted: the token comes from the distribution in force */
+                if (nrej > 0) {
+                    double best = -INFINITY, second = -INFINITY;
+                    for (long v = 0; v < V; ++v) {
+                        if (!(r[v] > 0.0)) continue;
+                        double score = log(r[v]);
+                        if (mode == ORACLE_SAMPLE)
+                            score += (double)fsd_oracle_gumbel(
+                                fsd_oracle_random_word(seed, offset, 0u, (uint32_t)(b + seq_offset), (uint32_t)v));
+                        if (score > best || y < 0) {
+                            if (y >= 0) second = best;
+                            best = score; y = (int32_t)v;
+                        } else if (score > second) {
+                            second = score;
+                        }
+                    }
+                    if (gap) gap[b] = best - second;
+                }
+                if (y < 0) {
+                    float g32;
+                    y = sample_row(target, toff, V, dt, mode, seed, offset, (uint32_t)(b + seq_offset), &g32);
+                    if (gap) gap[b] = (double)g32;
+                }
+                break;
+            }
+            if (!status) {
+                path_len[b] = n;
+                out_tokens[(size_t)b * (max_depth + 1) + n] = y;
+            } else {
+                for (int i = 0; i < max_depth; ++i) path_nodes[(size_t)b * max_depth + i] = -1;
+                for (int i = 0; i <= max_depth; ++i) out_tokens[(size_t)b * (max_depth + 1) + i] = -1;
+            }
+        }
+        row_status[b] = status;
+        free(depth); free(lse_d); free(p); free(r);
     }
     return 0;
 }

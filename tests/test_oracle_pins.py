@@ -459,6 +459,113 @@ def test_sd_identical_models_accept_everything(oracle):
     assert (out["out_tokens"][:, 5] >= 0).all()
 
 
+# ---- strict SD over a token tree (the family Sec. 2 cites; the tree analogue of sd_verify_chain)
+
+def test_sd_tree_chain_shaped_equals_sd_chain(oracle):
+    for dtype_seed, (B, K) in ((31, (40, 6)), (32, (25, 3))):
+        t, d, cand = _small_chain(dtype_seed, B=B, K=K, sigma=1.3)
+        parent = np.broadcast_to(np.arange(-1, K - 1, dtype=np.int32), (B, K)).copy()
+        for mode in (oracle.SAMPLE, oracle.GREEDY):
+            c = oracle.sd_verify_chain(t, d, cand, mode=mode, seed=9, offset=4)
+            tr = oracle.sd_verify_tree(t, d, cand, parent, max_depth=K, mode=mode, seed=9, offset=4)
+            assert (c["accept_len"] == tr["path_len"]).all()
+            assert (c["out_tokens"] == tr["out_tokens"]).all()
+            assert 0 < c["accept_len"].sum() < B * K            # both outcomes occur
+            for b in range(B):                                   # tried nodes: 0 .. first rejection
+                n = min(int(c["accept_len"][b]) + 1, K)
+                assert np.array_equal(c["log_ratio"][b, :n], tr["log_ratio"][b, :n])
+                assert np.isnan(tr["log_ratio"][b, n:]).all()
+
+
+def _tree_sd_trials(oracle, B, seed):
+    """Root with three children (own draft rows), child 0 with one child; tokens drawn from the drafts."""
+    rng = np.random.default_rng(seed)
+    V, N = 6, 4
+    zt = (rng.standard_normal((N + 1, V)) * 1.2).astype(np.float32)
+    zd = (rng.standard_normal((N, V)) * 1.2).astype(np.float32)
+    sm = lambda z: np.exp(z.astype(np.float64) - z.astype(np.float64).max()) / np.exp(z.astype(np.float64) - z.astype(np.float64).max()).sum()
+    P = [sm(z) for z in zt]
+    Q = [sm(z) for z in zd]
+    tok = np.stack([rng.choice(V, size=B, p=Q[j]) for j in range(N)], axis=1).astype(np.int32)
+    parent = np.broadcast_to(np.array([-1, -1, -1, 0], dtype=np.int32), (B, N)).copy()
+    t = np.broadcast_to(zt, (B, N + 1, V)).copy()
+    d = np.broadcast_to(zd, (B, N, V)).copy()
+    out = oracle.sd_verify_tree(t, d, tok, parent, max_depth=2, seed=seed + 100)
+    return P, Q, tok, out
+
+
+def test_sd_tree_preserves_the_target_distribution(oracle):
+    """Whatever the drafts propose, every emitted token follows the target row of its context."""
+    B = 60_000
+    P, Q, tok, out = _tree_sd_trials(oracle, B, 5)
+    V = 6
+    first = out["out_tokens"][:, 0]
+    obs = np.bincount(first, minlength=V)
+    assert (((obs - B * P[0]) ** 2 / (B * P[0])).sum()) < 25.7           # 5 dof, p = 1e-4
+    # second token after the path went through node 0: the target row of that context
+    sel = (out["path_len"] >= 1) & (out["path_nodes"][:, 0] == 0)
+    assert sel.sum() > 5000
+    obs2 = np.bincount(out["out_tokens"][sel, 1], minlength=V)
+    assert (((obs2 - sel.sum() * P[1]) ** 2 / (sel.sum() * P[1])).sum()) < 25.7
+    # after node 1 or 2 (leaves) likewise, from rows 2 and 3
+    for j in (1, 2):
+        s2 = (out["path_len"] == 1) & (out["path_nodes"][:, 0] == j)
+        if s2.sum() > 2000:
+            o = np.bincount(out["out_tokens"][s2, 1], minlength=V)
+            assert (((o - s2.sum() * P[j + 1]) ** 2 / (s2.sum() * P[j + 1])).sum()) < 25.7
+
+
+def test_sd_tree_acceptance_rates_follow_the_residual_chain(oracle):
+    """P(child 0) = 1 - TV(p, q0); P(child 1) = TV(p, q0) (1 - TV(p1, q1)), p1 = norm((p - q0)+); ..."""
+    B = 60_000
+    P, Q, tok, out = _tree_sd_trials(oracle, B, 6)
+    p = P[0].copy()
+    reach = 1.0
+    first = np.where(out["path_len"] >= 1, out["path_nodes"][:, 0], -1)
+    for j in range(3):
+        tv = 0.5 * np.abs(p - Q[j]).sum()
+        want = reach * (1 - tv)
+        got = (first == j).mean()
+        assert abs(got - want) < 5 * math.sqrt(want * (1 - want) / B) + 1e-9, (j, got, want)
+        reach *= tv
+        p = np.maximum(p - Q[j], 0)
+        p /= p.sum()
+    # nobody accepted: the token follows the last residual
+    none = first == -1
+    assert abs(none.mean() - reach) < 5 * math.sqrt(reach * (1 - reach) / B) + 1e-9
+    obs = np.bincount(out["out_tokens"][none, 0], minlength=6)
+    assert (obs[p == 0] == 0).all()
+    m = p > 0
+    assert (((obs[m] - none.sum() * p[m]) ** 2 / (none.sum() * p[m])).sum()) < 25.7
+
+
+def test_sd_tree_identical_draft_accepts_first_child(oracle):
+    rng = np.random.default_rng(8)
+    B, N, V = 30, 3, 8
+    t = (rng.standard_normal((B, N + 1, V)) * 1.5).astype(np.float32)
+    d = (rng.standard_normal((B, N, V)) * 1.5).astype(np.float32)
+    d[:, 0] = t[:, 0]                                            # child 0 proposed from the target itself
+    tok = rng.integers(0, V, size=(B, N)).astype(np.int32)
+    parent = np.full((B, N), -1, dtype=np.int32)
+    out = oracle.sd_verify_tree(t, d, tok, parent, max_depth=1, seed=3)
+    assert (out["path_len"] == 1).all() and (out["path_nodes"][:, 0] == 0).all()
+    assert (out["log_ratio"][:, 0] == 0).all() and np.isnan(out["log_ratio"][:, 1:]).all()
+
+
+def test_sd_tree_flags_bad_input(oracle):
+    t, d, cand = _small_chain(4, B=1, K=4)
+    ok = np.array([[-1, 0, 0, 1]], dtype=np.int32)
+    assert oracle.sd_verify_tree(t, d, cand, ok, max_depth=3)["row_status"][0] == 0
+    bad = np.array([[-1, 0, 2, 1]], dtype=np.int32)
+    assert oracle.sd_verify_tree(t, d, cand, bad, max_depth=4)["row_status"][0] & oracle.ST_BAD_PARENT
+    out = oracle.sd_verify_tree(t, d, cand, np.array([[-1, 0, 1, 2]], dtype=np.int32), max_depth=2)
+    assert out["row_status"][0] & oracle.ST_TOO_DEEP and out["path_len"][0] == 0 and (out["out_tokens"] == -1).all()
+    c2 = cand.copy(); c2[0, 3] = 8
+    assert oracle.sd_verify_tree(t, d, c2, ok, max_depth=3)["row_status"][0] & oracle.ST_BAD_TOKEN
+    t2 = t.copy(); t2[0, 0, 2] = np.nan
+    assert oracle.sd_verify_tree(t2, d, cand, ok, max_depth=3)["row_status"][0] & oracle.ST_NONFINITE
+
+
 # ---- reducible FSD (Sec. 4.2): "div <= T or the strict SD test"
 
 def test_rfsd_reduces_to_sd_and_to_fsd(oracle):
