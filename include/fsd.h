@@ -150,6 +150,32 @@ int sd_verify_chain(const void* target_logits, const void* draft_logits, const i
                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Strict speculative decoding over a token tree: the tree analogue of
+ * sd_verify_chain, for the tree-structured proposals of the methods the paper's
+ * Sec. 2 cites (item 1) and Sec. 6.4 builds on.  The paper gives no procedure
+ * of its own; this is the multi-round rejection rule of that family on the
+ * tensors of fsd_verify_tree.  At the current context, with target
+ * distribution p, the children are tried in index order: child j is accepted
+ * iff min(1, p(x_j)/q_j(x_j)) > y_j (Sec. 3, eq. 1-2; y_j the uniform number
+ * of index j) and the walk moves to the context after node j; after a
+ * rejection p becomes the normalised positive part of p - q_j (Sec. 3, eq. 3)
+ * before the next child is tried.  When no child is accepted the token is
+ * drawn from the p in force: the target row itself at a node without
+ * children, otherwise the residual of the last rejection.  Every emitted
+ * token then follows the target distribution of its context.  With one child
+ * per node the outputs are sd_verify_chain's.
+ *
+ *   inputs and path_len / path_nodes / out_tokens / row_status as in fsd_verify_tree
+ *   log_ratio [B, N] out  optional: ln p(x_j) - ln q_j(x_j) with the p in
+ *                         force when node j was tried, NaN for nodes never tried
+ */
+int sd_verify_tree(const void* target_logits, const void* draft_logits, const int32_t* node_tokens,
+                   const int32_t* parent, int B, int N, int max_depth, int V, int dtype, int mode,
+                   uint64_t seed, uint64_t offset, int32_t* path_len, int32_t* path_nodes,
+                   int32_t* out_tokens, float* log_ratio, int32_t* row_status, void* workspace,
+                   size_t workspace_bytes, void* hip_stream);
+
+/*
  * fsd_verify_chain with the usual sampling-method warpers applied where the
  * token is drawn (paper Sec. 4: "whatever sampling method the user sets"), in
  * this order, on the target row the token comes from:

@@ -54,6 +54,9 @@ def library() -> ctypes.CDLL:
         L.sd_verify_chain.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, u64, u64,
                                       vp, vp, vp, vp, vp, sz, vp]
         L.sd_verify_chain.restype = i32
+        L.sd_verify_tree.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, u64, u64,
+                                     vp, vp, vp, vp, vp, vp, sz, vp]
+        L.sd_verify_tree.restype = i32
         L.rfsd_verify_chain.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, f32, i32, u64, u64,
                                         vp, vp, vp, vp, vp, vp, sz, vp]
         L.rfsd_verify_chain.restype = i32
@@ -236,6 +239,38 @@ def sd_verify_chain(target, draft, cand, mode=SAMPLE, seed=0, offset=0, *, out=N
                                    _ptr(out.get("row_status")), wptr, wbytes, _stream(stream))
     if st != 0:
         raise FsdError(st, "sd_verify_chain")
+    out["_workspace"] = workspace
+    return out
+
+
+def sd_verify_tree(target, draft, node_tokens, parent, max_depth, mode=SAMPLE, seed=0, offset=0, *, out=None,
+                   workspace=None, stream=None):
+    """strict speculative decoding over a token tree (tensors of fsd_verify_tree) -> path_len, path_nodes,
+    out_tokens, log_ratio [B,N] (NaN for nodes never tried), row_status."""
+    import torch
+
+    B, N1, V = target.shape
+    N = N1 - 1
+    dt = _dtype_code(target)
+    _check(target, "target")
+    _check(draft, "draft", (B, N, V), target.dtype)
+    _check(node_tokens, "node_tokens", (B, N), torch.int32)
+    _check(parent, "parent", (B, N), torch.int32)
+    dev = target.device
+    if out is None:
+        out = dict(path_len=torch.empty(B, dtype=torch.int32, device=dev),
+                   path_nodes=torch.empty((B, max_depth), dtype=torch.int32, device=dev),
+                   out_tokens=torch.empty((B, max_depth + 1), dtype=torch.int32, device=dev),
+                   log_ratio=torch.empty((B, N), dtype=torch.float32, device=dev),
+                   row_status=torch.empty(B, dtype=torch.int32, device=dev))
+    need = fsd_workspace_bytes(B, N, V, dt)
+    workspace, wptr, wbytes = _workspace(workspace, need, dev)
+    st = library().sd_verify_tree(_ptr(target), _ptr(draft), _ptr(node_tokens), _ptr(parent), B, N, max_depth, V,
+                                  dt, mode, seed, offset, _ptr(out["path_len"]), _ptr(out["path_nodes"]),
+                                  _ptr(out["out_tokens"]), _ptr(out.get("log_ratio")), _ptr(out.get("row_status")),
+                                  wptr, wbytes, _stream(stream))
+    if st != 0:
+        raise FsdError(st, "sd_verify_tree")
     out["_workspace"] = workspace
     return out
 

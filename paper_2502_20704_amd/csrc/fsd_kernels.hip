@@ -28,11 +28,12 @@ constexpr int kWG = 256;          // threads per workgroup (4 wavefronts of 64)
 constexpr int kMaxRows = 2048;    // K or N
 constexpr float kLog2e = 1.44269504088896340736f;
 constexpr double kLn2 = 0.69314718055994530942;
+constexpr double kLog2eD = 1.44269504088896340736;
 
 // MODE_KL: single-pass KL (absolute error ~1e-7, enough for bfloat16 inputs); MODE_KLP: two-phase,
 // pointwise non-negative KL for binary32 inputs; MODE_LSE: normalisers only (strict SD)
 enum { MODE_KL = 0, MODE_JS = 1, MODE_TV = 2, MODE_LSE = 3, MODE_KLP = 4 };
-enum { KIND_CHAIN = 0, KIND_TREE = 1, KIND_SD = 2, KIND_RFSD = 3 };
+enum { KIND_CHAIN = 0, KIND_TREE = 1, KIND_SD = 2, KIND_RFSD = 3, KIND_TREESD = 4 };
 
 #define AGENT __HIP_MEMORY_SCOPE_AGENT
 
@@ -260,6 +261,9 @@ struct Ws {
     double* lr;          // [R] strict SD: ln p(x) - ln q(x)
     unsigned long long* spart;  // [B][GS][4]
     float* thr;          // [B] warpers: smallest kept scaled logit of the sampled row
+    int* tsd;            // [B][4 + rows] strict SD on a tree, from the walk to the sampler: status, depth,
+                         // last node (-1 = root), length of the residual chain, then the chain's nodes
+    float* tsd_invz;     // [B][rows] 1 / normaliser of the chain's residuals (all but the last)
 };
 
 struct PairParams {
@@ -1104,6 +1108,7 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
     int n = 0;         // accepted prefix length / path depth
     int sample_row = 0;
     int winner = -1;
+    int nchain = 0;    // strict SD on a tree: rejected siblings whose draft rows shape the residual
     if constexpr (KIND == KIND_CHAIN || KIND == KIND_SD || KIND == KIND_RFSD) {
         for (int i = tid; i < rows; i += kWG) {
             const int pr = b * rows + i;
@@ -1128,6 +1133,23 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
         __syncthreads();
         n = s_n;
         sample_row = n;
+    } else if constexpr (KIND == KIND_TREESD) {
+        // the walk kernel has decided: depth, last node, and the residual chain the token comes from
+        const int* hdr = P.ws.tsd + static_cast<size_t>(b) * (4 + rows);
+        if (tid == 0) s_st = hdr[0];
+        n = hdr[1];
+        sample_row = hdr[2] + 1;
+        nchain = hdr[3];
+        int* ch = s_dyn;
+        float* iz = reinterpret_cast<float*>(s_dyn + rows);
+        float* ldv = reinterpret_cast<float*>(s_dyn + 2 * rows);
+        for (int m = tid; m < nchain; m += kWG) {
+            const int c = hdr[4 + m];
+            ch[m] = c;
+            iz[m] = P.ws.tsd_invz[static_cast<size_t>(b) * rows + m];
+            ldv[m] = static_cast<float>(P.ws.lse2[2 * (static_cast<size_t>(b) * rows + c) + 1]);
+        }
+        __syncthreads();
     } else {
         int* par = s_dyn;
         int* anc = s_dyn + rows;
@@ -1181,6 +1203,12 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
     bool residual = false;
     const char* drow = nullptr;
     float lt = 0.0f, ld = 0.0f;
+    if constexpr (KIND == KIND_TREESD) {
+        if (nchain > 0 && !status) {
+            residual = true;
+            lt = static_cast<float>(P.ws.lse2[2 * (static_cast<size_t>(b) * rows + s_dyn[nchain - 1])]);
+        }
+    }
     if constexpr (KIND == KIND_SD || KIND == KIND_RFSD) {
         if (n < rows) {   // rejected at n: the residual of Sec. 3 eq. 3 needs the draft row as well
             residual = true;
@@ -1227,7 +1255,31 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
                 thr = fmaxf(thr, wave_max(live ? zm : neg_inf()) - 2.82f);
             }
             if (live) {
-            if (residual) {
+            float rres[VE];   // strict SD on a tree: p after the chain's rejections, minus the last draft row
+            if constexpr (KIND == KIND_TREESD) {
+                if (residual) {
+                    const int* ch = s_dyn;
+                    const float* iz = reinterpret_cast<const float*>(s_dyn + rows);
+                    const float* ldv = reinterpret_cast<const float*>(s_dyn + 2 * rows);
+#pragma unroll
+                    for (int e = 0; e < VE; ++e) rres[e] = hw_exp2(fmaf(z[e], kLog2e, -lt));
+                    for (int m = 0; m < nchain; ++m) {
+                        const char* dr = P.draft + (static_cast<size_t>(b) * rows + ch[m]) * static_cast<size_t>(P.V) * ES;
+                        const uint4 rawd = load_slot<BF16, ALIGNED>(dr, s, P.V);
+                        unpack<BF16>(rawd, zd);
+                        const float ldm = ldv[m];
+                        if (m + 1 < nchain) {
+                            const float izm = iz[m];
+#pragma unroll
+                            for (int e = 0; e < VE; ++e)
+                                rres[e] = fmaxf(rres[e] - hw_exp2(fmaf(zd[e], kLog2e, -ldm)), 0.0f) * izm;
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < VE; ++e) rres[e] = rres[e] - hw_exp2(fmaf(zd[e], kLog2e, -ldm));
+                        }
+                    }
+                }
+            } else if (residual) {
                 const uint4 rawd = load_slot<BF16, ALIGNED>(drow, s, P.V);
                 unpack<BF16>(rawd, zd);
             }
@@ -1247,9 +1299,14 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
                     bad |= !(zz < __builtin_inff());
                     float lnr = neg_inf();
                     if (residual) {
-                        const float p = hw_exp2(fmaf(zz, kLog2e, -lt));
-                        const float qq = hw_exp2(fmaf(zd[blk * 4 + q], kLog2e, -ld));
-                        const float r = p - qq;
+                        float r;
+                        if constexpr (KIND == KIND_TREESD) {
+                            r = rres[blk * 4 + q];
+                        } else {
+                            const float p = hw_exp2(fmaf(zz, kLog2e, -lt));
+                            const float qq = hw_exp2(fmaf(zd[blk * 4 + q], kLog2e, -ld));
+                            r = p - qq;
+                        }
                         if (r > 0.0f) lnr = hw_log2(r) * static_cast<float>(kLn2);
                     }
                     if (P.mode == FSD_SAMPLE) {
@@ -1324,9 +1381,18 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
     status = s_st;
     const int token = s_key;
     if (status) n = 0;
-    const int width = (KIND == KIND_TREE) ? P.max_depth + 1 : rows + 1;
+    const int width = (KIND == KIND_TREE || KIND == KIND_TREESD) ? P.max_depth + 1 : rows + 1;
     int32_t* out = P.out_tokens + static_cast<size_t>(b) * width;
-    if constexpr (KIND == KIND_TREE) {
+    if constexpr (KIND == KIND_TREESD) {
+        // the walk has written the path and its tokens; add the drawn token, or take it all back
+        if (status) {
+            int32_t* pn = P.path_nodes + static_cast<size_t>(b) * P.max_depth;
+            for (int i = tid; i < P.max_depth; i += kWG) pn[i] = -1;
+            for (int i = tid; i < width; i += kWG) out[i] = -1;
+        } else if (tid == 0) {
+            out[n] = token;
+        }
+    } else if constexpr (KIND == KIND_TREE) {
         int32_t* pn = P.path_nodes + static_cast<size_t>(b) * P.max_depth;
         for (int i = tid; i < P.max_depth; i += kWG) pn[i] = -1;
         for (int i = tid; i < width; i += kWG) out[i] = (i == n && !status) ? token : -1;
@@ -1353,6 +1419,174 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
     if (tid == 0) {
         P.out_len[b] = n;
         if (P.row_status) P.row_status[b] = status;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// strict SD over a token tree: the walk
+//
+// The tree analogue of strict SD's acceptance (Sec. 3, eq. 1-3, applied child by child as in the
+// tree-verification methods Sec. 2 cites).  At the current context with target distribution p the
+// children are tried in index order: child j is accepted iff min(1, p(x_j)/q_j(x_j)) > y_j; after a
+// rejection p becomes the normalised positive part of p - q_j.  One workgroup per sequence walks
+// the tree.  The first child of a context is tested against the log-ratio the reduction kernel has
+// stored; a later child needs p after the rejections so far, evaluated at its token through the
+// chain of rejected draft rows, and every rejection that is followed by another sibling costs one
+// pass over the vocabulary for its normaliser.  The token itself is drawn by accept_sample from
+// what this kernel leaves in the workspace.
+struct WalkParams {
+    const char* target;
+    const char* draft;
+    const int32_t* tokens;    // [B,N]
+    const int32_t* parent;    // [B,N]
+    int rows;                 // N
+    int max_depth;
+    long V;
+    long nslots;
+    unsigned seed_lo, seed_hi, off_lo, off_hi;
+    int32_t* path_nodes;      // [B,max_depth]
+    int32_t* out_tokens;      // [B,max_depth+1]
+    float* user_ratio;        // optional [B,N]
+    Ws ws;
+};
+
+constexpr int kWalkWG = 1024;
+
+template <bool BF16, bool ALIGNED>
+__global__ __launch_bounds__(kWalkWG) void tree_sd_walk(WalkParams P) {
+    constexpr int VE = Slot<BF16>::VE;
+    constexpr int ES = BF16 ? 2 : 4;
+    extern __shared__ int s_walk[];   // par[N], dep[N], chain[N], then Z[N] (float64)
+    __shared__ double s_red[kWalkWG / 64];
+    __shared__ int s_st;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b = blockIdx.x, N = P.rows;
+    int* par = s_walk;
+    int* dep = s_walk + N;
+    int* chain = s_walk + 2 * N;
+    double* Zs = reinterpret_cast<double*>(s_walk + 3 * N + (N & 1));
+    int* hdr = P.ws.tsd + static_cast<size_t>(b) * (4 + N);
+    float* invz = P.ws.tsd_invz + static_cast<size_t>(b) * N;
+    int32_t* pn = P.path_nodes + static_cast<size_t>(b) * P.max_depth;
+    int32_t* out = P.out_tokens + static_cast<size_t>(b) * (P.max_depth + 1);
+    const int32_t* tok = P.tokens + static_cast<size_t>(b) * N;
+
+    if (tid == 0) s_st = 0;
+    __syncthreads();
+    for (int j = tid; j < N; j += kWalkWG) {
+        const size_t pr = static_cast<size_t>(b) * N + j;
+        int p = P.parent[pr];
+        if (p < -1 || p >= j) { atomicOr(&s_st, FSD_ROW_BAD_PARENT); p = -1; }
+        const int st = P.ws.pst[pr];
+        if (st) atomicOr(&s_st, st);
+        par[j] = p;
+        if (P.user_ratio) P.user_ratio[pr] = __builtin_nanf("");
+    }
+    for (int i = tid; i < P.max_depth; i += kWalkWG) pn[i] = -1;
+    for (int i = tid; i <= P.max_depth; i += kWalkWG) out[i] = -1;
+    __syncthreads();
+    if (tid == 0) {
+        for (int j = 0; j < N; ++j) {   // parents come first, so one sweep gives the depths
+            dep[j] = par[j] < 0 ? 1 : dep[par[j]] + 1;
+            if (dep[j] > P.max_depth) s_st |= FSD_ROW_TOO_DEEP;
+        }
+    }
+    __syncthreads();
+    int status = s_st;
+    if (status & FSD_ROW_BAD_PARENT) status &= ~FSD_ROW_TOO_DEEP;
+    if (P.ws.counters[1]) status |= FSD_ROW_INTERNAL;
+    if (status) {
+        if (tid == 0) { hdr[0] = status; hdr[1] = 0; hdr[2] = -1; hdr[3] = 0; }
+        return;
+    }
+
+    const size_t rowb = static_cast<size_t>(P.V) * ES;
+    int cur = -1, n = 0, nrej = 0, last_j = -1, before_last = 0;
+    for (;;) {   // every value below is the same in all threads
+        const char* trow = P.target + (static_cast<size_t>(b) * (N + 1) + (cur + 1)) * rowb;
+        nrej = 0; last_j = -1; before_last = 0;
+        int next = -1;
+        for (int j = cur + 1; j < N; ++j) {
+            if (par[j] != cur) continue;
+            const size_t pr = static_cast<size_t>(b) * N + j;
+            const char* drow = P.draft + pr * rowb;
+            const int x = tok[j];
+            const double lt2 = P.ws.lse2[2 * pr], ld2 = P.ws.lse2[2 * pr + 1];
+            double ratio;
+            if (nrej == 0) {
+                ratio = P.ws.lr[pr];
+            } else {
+                double r = exp2(static_cast<double>(load_elem<BF16>(trow, x)) * kLog2eD - lt2);
+                for (int m = 0; m < nrej; ++m) {
+                    const size_t pc = static_cast<size_t>(b) * N + chain[m];
+                    const double q = exp2(static_cast<double>(load_elem<BF16>(P.draft + pc * rowb, x)) * kLog2eD - P.ws.lse2[2 * pc + 1]);
+                    r = fmax(r - q, 0.0) / Zs[m];
+                }
+                const double lq = (static_cast<double>(load_elem<BF16>(drow, x)) * kLog2eD - ld2) * kLn2;
+                ratio = (r > 0.0) ? log(r) - lq : -__builtin_inf();
+            }
+            // Sec. 3 eq. 1-2 in the log domain, with the uniform number of index j
+            const U4 rw = philox4x32_10((static_cast<unsigned>(j) >> 2) | (1u << 30), static_cast<unsigned>(b), P.off_lo,
+                                        P.off_hi, P.seed_lo, P.seed_hi);
+            const unsigned wsel = (j & 3) == 0 ? rw.x : (j & 3) == 1 ? rw.y : (j & 3) == 2 ? rw.z : rw.w;
+            const double u = static_cast<double>(word_to_uniform(wsel));
+            const double thr = ratio < 0.0 ? ratio : 0.0;
+            if (tid == 0 && P.user_ratio) P.user_ratio[pr] = static_cast<float>(ratio);
+            if (thr - log(u) > 0.0) { next = j; break; }
+            last_j = j;
+            before_last = nrej;
+            bool more = false;
+            for (int j2 = j + 1; j2 < N; ++j2) more |= (par[j2] == cur);
+            if (!more) break;
+            // ---- the normaliser of the positive part of p - q_j, p being the distribution in force
+            const float ltf = static_cast<float>(lt2), ldf = static_cast<float>(ld2);
+            double acc = 0.0;
+            for (long sl = tid; sl < P.nslots; sl += kWalkWG) {
+                float z[VE], zd[VE], pv[VE];
+                unpack<BF16>(load_slot<BF16, ALIGNED>(trow, sl, P.V), z);
+#pragma unroll
+                for (int e = 0; e < VE; ++e) pv[e] = hw_exp2(fmaf(z[e], kLog2e, -ltf));
+                for (int m = 0; m < nrej; ++m) {
+                    const size_t pc = static_cast<size_t>(b) * N + chain[m];
+                    unpack<BF16>(load_slot<BF16, ALIGNED>(P.draft + pc * rowb, sl, P.V), zd);
+                    const float ldm = static_cast<float>(P.ws.lse2[2 * pc + 1]), izm = invz[m];
+#pragma unroll
+                    for (int e = 0; e < VE; ++e) pv[e] = fmaxf(pv[e] - hw_exp2(fmaf(zd[e], kLog2e, -ldm)), 0.0f) * izm;
+                }
+                unpack<BF16>(load_slot<BF16, ALIGNED>(drow, sl, P.V), zd);
+                float part = 0.0f;
+#pragma unroll
+                for (int e = 0; e < VE; ++e) part += fmaxf(pv[e] - hw_exp2(fmaf(zd[e], kLog2e, -ldf)), 0.0f);
+                acc += static_cast<double>(part);
+            }
+            acc = wave_sum(acc);
+            __syncthreads();   // the previous round's readers are done with s_red
+            if (lane == 0) s_red[wave] = acc;
+            __syncthreads();
+            double Z = 0.0;
+            for (int w = 0; w < kWalkWG / 64; ++w) Z += s_red[w];   // same order in every thread
+            if (Z > 0.0) {
+                if (tid == 0) { chain[nrej] = j; Zs[nrej] = Z; invz[nrej] = static_cast<float>(1.0 / Z); }
+                __threadfence_block();
+                __syncthreads();
+                ++nrej;
+            }
+        }
+        if (next < 0) break;
+        if (tid == 0) { pn[n] = next; out[n] = tok[next]; }
+        ++n;
+        cur = next;
+    }
+    // ---- what the sampler needs: the residual chain ends with the last rejected child, whose
+    // normaliser nobody needs
+    if (tid == 0) {
+        hdr[0] = 0;
+        hdr[1] = n;
+        hdr[2] = cur;
+        const int nchain = (last_j >= 0) ? before_last + 1 : 0;
+        hdr[3] = nchain;
+        for (int m = 0; m < before_last && m < nchain; ++m) hdr[4 + m] = chain[m];
+        if (nchain > 0) hdr[4 + nchain - 1] = last_j;
     }
 }
 
@@ -1607,7 +1841,7 @@ struct Plan {
     int VE, NV, G, spm, GS, sps;   // G = wavefronts per pair
     long nslots;
     size_t off_counters, n_counters, off_part1, off_part2, zero_bytes, off_div, off_pst, off_lse2, off_lr, off_spart,
-        off_thr, bytes;
+        off_thr, off_tsd, off_tsdz, bytes;
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -1655,6 +1889,8 @@ bool make_plan(int B, int rows, long V, int dtype, Plan& p) {
     p.off_lr = o; o = align_up(o + R * 8, 256);
     p.off_spart = o; o = align_up(o + static_cast<size_t>(B) * p.GS * 32, 256);
     p.off_thr = o; o = align_up(o + static_cast<size_t>(B) * 4, 256);
+    p.off_tsd = o; o = align_up(o + static_cast<size_t>(B) * (4 + rows) * 4, 256);
+    p.off_tsdz = o; o = align_up(o + static_cast<size_t>(B) * rows * 4, 256);
     p.bytes = o;
     return true;
 }
@@ -1673,6 +1909,8 @@ Ws carve(void* workspace, const Plan& p, int B, int rows) {
     w.lr = reinterpret_cast<double*>(base + p.off_lr);
     w.spart = reinterpret_cast<unsigned long long*>(base + p.off_spart);
     w.thr = reinterpret_cast<float*>(base + p.off_thr);
+    w.tsd = reinterpret_cast<int*>(base + p.off_tsd);
+    w.tsd_invz = reinterpret_cast<float*>(base + p.off_tsdz);
     return w;
 }
 
@@ -1790,6 +2028,7 @@ void launch_sample_k(int kind, dim3 grid, size_t lds, hipStream_t st, const Samp
         case KIND_CHAIN: hipLaunchKernelGGL((accept_sample<BF16, ALIGNED, KIND_CHAIN>), grid, dim3(kWG), lds, st, P); break;
         case KIND_TREE: hipLaunchKernelGGL((accept_sample<BF16, ALIGNED, KIND_TREE>), grid, dim3(kWG), lds, st, P); break;
         case KIND_RFSD: hipLaunchKernelGGL((accept_sample<BF16, ALIGNED, KIND_RFSD>), grid, dim3(kWG), lds, st, P); break;
+        case KIND_TREESD: hipLaunchKernelGGL((accept_sample<BF16, ALIGNED, KIND_TREESD>), grid, dim3(kWG), lds, st, P); break;
         default: hipLaunchKernelGGL((accept_sample<BF16, ALIGNED, KIND_SD>), grid, dim3(kWG), lds, st, P); break;
     }
 }
@@ -1815,12 +2054,13 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
         int32_t* row_status, void* workspace, size_t workspace_bytes, void* hip_stream,
         float temperature = 1.0f, int top_k = 0, float top_p = 1.0f) {
     if (!target || !draft || !tokens || !out_len || !out_tokens) return FSD_ERR_NULL;
-    if (kind == KIND_TREE && (!parent || !path_nodes)) return FSD_ERR_NULL;
+    const bool tree = (kind == KIND_TREE || kind == KIND_TREESD);
+    if (tree && (!parent || !path_nodes)) return FSD_ERR_NULL;
     if (dtype != FSD_F32 && dtype != FSD_BF16) return FSD_ERR_DTYPE;
-    if (kind != KIND_SD && (div < FSD_DIV_KL || div > FSD_DIV_TV)) return FSD_ERR_DIV;
+    if (kind != KIND_SD && kind != KIND_TREESD && (div < FSD_DIV_KL || div > FSD_DIV_TV)) return FSD_ERR_DIV;
     if (mode != FSD_SAMPLE && mode != FSD_GREEDY) return FSD_ERR_MODE;
     if (T != T) return FSD_ERR_SHAPE;
-    if (kind == KIND_TREE && (max_depth < 1 || max_depth > kMaxRows)) return FSD_ERR_SHAPE;
+    if (tree && (max_depth < 1 || max_depth > kMaxRows)) return FSD_ERR_SHAPE;
     if (!(temperature >= 1e-3f && temperature <= 1e3f) || top_k < 0 || !(top_p > 0.0f && top_p <= 1.0f)) return FSD_ERR_SHAPE;
     Plan p;
     if (!make_plan(B, rows, V, dtype, p)) return FSD_ERR_SHAPE;
@@ -1839,7 +2079,7 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
     PairParams pp;
     pp.target = static_cast<const char*>(target);
     pp.draft = static_cast<const char*>(draft);
-    pp.parent = (kind == KIND_TREE) ? parent : nullptr;
+    pp.parent = tree ? parent : nullptr;
     pp.cand = tokens;
     pp.rows = rows;
     pp.npairs = R;
@@ -1855,7 +2095,7 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
     pp.user_ratio = user_ratio;
     pp.want_ratio = (kind == KIND_RFSD) ? 1 : 0;
     pp.ws = ws;
-    int k1mode = (kind == KIND_SD) ? MODE_LSE : div;
+    int k1mode = (kind == KIND_SD || kind == KIND_TREESD) ? MODE_LSE : div;
     if (k1mode == MODE_KL && dtype == FSD_F32) k1mode = MODE_KLP;
     launch_pair(dtype, p.NV, k1mode, aligned, st, pp);
 
@@ -1907,7 +2147,33 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
         sp.thr = ws.thr;
         sp.inv_temp = wp.inv_temp;
     }
-    const size_t lds = (kind == KIND_TREE) ? static_cast<size_t>(rows) * 16 : 0;
+    if (kind == KIND_TREESD) {
+        // strict SD on a tree: one workgroup per sequence walks the tree before the token is drawn
+        WalkParams wk;
+        wk.target = sp.target;
+        wk.draft = sp.draft;
+        wk.tokens = tokens;
+        wk.parent = parent;
+        wk.rows = rows;
+        wk.max_depth = max_depth;
+        wk.V = V;
+        wk.nslots = p.nslots;
+        wk.seed_lo = sp.seed_lo; wk.seed_hi = sp.seed_hi; wk.off_lo = sp.off_lo; wk.off_hi = sp.off_hi;
+        wk.path_nodes = path_nodes;
+        wk.out_tokens = out_tokens;
+        wk.user_ratio = user_ratio;
+        wk.ws = ws;
+        const size_t wlds = static_cast<size_t>(rows) * 20 + 16;
+        if (dtype == FSD_BF16) {
+            if (aligned) hipLaunchKernelGGL((tree_sd_walk<true, true>), dim3(B), dim3(kWalkWG), wlds, st, wk);
+            else hipLaunchKernelGGL((tree_sd_walk<true, false>), dim3(B), dim3(kWalkWG), wlds, st, wk);
+        } else {
+            if (aligned) hipLaunchKernelGGL((tree_sd_walk<false, true>), dim3(B), dim3(kWalkWG), wlds, st, wk);
+            else hipLaunchKernelGGL((tree_sd_walk<false, false>), dim3(B), dim3(kWalkWG), wlds, st, wk);
+        }
+    }
+    const size_t lds = (kind == KIND_TREE) ? static_cast<size_t>(rows) * 16
+                     : (kind == KIND_TREESD) ? static_cast<size_t>(rows) * 12 : 0;
     launch_sample(dtype, aligned, kind, dim3(p.GS, B), lds, st, sp);
 
     return (hipGetLastError() == hipSuccess) ? FSD_OK : FSD_ERR_LAUNCH;
@@ -2015,6 +2281,15 @@ int fsd_verify_chain_warped(const void* target_logits, const void* draft_logits,
     return run(KIND_CHAIN, target_logits, draft_logits, cand_tokens, nullptr, B, K, 0, V, dtype, div, T, mode, seed,
                offset, accept_len, nullptr, out_tokens, divergences, nullptr, row_status, workspace, workspace_bytes,
                hip_stream, temperature, top_k, top_p);
+}
+
+int sd_verify_tree(const void* target_logits, const void* draft_logits, const int32_t* node_tokens,
+                   const int32_t* parent, int B, int N, int max_depth, int V, int dtype, int mode, uint64_t seed,
+                   uint64_t offset, int32_t* path_len, int32_t* path_nodes, int32_t* out_tokens, float* log_ratio,
+                   int32_t* row_status, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return run(KIND_TREESD, target_logits, draft_logits, node_tokens, parent, B, N, max_depth, V, dtype, FSD_DIV_KL,
+               0.0f, mode, seed, offset, path_len, path_nodes, out_tokens, nullptr, log_ratio, row_status, workspace,
+               workspace_bytes, hip_stream);
 }
 
 int rfsd_verify_chain(const void* target_logits, const void* draft_logits, const int32_t* cand_tokens, int B, int K,

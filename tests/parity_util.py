@@ -93,3 +93,4 @@ CHAIN_KEYS = ("accept_len", "out_tokens", "divergences", "row_status")
 TREE_KEYS = ("path_len", "path_nodes", "out_tokens", "divergences", "row_status")
 RFSD_KEYS = ("accept_len", "out_tokens", "divergences", "log_ratio", "row_status")
 SD_KEYS = ("accept_len", "out_tokens", "log_ratio", "row_status")
+TREESD_KEYS = ("path_len", "path_nodes", "out_tokens", "log_ratio", "row_status")

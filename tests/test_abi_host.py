@@ -86,6 +86,23 @@ def test_tree_and_sd_argument_errors():
     assert st == -5
 
 
+def test_sd_tree_argument_errors():
+    L = fsd.library()
+    big = 1 << 30
+    st = L.sd_verify_tree(FAKE, FAKE, FAKE, None, 1, 4, 3, 100, fsd.F32, 0, 0, 0, FAKE, FAKE, FAKE, None, None,
+                          FAKE, big, None)
+    assert st == -1                                           # parent missing
+    st = L.sd_verify_tree(FAKE, FAKE, FAKE, FAKE, 1, 4, 0, 100, fsd.F32, 0, 0, 0, FAKE, FAKE, FAKE, None, None,
+                          FAKE, big, None)
+    assert st == -2                                           # max_depth < 1
+    st = L.sd_verify_tree(FAKE, FAKE, FAKE, FAKE, 1, 4, 3, 100, fsd.F32, 5, 0, 0, FAKE, FAKE, FAKE, None, None,
+                          FAKE, big, None)
+    assert st == -6                                           # unknown sampling mode
+    st = L.sd_verify_tree(FAKE, FAKE, FAKE, FAKE, 1, 4, 3, 100, fsd.F32, 0, 0, 0, FAKE, FAKE, FAKE, None, None,
+                          FAKE, 8, None)
+    assert st == -5                                           # workspace too small
+
+
 def test_rfsd_and_calibration_argument_errors():
     L = fsd.library()
     big = 1 << 30

@@ -492,6 +492,129 @@ def test_tree_bad_parent_and_depth(torch_cuda, oracle):
     assert (g["path_len"] == 0).all() and (g["out_tokens"] == -1).all() and (g["path_nodes"] == -1).all()
 
 
+# ------------------------------------------------------------------ strict SD over a token tree
+
+def run_sd_tree(torch, inp, max_depth, mode=fsd.SAMPLE, seed=0, offset=0):
+    d = pu.to_dev(inp, ("target", "draft", "node_tokens", "parent"))
+    out = fsd.sd_verify_tree(d["target"], d["draft"], d["node_tokens"], d["parent"], max_depth, mode, seed, offset)
+    torch.cuda.synchronize()
+    return pu.host(out, pu.TREESD_KEYS)
+
+
+def check_sd_tree(g, o, what):
+    """Paths and tokens are exact unless a test sits on its threshold (|margin| <= 1e-5 in the oracle)
+    or the residual draw has a runner-up within 1e-4; log-ratios of the nodes that were tried agree to
+    5e-5 (those of later siblings carry the binary32 normalisers of the residual chain)."""
+    assert (g["row_status"] == o["row_status"]).all(), what
+    near = np.abs(np.nan_to_num(o["margin"], nan=1.0)) <= 1e-5
+    n_near = n_tie = 0
+    for b in range(o["path_len"].shape[0]):
+        same = int(g["path_len"][b]) == int(o["path_len"][b]) and (g["path_nodes"][b] == o["path_nodes"][b]).all()
+        if not same:
+            assert near[b].any(), f"{what}: tree {b} path gpu {g['path_nodes'][b]} oracle {o['path_nodes'][b]}"
+            n_near += 1
+            continue
+        tried = ~np.isnan(o["log_ratio"][b])
+        assert (np.isnan(g["log_ratio"][b]) == ~tried).all(), f"{what}: tree {b} tried nodes differ"
+        fin = np.isfinite(o["log_ratio"][b])
+        assert (np.isfinite(g["log_ratio"][b]) == fin).all(), what
+        assert np.allclose(g["log_ratio"][b][fin], o["log_ratio"][b][fin], rtol=5e-5, atol=5e-5), \
+            f"{what}: tree {b} log_ratio gpu {g['log_ratio'][b][fin]} oracle {o['log_ratio'][b][fin]}"
+        if not (g["out_tokens"][b] == o["out_tokens"][b]).all():
+            assert o["gap"][b] < 1e-4, f"{what}: tree {b} tokens gpu {g['out_tokens'][b]} oracle {o['out_tokens'][b]} gap {o['gap'][b]}"
+            n_tie += 1
+    assert n_near + n_tie <= max(2, o["path_len"].shape[0] // 20), what
+    return dict(near=n_near, ties=n_tie)
+
+
+def _random_tree_inputs(rng, B, N, V, dtype, star=False, noise=(0.2, 1.2)):
+    if star:
+        parent = np.full((B, N), -1, dtype=np.int32)
+    else:
+        parent = np.stack([np.array([-1] + [int(rng.integers(-1, j)) for j in range(1, N)], dtype=np.int32)
+                           for _ in range(B)])
+    t = (rng.standard_normal((B, N + 1, V)) * 2).astype(np.float32)
+    d = np.empty((B, N, V), dtype=np.float32)
+    toks = np.empty((B, N), dtype=np.int32)
+    for b in range(B):
+        for j in range(N):
+            d[b, j] = t[b, parent[b, j] + 1] + rng.standard_normal(V) * rng.uniform(*noise)
+            q = np.exp(d[b, j].astype(np.float64) - d[b, j].max())
+            toks[b, j] = rng.choice(V, p=q / q.sum())          # proposals come from the draft rows
+    if dtype == "bf16":
+        t, d = synth.to_bf16_bits(t), synth.to_bf16_bits(d)
+    return dict(target=t, draft=d, node_tokens=toks, parent=parent)
+
+
+def test_sd_tree_small_random(torch_cuda, oracle):
+    rng = np.random.default_rng(15)
+    for trial, (N, V, dtype) in enumerate([(10, 8, "f32"), (33, 1000, "bf16"), (60, 4097, "f32"), (200, 512, "bf16"),
+                                           (1, 64, "f32"), (24, 9000, "bf16")]):
+        inp = _random_tree_inputs(rng, 6, N, V, dtype)
+        for mode in (fsd.SAMPLE, fsd.GREEDY):
+            print(f"sd tree N={N} V={V} {dtype} mode={mode}", flush=True)
+            g = run_sd_tree(torch_cuda, inp, N, mode, seed=trial, offset=2)
+            o = oracle.sd_verify_tree(inp["target"], inp["draft"], inp["node_tokens"], inp["parent"], N, mode,
+                                      seed=trial, offset=2)
+            r = check_sd_tree(g, o, f"sd tree N={N} V={V} {dtype} mode={mode}")
+            print("   ", r, "path_len", np.bincount(o["path_len"]), flush=True)
+
+
+def test_sd_tree_star_many_rejections(torch_cuda, oracle):
+    """all nodes are children of the root and the drafts are far from the target: long residual chains"""
+    rng = np.random.default_rng(16)
+    for (N, V, dtype) in ((12, 1000, "f32"), (9, 4097, "bf16"), (16, 50000, "bf16")):
+        inp = _random_tree_inputs(rng, 8, N, V, dtype, star=True, noise=(1.5, 3.0))
+        print(f"sd star N={N} V={V} {dtype}", flush=True)
+        g = run_sd_tree(torch_cuda, inp, 1, seed=3, offset=1)
+        o = oracle.sd_verify_tree(inp["target"], inp["draft"], inp["node_tokens"], inp["parent"], 1, seed=3, offset=1)
+        r = check_sd_tree(g, o, f"sd star N={N} V={V} {dtype}")
+        tried = (~np.isnan(o["log_ratio"])).sum(axis=1)
+        print("   ", r, "nodes tried per tree", tried, flush=True)
+        assert tried.max() >= 4          # the case is exercised
+
+
+def test_sd_tree_chain_shaped_equals_sd_chain(torch_cuda):
+    inp = synth.chain_inputs(5, 6, 9000, "bf16", "peaked", 1.0, seed=4)
+    parent = np.broadcast_to(np.arange(-1, 5, dtype=np.int32), (5, 6)).copy()
+    tinp = dict(target=inp["target"], draft=inp["draft"], node_tokens=inp["cand"], parent=parent)
+    d = pu.to_dev(inp, ("target", "draft", "cand"))
+    for mode in (fsd.SAMPLE, fsd.GREEDY):
+        out = fsd.sd_verify_chain(d["target"], d["draft"], d["cand"], mode, seed=8, offset=3)
+        torch_cuda.cuda.synchronize()
+        c = pu.host(out, pu.SD_KEYS)
+        t = run_sd_tree(torch_cuda, tinp, 6, mode, seed=8, offset=3)
+        assert (c["accept_len"] == t["path_len"]).all()
+        assert (c["out_tokens"] == t["out_tokens"]).all()
+        for b in range(5):
+            n = min(int(c["accept_len"][b]) + 1, 6)
+            assert np.array_equal(c["log_ratio"][b, :n], t["log_ratio"][b, :n])
+            assert np.isnan(t["log_ratio"][b, n:]).all()
+
+
+def test_sd_tree_bad_input(torch_cuda, oracle):
+    inp = synth.chain_inputs(3, 4, 500, "f32", "gauss2", 1.0, seed=4)
+    parent = np.array([[-1, 0, 2, 1], [-1, 0, 1, 2], [-1, -1, 0, 0]], dtype=np.int32)
+    toks = inp["cand"].copy()
+    toks[2, 3] = 500                                              # token id out of range
+    tinp = dict(target=inp["target"], draft=inp["draft"], node_tokens=toks, parent=parent)
+    g = run_sd_tree(torch_cuda, tinp, 2)
+    o = oracle.sd_verify_tree(inp["target"], inp["draft"], toks, parent, 2)
+    assert list(o["row_status"]) == [fsd.ROW_BAD_PARENT, fsd.ROW_TOO_DEEP, fsd.ROW_BAD_TOKEN]
+    assert list(g["row_status"]) == list(o["row_status"])
+    assert (g["path_len"] == 0).all() and (g["out_tokens"] == -1).all() and (g["path_nodes"] == -1).all()
+
+
+def test_config_c4_strict_sd_tree(torch_cuda, oracle):
+    inp = synth.config_inputs("C4", seed=0)
+    md = int(inp["max_depth"])
+    g = run_sd_tree(torch_cuda, inp, md, seed=6, offset=2)
+    o = oracle.sd_verify_tree(inp["target"], inp["draft"], inp["node_tokens"], inp["parent"], md, seed=6, offset=2)
+    r = check_sd_tree(g, o, "C4 strict SD")
+    print("C4 strict SD", r, "path_len histogram", np.bincount(o["path_len"]),
+          "nodes tried", (~np.isnan(o["log_ratio"])).sum(axis=1), flush=True)
+
+
 # ------------------------------------------------------------------------------- robustness
 
 def test_bounded_wait_expires_cleanly(torch_cuda, oracle):
