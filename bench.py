@@ -45,6 +45,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="C2", choices=["C2", "C3", "C4"])
     ap.add_argument("--div", default="js", choices=["kl", "js", "tv"])
+    ap.add_argument("--method", default="fsd", choices=["fsd", "sd", "rfsd"],
+                    help="fsd: the paper's rule (default); sd: the strict baseline (chain or tree); rfsd: reducible FSD (chain)")
     ap.add_argument("--sets", type=int, default=0, help="distinct input sets to rotate (0 = enough for > 1 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -92,9 +94,23 @@ def main() -> int:
     ws = torch.empty(fsd.fsd_workspace_bytes(B, rows, V, dt_code) + 256, dtype=torch.uint8, device="cuda")
     outs = [None] * nsets
 
+    if args.method == "rfsd" and tree:
+        print("reducible FSD is built for chains only", file=sys.stderr)
+        return 2
+
     def step(i):
         d = sets[i % nsets]
-        if tree:
+        if args.method == "sd" and tree:
+            outs[i % nsets] = fsd.sd_verify_tree(d["target"], d["draft"], d["node_tokens"], d["parent"],
+                                                 d["max_depth"], fsd.SAMPLE, seed=1, offset=i,
+                                                 out=outs[i % nsets], workspace=ws)
+        elif args.method == "sd":
+            outs[i % nsets] = fsd.sd_verify_chain(d["target"], d["draft"], d["cand"], fsd.SAMPLE, seed=1, offset=i,
+                                                  out=outs[i % nsets], workspace=ws)
+        elif args.method == "rfsd":
+            outs[i % nsets] = fsd.rfsd_verify_chain(d["target"], d["draft"], d["cand"], T, div, fsd.SAMPLE, seed=1,
+                                                    offset=i, out=outs[i % nsets], workspace=ws)
+        elif tree:
             outs[i % nsets] = fsd.fsd_verify_tree(d["target"], d["draft"], d["node_tokens"], d["parent"],
                                                   d["max_depth"], T, div, fsd.SAMPLE, seed=1, offset=i,
                                                   out=outs[i % nsets], workspace=ws)
@@ -128,8 +144,9 @@ def main() -> int:
     value = positions * args.steps / (t1 - t0)
     alg_bytes = 2 * V * es * positions          # one target row + one draft row per position, read once
     achieved = alg_bytes / (k1_mean_ms * 1e-3) / 1e9 if n_ev else None
+    rule = {"fsd": f"{args.div.upper()} T={T}", "sd": "strict SD", "rfsd": f"reducible {args.div.upper()} T={T}"}[args.method]
     workload = (f"{args.config}: {'tree' if tree else 'chain'} verify B={B} {'N' if tree else 'K'}={rows} V={V} "
-                f"{cfg['dtype']} {args.div.upper()} T={T}")
+                f"{cfg['dtype']} {rule}")
 
     result = {
         "metric": "verified candidate positions/sec and achieved HBM GB/s (% peak) at V=128256",
@@ -159,7 +176,17 @@ def main() -> int:
         t0 = time.perf_counter()
         npos = 0
         for inp in host_sets * 3:
-            if tree:
+            if args.method == "sd" and tree:
+                nb = min(B, 8)
+                oracle.sd_verify_tree(inp["target"][:nb], inp["draft"][:nb], inp["node_tokens"][:nb],
+                                      inp["parent"][:nb], int(inp["max_depth"]), seed=1)
+            elif args.method == "sd":
+                nb = min(B, 64)
+                oracle.sd_verify_chain(inp["target"][:nb], inp["draft"][:nb], inp["cand"][:nb], seed=1)
+            elif args.method == "rfsd":
+                nb = min(B, 64)
+                oracle.rfsd_verify_chain(inp["target"][:nb], inp["draft"][:nb], inp["cand"][:nb], T, div, seed=1)
+            elif tree:
                 nb = min(B, 8)
                 oracle.verify_tree(inp["target"][:nb], inp["draft"][:nb], inp["node_tokens"][:nb], inp["parent"][:nb],
                                    int(inp["max_depth"]), T, div, seed=1)

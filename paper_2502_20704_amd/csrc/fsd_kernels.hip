@@ -26,6 +26,7 @@ namespace {
 
 constexpr int kWG = 256;          // threads per workgroup (4 wavefronts of 64)
 constexpr int kMaxRows = 2048;    // K or N
+constexpr int kWalkShare = 8;     // workgroups that share a sequence's passes in the tree walk (at most)
 constexpr float kLog2e = 1.44269504088896340736f;
 constexpr double kLn2 = 0.69314718055994530942;
 constexpr double kLog2eD = 1.44269504088896340736;
@@ -264,6 +265,7 @@ struct Ws {
     int* tsd;            // [B][4 + rows] strict SD on a tree, from the walk to the sampler: status, depth,
                          // last node (-1 = root), length of the residual chain, then the chain's nodes
     float* tsd_invz;     // [B][rows] 1 / normaliser of the chain's residuals (all but the last)
+    unsigned long long* wz;     // [B][rows][kWalkShare] the walk's partial normalisers, one round per rejection
 };
 
 struct PairParams {
@@ -1434,6 +1436,13 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
 // chain of rejected draft rows, and every rejection that is followed by another sibling costs one
 // pass over the vocabulary for its normaliser.  The token itself is drawn by accept_sample from
 // what this kernel leaves in the workspace.
+//
+// gridDim.x workgroups share a sequence (all of them resident at once, which the host checks):
+// every one walks the same tree and takes the same decisions, a pass is split between them, and
+// the partial sums meet through 64-bit words in the workspace that are zero until posted, one
+// round of words per pass.  Every workgroup adds the partials in the same order, so all see the
+// same normaliser.  Waiting is bounded: a workgroup that gives up sets the call's internal-error
+// flag and leaves.  Workgroup 0 of a sequence writes the outputs.
 struct WalkParams {
     const char* target;
     const char* draft;
@@ -1447,6 +1456,7 @@ struct WalkParams {
     int32_t* path_nodes;      // [B,max_depth]
     int32_t* out_tokens;      // [B,max_depth+1]
     float* user_ratio;        // optional [B,N]
+    unsigned spin_limit;
     Ws ws;
 };
 
@@ -1460,11 +1470,16 @@ __global__ __launch_bounds__(kWalkWG) void tree_sd_walk(WalkParams P) {
     __shared__ double s_red[kWalkWG / 64];
     __shared__ int s_st;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int b = blockIdx.x, N = P.rows;
+    const int b = blockIdx.y, N = P.rows;
+    const int g = blockIdx.x, GSW = gridDim.x;
+    const bool writer = (g == 0);
     int* par = s_walk;
     int* dep = s_walk + N;
     int* chain = s_walk + 2 * N;
-    double* Zs = reinterpret_cast<double*>(s_walk + 3 * N + (N & 1));
+    float* s_invz = reinterpret_cast<float*>(s_walk + 3 * N);
+    double* Zs = reinterpret_cast<double*>(s_walk + 4 * N);
+    const double* lr_of = P.ws.lr + static_cast<size_t>(b) * N;
+    const double* lse_of = P.ws.lse2 + 2 * static_cast<size_t>(b) * N;
     int* hdr = P.ws.tsd + static_cast<size_t>(b) * (4 + N);
     float* invz = P.ws.tsd_invz + static_cast<size_t>(b) * N;
     int32_t* pn = P.path_nodes + static_cast<size_t>(b) * P.max_depth;
@@ -1480,10 +1495,12 @@ __global__ __launch_bounds__(kWalkWG) void tree_sd_walk(WalkParams P) {
         const int st = P.ws.pst[pr];
         if (st) atomicOr(&s_st, st);
         par[j] = p;
-        if (P.user_ratio) P.user_ratio[pr] = __builtin_nanf("");
+        if (writer && P.user_ratio) P.user_ratio[pr] = __builtin_nanf("");
     }
-    for (int i = tid; i < P.max_depth; i += kWalkWG) pn[i] = -1;
-    for (int i = tid; i <= P.max_depth; i += kWalkWG) out[i] = -1;
+    if (writer) {
+        for (int i = tid; i < P.max_depth; i += kWalkWG) pn[i] = -1;
+        for (int i = tid; i <= P.max_depth; i += kWalkWG) out[i] = -1;
+    }
     __syncthreads();
     if (tid == 0) {
         for (int j = 0; j < N; ++j) {   // parents come first, so one sweep gives the depths
@@ -1496,9 +1513,14 @@ __global__ __launch_bounds__(kWalkWG) void tree_sd_walk(WalkParams P) {
     if (status & FSD_ROW_BAD_PARENT) status &= ~FSD_ROW_TOO_DEEP;
     if (P.ws.counters[1]) status |= FSD_ROW_INTERNAL;
     if (status) {
-        if (tid == 0) { hdr[0] = status; hdr[1] = 0; hdr[2] = -1; hdr[3] = 0; }
+        if (writer && tid == 0) { hdr[0] = status; hdr[1] = 0; hdr[2] = -1; hdr[3] = 0; }
         return;
     }
+    // this workgroup's share of a pass
+    const long share = (P.nslots + GSW - 1) / GSW;
+    const long sl_lo = static_cast<long>(g) * share;
+    const long sl_hi = (sl_lo + share < P.nslots) ? sl_lo + share : P.nslots;
+    int round = 0;   // passes so far in this sequence
 
     const size_t rowb = static_cast<size_t>(P.V) * ES;
     int cur = -1, n = 0, nrej = 0, last_j = -1, before_last = 0;
@@ -1511,15 +1533,15 @@ __global__ __launch_bounds__(kWalkWG) void tree_sd_walk(WalkParams P) {
             const size_t pr = static_cast<size_t>(b) * N + j;
             const char* drow = P.draft + pr * rowb;
             const int x = tok[j];
-            const double lt2 = P.ws.lse2[2 * pr], ld2 = P.ws.lse2[2 * pr + 1];
+            const double lt2 = lse_of[2 * j], ld2 = lse_of[2 * j + 1];
             double ratio;
             if (nrej == 0) {
-                ratio = P.ws.lr[pr];
+                ratio = lr_of[j];
             } else {
                 double r = exp2(static_cast<double>(load_elem<BF16>(trow, x)) * kLog2eD - lt2);
                 for (int m = 0; m < nrej; ++m) {
                     const size_t pc = static_cast<size_t>(b) * N + chain[m];
-                    const double q = exp2(static_cast<double>(load_elem<BF16>(P.draft + pc * rowb, x)) * kLog2eD - P.ws.lse2[2 * pc + 1]);
+                    const double q = exp2(static_cast<double>(load_elem<BF16>(P.draft + pc * rowb, x)) * kLog2eD - lse_of[2 * chain[m] + 1]);
                     r = fmax(r - q, 0.0) / Zs[m];
                 }
                 const double lq = (static_cast<double>(load_elem<BF16>(drow, x)) * kLog2eD - ld2) * kLn2;
@@ -1531,7 +1553,7 @@ __global__ __launch_bounds__(kWalkWG) void tree_sd_walk(WalkParams P) {
             const unsigned wsel = (j & 3) == 0 ? rw.x : (j & 3) == 1 ? rw.y : (j & 3) == 2 ? rw.z : rw.w;
             const double u = static_cast<double>(word_to_uniform(wsel));
             const double thr = ratio < 0.0 ? ratio : 0.0;
-            if (tid == 0 && P.user_ratio) P.user_ratio[pr] = static_cast<float>(ratio);
+            if (writer && tid == 0 && P.user_ratio) P.user_ratio[pr] = static_cast<float>(ratio);
             if (thr - log(u) > 0.0) { next = j; break; }
             last_j = j;
             before_last = nrej;
@@ -1540,24 +1562,55 @@ __global__ __launch_bounds__(kWalkWG) void tree_sd_walk(WalkParams P) {
             if (!more) break;
             // ---- the normaliser of the positive part of p - q_j, p being the distribution in force
             const float ltf = static_cast<float>(lt2), ldf = static_cast<float>(ld2);
+            // CH slots per thread at a time, row by row: the CH loads of a row are in flight together
+            // (one slot at a time, each load waited for the one before it)
+            constexpr int CH = BF16 ? 4 : 8;
             double acc = 0.0;
-            for (long sl = tid; sl < P.nslots; sl += kWalkWG) {
-                float z[VE], zd[VE], pv[VE];
-                unpack<BF16>(load_slot<BF16, ALIGNED>(trow, sl, P.V), z);
+            for (long base = sl_lo; base < sl_hi; base += static_cast<long>(kWalkWG) * CH) {
+                float pv[CH][VE];
+                uint4 raw[CH];
+                long slc[CH];
+                bool in[CH];
 #pragma unroll
-                for (int e = 0; e < VE; ++e) pv[e] = hw_exp2(fmaf(z[e], kLog2e, -ltf));
+                for (int c = 0; c < CH; ++c) {
+                    const long sl = base + static_cast<long>(c) * kWalkWG + tid;
+                    in[c] = sl < sl_hi;
+                    slc[c] = in[c] ? sl : P.nslots - 1;
+                    raw[c] = load_slot<BF16, ALIGNED>(trow, slc[c], P.V);
+                }
+#pragma unroll
+                for (int c = 0; c < CH; ++c) {
+                    float z[VE];
+                    unpack<BF16>(raw[c], z);
+#pragma unroll
+                    for (int e = 0; e < VE; ++e) pv[c][e] = in[c] ? hw_exp2(fmaf(z[e], kLog2e, -ltf)) : 0.0f;
+                }
                 for (int m = 0; m < nrej; ++m) {
                     const size_t pc = static_cast<size_t>(b) * N + chain[m];
-                    unpack<BF16>(load_slot<BF16, ALIGNED>(P.draft + pc * rowb, sl, P.V), zd);
-                    const float ldm = static_cast<float>(P.ws.lse2[2 * pc + 1]), izm = invz[m];
+                    const char* cr = P.draft + pc * rowb;
 #pragma unroll
-                    for (int e = 0; e < VE; ++e) pv[e] = fmaxf(pv[e] - hw_exp2(fmaf(zd[e], kLog2e, -ldm)), 0.0f) * izm;
+                    for (int c = 0; c < CH; ++c) raw[c] = load_slot<BF16, ALIGNED>(cr, slc[c], P.V);
+                    const float ldm = static_cast<float>(lse_of[2 * chain[m] + 1]), izm = s_invz[m];
+#pragma unroll
+                    for (int c = 0; c < CH; ++c) {
+                        float zd[VE];
+                        unpack<BF16>(raw[c], zd);
+#pragma unroll
+                        for (int e = 0; e < VE; ++e)
+                            pv[c][e] = fmaxf(pv[c][e] - hw_exp2(fmaf(zd[e], kLog2e, -ldm)), 0.0f) * izm;
+                    }
                 }
-                unpack<BF16>(load_slot<BF16, ALIGNED>(drow, sl, P.V), zd);
-                float part = 0.0f;
 #pragma unroll
-                for (int e = 0; e < VE; ++e) part += fmaxf(pv[e] - hw_exp2(fmaf(zd[e], kLog2e, -ldf)), 0.0f);
-                acc += static_cast<double>(part);
+                for (int c = 0; c < CH; ++c) raw[c] = load_slot<BF16, ALIGNED>(drow, slc[c], P.V);
+#pragma unroll
+                for (int c = 0; c < CH; ++c) {
+                    float zd[VE];
+                    unpack<BF16>(raw[c], zd);
+                    float part = 0.0f;
+#pragma unroll
+                    for (int e = 0; e < VE; ++e) part += fmaxf(pv[c][e] - hw_exp2(fmaf(zd[e], kLog2e, -ldf)), 0.0f);
+                    acc += static_cast<double>(part);
+                }
             }
             acc = wave_sum(acc);
             __syncthreads();   // the previous round's readers are done with s_red
@@ -1565,21 +1618,47 @@ __global__ __launch_bounds__(kWalkWG) void tree_sd_walk(WalkParams P) {
             __syncthreads();
             double Z = 0.0;
             for (int w = 0; w < kWalkWG / 64; ++w) Z += s_red[w];   // same order in every thread
+            if (GSW > 1) {
+                // ---- meet the other workgroups of the sequence: post this share, read all of them
+                unsigned long long* const words = P.ws.wz + (static_cast<size_t>(b) * N + round) * kWalkShare;
+                if (tid == 0) post64(words + g, dbits(Z));
+                __syncthreads();   // everyone has read s_red
+                if (tid < GSW) {
+                    unsigned long long v = 0;
+                    unsigned polls = 0;
+                    for (;;) {
+                        v = read64(words + tid);
+                        if (v != 0 || polls++ >= P.spin_limit) break;
+                        __builtin_amdgcn_s_sleep(2);
+                    }
+                    s_red[tid] = (v != 0) ? bitsd(v) : __builtin_nan("");
+                }
+                __syncthreads();
+                Z = 0.0;
+                for (int w = 0; w < GSW; ++w) Z += s_red[w];
+                if (Z != Z) {   // a workgroup of this sequence never posted: give up, the call reports it
+                    if (tid == 0) atomicOr(P.ws.counters + 1, 1u);
+                    return;
+                }
+            }
+            ++round;
             if (Z > 0.0) {
-                if (tid == 0) { chain[nrej] = j; Zs[nrej] = Z; invz[nrej] = static_cast<float>(1.0 / Z); }
-                __threadfence_block();
+                if (tid == 0) {
+                    chain[nrej] = j; Zs[nrej] = Z; s_invz[nrej] = static_cast<float>(1.0 / Z);
+                    if (writer) invz[nrej] = static_cast<float>(1.0 / Z);
+                }
                 __syncthreads();
                 ++nrej;
             }
         }
         if (next < 0) break;
-        if (tid == 0) { pn[n] = next; out[n] = tok[next]; }
+        if (writer && tid == 0) { pn[n] = next; out[n] = tok[next]; }
         ++n;
         cur = next;
     }
     // ---- what the sampler needs: the residual chain ends with the last rejected child, whose
     // normaliser nobody needs
-    if (tid == 0) {
+    if (writer && tid == 0) {
         hdr[0] = 0;
         hdr[1] = n;
         hdr[2] = cur;
@@ -1840,7 +1919,7 @@ __global__ void calib_result(const CalibState* st, long n, float* T_out, float* 
 struct Plan {
     int VE, NV, G, spm, GS, sps;   // G = wavefronts per pair
     long nslots;
-    size_t off_counters, n_counters, off_part1, off_part2, zero_bytes, off_div, off_pst, off_lse2, off_lr, off_spart,
+    size_t off_counters, n_counters, off_part1, off_part2, off_wz, zero_bytes, off_div, off_pst, off_lse2, off_lr, off_spart,
         off_thr, off_tsd, off_tsdz, bytes;
 };
 
@@ -1882,6 +1961,7 @@ bool make_plan(int B, int rows, long V, int dtype, Plan& p) {
     p.off_counters = o; p.n_counters = 64 + B; o = align_up(o + p.n_counters * 4, 256);
     p.off_part1 = o; o = align_up(o + R * p.G * 32, 256);
     p.off_part2 = o; o = align_up(o + R * p.G * 32, 256);
+    p.off_wz = o; o = align_up(o + R * kWalkShare * 8, 256);
     p.zero_bytes = o;
     p.off_div = o; o = align_up(o + R * 4, 256);
     p.off_pst = o; o = align_up(o + R * 4, 256);
@@ -1911,6 +1991,7 @@ Ws carve(void* workspace, const Plan& p, int B, int rows) {
     w.thr = reinterpret_cast<float*>(base + p.off_thr);
     w.tsd = reinterpret_cast<int*>(base + p.off_tsd);
     w.tsd_invz = reinterpret_cast<float*>(base + p.off_tsdz);
+    w.wz = reinterpret_cast<unsigned long long*>(base + p.off_wz);
     return w;
 }
 
@@ -2042,6 +2123,24 @@ void launch_sample(int dtype, bool aligned, int kind, dim3 grid, size_t lds, hip
     }
 }
 
+// The workgroups that share a sequence wait for each other, so the whole grid has to be resident:
+// as many per sequence as fit (at most kWalkShare, and no more than there are passes' worth of
+// slots), a single one otherwise.
+template <typename Kernel>
+void launch_walk(Kernel kernel, int B, long nslots, size_t lds, hipStream_t st, const WalkParams& P) {
+    int dev = 0, per_cu = 0, cus = 0;
+    (void)hipGetDevice(&dev);
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kWalkWG, lds) != hipSuccess) per_cu = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 0;
+    (void)hipGetLastError();
+    long gsw = (static_cast<long>(per_cu) * cus) / B;
+    if (gsw > kWalkShare) gsw = kWalkShare;
+    const long by_work = (nslots + kWalkWG - 1) / kWalkWG;
+    if (gsw > by_work) gsw = by_work;
+    if (gsw < 1) gsw = 1;
+    hipLaunchKernelGGL(kernel, dim3(static_cast<unsigned>(gsw), static_cast<unsigned>(B)), dim3(kWalkWG), lds, st, P);
+}
+
 bool is_aligned(const void* a, const void* b, long V, int VE) {
     return (V % VE == 0) && (reinterpret_cast<uintptr_t>(a) % 16 == 0) &&
            (b == nullptr || reinterpret_cast<uintptr_t>(b) % 16 == 0);
@@ -2163,13 +2262,14 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
         wk.out_tokens = out_tokens;
         wk.user_ratio = user_ratio;
         wk.ws = ws;
-        const size_t wlds = static_cast<size_t>(rows) * 20 + 16;
+        wk.spin_limit = g_spin_limit;
+        const size_t wlds = static_cast<size_t>(rows) * 24 + 16;
         if (dtype == FSD_BF16) {
-            if (aligned) hipLaunchKernelGGL((tree_sd_walk<true, true>), dim3(B), dim3(kWalkWG), wlds, st, wk);
-            else hipLaunchKernelGGL((tree_sd_walk<true, false>), dim3(B), dim3(kWalkWG), wlds, st, wk);
+            if (aligned) launch_walk(tree_sd_walk<true, true>, B, p.nslots, wlds, st, wk);
+            else launch_walk(tree_sd_walk<true, false>, B, p.nslots, wlds, st, wk);
         } else {
-            if (aligned) hipLaunchKernelGGL((tree_sd_walk<false, true>), dim3(B), dim3(kWalkWG), wlds, st, wk);
-            else hipLaunchKernelGGL((tree_sd_walk<false, false>), dim3(B), dim3(kWalkWG), wlds, st, wk);
+            if (aligned) launch_walk(tree_sd_walk<false, true>, B, p.nslots, wlds, st, wk);
+            else launch_walk(tree_sd_walk<false, false>, B, p.nslots, wlds, st, wk);
         }
     }
     const size_t lds = (kind == KIND_TREE) ? static_cast<size_t>(rows) * 16
