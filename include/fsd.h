@@ -262,6 +262,12 @@ int fsd_debug_set_shape(int wavefronts, int slots_per_thread);
  * the number of its workgroups the device can hold at once, which caps it. */
 void fsd_debug_last_launch(int* grid, int* resident);
 
+/* Test hook: byte offset, inside a workspace of fsd_workspace_bytes(B,
+ * rows_per_seq, V, dtype), of the B binary32 values fsd_verify_chain_warped
+ * leaves there: per sequence the smallest scaled logit its warpers kept on the
+ * row the token was drawn from (-inf when nothing is cut).  0 for bad shapes. */
+size_t fsd_debug_warp_threshold_offset(int B, int rows_per_seq, int V, int dtype);
+
 #ifdef __cplusplus
 }
 #endif

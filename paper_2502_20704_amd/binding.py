@@ -343,6 +343,19 @@ def debug_set_spin_limit(polls: int) -> int:
     return int(library().fsd_debug_set_spin_limit(polls))
 
 
+def debug_warp_thresholds(out, B: int, rows: int, V: int, dtype_code: int):
+    """the per-sequence cut fsd_verify_chain_warped left in its workspace (test hook), as a float32 tensor [B]"""
+    import torch
+
+    L = library()
+    L.fsd_debug_warp_threshold_offset.argtypes = [ctypes.c_int] * 4
+    L.fsd_debug_warp_threshold_offset.restype = ctypes.c_size_t
+    off = L.fsd_debug_warp_threshold_offset(B, rows, V, dtype_code)
+    ws = out["_workspace"]
+    base = (-ws.data_ptr()) % 256          # the binding hands the library a 256-byte aligned start
+    return ws[base + off: base + off + 4 * B].view(torch.float32).clone()
+
+
 def debug_set_shape(wavefronts: int, slots_per_thread: int) -> None:
     st = library().fsd_debug_set_shape(wavefronts, slots_per_thread)
     if st != 0:

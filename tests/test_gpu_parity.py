@@ -311,10 +311,14 @@ def run_warped(torch_cuda, inp, T, div, mode, seed, offset, **kw):
     d = pu.to_dev(inp, ("target", "draft", "cand"))
     out = fsd.fsd_verify_chain_warped(d["target"], d["draft"], d["cand"], T, div, mode, seed, offset, **kw)
     torch_cuda.cuda.synchronize()
-    return pu.host(out, pu.CHAIN_KEYS)
+    g = pu.host(out, pu.CHAIN_KEYS)
+    B, K1, V = d["target"].shape
+    code = fsd.BF16 if inp["target"].dtype == np.uint16 else fsd.F32
+    g["threshold"] = fsd.debug_warp_thresholds(out, B, K1 - 1, V, code).cpu().numpy()
+    return g
 
 
-def check_warped(g, o, T, tol, what):
+def check_warped(g, o, T, tol, what, sampled=True, cut_active=True):
     """as check_chain; a token may differ where the nucleus mass sat on top_p (the kept set then
     differs by one value) or where two scores tie to 1e-6"""
     assert (g["row_status"] == o["row_status"]).all(), what
@@ -325,6 +329,11 @@ def check_warped(g, o, T, tol, what):
         if g["accept_len"][b] != o["accept_len"][b]:
             n_soft += 1
             continue
+        # the cut itself (the smallest kept scaled logit), not only the token it leads to: exact unless
+        # the nucleus mass sits on top_p
+        if sampled and o["row_status"][b] == 0 and o["slack"][b] >= 1e-5 and cut_active:
+            assert g["threshold"][b] == o["threshold"][b], \
+                f"{what}: cut[{b}] gpu {g['threshold'][b]} oracle {o['threshold'][b]} slack {o['slack'][b]}"
         if not (g["out_tokens"][b] == o["out_tokens"][b]).all():
             assert o["slack"][b] < 1e-5 or o["gap"][b] < 1e-6, \
                 f"{what}: tokens[{b}] gpu {g['out_tokens'][b]} oracle {o['out_tokens'][b]} slack {o['slack'][b]} gap {o['gap'][b]}"
@@ -344,7 +353,8 @@ def test_warpers_small(torch_cuda, oracle):
         for kw in WARPS:
             g = run_warped(torch_cuda, inp, 0.1, fsd.DIV_JS, fsd.SAMPLE, 5, 2, **kw)
             o = oracle.verify_chain_warped(inp["target"], inp["draft"], inp["cand"], 0.1, fsd.DIV_JS, fsd.SAMPLE, 5, 2, **kw)
-            check_warped(g, o, 0.1, tol, f"warped B={B} K={K} V={V} {dtype} {kw}")
+            active = 0 < kw.get("top_k", 0) < V or kw.get("top_p", 1.0) < 1.0   # otherwise no selection runs
+            check_warped(g, o, 0.1, tol, f"warped B={B} K={K} V={V} {dtype} {kw}", cut_active=active)
     # warpers off: the plain call, bit for bit; greedy ignores them
     inp = synth.chain_inputs(5, 9, 32000, "bf16", "zipf", (0.25, 4.0), seed=72)
     a = run_chain(torch_cuda, inp, 0.1, fsd.DIV_JS, seed=5, offset=2)
@@ -353,6 +363,32 @@ def test_warpers_small(torch_cuda, oracle):
     gr = run_chain(torch_cuda, inp, 0.1, fsd.DIV_JS, mode=fsd.GREEDY, seed=5, offset=2)
     for k in pu.CHAIN_KEYS:
         assert np.array_equal(a[k], b[k]) and np.array_equal(c[k], gr[k]), k
+
+
+def test_warpers_selection_edge_cases(torch_cuda, oracle):
+    """the cut is exact on every path of the selection: the short way (per-thread maxima), its
+    overflow into the general path (many equal entries), top-k beyond the short way's reach, a
+    nucleus that fits the candidate list and one that does not"""
+    rng = np.random.default_rng(81)
+    B, K, V = 6, 2, 40000
+    t = (rng.standard_normal((B, K + 1, V)) * 2).astype(np.float32)
+    d = (t[:, :K] + rng.standard_normal((B, K, V)).astype(np.float32) * 0.5).astype(np.float32)
+    t[0] = 1.25                                   # all equal: every entry ties with the k-th largest
+    t[1, :, :30000] = -3.0                        # three quarters of the row tie far below the top
+    t[2] = (rng.standard_normal((K + 1, V)) * 0.05).astype(np.float32)   # nearly flat: a huge nucleus
+    t[3, :, 7] += 30.0                            # one dominant entry: the nucleus is that entry
+    cand = rng.integers(0, V, (B, K)).astype(np.int32)
+    for dtype in ("f32", "bf16"):
+        inp = dict(target=t, draft=d, cand=cand)
+        if dtype == "bf16":
+            inp = dict(target=synth.to_bf16_bits(t), draft=synth.to_bf16_bits(d), cand=cand)
+        for kw in (dict(top_k=5), dict(top_k=512), dict(top_k=513), dict(top_k=3000), dict(top_k=20000),
+                   dict(top_p=0.5), dict(top_p=0.97), dict(top_k=300, top_p=0.9),
+                   dict(temperature=2.5, top_k=1000, top_p=0.99)):
+            print("selection edge cases", dtype, kw, flush=True)
+            g = run_warped(torch_cuda, inp, 0.1, fsd.DIV_TV, fsd.SAMPLE, 9, 4, **kw)
+            o = oracle.verify_chain_warped(inp["target"], inp["draft"], inp["cand"], 0.1, fsd.DIV_TV, fsd.SAMPLE, 9, 4, **kw)
+            check_warped(g, o, 0.1, pu.rel_tol(dtype), f"selection edge cases {dtype} {kw}")
 
 
 def test_config_c2_warped(torch_cuda, oracle):
