@@ -1137,11 +1137,18 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
         sample_row = n;
     } else if constexpr (KIND == KIND_TREESD) {
         // the walk kernel has decided: depth, last node, and the residual chain the token comes from
+        // (if the walk gave up on a bounded wait it may have written nothing: the header is then
+        // whatever an earlier call left, so nothing in it is trusted)
         const int* hdr = P.ws.tsd + static_cast<size_t>(b) * (4 + rows);
-        if (tid == 0) s_st = hdr[0];
-        n = hdr[1];
-        sample_row = hdr[2] + 1;
-        nchain = hdr[3];
+        const bool gave_up = P.ws.counters[1] != 0;
+        if (tid == 0) s_st = gave_up ? FSD_ROW_INTERNAL : hdr[0];
+        n = gave_up ? 0 : hdr[1];
+        sample_row = gave_up ? 0 : hdr[2] + 1;
+        nchain = gave_up ? 0 : hdr[3];
+        if (n < 0 || n > P.max_depth || sample_row < 0 || sample_row > rows || nchain < 0 || nchain > rows) {
+            n = 0; sample_row = 0; nchain = 0;
+            if (tid == 0) s_st = FSD_ROW_INTERNAL;
+        }
         int* ch = s_dyn;
         float* iz = reinterpret_cast<float*>(s_dyn + rows);
         float* ldv = reinterpret_cast<float*>(s_dyn + 2 * rows);

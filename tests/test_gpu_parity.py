@@ -641,6 +641,29 @@ def test_sd_tree_bad_input(torch_cuda, oracle):
     assert (g["path_len"] == 0).all() and (g["out_tokens"] == -1).all() and (g["path_nodes"] == -1).all()
 
 
+def test_sd_tree_bounded_wait_expires_cleanly(torch_cuda, oracle):
+    """the workgroups that share a tree's passes wait for each other with a poll budget: with a budget of
+    zero the call ends, and every sequence is either right or flagged FSD_ROW_INTERNAL with empty outputs"""
+    rng = np.random.default_rng(17)
+    inp = _random_tree_inputs(rng, 4, 12, 50000, "bf16", star=True, noise=(1.5, 3.0))
+    o = oracle.sd_verify_tree(inp["target"], inp["draft"], inp["node_tokens"], inp["parent"], 1, seed=3, offset=1)
+    prev = fsd.debug_set_spin_limit(0)
+    try:
+        g = run_sd_tree(torch_cuda, inp, 1, seed=3, offset=1)
+    finally:
+        fsd.debug_set_spin_limit(prev)
+    # (the normalisers come from the single-pass reduction, whose finisher flags the pair it could not
+    # finish: a sequence is either flagged, with empty outputs, or right)
+    bad = (g["row_status"] & fsd.ROW_INTERNAL) != 0
+    assert ((g["row_status"] == 0) | bad).all()
+    assert (g["path_len"][bad] == 0).all() and (g["out_tokens"][bad] == -1).all() and (g["path_nodes"][bad] == -1).all()
+    if (~bad).any():
+        check_sd_tree({k: v[~bad] for k, v in g.items()}, {k: v[~bad] for k, v in o.items()},
+                      "zero poll budget, sequences that were not flagged")
+    g = run_sd_tree(torch_cuda, inp, 1, seed=3, offset=1)
+    check_sd_tree(g, o, "after restoring the poll budget")
+
+
 def test_config_c4_strict_sd_tree(torch_cuda, oracle):
     inp = synth.config_inputs("C4", seed=0)
     md = int(inp["max_depth"])
