@@ -38,7 +38,7 @@ enum { KIND_CHAIN = 0, KIND_TREE = 1, KIND_SD = 2, KIND_RFSD = 3, KIND_TREESD = 
 
 #define AGENT __HIP_MEMORY_SCOPE_AGENT
 
-// Optional phase timing of pair_reduce (development builds only: -DFSD_PHASE_TIMING).
+// Optional phase timing of pair_kernel (development builds only: -DFSD_PHASE_TIMING).
 #ifdef FSD_PHASE_TIMING
 #define PT(i) do { const unsigned long long pt_now = __builtin_readcyclecounter(); pt_acc[i] += pt_now - pt_last; pt_last = pt_now; } while (0)
 #else
@@ -316,19 +316,18 @@ __global__ void zero_counters(uint4* p, long n16) {
 //             sums in member order (fixed order: results are bit-identical run to run) and writes
 //             divergence and status.
 //
-// The kernel is persistent and software-pipelined by one pair: in a step a wavefront runs phase 1
-// of pair j and then phase 2 of pair j-1 from a second set of exponentials.  Memory operations
-// return in the order they were issued, which fixes the order of the requests in a step (see
-// `step`): small exchange words first, the next pair's logits as soon as phase 1 has consumed the
-// registers, and nothing after that waits on memory unless a team member is late.  In practice
-// the slowest member of a team sets the pace and the others do wait for its words; that wait
-// coincides with the flight time of their own prefetch.  A step therefore costs about phase 1
-// plus one memory latency, whatever phase 2 does: this, not arithmetic or bandwidth, bounds the
-// two-phase modes at two wavefronts per SIMD (the registers of two sets of exponentials).
-// The single-pass modes (bfloat16 KL, the normalisers of strict SD) have no phase 2.  Waiting is
-// bounded (spin_limit polls, then FSD_ROW_INTERNAL), so every wavefront reaches the end of the
-// kernel whatever happens; all team members are resident by construction (the grid never exceeds
-// what fits on the device at once).
+// The kernel is persistent and software-pipelined: in a step a wavefront runs phase 1 of pair j
+// and then phase 2 of pair j - LAG from an older set of kept exponentials (LAG = 1, or 2 where
+// the registers allow a third set).  Memory operations return in the order they were issued,
+// which fixes the order of the requests in a step (see `step`): small exchange words first, the
+// next pair's logits as soon as phase 1 has consumed the registers (a whole step ahead where a
+// second set of logit registers fits), and nothing after that waits on memory unless a team
+// member is late.  The bfloat16 two-phase kernels (two wavefronts per SIMD) are bound by
+// vector-ALU issue; the binary32 ones (one wavefront per SIMD) by the exposed latencies, which the
+// longer lag and the earlier prefetch hide.  The single-pass modes (bfloat16 KL, the normalisers
+// of strict SD) have no phase 2.  Waiting is bounded (spin_limit polls, then FSD_ROW_INTERNAL),
+// so every wavefront reaches the end of the kernel whatever happens; all team members are
+// resident by construction (the grid never exceeds what fits on the device at once).
 
 // The exchange words are only ever touched with device-scope atomic loads and stores, which are
 // performed at the memory side: no cache write-back or invalidate is needed to see them.  They are
@@ -2214,7 +2213,7 @@ unsigned g_spin_limit = 1u << 22;
 unsigned long long* g_dbg = nullptr;
 #endif
 
-// ---- optional event timing of pair_reduce
+// ---- optional event timing of pair_kernel
 constexpr int kMaxProf = 4096;
 bool g_prof_on = false;
 int g_prof_n = 0;
