@@ -458,8 +458,14 @@ __device__ __noinline__ Sums<N> sum_more_rounds(const unsigned long long* p2, in
 
 template <int I> struct SetId { static constexpr int value = I; };
 
+// wavefronts per SIMD the register allocation has to leave room for
+constexpr int pair_kernel_waves(bool bf16, int nv, int mode) {
+    return (bf16 && nv == 5 && (mode == MODE_JS || mode == MODE_TV)) ? 2 : 1;
+}
+
 template <bool BF16, int NV, int MODE, bool ALIGNED>
-__global__ __launch_bounds__(kWG) void pair_kernel(PairParams P) {
+__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(pair_kernel_waves(BF16, NV, MODE))))
+void pair_kernel(PairParams P) {
     constexpr int VE = Slot<BF16>::VE;
     constexpr int ES = BF16 ? 2 : 4;
     constexpr bool TWO_PHASE = (MODE == MODE_JS || MODE == MODE_TV || MODE == MODE_KLP);
@@ -2157,7 +2163,7 @@ bool make_plan(int B, int rows, long V, int dtype, Plan& p) {
     p.nslots = (V + p.VE - 1) / p.VE;
     // 32 vocabulary entries of each row per lane: 4 slots of bfloat16, 8 of binary32
     p.NV = (dtype == FSD_BF16) ? 4 : 8;
-    if (g_shape_nv && !(dtype == FSD_BF16 && g_shape_nv > 4) && team_size(p.nslots, g_shape_nv) <= kMaxTeam) p.NV = g_shape_nv;
+    if (g_shape_nv && !(dtype == FSD_BF16 && g_shape_nv > 5) && team_size(p.nslots, g_shape_nv) <= kMaxTeam) p.NV = g_shape_nv;
     const long G = team_size(p.nslots, p.NV);
     if (G > kMaxTeam) return false;
     p.G = static_cast<int>(G);
@@ -2304,6 +2310,7 @@ void launch_pair(int dtype, int NV, int mode, bool aligned, hipStream_t st, cons
     }
     if (dtype == FSD_BF16) {
         if (NV == 2) launch_pair_m<true, 2>(mode, aligned, st, P);
+        else if (NV == 5) launch_pair_m<true, 5>(mode, aligned, st, P);
         else launch_pair_m<true, 4>(mode, aligned, st, P);
     } else {
         if (NV == 2) launch_pair_m<false, 2>(mode, aligned, st, P);
@@ -2409,6 +2416,16 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
     pp.ws = ws;
     int k1mode = (kind == KIND_SD || kind == KIND_TREESD) ? MODE_LSE : div;
     if (k1mode == MODE_KL && dtype == FSD_F32) k1mode = MODE_KLP;
+    if (dtype == FSD_BF16 && !g_shape_nv && (k1mode == MODE_JS || k1mode == MODE_TV)) {
+        // The bfloat16 two-phase kernels are bound by instruction issue, a third of it per step and not
+        // per entry: 5 slots per lane instead of 4 is the most that fits two wavefronts per SIMD (256
+        // registers).  The workspace is laid out for the larger team of the 4-slot shape.
+        p.NV = 5;
+        p.G = static_cast<int>(team_size(p.nslots, 5));
+        p.spm = static_cast<int>((p.nslots + p.G - 1) / p.G);
+        pp.spm = p.spm;
+        pp.G = p.G;
+    }
     launch_pair(dtype, p.NV, k1mode, aligned, st, pp);
 
     SampleParams sp;
@@ -2640,7 +2657,8 @@ int fsd_profile_collect(float* mean_ms, float* min_ms) {
 
 int fsd_debug_set_shape(int wavefronts, int slots_per_thread) {
     const bool ok = (wavefronts == 0 || wavefronts == 4) &&
-                    (slots_per_thread == 0 || slots_per_thread == 2 || slots_per_thread == 4 || slots_per_thread == 8);
+                    (slots_per_thread == 0 || slots_per_thread == 2 || slots_per_thread == 4 || slots_per_thread == 5 ||
+                     slots_per_thread == 8);
     if (!ok) return FSD_ERR_SHAPE;
     g_shape_nv = slots_per_thread;
     return FSD_OK;
