@@ -413,20 +413,17 @@ __device__ __forceinline__ bool await_n(const unsigned long long* p, int GW, int
 }
 
 // binary32 merge of one round of team words (two-phase format: word 0 = the two reference
-// exponents, word 1 = the two sums) into running (K, z) pairs.  Exact power-of-two rescaling.
+// exponents, word 1 = the two sums) into sums relative to the fixed references (n.Kt, n.Kd): the
+// reading wavefront's own exponents.  Exact power-of-two rescaling; a member far above the reader
+// makes the sum overflow to +inf, the reader's factor 1/sum is then 0, and so are its p and q:
+// they are below 2^-127 of the row's mass.
 struct TeamNorm { float Kt, Kd, zt, zd; bool ok; };
 
 __device__ __forceinline__ void merge_round(const unsigned long long (&w)[2], bool in, TeamNorm& n) {
     const float tk_t = lo_f(w[0]), tk_d = hi_f(w[0]);
     const float tSt = in ? lo_f(w[1]) : 0.0f, tSd = in ? hi_f(w[1]) : 0.0f;
-    const float nKt = fmaxf(n.Kt, wave_max((tSt > 0.0f) ? tk_t : neg_inf()));
-    const float nKd = fmaxf(n.Kd, wave_max((tSd > 0.0f) ? tk_d : neg_inf()));
-    n.zt = ((n.zt > 0.0f) ? ldexpf(n.zt, kdiff(n.Kt, nKt)) : n.zt) +
-           wave_sumf((tSt > 0.0f) ? ldexpf(tSt, kdiff(tk_t, nKt)) : (tSt != tSt ? tSt : 0.0f));
-    n.zd = ((n.zd > 0.0f) ? ldexpf(n.zd, kdiff(n.Kd, nKd)) : n.zd) +
-           wave_sumf((tSd > 0.0f) ? ldexpf(tSd, kdiff(tk_d, nKd)) : (tSd != tSd ? tSd : 0.0f));
-    n.Kt = nKt;
-    n.Kd = nKd;
+    n.zt += wave_sumf((tSt > 0.0f) ? ldexpf(tSt, kdiff(tk_t, n.Kt)) : (tSt != tSt ? tSt : 0.0f));
+    n.zd += wave_sumf((tSd > 0.0f) ? ldexpf(tSd, kdiff(tk_d, n.Kd)) : (tSd != tSd ? tSd : 0.0f));
 }
 // teams of more than 64 wavefronts: the members beyond the first round
 __device__ __noinline__ TeamNorm merge_more_rounds(const unsigned long long* p1, int GW, unsigned limit, TeamNorm n) {
@@ -737,7 +734,7 @@ void pair_kernel(PairParams P) {
     auto merge_team = [&](const Pend& pp, unsigned long long (&w)[2], unsigned long long (&w2)[2], float& ft, float& fd) __attribute__((always_inline)) -> bool {
         const unsigned long long* p1 = part1 + static_cast<size_t>(pp.pair) * GW * 4;
         // binary32 is enough: the normalisers enter p and q as common factors
-        TeamNorm n{neg_inf(), neg_inf(), 0.0f, 0.0f, true};
+        TeamNorm n{pp.kt, pp.kd, 0.0f, 0.0f, true};
         n.ok = await_n<2>(p1, GW, 0, P.spin_limit, w);
         merge_round(w, lane < GW, n);
         if (GW > 64) {
@@ -746,13 +743,14 @@ void pair_kernel(PairParams P) {
             merge_round(w2, 64 + lane < GW, n);
             if (GW > 128) n = merge_more_rounds(p1, GW, P.spin_limit, n);
         }
-        const float Kt = n.Kt, Kd = n.Kd, zt = n.zt, zd = n.zd;
         const bool ok = n.ok;
-        const float rzt = 1.0f / zt, rzd = 1.0f / zd;   // inf for a row without mass, NaN for a bad one
-        // ft = 2^(k_wave - K) / S: an exact power of two times one rounded reciprocal.  A wavefront
-        // without mass has only zeros in e; its factor is 0 (NaN if the row is unusable).
-        ft = pp.mass_t ? ldexpf(rzt, kdiff(pp.kt, Kt)) : rzt * 0.0f;
-        fd = pp.mass_d ? ldexpf(rzd, kdiff(pp.kd, Kd)) : rzd * 0.0f;
+        // the row's sum relative to this wavefront's own reference exponent: p = e / sum.  The
+        // hardware reciprocal (1 ulp) is as good as a division here: the factor is common to a row.
+        // inf for a row without mass, NaN for a bad one
+        const float rzt = __builtin_amdgcn_rcpf(n.zt), rzd = __builtin_amdgcn_rcpf(n.zd);
+        // A wavefront without mass has only zeros in e; its factor is 0 (NaN if the row is unusable).
+        ft = pp.mass_t ? rzt : rzt * 0.0f;
+        fd = pp.mass_d ? rzd : rzd * 0.0f;
         return ok;
     };
 
