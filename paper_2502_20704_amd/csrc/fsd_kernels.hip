@@ -796,7 +796,17 @@ void pair_kernel(PairParams P) {
                 const float p = fmaf(t4[i], ft, kTiny), q = fmaf(d4[i], fd, kTiny);
                 const float d = p - q, sum = p + q;
                 const float inv = __builtin_amdgcn_rcpf(sum);
-                const float u = fmaxf(fmaf(d, inv, 1.0f), kTiny), v = fmaxf(2.0f - u, kTiny);
+                float u = fmaxf(fmaf(d, inv, 1.0f), kTiny), v = fmaxf(2.0f - u, kTiny);
+                if constexpr (MODE == MODE_KLP) {
+                    // u = 1 + r and v = 2 - u carry an absolute error of 2^-23: harmless for JS, where a
+                    // small u or v comes with a small weight, but KL weighs ln(u/v) with the larger of the
+                    // two.  Far from p = q the smaller one is taken from its own quotient instead (a
+                    // relative error); near p = q the exact complement is what keeps the first-order
+                    // terms cancelling.
+                    const float inv2 = inv + inv;
+                    if (u < 0.5f) u = fmaxf(p * inv2, kTiny);
+                    if (v < 0.5f) v = fmaxf(q * inv2, kTiny);
+                }
                 if constexpr (MODE == MODE_JS) {
                     // p ln(2p/s) + q ln(2q/s) = ln2 (p log2 u + q log2 v); the rounding of u = 1 + r
                     // cancels between the two terms because p/u = q/v

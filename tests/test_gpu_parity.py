@@ -146,6 +146,30 @@ def test_masked_entries_and_closed_form(torch_cuda, oracle):
             pu.check_chain(g, o, 0.5, pu.rel_tol(dtype), f"masked {dtype} div={div}")
 
 
+def test_wide_dynamic_range_across_the_team(torch_cuda, oracle):
+    """slices of one row whose maxima lie hundreds of units apart: the wavefronts of a team then hold
+    reference exponents more than 127 apart, sums relative to the lower ones overflow, and their
+    entries must come out as weightless, not as NaN"""
+    rng = np.random.default_rng(33)
+    B, K, V = 3, 3, 70000
+    base = np.where(np.arange(V) < V // 2, -180.0, 150.0).astype(np.float32)      # first half far below
+    t = (base + rng.standard_normal((B, K + 1, V)).astype(np.float32) * 2).astype(np.float32)
+    d = (base + rng.standard_normal((B, K, V)).astype(np.float32) * 2).astype(np.float32)
+    d[1] = t[1, :K]                                                               # identical rows too
+    t[2, :, : V // 2] = -np.inf                                                   # and a masked half
+    cand = rng.integers(0, V, (B, K)).astype(np.int32)
+    for dtype in ("f32", "bf16"):
+        inp = dict(target=t, draft=d, cand=cand)
+        if dtype == "bf16":
+            inp = dict(target=synth.to_bf16_bits(t), draft=synth.to_bf16_bits(d), cand=cand)
+        for div in (fsd.DIV_JS, fsd.DIV_KL, fsd.DIV_TV):
+            g = run_chain(torch_cuda, inp, 0.3, div, seed=2)
+            o = oracle.verify_chain(inp["target"], inp["draft"], inp["cand"], 0.3, div, seed=2)
+            assert (g["row_status"] == 0).all() and np.isfinite(g["divergences"]).all()
+            pu.check_chain(g, o, 0.3, pu.rel_tol(dtype), f"wide range {dtype} div={div}")
+            assert (g["divergences"][1] == 0).all()
+
+
 def test_nonfinite_rows_are_flagged(torch_cuda, oracle):
     inp = synth.chain_inputs(4, 3, 3000, "f32", "gauss2", 1.0, seed=2)
     inp["target"][0, 1, 77] = np.nan
