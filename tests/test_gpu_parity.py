@@ -170,6 +170,37 @@ def test_wide_dynamic_range_across_the_team(torch_cuda, oracle):
             assert (g["divergences"][1] == 0).all()
 
 
+def test_accuracy_envelope_on_nearly_identical_rows(torch_cuda, oracle):
+    """The kernels evaluate p and q in binary32, so a divergence carries an absolute error of about 1e-7
+    times the mass involved, whatever its size: the relative bar (1e-5 binary32 logits, 2e-3 bfloat16)
+    is met above 2e-2 resp. 1e-4, and below that the absolute error stays under 2.5e-7.  Rows that
+    differ by noise of 0.001 ... 0.1 on flat and on peaked targets put divergences from 1e-9 to 1e-1."""
+    rng = np.random.default_rng(11)
+    B, K, V = 3, 3, 20000
+    seen_small = 0
+    for scale in (0.3, 3.0, 8.0):
+        for noise in (0.001, 0.01, 0.1):
+            t = (rng.standard_normal((B, K + 1, V)) * scale).astype(np.float32)
+            d = (t[:, :K] + rng.standard_normal((B, K, V)) * noise).astype(np.float32)
+            cand = rng.integers(0, V, (B, K)).astype(np.int32)
+            for dtype in ("f32", "bf16"):
+                inp = dict(target=t, draft=d, cand=cand)
+                if dtype == "bf16":
+                    inp = dict(target=synth.to_bf16_bits(t), draft=synth.to_bf16_bits(d), cand=cand)
+                floor = 2e-2 if dtype == "f32" else 1e-4
+                for div in (fsd.DIV_KL, fsd.DIV_JS, fsd.DIV_TV):
+                    g = run_chain(torch_cuda, inp, 0.3, div)["divergences"].astype(np.float64)
+                    o = oracle.verify_chain(inp["target"], inp["draft"], inp["cand"], 0.3, div)["divs"]
+                    err = np.abs(g - o)
+                    what = f"scale={scale} noise={noise} {dtype} div={div}"
+                    assert err.max() <= 2.5e-7, f"{what}: absolute error {err.max():.2e}"
+                    big = o >= floor
+                    assert (err[big] <= pu.rel_tol(dtype) * o[big]).all(), f"{what}: relative error above the floor"
+                    assert (g >= 0).all()
+                    seen_small += int((~big).sum())
+    assert seen_small > 100          # the regime below the floors was exercised
+
+
 def test_nonfinite_rows_are_flagged(torch_cuda, oracle):
     inp = synth.chain_inputs(4, 3, 3000, "f32", "gauss2", 1.0, seed=2)
     inp["target"][0, 1, 77] = np.nan
