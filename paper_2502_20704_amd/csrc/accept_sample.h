@@ -1,0 +1,393 @@
+// Acceptance (chain prefix, tree path, strict SD, reducible FSD) and the Gumbel-max draw.
+// Part of libfsd (gfx950); included by fsd_kernels.hip, which holds the host side and the C ABI.
+#ifndef FSD_CSRC_ACCEPT_SAMPLE_H_
+#define FSD_CSRC_ACCEPT_SAMPLE_H_
+
+#include "device_common.h"
+
+namespace {
+
+// ------------------------------------------------------------------------------------------
+// kernel 2: acceptance + extra token
+
+struct SampleParams {
+    const char* target;
+    const char* draft;        // strict SD only
+    const int32_t* tokens;    // cand [B,K] or node_tokens [B,N]
+    const int32_t* parent;    // tree only
+    int rows;                 // K or N
+    int max_depth;            // tree only
+    long V;
+    long nslots;
+    int sps;                  // slots per sampler workgroup
+    int GS;
+    float T;
+    int mode;
+    unsigned seed_lo, seed_hi, off_lo, off_hi;
+    int32_t* out_len;
+    int32_t* out_tokens;
+    int32_t* path_nodes;      // tree only
+    int32_t* row_status;      // optional
+    const float* thr;         // optional [B]: warpers, smallest kept scaled logit of the sampled row
+    float inv_temp;           // warpers: binary32(1 / temperature), 1 otherwise
+    Ws ws;
+};
+
+struct Best { float score; int idx; };
+
+__device__ __forceinline__ Best better(Best a, Best b) {
+    return (b.score > a.score || (b.score == a.score && b.idx < a.idx)) ? b : a;
+}
+__device__ __forceinline__ Best wave_best(Best v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        Best other{__shfl_xor(v.score, o), __shfl_xor(v.idx, o)};
+        v = better(v, other);
+    }
+    return v;
+}
+
+template <bool BF16, bool ALIGNED, int KIND>
+__global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
+    constexpr int VE = Slot<BF16>::VE;
+    constexpr int ES = BF16 ? 2 : 4;
+    extern __shared__ int s_dyn[];   // tree: par[N], anc[N], acc[N], dep[N]
+    __shared__ int s_n, s_st, s_key, s_last;
+    __shared__ Best s_best[8];
+    __shared__ int s_bad[4];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int gs = blockIdx.x, b = blockIdx.y;
+    const int rows = P.rows;
+
+    if (tid == 0) { s_n = rows; s_st = 0; s_key = 0; }
+    __syncthreads();
+
+    // ---- which positions are accepted
+    int n = 0;         // accepted prefix length / path depth
+    int sample_row = 0;
+    int winner = -1;
+    int nchain = 0;    // strict SD on a tree: rejected siblings whose draft rows shape the residual
+    if constexpr (KIND == KIND_CHAIN || KIND == KIND_SD || KIND == KIND_RFSD) {
+        for (int i = tid; i < rows; i += kWG) {
+            const int pr = b * rows + i;
+            const int st = P.ws.pst[pr];
+            bool ok = false;
+            if constexpr (KIND == KIND_CHAIN || KIND == KIND_RFSD) {
+                ok = (P.ws.div[pr] <= P.T);   // Sec. 4 eq. 4 (NaN compares false)
+            }
+            if constexpr (KIND == KIND_SD || KIND == KIND_RFSD) {   // reducible FSD (Sec. 4.2): either rule accepts
+                // Sec. 3 eq. 1-2 in the log domain: min(1, p/q) > u  <=>  min(0, ln p - ln q) - ln u > 0
+                const double ratio = P.ws.lr[pr];
+                const U4 r = philox4x32_10((static_cast<unsigned>(i) >> 2) | (1u << 30), static_cast<unsigned>(b),
+                                           P.off_lo, P.off_hi, P.seed_lo, P.seed_hi);
+                const unsigned wsel = (i & 3) == 0 ? r.x : (i & 3) == 1 ? r.y : (i & 3) == 2 ? r.z : r.w;
+                const double u = static_cast<double>(word_to_uniform(wsel));
+                const double thr = ratio < 0.0 ? ratio : 0.0;
+                ok = ok || (thr - log(u) > 0.0);
+            }
+            if (st) atomicOr(&s_st, st);
+            if (!ok) atomicMin(&s_n, i);
+        }
+        __syncthreads();
+        n = s_n;
+        sample_row = n;
+    } else if constexpr (KIND == KIND_TREESD) {
+        // the walk kernel has decided: depth, last node, and the residual chain the token comes from
+        // (if the walk gave up on a bounded wait it may have written nothing: the header is then
+        // whatever an earlier call left, so nothing in it is trusted)
+        const int* hdr = P.ws.tsd + static_cast<size_t>(b) * (4 + rows);
+        const bool gave_up = P.ws.counters[1] != 0;
+        if (tid == 0) s_st = gave_up ? FSD_ROW_INTERNAL : hdr[0];
+        n = gave_up ? 0 : hdr[1];
+        sample_row = gave_up ? 0 : hdr[2] + 1;
+        nchain = gave_up ? 0 : hdr[3];
+        if (n < 0 || n > P.max_depth || sample_row < 0 || sample_row > rows || nchain < 0 || nchain > rows) {
+            n = 0; sample_row = 0; nchain = 0;
+            if (tid == 0) s_st = FSD_ROW_INTERNAL;
+        }
+        int* ch = s_dyn;
+        float* iz = reinterpret_cast<float*>(s_dyn + rows);
+        float* ldv = reinterpret_cast<float*>(s_dyn + 2 * rows);
+        for (int m = tid; m < nchain; m += kWG) {
+            const int c = hdr[4 + m];
+            ch[m] = c;
+            iz[m] = P.ws.tsd_invz[static_cast<size_t>(b) * rows + m];
+            ldv[m] = static_cast<float>(P.ws.lse2[2 * (static_cast<size_t>(b) * rows + c) + 1]);
+        }
+        __syncthreads();
+    } else {
+        int* par = s_dyn;
+        int* anc = s_dyn + rows;
+        int* acc = s_dyn + 2 * rows;
+        int* dep = s_dyn + 3 * rows;
+        for (int j = tid; j < rows; j += kWG) {
+            const int pr = b * rows + j;
+            int p = P.parent[pr];
+            if (p < -1 || p >= j) { atomicOr(&s_st, FSD_ROW_BAD_PARENT); p = -1; }
+            const int st = P.ws.pst[pr];
+            if (st) atomicOr(&s_st, st);
+            par[j] = p; anc[j] = p; dep[j] = 1;
+            acc[j] = (P.ws.div[pr] <= P.T) ? 1 : 0;
+        }
+        __syncthreads();
+        // pointer jumping: after r rounds anc[j] is the 2^r-th ancestor, acc/dep cover that stretch
+        for (int span = 1; span < rows; span <<= 1) {
+            int na[kMaxRows / kWG], nacc[kMaxRows / kWG], nd[kMaxRows / kWG];
+#pragma unroll
+            for (int q = 0; q < kMaxRows / kWG; ++q) {
+                const int j = tid + q * kWG;
+                if (j < rows) {
+                    const int a = anc[j];
+                    na[q] = a; nacc[q] = acc[j]; nd[q] = dep[j];
+                    if (a >= 0) { na[q] = anc[a]; nacc[q] = acc[j] & acc[a]; nd[q] = dep[j] + dep[a]; }
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < kMaxRows / kWG; ++q) {
+                const int j = tid + q * kWG;
+                if (j < rows) { anc[j] = na[q]; acc[j] = nacc[q]; dep[j] = nd[q]; }
+            }
+            __syncthreads();
+        }
+        for (int j = tid; j < rows; j += kWG) {
+            if (dep[j] > P.max_depth) atomicOr(&s_st, FSD_ROW_TOO_DEEP);
+            if (acc[j]) atomicMax(&s_key, (dep[j] << 11) | (kMaxRows - 1 - j));   // deepest, then lowest index
+        }
+        __syncthreads();
+        const int key = s_key;
+        if (key) { n = key >> 11; winner = kMaxRows - 1 - (key & (kMaxRows - 1)); }
+        sample_row = winner + 1;
+    }
+    int status = s_st;
+    if (status & FSD_ROW_BAD_PARENT) status &= ~FSD_ROW_TOO_DEEP;   // depths mean nothing in a malformed tree
+    if (P.ws.counters[1]) status |= FSD_ROW_INTERNAL;   // a bounded wait of the reduction kernel expired
+
+    // ---- Gumbel-max over this workgroup's share of the sampled target row
+    const char* trow = P.target + (static_cast<size_t>(b) * (rows + 1) + sample_row) * static_cast<size_t>(P.V) * ES;
+    bool residual = false;
+    const char* drow = nullptr;
+    float lt = 0.0f, ld = 0.0f;
+    if constexpr (KIND == KIND_TREESD) {
+        if (nchain > 0 && !status) {
+            residual = true;
+            lt = static_cast<float>(P.ws.lse2[2 * (static_cast<size_t>(b) * rows + s_dyn[nchain - 1])]);
+        }
+    }
+    if constexpr (KIND == KIND_SD || KIND == KIND_RFSD) {
+        if (n < rows) {   // rejected at n: the residual of Sec. 3 eq. 3 needs the draft row as well
+            residual = true;
+            drow = P.draft + (static_cast<size_t>(b) * rows + n) * static_cast<size_t>(P.V) * ES;
+            lt = static_cast<float>(P.ws.lse2[2 * (b * rows + n)]);
+            ld = static_cast<float>(P.ws.lse2[2 * (b * rows + n) + 1]);
+        }
+    }
+    Best best{neg_inf(), 0x7FFFFFFF}, rbest{neg_inf(), 0x7FFFFFFF};
+    int bad = 0;
+    if (!status) {
+        const long s0 = static_cast<long>(gs) * P.sps;
+        const long s1 = (s0 + P.sps < P.nslots) ? s0 + P.sps : P.nslots;
+        // Scores already seen anywhere in the wavefront: an entry whose score cannot reach them cannot
+        // be the argmax, and its Gumbel variate (two logarithms) is not evaluated.  The bound:
+        // G = -ln(-ln u) <= -ln(1 - u), and 1 - u = m 2^-24 with the integer m below, so
+        // G <= ln2 (24 - floor(log2 m)) = ln2 (clz(m) - 7); 1e-3 covers the rounding of the
+        // logarithm routine by a wide margin.
+        float thr = neg_inf(), rthr = neg_inf();
+        const float thr_b = P.thr ? P.thr[b] : neg_inf();
+        // the trip count is the same for every lane: the thresholds are wavefront reductions
+        for (long sb = s0; sb < s1; sb += kWG) {
+            const long s = sb + tid;
+            const bool live = s < s1;
+            float z[VE], zd[VE];
+            const uint4 raw = load_slot<BF16, ALIGNED>(trow, live ? s : s1 - 1, P.V);
+            unpack<BF16>(raw, z);
+            if (P.thr && P.mode == FSD_SAMPLE) {
+                // temperature, then the kept set of top-k / top-p: everything else leaves the draw
+#pragma unroll
+                for (int e = 0; e < VE; ++e) {
+                    bad |= !(z[e] < __builtin_inff());
+                    const float sv = __fmul_rn(z[e], P.inv_temp);
+                    z[e] = (sv >= thr_b) ? sv : neg_inf();
+                }
+            }
+            if (P.mode == FSD_SAMPLE) {
+                // No variate is below -ln(24 ln 2) = -2.8116 (u >= 2^-24), so the largest logit seen minus
+                // 2.82 is already a score the winner must reach: most entries are ruled out before any
+                // variate has been evaluated at all.
+                float zm = neg_inf();
+#pragma unroll
+                for (int e = 0; e < VE; ++e) zm = fmaxf(zm, z[e]);
+                thr = fmaxf(thr, wave_max(live ? zm : neg_inf()) - 2.82f);
+            }
+            if (live) {
+            float rres[VE];   // strict SD on a tree: p after the chain's rejections, minus the last draft row
+            if constexpr (KIND == KIND_TREESD) {
+                if (residual) {
+                    const int* ch = s_dyn;
+                    const float* iz = reinterpret_cast<const float*>(s_dyn + rows);
+                    const float* ldv = reinterpret_cast<const float*>(s_dyn + 2 * rows);
+#pragma unroll
+                    for (int e = 0; e < VE; ++e) rres[e] = hw_exp2(fmaf(z[e], kLog2e, -lt));
+                    for (int m = 0; m < nchain; ++m) {
+                        const char* dr = P.draft + (static_cast<size_t>(b) * rows + ch[m]) * static_cast<size_t>(P.V) * ES;
+                        const uint4 rawd = load_slot<BF16, ALIGNED>(dr, s, P.V);
+                        unpack<BF16>(rawd, zd);
+                        const float ldm = ldv[m];
+                        if (m + 1 < nchain) {
+                            const float izm = iz[m];
+#pragma unroll
+                            for (int e = 0; e < VE; ++e)
+                                rres[e] = fmaxf(rres[e] - hw_exp2(fmaf(zd[e], kLog2e, -ldm)), 0.0f) * izm;
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < VE; ++e) rres[e] = rres[e] - hw_exp2(fmaf(zd[e], kLog2e, -ldm));
+                        }
+                    }
+                }
+            } else if (residual) {
+                const uint4 rawd = load_slot<BF16, ALIGNED>(drow, s, P.V);
+                unpack<BF16>(rawd, zd);
+            }
+#pragma unroll
+            for (int blk = 0; blk < VE / 4; ++blk) {
+                const long e0 = s * VE + blk * 4;
+                unsigned w4[4] = {0u, 0u, 0u, 0u};
+                if (P.mode == FSD_SAMPLE) {
+                    const U4 r = philox4x32_10(static_cast<unsigned>(e0 >> 2), static_cast<unsigned>(b), P.off_lo,
+                                               P.off_hi, P.seed_lo, P.seed_hi);
+                    w4[0] = r.x; w4[1] = r.y; w4[2] = r.z; w4[3] = r.w;
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float zz = z[blk * 4 + q];
+                    const int idx = static_cast<int>(e0 + q);
+                    bad |= !(zz < __builtin_inff());
+                    float lnr = neg_inf();
+                    if (residual) {
+                        float r;
+                        if constexpr (KIND == KIND_TREESD) {
+                            r = rres[blk * 4 + q];
+                        } else {
+                            const float p = hw_exp2(fmaf(zz, kLog2e, -lt));
+                            const float qq = hw_exp2(fmaf(zd[blk * 4 + q], kLog2e, -ld));
+                            r = p - qq;
+                        }
+                        if (r > 0.0f) lnr = hw_log2(r) * static_cast<float>(kLn2);
+                    }
+                    if (P.mode == FSD_SAMPLE) {
+                        const unsigned m = 0x00FFFFFFu ^ ((w4[q] >> 9) << 1);   // (1 - u) 2^24, odd, >= 1
+                        const float gb = fmaf(static_cast<float>(__clz(static_cast<int>(m)) - 7), 0.693148f, 1e-3f);
+                        const bool may = !(__fadd_rn(zz, gb) < thr) || (residual && !(__fadd_rn(lnr, gb) < rthr));
+                        if (may) {
+                            const float g = gumbel(w4[q]);
+                            const float score = __fadd_rn(zz, g);
+                            if (score > best.score) best = Best{score, idx};
+                            if (lnr > neg_inf()) {
+                                const float rs = __fadd_rn(lnr, g);
+                                if (rs > rbest.score) rbest = Best{rs, idx};
+                            }
+                        }
+                    } else {
+                        if (zz > best.score) best = Best{zz, idx};
+                        if (lnr > rbest.score) rbest = Best{lnr, idx};
+                    }
+                }
+            }
+            }
+            if (P.mode == FSD_SAMPLE) {
+                thr = fmaxf(thr, wave_max(best.score));
+                if (residual) rthr = wave_max(rbest.score);
+            }
+        }
+    }
+    best = wave_best(best);
+    rbest = wave_best(rbest);
+    bad = __any(bad);
+    if (lane == 0) { s_best[wave] = best; s_best[4 + wave] = rbest; s_bad[wave] = bad; }
+    __syncthreads();
+    if (tid == 0) {
+        Best m = s_best[0], r = s_best[4];
+        int bd = s_bad[0];
+        for (int k = 1; k < 4; ++k) { m = better(m, s_best[k]); r = better(r, s_best[4 + k]); bd |= s_bad[k]; }
+        unsigned long long* slot = P.ws.spart + (static_cast<size_t>(b) * P.GS + gs) * 4;
+        __hip_atomic_store(slot + 0, (static_cast<unsigned long long>(__float_as_uint(m.score)) << 32) | static_cast<unsigned>(m.idx), __ATOMIC_RELAXED, AGENT);
+        __hip_atomic_store(slot + 1, (static_cast<unsigned long long>(__float_as_uint(r.score)) << 32) | static_cast<unsigned>(r.idx), __ATOMIC_RELAXED, AGENT);
+        __hip_atomic_store(slot + 2, static_cast<unsigned long long>(bd), __ATOMIC_RELAXED, AGENT);
+        // The three words above are device-scope atomic stores, performed at the memory side; the
+        // wait for their completion orders them before the count (a device-scope release would also
+        // write the whole L2 back, which costs far more than the kernel's arithmetic).  The reader
+        // uses device-scope atomic loads, so it needs no invalidate either.
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        const unsigned prev = __hip_atomic_fetch_add(P.ws.sdone + b, 1u, __ATOMIC_RELAXED, AGENT);
+        s_last = (prev == static_cast<unsigned>(P.GS) - 1u) ? 1 : 0;
+    }
+    __syncthreads();
+    if (!s_last) return;
+
+    // ---- the last workgroup of the sequence merges the shares and writes the outputs
+    if (tid == 0) {
+        Best m{neg_inf(), 0x7FFFFFFF}, r{neg_inf(), 0x7FFFFFFF};
+        int bd = 0;
+        for (int k = 0; k < P.GS; ++k) {
+            const unsigned long long* slot = P.ws.spart + (static_cast<size_t>(b) * P.GS + k) * 4;
+            const unsigned long long w0 = __hip_atomic_load(slot + 0, __ATOMIC_RELAXED, AGENT);
+            const unsigned long long w1 = __hip_atomic_load(slot + 1, __ATOMIC_RELAXED, AGENT);
+            bd |= static_cast<int>(__hip_atomic_load(slot + 2, __ATOMIC_RELAXED, AGENT));
+            m = better(m, Best{__uint_as_float(static_cast<unsigned>(w0 >> 32)), static_cast<int>(static_cast<unsigned>(w0))});
+            r = better(r, Best{__uint_as_float(static_cast<unsigned>(w1 >> 32)), static_cast<int>(static_cast<unsigned>(w1))});
+        }
+        int st = status;
+        if (!st && (bd || m.idx == 0x7FFFFFFF)) st |= FSD_ROW_NONFINITE;
+        const int tok = (residual && r.idx != 0x7FFFFFFF) ? r.idx : m.idx;
+        s_st = st;
+        s_key = tok;
+    }
+    __syncthreads();
+    status = s_st;
+    const int token = s_key;
+    if (status) n = 0;
+    const int width = (KIND == KIND_TREE || KIND == KIND_TREESD) ? P.max_depth + 1 : rows + 1;
+    int32_t* out = P.out_tokens + static_cast<size_t>(b) * width;
+    if constexpr (KIND == KIND_TREESD) {
+        // the walk has written the path and its tokens; add the drawn token, or take it all back
+        if (status) {
+            int32_t* pn = P.path_nodes + static_cast<size_t>(b) * P.max_depth;
+            for (int i = tid; i < P.max_depth; i += kWG) pn[i] = -1;
+            for (int i = tid; i < width; i += kWG) out[i] = -1;
+        } else if (tid == 0) {
+            out[n] = token;
+        }
+    } else if constexpr (KIND == KIND_TREE) {
+        int32_t* pn = P.path_nodes + static_cast<size_t>(b) * P.max_depth;
+        for (int i = tid; i < P.max_depth; i += kWG) pn[i] = -1;
+        for (int i = tid; i < width; i += kWG) out[i] = (i == n && !status) ? token : -1;
+        __syncthreads();
+        if (tid == 0 && !status) {
+            const int* par = s_dyn;
+            int jn = winner;
+            for (int i = n - 1; i >= 0 && jn >= 0; --i) {
+                pn[i] = jn;
+                out[i] = P.tokens[static_cast<size_t>(b) * rows + jn];
+                jn = par[jn];
+            }
+        }
+    } else {
+        for (int i = tid; i < width; i += kWG) {
+            int v = -1;
+            if (!status) {
+                if (i < n) v = P.tokens[static_cast<size_t>(b) * rows + i];
+                else if (i == n) v = token;
+            }
+            out[i] = v;
+        }
+    }
+    if (tid == 0) {
+        P.out_len[b] = n;
+        if (P.row_status) P.row_status[b] = status;
+    }
+}
+
+}  // namespace
+
+#endif  // FSD_CSRC_ACCEPT_SAMPLE_H_

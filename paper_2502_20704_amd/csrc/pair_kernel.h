@@ -1,0 +1,778 @@
+// The vocabulary-reduction kernel (softmax normalisers and divergence of every row pair).
+// Part of libfsd (gfx950); included by fsd_kernels.hip, which holds the host side and the C ABI.
+#ifndef FSD_CSRC_PAIR_KERNEL_H_
+#define FSD_CSRC_PAIR_KERNEL_H_
+
+#include "device_common.h"
+
+namespace {
+
+// ------------------------------------------------------------------------------------------
+// kernel 1: vocabulary reduction over row pairs
+//
+// One (target row, draft row) pair is split over a team of GW wavefronts.  Every wavefront loads
+// its slice of both rows ONCE into registers (NV 16-byte slots of each row per lane) and works on
+// its own: there is no barrier and no shared memory, the wavefronts of a team only meet through
+// 64-bit words in the workspace.
+//
+//   phase 1   maximum of the slice (DPP reduction), integer reference exponent k = ceil(max log2e),
+//             e = 2^(z log2e - k) for every entry, their sums; posted as exchange words (two-phase
+//             modes: the two exponents in one word, the two sums as binary32 in another).
+//   exchange  (two-phase divergences) every wavefront reads the whole team's words and merges them
+//             into row-wide normalisers.
+//   phase 2   from the kept exponentials: p = e_t f_t, q = e_d f_d, the divergence's terms, one
+//             (TV: two) word(s) of partial sums posted.
+//   finish    the team's wavefronts take turns as finisher of a pair: it adds the posted partial
+//             sums in member order (fixed order: results are bit-identical run to run) and writes
+//             divergence and status.
+//
+// The kernel is persistent and software-pipelined: in a step a wavefront runs phase 1 of pair j
+// and then phase 2 of pair j - LAG from an older set of kept exponentials (LAG = 1, or 2 where
+// the registers allow a third set).  Memory operations return in the order they were issued,
+// which fixes the order of the requests in a step (see `step`): small exchange words first, the
+// next pair's logits as soon as phase 1 has consumed the registers (a whole step ahead where a
+// second set of logit registers fits), and nothing after that waits on memory unless a team
+// member is late.  The bfloat16 two-phase kernels (two wavefronts per SIMD) are bound by
+// vector-ALU issue; the binary32 ones (one wavefront per SIMD) by the exposed latencies, which the
+// longer lag and the earlier prefetch hide.  The single-pass modes (bfloat16 KL, the normalisers
+// of strict SD) have no phase 2.  Waiting is bounded (spin_limit polls, then FSD_ROW_INTERNAL),
+// so every wavefront reaches the end of the kernel whatever happens; all team members are
+// resident by construction (the grid never exceeds what fits on the device at once).
+
+// The exchange words are only ever touched with device-scope atomic loads and stores, which are
+// performed at the memory side: no cache write-back or invalidate is needed to see them.  They are
+// cleared before the kernel starts and a posted word is never zero (+0.0 is posted as -0.0), so
+// each word says by itself whether it has arrived: no counter or fence sits between a post and
+// its use.
+__device__ __forceinline__ void post64(unsigned long long* p, unsigned long long v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, AGENT);
+}
+__device__ __forceinline__ unsigned long long read64(const unsigned long long* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, AGENT);
+}
+__device__ __forceinline__ unsigned long long dbits(double x) {   // never 0
+    const unsigned long long u = static_cast<unsigned long long>(__double_as_longlong(x));
+    return u ? u : 0x8000000000000000ull;
+}
+__device__ __forceinline__ double bitsd(unsigned long long x) {
+    return __longlong_as_double(static_cast<long long>(x));
+}
+__device__ __forceinline__ unsigned fbits(float x) {              // never 0
+    const unsigned u = __float_as_uint(x);
+    return u ? u : 0x80000000u;
+}
+
+// Reference exponents are integers (k = ceil(max * log2e)), so moving a sum from one reference
+// to another is an exact scaling by a power of two.
+__device__ __forceinline__ int kdiff(float k, float M) { return static_cast<int>(k - M); }
+
+// two binary32 values in one exchange word (never 0: +0.0 in the low half is posted as -0.0)
+__device__ __forceinline__ unsigned long long pack2(float lo, float hi) {
+    return static_cast<unsigned long long>(fbits(lo)) | (static_cast<unsigned long long>(__float_as_uint(hi)) << 32);
+}
+__device__ __forceinline__ float lo_f(unsigned long long w) { return __uint_as_float(static_cast<unsigned>(w)); }
+__device__ __forceinline__ float hi_f(unsigned long long w) { return __uint_as_float(static_cast<unsigned>(w >> 32)); }
+
+// A pair owns 4 GW words of an exchange array, of which a mode uses N per member: word k of member
+// m sits at [m N + k], so that a member's post is one contiguous store and the 64 lanes of a
+// request touch consecutive words.  Lane l reads the N words of member (base + l); lanes beyond
+// the team re-read the last member's (no branch around the loads, see load_item).  Nothing looks at the values here, so the loads stay in flight until they are
+// awaited.  With spread == false every lane reads member 0 (a request whose result is not needed
+// costs one cache line).
+template <int N>
+__device__ __forceinline__ void request_n(const unsigned long long* p, int GW, int base, unsigned long long (&w)[N],
+                                          bool spread = true) {
+    const int m = base + static_cast<int>(threadIdx.x & 63);
+    const int mm = spread ? ((m < GW) ? m : GW - 1) : 0;
+#pragma unroll
+    for (int k = 0; k < N; ++k) w[k] = read64(p + mm * N + k);
+}
+// The words are normally there when they are looked at.  Everything that loops over memory (asking
+// again, further rounds of 64 members) lives in functions that are NOT inlined: the compiler's
+// bookkeeping of outstanding memory operations stays exact in the caller, which then never waits
+// for the logits it has just requested for the next pair.
+template <int N> struct WordsN { unsigned long long w[N]; bool ok; };
+
+template <int N>
+__device__ __noinline__ WordsN<N> repoll_n(const unsigned long long* p, int GW, int base, unsigned limit) {
+    WordsN<N> r;
+    r.ok = true;
+    unsigned polls = 0;
+    for (;;) {
+        request_n<N>(p, GW, base, r.w);
+        bool missing = false;   // duplicates included: harmless
+#pragma unroll
+        for (int k = 0; k < N; ++k) missing |= (r.w[k] == 0);
+        if (!__any(missing)) break;
+        if (polls++ >= limit) { r.ok = false; break; }
+        __builtin_amdgcn_s_sleep(1);
+    }
+    return r;
+}
+template <int N>
+__device__ __forceinline__ bool await_n(const unsigned long long* p, int GW, int base, unsigned limit,
+                                        unsigned long long (&w)[N]) {
+    bool missing = false;
+#pragma unroll
+    for (int k = 0; k < N; ++k) missing |= (w[k] == 0);
+    if (!__any(missing)) return true;
+    const WordsN<N> r = repoll_n<N>(p, GW, base, limit);
+#pragma unroll
+    for (int k = 0; k < N; ++k) w[k] = r.w[k];
+    return r.ok;
+}
+
+// binary32 merge of one round of team words (two-phase format: word 0 = the two reference
+// exponents, word 1 = the two sums) into sums relative to the fixed references (n.Kt, n.Kd): the
+// reading wavefront's own exponents.  Exact power-of-two rescaling; a member far above the reader
+// makes the sum overflow to +inf, the reader's factor 1/sum is then 0, and so are its p and q:
+// they are below 2^-127 of the row's mass.
+struct TeamNorm { float Kt, Kd, zt, zd; bool ok; };
+
+__device__ __forceinline__ void merge_round(const unsigned long long (&w)[2], bool in, TeamNorm& n) {
+    const float tk_t = lo_f(w[0]), tk_d = hi_f(w[0]);
+    const float tSt = in ? lo_f(w[1]) : 0.0f, tSd = in ? hi_f(w[1]) : 0.0f;
+    n.zt += wave_sumf((tSt > 0.0f) ? ldexpf(tSt, kdiff(tk_t, n.Kt)) : (tSt != tSt ? tSt : 0.0f));
+    n.zd += wave_sumf((tSd > 0.0f) ? ldexpf(tSd, kdiff(tk_d, n.Kd)) : (tSd != tSd ? tSd : 0.0f));
+}
+// teams of more than 64 wavefronts: the members beyond the first round
+__device__ __noinline__ TeamNorm merge_more_rounds(const unsigned long long* p1, int GW, unsigned limit, TeamNorm n) {
+    for (int base = 128; base < GW; base += 64) {
+        const WordsN<2> r = repoll_n<2>(p1, GW, base, limit);
+        if (!r.ok) n.ok = false;
+        merge_round(r.w, base + static_cast<int>(threadIdx.x & 63) < GW, n);
+    }
+    return n;
+}
+// the divergence words of the members beyond the first round, added in member order (each word
+// holds two binary32 partial sums)
+template <int N> struct Sums { double lo[N], hi[N]; bool ok; };
+
+template <int N>
+__device__ __noinline__ Sums<N> sum_more_rounds(const unsigned long long* p2, int GW, unsigned limit, Sums<N> s) {
+    for (int base = 64; base < GW; base += 64) {
+        const WordsN<N> r = repoll_n<N>(p2, GW, base, limit);
+        if (!r.ok) s.ok = false;
+        const bool in = base + static_cast<int>(threadIdx.x & 63) < GW;
+#pragma unroll
+        for (int k = 0; k < N; ++k) {
+            s.lo[k] += wave_sum(in ? static_cast<double>(lo_f(r.w[k])) : 0.0);
+            s.hi[k] += wave_sum(in ? static_cast<double>(hi_f(r.w[k])) : 0.0);
+        }
+    }
+    return s;
+}
+
+template <int I> struct SetId { static constexpr int value = I; };
+
+// wavefronts per SIMD the register allocation has to leave room for
+constexpr int pair_kernel_waves(bool bf16, int nv, int mode) {
+    return (bf16 && nv == 5 && (mode == MODE_JS || mode == MODE_TV)) ? 2 : 1;
+}
+
+template <bool BF16, int NV, int MODE, bool ALIGNED>
+__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(pair_kernel_waves(BF16, NV, MODE))))
+void pair_kernel(PairParams P) {
+    constexpr int VE = Slot<BF16>::VE;
+    constexpr int ES = BF16 ? 2 : 4;
+    constexpr bool TWO_PHASE = (MODE == MODE_JS || MODE == MODE_TV || MODE == MODE_KLP);
+    constexpr int NE = TWO_PHASE ? NV * VE : 1;   // exponentials kept per row and lane
+    constexpr int PW = (MODE == MODE_TV) ? 2 : 1;   // divergence words a member posts (two sums each)
+    constexpr int FW = TWO_PHASE ? PW : 4;          // words per member the finisher reads
+    // binary32 logits: the two-phase kernels hold 8 slots of each row per lane and one wavefront per
+    // SIMD anyway, which leaves registers for a second set of logits
+    constexpr bool DEEP = !BF16 && TWO_PHASE && NV == 8;
+    // Phase 2 of a pair runs LAG steps after its phase 1.  With one step, a wavefront's own chain
+    // from one phase 1 to the next still holds the whole latency of the exchange (post, then the
+    // slowest member's words), which only another wavefront on the same SIMD can fill; with two,
+    // every member's words have long been posted when they are looked at.  That takes a third set
+    // of kept exponentials: the binary32 kernels with 8 slots per lane run one wavefront per SIMD
+    // and have the registers.  (The bfloat16 kernels run two per SIMD and are bound by vector-ALU
+    // issue: a third set kept in LDS removed their waits and left their time unchanged.)
+    constexpr int LAG = (TWO_PHASE && !BF16 && NV == 8) ? 2 : 1;
+    constexpr int NB = LAG + 1;                      // sets of kept exponentials
+    constexpr int NC = (NE + 3) / 4;                 // chunks of four per row
+    constexpr float kTiny = 2e-38f;   // keeps p + q > 0 without changing any result
+    constexpr int kWavesPerWG = kWG / 64;
+
+    // the wavefront's number as a scalar: everything derived from it (member, slot range, exchange
+    // addresses) then lives in scalar registers
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
+    // NB sets of kept exponentials, named by SetId<> so that every index is a constant and the
+    // arrays stay in registers; accessed four at a time
+    float et[NB][NE], ed[NB][NE];
+    auto put4 = [&](auto S, int c, const float (&t4)[4], const float (&d4)[4]) __attribute__((always_inline)) {
+        constexpr int s_ = decltype(S)::value;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { et[s_][4 * c + i] = t4[i]; ed[s_][4 * c + i] = d4[i]; }
+    };
+    auto get4 = [&](auto S, int c, float (&t4)[4], float (&d4)[4]) __attribute__((always_inline)) {
+        constexpr int s_ = decltype(S)::value;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { t4[i] = et[s_][4 * c + i]; d4[i] = ed[s_][4 * c + i]; }
+    };
+    const int GW = P.G;                                   // wavefronts per pair
+    const int wgs_per_team = GW / kWavesPerWG;
+    // A team is a run of consecutive workgroups, which the dispatcher spreads over the XCDs.  (Two
+    // other deals were measured at C2 and dropped: teams whose workgroups all sit on one XCD ran a
+    // third slower, and teams made half of early and half of late arrivals on the compute units
+    // ended together but no sooner: the kernel is bound by vector-ALU issue either way.)
+    const int nteams = static_cast<int>(gridDim.x) / wgs_per_team;
+    const int team = static_cast<int>(blockIdx.x) / wgs_per_team;
+    const int wg_in_team = static_cast<int>(blockIdx.x) % wgs_per_team;
+    const int member = wg_in_team * kWavesPerWG + wave;
+    const long s0 = static_cast<long>(member) * P.spm;
+    const long s1 = (s0 + P.spm < P.nslots) ? s0 + P.spm : P.nslots;
+    unsigned long long* const part1 = P.ws.part1;
+    unsigned long long* const part2 = reinterpret_cast<unsigned long long*>(P.ws.part2);
+    // the words the finisher of a pair reads: divergence sums (two-phase) or phase-1 words
+    unsigned long long* const finw = TWO_PHASE ? part2 : part1;
+#ifdef FSD_PHASE_TIMING
+    unsigned long long pt_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const unsigned long long pt_wall = wall_clock64();
+    const unsigned long long pt_first = __builtin_readcyclecounter();
+    unsigned long long pt_last = pt_first;
+#endif
+
+    auto row_ptrs = [&](int pair, const char*& tptr, const char*& dptr) __attribute__((always_inline)) {
+        const int b = pair / P.rows;
+        const int j = pair - b * P.rows;
+        int trow = j;
+        if (P.parent) {
+            const int par = P.parent[pair];
+            trow = (par >= -1 && par < j) ? par + 1 : 0;   // invalid parents are reported by the next kernel
+        }
+        tptr = P.target + (static_cast<size_t>(b) * (P.rows + 1) + trow) * static_cast<size_t>(P.V) * ES;
+        dptr = P.draft + static_cast<size_t>(pair) * static_cast<size_t>(P.V) * ES;
+    };
+    // ---- the only HBM reads of the reduction: NV slots of each row per lane
+    // Every lane always loads (a lane without a slot of its own re-reads a valid one and the value is
+    // replaced by -inf afterwards): loads that sit inside branches would make the compiler wait for
+    // all outstanding memory operations at every later use, and the prefetch would no longer overlap.
+    // Slot k of this lane is sl0 + 64 k; it is the lane's own while below s1 (computed where needed:
+    // kept per slot, these would cost registers the two-phase kernels do not have).
+    const int sl0 = static_cast<int>(s0) + lane;
+    const int sl_last = (s1 > s0) ? static_cast<int>(s1) - 1 : 0;
+    const int sl_end = static_cast<int>(s1);
+    const bool fill_needed = s0 + NV * 64 > s1;   // wavefront-uniform: some lane lacks a slot
+    auto load_item = [&](uint4 (&ra)[NV], uint4 (&rb)[NV], int pair, bool wanted = true) __attribute__((always_inline)) {
+        const char *tptr, *dptr;
+        row_ptrs(pair, tptr, dptr);
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            const int sk = sl0 + 64 * k;
+            const long sl = wanted ? (sk < sl_end ? sk : sl_last) : 0;   // not wanted: one cached slot for all lanes
+            ra[k] = load_slot<BF16, ALIGNED>(tptr, sl, P.V);
+            rb[k] = load_slot<BF16, ALIGNED>(dptr, sl, P.V);
+        }
+    };
+    auto fill_unowned = [&](uint4 (&ra)[NV], uint4 (&rb)[NV]) __attribute__((always_inline)) {
+        if (fill_needed) {
+#pragma unroll
+            for (int k = 0; k < NV; ++k) {
+                if (sl0 + 64 * k >= sl_end) { ra[k] = slot_neg_inf<BF16>(); rb[k] = slot_neg_inf<BF16>(); }
+            }
+        }
+    };
+
+    // strict SD's ln p(x) - ln q(x) at the candidate token (Sec. 3, eq. 1) from the rows' log2-sum-exp2;
+    // lane 0 only.  Returns the status bits it adds.
+    auto write_ratio = [&](int pair, double lse2_t, double lse2_d, int status, float* user) __attribute__((always_inline)) -> int {
+        const int x = P.cand[pair];
+        double ratio = __builtin_nan("");
+        int add = 0;
+        if (x < 0 || x >= P.V) {
+            add = FSD_ROW_BAD_TOKEN;
+        } else if (!(status & FSD_ROW_NONFINITE)) {
+            const char *tptr, *dptr;
+            row_ptrs(pair, tptr, dptr);
+            const double lp = static_cast<double>(load_elem<BF16>(tptr, x)) - lse2_t * kLn2;
+            const double lq = static_cast<double>(load_elem<BF16>(dptr, x)) - lse2_d * kLn2;
+            ratio = (lp == -__builtin_inf()) ? -__builtin_inf() : lp - lq;
+        }
+        P.ws.lr[pair] = ratio;
+        if (user) user[pair] = static_cast<float>(ratio);
+        return add;
+    };
+
+    // ---- finishing a pair: add what the team posted for it, in member order.  fw holds the words of
+    // the first 64 members, requested earlier.
+    auto finish_two_phase = [&](int pair, unsigned long long (&fw)[FW]) __attribute__((always_inline)) {
+        const unsigned long long* p2 = part2 + static_cast<size_t>(pair) * GW * 4;
+        unsigned long long f[PW];
+#pragma unroll
+        for (int k = 0; k < PW; ++k) f[k] = fw[k % FW];
+        Sums<PW> s;
+        s.ok = await_n<PW>(p2, GW, 0, P.spin_limit, f);
+#pragma unroll
+        for (int k = 0; k < PW; ++k) {
+            s.lo[k] = wave_sum((lane < GW) ? static_cast<double>(lo_f(f[k])) : 0.0);
+            s.hi[k] = wave_sum((lane < GW) ? static_cast<double>(hi_f(f[k])) : 0.0);
+        }
+        if (GW > 64) s = sum_more_rounds<PW>(p2, GW, P.spin_limit, s);
+        double value;
+        if constexpr (MODE == MODE_TV) {
+            // the sums of (p - q)+ and of (q - p)+ are the same number; the side that avoids the
+            // heavy entries (smaller sum of p + q over its entries) carries the smaller rounding
+            // error, which matters for nearly one-hot rows
+            const double A = s.lo[0], Bn = s.hi[0], MA = s.lo[1], MB = s.hi[1];
+            value = (MA != MA || MB != MB) ? __builtin_nan("") : (MA <= MB ? A : Bn);
+        } else {
+            value = 0.5 * kLn2 * s.lo[0];
+        }
+        int status = 0;
+        if (value != value) status |= FSD_ROW_NONFINITE;   // NaN / +inf logits, or a row without mass
+        if (!s.ok) status |= FSD_ROW_INTERNAL;
+        if (value < 0.0) value = 0.0;
+        if (status) value = __builtin_nan("");
+        double lse2_t = 0.0, lse2_d = 0.0;
+        if (P.want_ratio) {
+            // reducible FSD also needs the rows' normalisers: the team's phase-1 words once more, this
+            // time merged in float64 (they were all posted before the divergence words read above)
+            const unsigned long long* p1 = part1 + static_cast<size_t>(pair) * GW * 4;
+            float Kt = neg_inf(), Kd = neg_inf();
+            double Zt = 0.0, Zd = 0.0;
+            bool ok = true;
+            for (int base = 0; base < GW; base += 64) {
+                const WordsN<2> r = repoll_n<2>(p1, GW, base, P.spin_limit);
+                ok &= r.ok;
+                const bool in = base + lane < GW;
+                const float kt = lo_f(r.w[0]), kd = hi_f(r.w[0]);
+                const double St = in ? static_cast<double>(lo_f(r.w[1])) : 0.0, Sd = in ? static_cast<double>(hi_f(r.w[1])) : 0.0;
+                const float nKt = fmaxf(Kt, wave_max((St > 0.0) ? kt : neg_inf()));
+                const float nKd = fmaxf(Kd, wave_max((Sd > 0.0) ? kd : neg_inf()));
+                Zt = ((Zt > 0.0) ? ldexp(Zt, kdiff(Kt, nKt)) : Zt) + wave_sum((St > 0.0) ? ldexp(St, kdiff(kt, nKt)) : 0.0);
+                Zd = ((Zd > 0.0) ? ldexp(Zd, kdiff(Kd, nKd)) : Zd) + wave_sum((Sd > 0.0) ? ldexp(Sd, kdiff(kd, nKd)) : 0.0);
+                Kt = nKt;
+                Kd = nKd;
+            }
+            if (!ok) status |= FSD_ROW_INTERNAL;
+            lse2_t = static_cast<double>(Kt) + log2(Zt);
+            lse2_d = static_cast<double>(Kd) + log2(Zd);
+        }
+        if (lane == 0) {
+            if (P.want_ratio) status |= write_ratio(pair, lse2_t, lse2_d, status, P.user_ratio);
+            P.ws.div[pair] = static_cast<float>(value);
+            P.ws.lse2[2 * pair] = lse2_t;
+            P.ws.lse2[2 * pair + 1] = lse2_d;
+            if (P.user_div) P.user_div[pair] = static_cast<float>(value);
+            P.ws.pst[pair] = status;
+        }
+    };
+    auto finish_single_pass = [&](int pair, unsigned long long (&fw)[FW]) __attribute__((always_inline)) {
+        const unsigned long long* p1 = part1 + static_cast<size_t>(pair) * GW * 4;
+        // online merge over rounds of 64 members, float64, exact rescaling between references
+        float Kt = neg_inf(), Kd = neg_inf();
+        double Zt = 0.0, Zd = 0.0, Wt = 0.0;
+        bool ok = true, winf = false;
+        for (int base = 0; base < GW; base += 64) {
+            unsigned long long w[4];
+            if (base == 0) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) w[k] = fw[k % FW];
+                ok &= await_n<4>(p1, GW, 0, P.spin_limit, w);
+            } else {
+                const WordsN<4> r = repoll_n<4>(p1, GW, base, P.spin_limit);
+                ok &= r.ok;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) w[k] = r.w[k];
+            }
+            const bool in = base + lane < GW;
+            const float kt = lo_f(w[0]), kd = hi_f(w[0]);
+            const double St = in ? bitsd(w[1]) : 0.0, Sd = in ? bitsd(w[2]) : 0.0, W = in ? bitsd(w[3]) : 0.0;
+            const float nKt = fmaxf(Kt, wave_max((St > 0.0) ? kt : neg_inf()));
+            const float nKd = fmaxf(Kd, wave_max((Sd > 0.0) ? kd : neg_inf()));
+            Zt = ((Zt > 0.0) ? ldexp(Zt, kdiff(Kt, nKt)) : Zt) +
+                 wave_sum((St > 0.0) ? ldexp(St, kdiff(kt, nKt)) : (St != St ? St : 0.0));
+            Zd = ((Zd > 0.0) ? ldexp(Zd, kdiff(Kd, nKd)) : Zd) +
+                 wave_sum((Sd > 0.0) ? ldexp(Sd, kdiff(kd, nKd)) : (Sd != Sd ? Sd : 0.0));
+            if constexpr (MODE == MODE_KL) {
+                winf |= __any(in && W == __builtin_inf()) != 0;
+                Wt = ((Kt > neg_inf()) ? ldexp(Wt, kdiff(Kt, nKt)) : Wt) +
+                     wave_sum((St > 0.0 && W == W && W != __builtin_inf()) ? ldexp(W, kdiff(kt, nKt)) : 0.0);
+            }
+            Kt = nKt;
+            Kd = nKd;
+        }
+        int status = 0;
+        const bool bad = !(Zt > 0.0) || !(Zd > 0.0) || !(Zt < __builtin_inf()) || !(Zd < __builtin_inf()) ||
+                         !(Kt < __builtin_inff()) || !(Kd < __builtin_inff());
+        if (bad) status |= FSD_ROW_NONFINITE;
+        if (!ok) status |= FSD_ROW_INTERNAL;
+        const double lse2_t = static_cast<double>(Kt) + log2(Zt), lse2_d = static_cast<double>(Kd) + log2(Zd);
+        double value = 0.0;
+        if constexpr (MODE == MODE_KL) {
+            // KL = sum_v p_v (a_v - b_v) - (lse_t - lse_d), p_v = 2^(a log2e - Kt) / Zt
+            value = winf ? __builtin_inf() : Wt / Zt - (lse2_t - lse2_d) * kLn2;
+        }
+        if (value < 0.0) value = 0.0;
+        if (status) value = __builtin_nan("");
+        if (lane == 0) {
+            P.ws.div[pair] = static_cast<float>(value);
+            P.ws.lse2[2 * pair] = lse2_t;
+            P.ws.lse2[2 * pair + 1] = lse2_d;
+            if (P.user_div) P.user_div[pair] = static_cast<float>(value);
+            if constexpr (MODE == MODE_LSE) {
+                status |= write_ratio(pair, lse2_t, lse2_d, status, P.user_div);
+            } else {
+                if (P.want_ratio) status |= write_ratio(pair, lse2_t, lse2_d, status, P.user_ratio);
+            }
+            P.ws.pst[pair] = status;
+        }
+    };
+    auto finish = [&](int pair, unsigned long long (&fw)[FW]) __attribute__((always_inline)) {
+        if constexpr (TWO_PHASE) finish_two_phase(pair, fw); else finish_single_pass(pair, fw);
+    };
+
+    // ---- state of the previous pair, whose phase 2 is still to come (two-phase modes)
+    struct Pend { int pair; float kt, kd; bool mass_t, mass_d, mask; };
+    Pend pend[LAG];   // [0] the last step's pair ... [LAG-1] the one whose phase 2 is due
+#pragma unroll
+    for (int i = 0; i < LAG; ++i) pend[i] = Pend{-1, 0.0f, 0.0f, false, false, false};
+    // pairs this wavefront has to finish: fin[0] now, fin[i] i steps from now.  A two-phase pair
+    // is finished NF steps after its phase 1.  Whoever starts step n has merged the team words of
+    // step n - 1, so every member has ended step n - 2 - LAG and with it phase 2 of the pair of step
+    // n - 2 - 2 LAG: the finisher's words are there when it asks, however far the team has spread.
+    constexpr int NF = TWO_PHASE ? 2 * LAG + 2 : 1;
+    int fin[NF];
+#pragma unroll
+    for (int i = 0; i < NF; ++i) fin[i] = -1;
+    int iter = 0;
+
+    // the previous pair's row-wide normalisers from the team's words (w holds the first 64 members'):
+    // factors ft, fd with p = e_t ft, q = e_d fd
+    auto merge_team = [&](const Pend& pp, unsigned long long (&w)[2], unsigned long long (&w2)[2], float& ft, float& fd) __attribute__((always_inline)) -> bool {
+        const unsigned long long* p1 = part1 + static_cast<size_t>(pp.pair) * GW * 4;
+        // binary32 is enough: the normalisers enter p and q as common factors
+        TeamNorm n{pp.kt, pp.kd, 0.0f, 0.0f, true};
+        n.ok = await_n<2>(p1, GW, 0, P.spin_limit, w);
+        merge_round(w, lane < GW, n);
+        if (GW > 64) {
+            // members 64..127 were requested with the first 64; larger teams ask for the rest here
+            if (!await_n<2>(p1, GW, 64, P.spin_limit, w2)) n.ok = false;
+            merge_round(w2, 64 + lane < GW, n);
+            if (GW > 128) n = merge_more_rounds(p1, GW, P.spin_limit, n);
+        }
+        const bool ok = n.ok;
+        // the row's sum relative to this wavefront's own reference exponent: p = e / sum.  The
+        // hardware reciprocal (1 ulp) is as good as a division here: the factor is common to a row.
+        // inf for a row without mass, NaN for a bad one
+        const float rzt = __builtin_amdgcn_rcpf(n.zt), rzd = __builtin_amdgcn_rcpf(n.zd);
+        // A wavefront without mass has only zeros in e; its factor is 0 (NaN if the row is unusable).
+        ft = pp.mass_t ? rzt : rzt * 0.0f;
+        fd = pp.mass_d ? rzd : rzd * 0.0f;
+        return ok;
+    };
+
+    // phase 2 of the previous pair from its kept exponentials
+    auto phase2 = [&](const Pend& pp, auto S, float ft, float fd, bool ok) __attribute__((always_inline)) {
+        // Only relative errors enter p and q, and the divergences below are functions of (p, q)
+        // alone, second order in r = (p - q)/(p + q): the result is the divergence of a slightly
+        // perturbed input.  u = 1 + r = 2p/s and v = 2 - u = 2q/s (exact subtraction).
+        unsigned long long word[PW];
+        if constexpr (MODE == MODE_TV) {
+            float A = 0.0f, Bn = 0.0f, MA = 0.0f, MB = 0.0f;
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                float t4[4], d4[4];
+                get4(S, c, t4, d4);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float p = t4[i] * ft, q = d4[i] * fd;   // separately rounded: p == q for equal rows
+                    const float d = p - q, sum = p + q;
+                    A += fmaxf(d, 0.0f);
+                    Bn += fmaxf(-d, 0.0f);
+                    MA += (d > 0.0f) ? sum : 0.0f;
+                    MB += (d < 0.0f) ? sum : 0.0f;
+                }
+            }
+            // max() drops NaN: an unusable row (NaN factor) is made to reach the side selection
+            if (ft != ft || fd != fd) { A = ft + fd; Bn = A; MA = A; MB = A; }
+            A = wave_sumf(A);
+            Bn = wave_sumf(Bn);
+            MA = wave_sumf(MA);
+            MB = wave_sumf(MB);
+            if (!ok) { A = __builtin_nanf(""); MA = A; }
+            word[0] = pack2(A, Bn);
+            word[1] = pack2(MA, MB);
+        } else {
+            float acc = 0.0f;
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+              float t4[4], d4[4];
+              get4(S, c, t4, d4);
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                const float p = fmaf(t4[i], ft, kTiny), q = fmaf(d4[i], fd, kTiny);
+                const float d = p - q, sum = p + q;
+                const float inv = __builtin_amdgcn_rcpf(sum);
+                float u = fmaxf(fmaf(d, inv, 1.0f), kTiny), v = fmaxf(2.0f - u, kTiny);
+                if constexpr (MODE == MODE_KLP) {
+                    // u = 1 + r and v = 2 - u carry an absolute error of 2^-23: harmless for JS, where a
+                    // small u or v comes with a small weight, but KL weighs ln(u/v) with the larger of the
+                    // two.  Far from p = q the smaller one is taken from its own quotient instead (a
+                    // relative error); near p = q the exact complement is what keeps the first-order
+                    // terms cancelling.
+                    const float inv2 = inv + inv;
+                    if (u < 0.5f) u = fmaxf(p * inv2, kTiny);
+                    if (v < 0.5f) v = fmaxf(q * inv2, kTiny);
+                }
+                if constexpr (MODE == MODE_JS) {
+                    // p ln(2p/s) + q ln(2q/s) = ln2 (p log2 u + q log2 v); the rounding of u = 1 + r
+                    // cancels between the two terms because p/u = q/v
+                    acc = fmaf(p, hw_log2(u), acc);
+                    acc = fmaf(q, hw_log2(v), acc);
+                } else {
+                    // p ln(p/q) + q - p = (s/2) [u ln(u/v) + v - u] >= 0 entry by entry (the added q - p
+                    // sums to zero).  Written in (u, v) only, the rounding of u cancels between the
+                    // two parts; p ln(u/v) - (p - q) would keep it to first order.
+                    acc = fmaf(sum, fmaf(u, hw_log2(u) - hw_log2(v), (v - u) * kLog2e), acc);
+                }
+              }
+            }
+            acc = wave_sumf(acc);
+            if constexpr (MODE == MODE_KLP) {
+                if (__any(pp.mask)) acc += __builtin_inff();   // draft masks an entry the target keeps; NaN stays NaN
+            }
+            if (!ok) acc = __builtin_nanf("");
+            word[0] = pack2(acc, 0.0f);
+        }
+        if (!ok && lane == 0) atomicOr(P.ws.counters + 1, 1u);
+        if (lane < PW) {
+            unsigned long long mine = word[0];
+#pragma unroll
+            for (int k = 1; k < PW; ++k) mine = (lane == k) ? word[k] : mine;
+            // the lane's offset is recomputed here (hidden from loop-invariant hoisting): kept across
+            // the loop it would be spilled, and the reload would wait for every load in flight
+            int l = lane;
+            asm volatile("" : "+v"(l));
+            post64(part2 + static_cast<size_t>(pp.pair) * GW * 4 + member * PW + l, mine);
+        }
+    };
+
+    auto finish_now = [&](int pair) __attribute__((always_inline)) {
+        unsigned long long fw[FW];
+        request_n<FW>(finw + static_cast<size_t>(pair) * GW * 4, GW, 0, fw);
+        finish(pair, fw);
+    };
+    // Single-pass modes: nothing makes the members of a team wait for each other, so they drift
+    // apart, and a finisher that looked for the words one step after its own post would wait for
+    // the slowest member (measured: a third of the kernel's time was this tail).  The finisher of
+    // a pair therefore looks kSpDelay steps later, or after its last step, whichever comes first:
+    // by then the words are there, and what little waiting is left falls where the kernel has to
+    // wait for its slowest wavefront anyway.  A member is named every GW steps, so one pending
+    // pair is all there is to remember.
+    const int sp_delay = (GW - 1 < 16) ? GW - 1 : 16;
+    int sp_pair = -1, sp_due = 0;
+
+    // One step: phase 1 of `pair` into (ect, ecd), then phase 2 of the previous pair from (ept, epd).
+    // Memory operations return in the order they were issued, so the order of the requests decides
+    // what can overlap: the small exchange words (the previous pair's team words, and the words of a
+    // pair this wavefront has to finish) are requested first, at the top of the step, where they sit
+    // behind the logits that are about to be used anyway; the logits of the next pair are requested
+    // as soon as phase 1 has consumed the registers; and nothing after that waits on memory unless a
+    // team member is late (then the words are asked for again, behind the prefetch).
+    // (ra, rb) hold the logits of `pair`, the next pair's go to (rna, rnb).  Where registers allow
+    // (DEEP) these are two sets and the next pair is requested at the top of the step, a whole step
+    // ahead; otherwise both names are the same set and the request follows phase 1.
+    // SC names the set that takes this pair's exponentials, SP the one written LAG steps ago.
+    auto step = [&](auto SC, auto SP, uint4 (&ra)[NV], uint4 (&rb)[NV], uint4 (&rna)[NV], uint4 (&rnb)[NV], int pair)
+                    __attribute__((always_inline)) {
+        unsigned long long w[2] = {1, 1}, w2[2] = {1, 1};
+        unsigned long long fw[FW];
+        const int fpair = TWO_PHASE ? fin[0] : ((sp_pair >= 0 && iter >= sp_due) ? sp_pair : -1);
+        const Pend due = pend[LAG - 1];
+        // Phase 1 and the request for the next pair's logits are what the whole team waits for: they
+        // run at raised priority; what follows overlaps with the memory latency and does not need it.
+        __builtin_amdgcn_s_setprio(3);
+        asm volatile("" ::: "memory");
+        if constexpr (TWO_PHASE)
+        {
+            const unsigned long long* const p1 = part1 + static_cast<size_t>(due.pair >= 0 ? due.pair : pair) * GW * 4;
+            request_n<2>(p1, GW, 0, w);
+            request_n<2>(p1, GW, 64, w2, GW > 64);
+        }
+        request_n<FW>(finw + static_cast<size_t>(fpair >= 0 ? fpair : pair) * GW * 4, GW, 0, fw, fpair >= 0);
+        if constexpr (DEEP) {
+            // this pair's logits arrived in the second set a step ago; move them and ask for the next pair's
+#pragma unroll
+            for (int k = 0; k < NV; ++k) { ra[k] = rna[k]; rb[k] = rnb[k]; }
+            asm volatile("" ::: "memory");
+            const bool more = pair + nteams < P.npairs;
+            load_item(rna, rnb, more ? pair + nteams : pair, more);
+        }
+        asm volatile("" ::: "memory");
+        fill_unowned(ra, rb);
+        // ---- phase 1: maximum, then sums of 2^(z log2e - k) with k = ceil(max log2e)
+        float mt = neg_inf(), md = neg_inf();
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            float a[VE], c[VE];
+            unpack<BF16>(ra[k], a);
+            unpack<BF16>(rb[k], c);
+#pragma unroll
+            for (int e = 0; e < VE; e += 2) { mt = fmaxf(fmaxf(mt, a[e]), a[e + 1]); md = fmaxf(fmaxf(md, c[e]), c[e + 1]); }
+        }
+        PT(0);   // load wait + max pass
+        mt = wave_max(mt);
+        md = wave_max(md);
+        const float kt = (mt == neg_inf()) ? 0.0f : ceilf(mt * kLog2e);
+        const float kd = (md == neg_inf()) ? 0.0f : ceilf(md * kLog2e);
+        float st = 0.0f, sd = 0.0f, wacc = 0.0f, dmax = neg_inf();
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            float a[VE], c[VE];
+            unpack<BF16>(ra[k], a);
+            unpack<BF16>(rb[k], c);
+            float xa_[VE], xb_[VE];
+#pragma unroll
+            for (int e = 0; e < VE; ++e) {
+                const float xa = hw_exp2(fmaf(a[e], kLog2e, -kt));
+                const float xb = hw_exp2(fmaf(c[e], kLog2e, -kd));
+                xa_[e] = xa;
+                xb_[e] = xb;
+                st += xa;
+                sd += xb;
+                if constexpr (MODE == MODE_KL || MODE == MODE_KLP) {
+                    const float diff = a[e] - c[e];
+                    dmax = fmaxf(dmax, diff);   // +inf iff the draft masks an entry the target does not
+                    if constexpr (MODE == MODE_KL) wacc = fmaf(xa, fminf(fmaxf(diff, -FLT_MAX), FLT_MAX), wacc);
+                }
+            }
+            if constexpr (TWO_PHASE) {
+#pragma unroll
+                for (int h = 0; h < VE / 4; ++h) {
+                    const float t4[4] = {xa_[4 * h], xa_[4 * h + 1], xa_[4 * h + 2], xa_[4 * h + 3]};
+                    const float d4[4] = {xb_[4 * h], xb_[4 * h + 1], xb_[4 * h + 2], xb_[4 * h + 3]};
+                    put4(SC, k * (VE / 4) + h, t4, d4);
+                }
+            }
+        }
+        PT(1);   // reductions + exp pass
+        // ---- the registers that held the logits are free: fetch the next pair (the request is
+        // unconditional: the last step asks for one slot of its own pair, which the caches hold)
+        asm volatile("" ::: "memory");
+        if constexpr (!DEEP) {
+            const bool more = pair + nteams < P.npairs;
+            load_item(rna, rnb, more ? pair + nteams : pair, more);
+        }
+        __builtin_amdgcn_s_setprio(0);
+        asm volatile("" ::: "memory");
+        // ---- post this wavefront's partial.  The two-phase modes need the normalisers to a relative
+        // 1e-7 only (common factors of p and q); the single-pass modes take them through a logarithm.
+        const unsigned long long w0 = pack2(kt, kd);
+        unsigned long long mine;
+        if constexpr (TWO_PHASE) {
+            st = wave_sumf(st);
+            sd = wave_sumf(sd);
+            mine = (lane == 0) ? w0 : pack2(st, sd);
+        } else {
+            const double pst_ = wave_sum(static_cast<double>(st));
+            const double psd_ = wave_sum(static_cast<double>(sd));
+            double pw_ = 0.0;
+            if constexpr (MODE == MODE_KL) {
+                pw_ = wave_sum(static_cast<double>(wacc));
+                if (wave_max(dmax) == __builtin_inff()) pw_ = __builtin_inf();
+            }
+            mine = (lane == 0) ? w0 : (lane == 1) ? dbits(pst_) : (lane == 2) ? dbits(psd_) : dbits(pw_);
+        }
+        constexpr int kPosted = TWO_PHASE ? 2 : 4;
+        unsigned long long* const post_at = part1 + static_cast<size_t>(pair) * GW * 4 + member * kPosted + (lane & 3);
+        if (lane < kPosted) post64(post_at, mine);
+        PT(3);   // wave sums, prefetch issue, post
+        if constexpr (TWO_PHASE) {
+            // ---- the previous pair's normalisers, then its phase 2
+            float ft = 0.0f, fd = 0.0f;
+            bool ok2 = false;
+            if (due.pair >= 0) ok2 = merge_team(due, w, w2, ft, fd);
+            PT(2);   // team merge (wait for the team's words)
+            if (due.pair >= 0) phase2(due, SP, ft, fd, ok2);
+            PT(4);   // phase 2
+            // the posted value and its address stay in their registers until here: reusing them
+            // earlier would make phase 2 wait for the store, and with it for the prefetch
+            asm volatile("" ::"v"(mine), "v"(post_at));
+#pragma unroll
+            for (int i = LAG - 1; i > 0; --i) pend[i] = pend[i - 1];
+            pend[0] = Pend{pair, kt, kd, (st > 0.0f) || (st != st), (sd > 0.0f) || (sd != sd), dmax == __builtin_inff()};
+        }
+        // ---- finishing duties: the pair whose turn has come, then note this pair if it is ours
+        if (fpair >= 0) finish(fpair, fw);
+        if constexpr (TWO_PHASE) {
+#pragma unroll
+            for (int i = 0; i + 1 < NF; ++i) fin[i] = fin[i + 1];
+            fin[NF - 1] = (iter % GW == member) ? pair : -1;   // the members take turns
+        } else {
+            if (fpair >= 0) sp_pair = -1;
+            if (iter % GW == member) { sp_pair = pair; sp_due = iter + sp_delay; }
+        }
+        PT(5);   // finishing duty
+        ++iter;
+    };
+
+    uint4 r0a[NV], r0b[NV], r1a[DEEP ? NV : 1], r1b[DEEP ? NV : 1];
+    int pair = team;
+    if (pair < P.npairs) {
+        if constexpr (DEEP) load_item(r1a, r1b, pair); else load_item(r0a, r0b, pair);
+    }
+    auto one_step = [&](auto SC, auto SP, int pr) __attribute__((always_inline)) {
+        if constexpr (DEEP) step(SC, SP, r0a, r0b, r1a, r1b, pr);
+        else step(SC, SP, r0a, r0b, r0a, r0b, pr);
+    };
+    if constexpr (TWO_PHASE) {
+        // step i keeps its exponentials in set i % NB and reads the set written LAG steps earlier
+        bool live = pair < P.npairs;
+        while (live) {
+            one_step(SetId<0>{}, SetId<1 % NB>{}, pair);
+            pair += nteams;
+            live = pair < P.npairs;
+            if (live) {
+                one_step(SetId<1>{}, SetId<2 % NB>{}, pair);
+                pair += nteams;
+                live = pair < P.npairs;
+            }
+            if constexpr (NB == 3) {
+                if (live) {
+                    one_step(SetId<2>{}, SetId<0>{}, pair);
+                    pair += nteams;
+                    live = pair < P.npairs;
+                }
+            }
+        }
+        // ---- drain: phase 2 of the pairs still pending, oldest first, then the finishes still owed
+#pragma unroll
+        for (int d = LAG; d >= 1; --d) {
+            const Pend pp = pend[d - 1];
+            if (pp.pair >= 0) {
+                unsigned long long w[2], w2[2];
+                float ft, fd;
+                request_n<2>(part1 + static_cast<size_t>(pp.pair) * GW * 4, GW, 0, w);
+                request_n<2>(part1 + static_cast<size_t>(pp.pair) * GW * 4, GW, 64, w2, GW > 64);
+                const bool ok2 = merge_team(pp, w, w2, ft, fd);
+                const int b = (iter + NB - d) % NB;   // written at step iter - d
+                if (b == 0) phase2(pp, SetId<0>{}, ft, fd, ok2);
+                else if (b == 1) phase2(pp, SetId<1>{}, ft, fd, ok2);
+                else phase2(pp, SetId<NB - 1>{}, ft, fd, ok2);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < NF; ++i) {
+            if (fin[i] >= 0) finish_now(fin[i]);
+        }
+    } else {
+        for (; pair < P.npairs; pair += nteams) one_step(SetId<0>{}, SetId<1>{}, pair);
+        if (sp_pair >= 0) finish_now(sp_pair);
+    }
+#ifdef FSD_PHASE_TIMING
+    PT(6);   // drain
+    if (P.dbg && lane == 0) {
+        unsigned long long* o = P.dbg + (static_cast<size_t>(blockIdx.x) * kWavesPerWG + wave) * 10;
+        for (int i = 0; i < 8; ++i) o[i] = pt_acc[i];
+        o[8] = pt_wall;
+        o[9] = pt_last - pt_first;
+    }
+#endif
+}
+
+}  // namespace
+
+#endif  // FSD_CSRC_PAIR_KERNEL_H_
