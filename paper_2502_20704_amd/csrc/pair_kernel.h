@@ -132,8 +132,11 @@ struct TeamNorm { float Kt, Kd, zt, zd; bool ok; };
 __device__ __forceinline__ void merge_round(const unsigned long long (&w)[2], bool in, TeamNorm& n) {
     const float tk_t = lo_f(w[0]), tk_d = hi_f(w[0]);
     const float tSt = in ? lo_f(w[1]) : 0.0f, tSd = in ? hi_f(w[1]) : 0.0f;
-    n.zt += wave_sumf((tSt > 0.0f) ? ldexpf(tSt, kdiff(tk_t, n.Kt)) : (tSt != tSt ? tSt : 0.0f));
-    n.zd += wave_sumf((tSd > 0.0f) ? ldexpf(tSd, kdiff(tk_d, n.Kd)) : (tSd != tSd ? tSd : 0.0f));
+    float at = (tSt > 0.0f) ? ldexpf(tSt, kdiff(tk_t, n.Kt)) : (tSt != tSt ? tSt : 0.0f);
+    float ad = (tSd > 0.0f) ? ldexpf(tSd, kdiff(tk_d, n.Kd)) : (tSd != tSd ? tSd : 0.0f);
+    wave_sumf2(at, ad);
+    n.zt += at;
+    n.zd += ad;
 }
 // teams of more than 64 wavefronts: the members beyond the first round
 __device__ __noinline__ TeamNorm merge_more_rounds(const unsigned long long* p1, int GW, unsigned limit, TeamNorm n) {
@@ -488,10 +491,8 @@ void pair_kernel(PairParams P) {
             }
             // max() drops NaN: an unusable row (NaN factor) is made to reach the side selection
             if (ft != ft || fd != fd) { A = ft + fd; Bn = A; MA = A; MB = A; }
-            A = wave_sumf(A);
-            Bn = wave_sumf(Bn);
-            MA = wave_sumf(MA);
-            MB = wave_sumf(MB);
+            wave_sumf2(A, Bn);
+            wave_sumf2(MA, MB);
             if (!ok) { A = __builtin_nanf(""); MA = A; }
             word[0] = pack2(A, Bn);
             word[1] = pack2(MA, MB);
@@ -614,8 +615,7 @@ void pair_kernel(PairParams P) {
             for (int e = 0; e < VE; e += 2) { mt = fmaxf(fmaxf(mt, a[e]), a[e + 1]); md = fmaxf(fmaxf(md, c[e]), c[e + 1]); }
         }
         PT(0);   // load wait + max pass
-        mt = wave_max(mt);
-        md = wave_max(md);
+        wave_max2(mt, md);
         const float kt = (mt == neg_inf()) ? 0.0f : ceilf(mt * kLog2e);
         const float kd = (md == neg_inf()) ? 0.0f : ceilf(md * kLog2e);
         float st = 0.0f, sd = 0.0f, wacc = 0.0f, dmax = neg_inf();
@@ -663,8 +663,7 @@ void pair_kernel(PairParams P) {
         const unsigned long long w0 = pack2(kt, kd);
         unsigned long long mine;
         if constexpr (TWO_PHASE) {
-            st = wave_sumf(st);
-            sd = wave_sumf(sd);
+            wave_sumf2(st, sd);
             mine = (lane == 0) ? w0 : pack2(st, sd);
         } else {
             const double pst_ = wave_sum(static_cast<double>(st));
