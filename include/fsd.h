@@ -101,6 +101,10 @@ const char* fsd_status_string(int status);
  *                              softmax(target[b, n_b]), then -1 padding
  *   divergences   [B, K] out   optional (NULL to skip), the chosen divergence
  *   row_status    [B]   out    optional (NULL to skip), see FSD_ROW_*
+ *
+ * A call only enqueues kernels on hip_stream (the workspace is cleared by a
+ * kernel, not by a memset), so it may be recorded into a HIP graph; seed and
+ * offset are then part of the recording.
  */
 int fsd_verify_chain(const void* target_logits, const void* draft_logits, const int32_t* cand_tokens,
                      int B, int K, int V, int dtype, int div, float T, int mode, uint64_t seed,

@@ -731,6 +731,52 @@ def test_config_c4_strict_sd_tree(torch_cuda, oracle):
 
 # ------------------------------------------------------------------------------- robustness
 
+def test_calls_can_be_captured_in_a_graph(torch_cuda):
+    """a verify call is kernel launches only (its clearing is a kernel too), so it can be recorded into a
+    HIP graph; every replay, with eager calls in between, gives the eager result"""
+    torch = torch_cuda
+    inp = synth.chain_inputs(6, 5, 32000, "bf16", "peaked", (0.25, 2.0), seed=12)
+    d = pu.to_dev(inp, ("target", "draft", "cand"))
+    other = pu.to_dev(synth.chain_inputs(6, 5, 32000, "bf16", "peaked", (0.25, 2.0), seed=13), ("target", "draft", "cand"))
+    eager = fsd.fsd_verify_chain(d["target"], d["draft"], d["cand"], 0.1, fsd.DIV_JS, fsd.SAMPLE, 4, 9)
+    eager_sd = fsd.sd_verify_chain(d["target"], d["draft"], d["cand"], fsd.SAMPLE, 4, 9)
+    torch.cuda.synchronize()
+    want = pu.host(eager, pu.CHAIN_KEYS)
+    want_sd = pu.host(eager_sd, pu.SD_KEYS)
+    # outputs and workspaces of the recorded calls exist before the capture: nothing allocates inside it
+    out = {k: torch.empty_like(v) for k, v in eager.items() if k != "_workspace"}
+    out_sd = {k: torch.empty_like(v) for k, v in eager_sd.items() if k != "_workspace"}
+    ws = torch.empty_like(eager["_workspace"])
+    ws_sd = torch.empty_like(eager_sd["_workspace"])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):       # one untimed pass on the capture stream first
+        fsd.fsd_verify_chain(d["target"], d["draft"], d["cand"], 0.1, fsd.DIV_JS, fsd.SAMPLE, 4, 9, out=out, workspace=ws)
+        fsd.sd_verify_chain(d["target"], d["draft"], d["cand"], fsd.SAMPLE, 4, 9, out=out_sd, workspace=ws_sd)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fsd.fsd_verify_chain(d["target"], d["draft"], d["cand"], 0.1, fsd.DIV_JS, fsd.SAMPLE, 4, 9, out=out, workspace=ws)
+        fsd.sd_verify_chain(d["target"], d["draft"], d["cand"], fsd.SAMPLE, 4, 9, out=out_sd, workspace=ws_sd)
+    for rep in range(3):
+        for k in pu.CHAIN_KEYS:
+            out[k].fill_(-7)
+        for k in pu.SD_KEYS:
+            out_sd[k].fill_(-7)
+        # the program's own eager work between the replays, on other inputs
+        fsd.fsd_verify_chain(other["target"], other["draft"], other["cand"], 0.2, fsd.DIV_TV, fsd.SAMPLE, rep, rep)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got, got_sd = pu.host(out, pu.CHAIN_KEYS), pu.host(out_sd, pu.SD_KEYS)
+        for k in pu.CHAIN_KEYS:
+            assert np.array_equal(got[k], want[k], equal_nan=True), (rep, k)
+        for k in pu.SD_KEYS:
+            assert np.array_equal(got_sd[k], want_sd[k], equal_nan=True), (rep, k)
+
+
+
 def test_bounded_wait_expires_cleanly(torch_cuda, oracle):
     """with a zero poll budget a workgroup may give up waiting for its team: the kernel still ends,
     and the call either is correct throughout or flags FSD_ROW_INTERNAL on every sequence."""
