@@ -63,6 +63,9 @@ def lib() -> ctypes.CDLL:
         L.sd_oracle_verify_chain.argtypes = [vp, vp, vp, i32, i32, i64, i32, i32, u64, u64, i32,
                                              vp, vp, vp, vp, vp, vp]
         L.sd_oracle_verify_chain.restype = c.c_int
+        L.fsd_oracle_verify_tree_warped.argtypes = [vp, vp, vp, vp, i32, i32, i32, i64, i32, i32, dbl, i32,
+                                                    u64, u64, i32, c.c_float, i32, dbl, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.fsd_oracle_verify_tree_warped.restype = c.c_int
         L.sd_oracle_verify_tree.argtypes = [vp, vp, vp, vp, i32, i32, i32, i64, i32, i32, u64, u64, i32,
                                             vp, vp, vp, vp, vp, vp, vp]
         L.sd_oracle_verify_tree.restype = c.c_int
@@ -178,6 +181,30 @@ def sd_verify_chain(target, draft, cand, mode=SAMPLE, seed=0, offset=0, seq_offs
                                  offset, seq_offset, _p(out["accept_len"]), _p(out["out_tokens"]),
                                  _p(out["log_ratio"]), _p(out["margin"]), _p(out["row_status"]),
                                  _p(out["gap"]))
+    return out
+
+
+def verify_tree_warped(target, draft, node_tokens, parent, max_depth, T, div=DIV_JS, mode=SAMPLE, seed=0,
+                       offset=0, seq_offset=0, temperature=1.0, top_k=0, top_p=1.0):
+    """verify_tree with temperature / top-k / top-p applied where the token is drawn."""
+    target, draft = _c(target), _c(draft)
+    node_tokens = _c(np.asarray(node_tokens, dtype=np.int32))
+    parent = _c(np.asarray(parent, dtype=np.int32))
+    B, N1, V = target.shape
+    N = N1 - 1
+    assert draft.shape == (B, N, V) and node_tokens.shape == (B, N) and parent.shape == (B, N)
+    assert temperature > 0 and top_k >= 0 and 0 < top_p <= 1
+    inv_temp = float(np.float32(1.0 / float(temperature)))
+    out = dict(path_len=np.zeros(B, np.int32), path_nodes=np.zeros((B, max_depth), np.int32),
+               out_tokens=np.zeros((B, max_depth + 1), np.int32), divs=np.zeros((B, N)),
+               row_status=np.zeros(B, np.int32), gap=np.zeros(B, np.float32),
+               threshold=np.zeros(B, np.float32), slack=np.zeros(B))
+    lib().fsd_oracle_verify_tree_warped(_p(target), _p(draft), _p(node_tokens), _p(parent), B, N, max_depth, V,
+                                        _dt(target), div, float(np.float32(T)), mode, seed, offset, seq_offset,
+                                        inv_temp, int(top_k), float(np.float32(top_p)), _p(out["path_len"]),
+                                        _p(out["path_nodes"]), _p(out["out_tokens"]), _p(out["divs"]),
+                                        _p(out["row_status"]), _p(out["gap"]), _p(out["threshold"]),
+                                        _p(out["slack"]))
     return out
 
 

@@ -280,11 +280,17 @@ int fsd_oracle_verify_chain(const void* target, const void* draft, const int32_t
  * draft [B,N,V], node_tokens [B,N], parent [B,N] (-1 = child of the root,
  * parent[j] < j).  Outputs: path_len [B], path_nodes [B,max_depth] (-1 padded),
  * out_tokens [B,max_depth+1] (-1 padded), divs [B,N], row_status [B]. */
-int fsd_oracle_verify_tree(const void* target, const void* draft, const int32_t* node_tokens,
-                           const int32_t* parent, int B, int N, int max_depth, long V, int dt,
-                           int div_kind, double T, int mode, uint64_t seed, uint64_t offset,
-                           int seq_offset, int32_t* path_len, int32_t* path_nodes, int32_t* out_tokens, double* divs,
-                           int32_t* row_status, float* gap) {
+static int32_t sample_row_warped(const void* base, size_t off, long V, int dt, int mode, uint64_t seed,
+                                 uint64_t offset, uint32_t b, float inv_temp, int top_k, double top_p,
+                                 float* gap, float* threshold, double* slack);
+
+/* warped != 0: the token is drawn with the sampling-method warpers (see sample_row_warped) */
+static int verify_tree_impl(const void* target, const void* draft, const int32_t* node_tokens,
+                            const int32_t* parent, int B, int N, int max_depth, long V, int dt,
+                            int div_kind, double T, int mode, uint64_t seed, uint64_t offset,
+                            int seq_offset, int32_t* path_len, int32_t* path_nodes, int32_t* out_tokens, double* divs,
+                            int32_t* row_status, float* gap, int warped, float inv_temp, int top_k, double top_p,
+                            float* threshold, double* slack) {
 #pragma omp parallel for schedule(dynamic, 1)
     for (int b = 0; b < B; ++b) {
         int status = 0;
@@ -331,14 +337,46 @@ int fsd_oracle_verify_tree(const void* target, const void* draft, const int32_t*
                 out_tokens[(size_t)b * (max_depth + 1) + i] = node_tokens[(size_t)b * N + j];
                 j = par[j];
             }
-            out_tokens[(size_t)b * (max_depth + 1) + win_depth] =
-                sample_row(target, soff, V, dt, mode, seed, offset, (uint32_t)(b + seq_offset), gap ? &gap[b] : NULL);
+            if (warped) {
+                float g32 = INFINITY;
+                out_tokens[(size_t)b * (max_depth + 1) + win_depth] =
+                    sample_row_warped(target, soff, V, dt, mode, seed, offset, (uint32_t)(b + seq_offset), inv_temp,
+                                      top_k, top_p, &g32, &threshold[b], &slack[b]);
+                if (gap) gap[b] = g32;
+            } else {
+                out_tokens[(size_t)b * (max_depth + 1) + win_depth] =
+                    sample_row(target, soff, V, dt, mode, seed, offset, (uint32_t)(b + seq_offset), gap ? &gap[b] : NULL);
+            }
         }
         row_status[b] = status;
         free(depth);
         free(live);
     }
     return 0;
+}
+
+int fsd_oracle_verify_tree(const void* target, const void* draft, const int32_t* node_tokens,
+                           const int32_t* parent, int B, int N, int max_depth, long V, int dt,
+                           int div_kind, double T, int mode, uint64_t seed, uint64_t offset,
+                           int seq_offset, int32_t* path_len, int32_t* path_nodes, int32_t* out_tokens, double* divs,
+                           int32_t* row_status, float* gap) {
+    return verify_tree_impl(target, draft, node_tokens, parent, B, N, max_depth, V, dt, div_kind, T, mode, seed, offset,
+                            seq_offset, path_len, path_nodes, out_tokens, divs, row_status, gap, 0, 1.0f, 0, 1.0, NULL,
+                            NULL);
+}
+
+/* fsd_oracle_verify_tree with the warpers applied where the token is drawn (Sec. 4: the sampling
+ * method is the user's); extra outputs threshold [B], slack [B] as in the chain version. */
+int fsd_oracle_verify_tree_warped(const void* target, const void* draft, const int32_t* node_tokens,
+                                  const int32_t* parent, int B, int N, int max_depth, long V, int dt,
+                                  int div_kind, double T, int mode, uint64_t seed, uint64_t offset,
+                                  int seq_offset, float inv_temp, int top_k, double top_p, int32_t* path_len,
+                                  int32_t* path_nodes, int32_t* out_tokens, double* divs, int32_t* row_status,
+                                  float* gap, float* threshold, double* slack) {
+    for (int b = 0; b < B; ++b) { threshold[b] = NAN; slack[b] = INFINITY; }
+    return verify_tree_impl(target, draft, node_tokens, parent, B, N, max_depth, V, dt, div_kind, T, mode, seed, offset,
+                            seq_offset, path_len, path_nodes, out_tokens, divs, row_status, gap, 1, inv_temp, top_k,
+                            top_p, threshold, slack);
 }
 
 /* -------------------------------------------------------------- strict SD */

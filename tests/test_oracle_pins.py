@@ -731,6 +731,26 @@ def test_nucleus_boundary_on_known_masses(oracle):
     assert (z >= w["threshold"][0]).sum() == 4
 
 
+def test_tree_warpers_follow_the_chain_warpers(oracle):
+    """the tree call draws its token like the chain call does: off = the plain tree call; on a chain-shaped
+    tree = the warped chain call; top_k = 1 = greedy"""
+    t, d, cand = _small_chain(41, B=12, K=5, V=8, sigma=1.4)
+    K = 5
+    parent = np.broadcast_to(np.arange(-1, K - 1, dtype=np.int32), (12, K)).copy()
+    plain = oracle.verify_tree(t, d, cand, parent, K, 0.05, seed=3, offset=2)
+    off = oracle.verify_tree_warped(t, d, cand, parent, K, 0.05, seed=3, offset=2)
+    assert (plain["out_tokens"] == off["out_tokens"]).all() and (plain["path_nodes"] == off["path_nodes"]).all()
+    for kw in (dict(temperature=0.6), dict(top_k=3), dict(top_p=0.7), dict(temperature=1.7, top_k=5, top_p=0.9)):
+        c = oracle.verify_chain_warped(t, d, cand, 0.05, seed=3, offset=2, **kw)
+        tr = oracle.verify_tree_warped(t, d, cand, parent, K, 0.05, seed=3, offset=2, **kw)
+        assert (c["accept_len"] == tr["path_len"]).all() and (c["out_tokens"] == tr["out_tokens"]).all()
+        assert np.array_equal(c["threshold"], tr["threshold"], equal_nan=True)
+    star = np.full((12, K), -1, dtype=np.int32)
+    g = oracle.verify_tree(t, d, cand, star, 1, 0.05, mode=oracle.GREEDY)
+    k1 = oracle.verify_tree_warped(t, d, cand, star, 1, 0.05, seed=9, top_k=1)
+    assert (g["out_tokens"] == k1["out_tokens"]).all()
+
+
 def test_warped_sampler_chi_square_v8(oracle):
     rng = np.random.default_rng(8)
     V, B = 8, 60000
