@@ -200,6 +200,18 @@ int fsd_verify_chain_warped(const void* target_logits, const void* draft_logits,
                             size_t workspace_bytes, void* hip_stream);
 
 /*
+ * fsd_verify_tree with the same warpers, applied to the target row after the
+ * last node of the accepted path.  Arguments as in fsd_verify_tree and
+ * fsd_verify_chain_warped.
+ */
+int fsd_verify_tree_warped(const void* target_logits, const void* draft_logits, const int32_t* node_tokens,
+                           const int32_t* parent, int B, int N, int max_depth, int V, int dtype, int div,
+                           float T, int mode, uint64_t seed, uint64_t offset, float temperature, int top_k,
+                           float top_p, int32_t* path_len, int32_t* path_nodes, int32_t* out_tokens,
+                           float* divergences, int32_t* row_status, void* workspace, size_t workspace_bytes,
+                           void* hip_stream);
+
+/*
  * Reducible FSD (paper Sec. 4.2, "Reducing FSD to standard SD"): position i is
  * accepted iff div(p_i, q_i) <= T (the rule of fsd_verify_chain) OR the strict
  * SD test of sd_verify_chain accepts the candidate token, with the same uniform

@@ -48,6 +48,9 @@ def library() -> ctypes.CDLL:
         L.fsd_verify_chain_warped.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, f32, i32, u64, u64, f32, i32, f32,
                                               vp, vp, vp, vp, vp, sz, vp]
         L.fsd_verify_chain_warped.restype = i32
+        L.fsd_verify_tree_warped.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, f32, i32, u64, u64, f32, i32,
+                                             f32, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.fsd_verify_tree_warped.restype = i32
         L.fsd_verify_tree.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, f32, i32, u64, u64,
                                       vp, vp, vp, vp, vp, vp, sz, vp]
         L.fsd_verify_tree.restype = i32
@@ -211,6 +214,38 @@ def fsd_verify_tree(target, draft, node_tokens, parent, max_depth, T, div=DIV_JS
                                    _stream(stream))
     if st != 0:
         raise FsdError(st, "fsd_verify_tree")
+    out["_workspace"] = workspace
+    return out
+
+
+def fsd_verify_tree_warped(target, draft, node_tokens, parent, max_depth, T, div=DIV_JS, mode=SAMPLE, seed=0,
+                           offset=0, *, temperature=1.0, top_k=0, top_p=1.0, out=None, workspace=None, stream=None):
+    """fsd_verify_tree with temperature / top-k / top-p applied where the token is drawn."""
+    import torch
+
+    B, N1, V = target.shape
+    N = N1 - 1
+    dt = _dtype_code(target)
+    _check(target, "target")
+    _check(draft, "draft", (B, N, V), target.dtype)
+    _check(node_tokens, "node_tokens", (B, N), torch.int32)
+    _check(parent, "parent", (B, N), torch.int32)
+    dev = target.device
+    if out is None:
+        out = dict(path_len=torch.empty(B, dtype=torch.int32, device=dev),
+                   path_nodes=torch.empty((B, max_depth), dtype=torch.int32, device=dev),
+                   out_tokens=torch.empty((B, max_depth + 1), dtype=torch.int32, device=dev),
+                   divergences=torch.empty((B, N), dtype=torch.float32, device=dev),
+                   row_status=torch.empty(B, dtype=torch.int32, device=dev))
+    need = fsd_workspace_bytes(B, N, V, dt)
+    workspace, wptr, wbytes = _workspace(workspace, need, dev)
+    st = library().fsd_verify_tree_warped(_ptr(target), _ptr(draft), _ptr(node_tokens), _ptr(parent), B, N, max_depth,
+                                          V, dt, div, float(T), mode, seed, offset, float(temperature), int(top_k),
+                                          float(top_p), _ptr(out["path_len"]), _ptr(out["path_nodes"]),
+                                          _ptr(out["out_tokens"]), _ptr(out.get("divergences")),
+                                          _ptr(out.get("row_status")), wptr, wbytes, _stream(stream))
+    if st != 0:
+        raise FsdError(st, "fsd_verify_tree_warped")
     out["_workspace"] = workspace
     return out
 

@@ -359,6 +359,7 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
         // warpers: one more kernel finds, per sequence, the smallest kept scaled logit
         WarpParams wp;
         wp.target = static_cast<const char*>(target);
+        wp.parent = (kind == KIND_TREE) ? parent : nullptr;
         wp.rows = rows;
         wp.V = V;
         wp.nslots = p.nslots;
@@ -505,6 +506,16 @@ int sd_verify_chain(const void* target_logits, const void* draft_logits, const i
     return run(KIND_SD, target_logits, draft_logits, cand_tokens, nullptr, B, K, 0, V, dtype, FSD_DIV_KL, 0.0f, mode,
                seed, offset, accept_len, nullptr, out_tokens, log_ratio, nullptr, row_status, workspace, workspace_bytes,
                hip_stream);
+}
+
+int fsd_verify_tree_warped(const void* target_logits, const void* draft_logits, const int32_t* node_tokens,
+                           const int32_t* parent, int B, int N, int max_depth, int V, int dtype, int div, float T,
+                           int mode, uint64_t seed, uint64_t offset, float temperature, int top_k, float top_p,
+                           int32_t* path_len, int32_t* path_nodes, int32_t* out_tokens, float* divergences,
+                           int32_t* row_status, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return run(KIND_TREE, target_logits, draft_logits, node_tokens, parent, B, N, max_depth, V, dtype, div, T, mode,
+               seed, offset, path_len, path_nodes, out_tokens, divergences, nullptr, row_status, workspace,
+               workspace_bytes, hip_stream, temperature, top_k, top_p);
 }
 
 int fsd_verify_chain_warped(const void* target_logits, const void* draft_logits, const int32_t* cand_tokens, int B,

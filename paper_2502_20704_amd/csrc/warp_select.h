@@ -30,7 +30,8 @@ __device__ __forceinline__ float key_value(unsigned k) {
 
 struct WarpParams {
     const char* target;
-    int rows;             // K
+    const int32_t* parent;   // tree: [B,N]; NULL for a chain
+    int rows;             // K or N
     long V;
     long nslots;
     float T;
@@ -68,14 +69,60 @@ __global__ __launch_bounds__(kWarpWG) void warp_select(WarpParams P) {
     const int b = blockIdx.x;
 
     // ---- the row the token will be drawn from: the first rejected position, or the row after the last
-    if (tid == 0) { s_n = P.rows; s_st = 0; }
+    // (chain); the row after the deepest node whose ancestors are all accepted, lowest index on ties (tree)
+    if (tid == 0) { s_n = P.rows; s_st = 0; s_match = 0u; }
     __syncthreads();
-    for (int i = tid; i < P.rows; i += kWarpWG) {
-        const int pr = b * P.rows + i;
-        if (P.ws.pst[pr]) atomicOr(&s_st, 1);
-        if (!(P.ws.div[pr] <= P.T)) atomicMin(&s_n, i);
+    if (P.parent == nullptr) {
+        for (int i = tid; i < P.rows; i += kWarpWG) {
+            const int pr = b * P.rows + i;
+            if (P.ws.pst[pr]) atomicOr(&s_st, 1);
+            if (!(P.ws.div[pr] <= P.T)) atomicMin(&s_n, i);
+        }
+        __syncthreads();
+    } else {
+        // pointer jumping over the parents, as in accept_sample; the list's memory is free until the select
+        const int rows = P.rows;
+        int* par = reinterpret_cast<int*>(s_lkey);
+        int* anc = par + rows;
+        int* acc = anc + rows;
+        int* dep = acc + rows;
+        for (int j = tid; j < rows; j += kWarpWG) {
+            const int pr = b * rows + j;
+            int p = P.parent[pr];
+            if (p < -1 || p >= j) { atomicOr(&s_st, 1); p = -1; }   // accept_sample reports it
+            if (P.ws.pst[pr]) atomicOr(&s_st, 1);
+            par[j] = p; anc[j] = p; dep[j] = 1;
+            acc[j] = (P.ws.div[pr] <= P.T) ? 1 : 0;
+        }
+        __syncthreads();
+        constexpr int PER = kMaxRows / kWarpWG;
+        for (int span = 1; span < rows; span <<= 1) {
+            int na[PER], nacc[PER], nd[PER];
+#pragma unroll
+            for (int q = 0; q < PER; ++q) {
+                const int j = tid + q * kWarpWG;
+                if (j < rows) {
+                    const int a = anc[j];
+                    na[q] = a; nacc[q] = acc[j]; nd[q] = dep[j];
+                    if (a >= 0) { na[q] = anc[a]; nacc[q] = acc[j] & acc[a]; nd[q] = dep[j] + dep[a]; }
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < PER; ++q) {
+                const int j = tid + q * kWarpWG;
+                if (j < rows) { anc[j] = na[q]; acc[j] = nacc[q]; dep[j] = nd[q]; }
+            }
+            __syncthreads();
+        }
+        for (int j = tid; j < rows; j += kWarpWG) {
+            if (acc[j]) atomicMax(&s_match, (static_cast<unsigned>(dep[j]) << 11) | static_cast<unsigned>(kMaxRows - 1 - j));
+        }
+        __syncthreads();
+        const unsigned key = s_match;
+        if (tid == 0) s_n = key ? (kMaxRows - 1 - static_cast<int>(key & (kMaxRows - 1))) + 1 : 0;
+        __syncthreads();
     }
-    __syncthreads();
     if (s_st || P.ws.counters[1]) {   // nothing will be drawn for this sequence
         if (tid == 0) P.thr[b] = neg_inf();
         return;

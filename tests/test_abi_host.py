@@ -86,6 +86,17 @@ def test_tree_and_sd_argument_errors():
     assert st == -5
 
 
+def test_tree_warped_argument_errors():
+    L = fsd.library()
+    big = 1 << 30
+    st = L.fsd_verify_tree_warped(FAKE, FAKE, FAKE, FAKE, 1, 4, 3, 100, fsd.F32, fsd.DIV_JS, 0.1, 0, 0, 0, 0.0, 0, 1.0,
+                                  FAKE, FAKE, FAKE, None, None, FAKE, big, None)
+    assert st == -2                                           # temperature out of range
+    st = L.fsd_verify_tree_warped(FAKE, FAKE, FAKE, None, 1, 4, 3, 100, fsd.F32, fsd.DIV_JS, 0.1, 0, 0, 0, 1.0, 0, 1.0,
+                                  FAKE, FAKE, FAKE, None, None, FAKE, big, None)
+    assert st == -1                                           # parent missing
+
+
 def test_sd_tree_argument_errors():
     L = fsd.library()
     big = 1 << 30

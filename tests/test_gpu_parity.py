@@ -446,6 +446,49 @@ def test_warpers_selection_edge_cases(torch_cuda, oracle):
             check_warped(g, o, 0.1, pu.rel_tol(dtype), f"selection edge cases {dtype} {kw}")
 
 
+def test_tree_warpers(torch_cuda, oracle):
+    """the tree call with warpers: the cut and the token against the oracle on random trees; off = the plain call"""
+    rng = np.random.default_rng(91)
+    for (N, V, dtype) in ((10, 1000, "f32"), (33, 9000, "bf16"), (200, 512, "bf16"), (1500, 64, "f32")):
+        B = 4
+        parent = np.stack([np.array([-1] + [int(rng.integers(-1, j)) for j in range(1, N)], dtype=np.int32)
+                           for _ in range(B)])
+        t = (rng.standard_normal((B, N + 1, V)) * 2).astype(np.float32)
+        d = np.empty((B, N, V), dtype=np.float32)
+        for b in range(B):
+            for j in range(N):
+                d[b, j] = t[b, parent[b, j] + 1] + rng.standard_normal(V) * rng.uniform(0.2, 1.2)
+        toks = rng.integers(0, V, (B, N)).astype(np.int32)
+        if dtype == "bf16":
+            t, d = synth.to_bf16_bits(t), synth.to_bf16_bits(d)
+        dv = pu.to_dev(dict(target=t, draft=d, node_tokens=toks, parent=parent), ("target", "draft", "node_tokens", "parent"))
+        code = fsd.BF16 if dtype == "bf16" else fsd.F32
+        for kw in (dict(), dict(temperature=0.7), dict(top_k=20), dict(top_p=0.8), dict(temperature=1.4, top_k=50, top_p=0.9)):
+            out = fsd.fsd_verify_tree_warped(dv["target"], dv["draft"], dv["node_tokens"], dv["parent"], N, 0.12,
+                                             fsd.DIV_JS, fsd.SAMPLE, 5, 2, **kw)
+            torch_cuda.cuda.synchronize()
+            g = pu.host(out, pu.TREE_KEYS)
+            o = oracle.verify_tree_warped(t, d, toks, parent, N, 0.12, fsd.DIV_JS, fsd.SAMPLE, 5, 2, **kw)
+            what = f"tree warped N={N} V={V} {dtype} {kw}"
+            assert (g["row_status"] == o["row_status"]).all(), what
+            thr = fsd.debug_warp_thresholds(out, B, N, V, code).cpu().numpy()
+            active = 0 < kw.get("top_k", 0) < V or kw.get("top_p", 1.0) < 1.0
+            near = pu.near_threshold(o["divs"], 0.12)
+            for b in range(B):
+                if not (g["path_nodes"][b] == o["path_nodes"][b]).all():
+                    assert near[b].any(), what
+                    continue
+                if active and o["slack"][b] >= 1e-5:
+                    assert thr[b] == o["threshold"][b], f"{what}: cut[{b}] gpu {thr[b]} oracle {o['threshold'][b]}"
+                if not (g["out_tokens"][b] == o["out_tokens"][b]).all():
+                    assert o["slack"][b] < 1e-5 or o["gap"][b] < 1e-6, f"{what}: tokens[{b}]"
+            if not kw:
+                plain = run_tree(torch_cuda, dict(target=t, draft=d, node_tokens=toks, parent=parent), 0.12, fsd.DIV_JS, N,
+                                 seed=5, offset=2)
+                for k in pu.TREE_KEYS:
+                    assert np.array_equal(plain[k], g[k], equal_nan=True), k
+
+
 def test_config_c2_warped(torch_cuda, oracle):
     inp = synth.config_inputs("C2", seed=0)
     for kw in (dict(temperature=0.8, top_k=50, top_p=0.9), dict(top_p=0.6)):
