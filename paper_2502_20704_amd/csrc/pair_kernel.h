@@ -574,8 +574,8 @@ void pair_kernel(PairParams P) {
     // as soon as phase 1 has consumed the registers; and nothing after that waits on memory unless a
     // team member is late (then the words are asked for again, behind the prefetch).
     // (ra, rb) hold the logits of `pair`, the next pair's go to (rna, rnb).  Where registers allow
-    // (DEEP) these are two sets and the next pair is requested at the top of the step, a whole step
-    // ahead; otherwise both names are the same set and the request follows phase 1.
+    // (DEEP) these are different sets and the next pair is requested at the top of the step, a whole
+    // step ahead; otherwise both names are the same set and the request follows phase 1.
     // SC names the set that takes this pair's exponentials, SP the one written LAG steps ago.
     auto step = [&](auto SC, auto SP, uint4 (&ra)[NV], uint4 (&rb)[NV], uint4 (&rna)[NV], uint4 (&rnb)[NV], int pair)
                     __attribute__((always_inline)) {
@@ -595,10 +595,7 @@ void pair_kernel(PairParams P) {
         }
         request_n<FW>(finw + static_cast<size_t>(fpair >= 0 ? fpair : pair) * GW * 4, GW, 0, fw, fpair >= 0);
         if constexpr (DEEP) {
-            // this pair's logits arrived in the second set a step ago; move them and ask for the next pair's
-#pragma unroll
-            for (int k = 0; k < NV; ++k) { ra[k] = rna[k]; rb[k] = rnb[k]; }
-            asm volatile("" ::: "memory");
+            // this pair's logits arrived in (ra, rb) during the last step; ask for the next pair's now
             const bool more = pair + nteams < P.npairs;
             load_item(rna, rnb, more ? pair + nteams : pair, more);
         }
@@ -708,14 +705,16 @@ void pair_kernel(PairParams P) {
         ++iter;
     };
 
-    uint4 r0a[NV], r0b[NV], r1a[DEEP ? NV : 1], r1b[DEEP ? NV : 1];
+    // DEEP: three sets of logit registers that rotate with the three sets of exponentials (two are in
+    // use at any time; the third saves copying 64 registers a step)
+    static_assert(!DEEP || NB == 3, "the logit sets rotate with the sets of exponentials");
+    constexpr int NR = DEEP ? 3 : 1;
+    uint4 rta[NR][NV], rtb[NR][NV];
     int pair = team;
-    if (pair < P.npairs) {
-        if constexpr (DEEP) load_item(r1a, r1b, pair); else load_item(r0a, r0b, pair);
-    }
+    if (pair < P.npairs) load_item(rta[0], rtb[0], pair);
     auto one_step = [&](auto SC, auto SP, int pr) __attribute__((always_inline)) {
-        if constexpr (DEEP) step(SC, SP, r0a, r0b, r1a, r1b, pr);
-        else step(SC, SP, r0a, r0b, r0a, r0b, pr);
+        constexpr int c = decltype(SC)::value % NR, n = (decltype(SC)::value + 1) % NR;
+        step(SC, SP, rta[c], rtb[c], rta[n], rtb[n], pr);
     };
     if constexpr (TWO_PHASE) {
         // step i keeps its exponentials in set i % NB and reads the set written LAG steps earlier
