@@ -129,11 +129,16 @@ __device__ __forceinline__ bool await_n(const unsigned long long* p, int GW, int
 // they are below 2^-127 of the row's mass.
 struct TeamNorm { float Kt, Kd, zt, zd; bool ok; };
 
-__device__ __forceinline__ void merge_round(const unsigned long long (&w)[2], bool in, TeamNorm& n) {
+// one member's sums moved to the references (0 for a lane beyond the team; NaN stays NaN)
+__device__ __forceinline__ void member_terms(const unsigned long long (&w)[2], bool in, const TeamNorm& n, float& at, float& ad) {
     const float tk_t = lo_f(w[0]), tk_d = hi_f(w[0]);
     const float tSt = in ? lo_f(w[1]) : 0.0f, tSd = in ? hi_f(w[1]) : 0.0f;
-    float at = (tSt > 0.0f) ? ldexpf(tSt, kdiff(tk_t, n.Kt)) : (tSt != tSt ? tSt : 0.0f);
-    float ad = (tSd > 0.0f) ? ldexpf(tSd, kdiff(tk_d, n.Kd)) : (tSd != tSd ? tSd : 0.0f);
+    at = (tSt > 0.0f) ? ldexpf(tSt, kdiff(tk_t, n.Kt)) : (tSt != tSt ? tSt : 0.0f);
+    ad = (tSd > 0.0f) ? ldexpf(tSd, kdiff(tk_d, n.Kd)) : (tSd != tSd ? tSd : 0.0f);
+}
+__device__ __forceinline__ void merge_round(const unsigned long long (&w)[2], bool in, TeamNorm& n) {
+    float at, ad;
+    member_terms(w, in, n, at, ad);
     wave_sumf2(at, ad);
     n.zt += at;
     n.zd += ad;
@@ -449,12 +454,21 @@ void pair_kernel(PairParams P) {
         // binary32 is enough: the normalisers enter p and q as common factors
         TeamNorm n{pp.kt, pp.kd, 0.0f, 0.0f, true};
         n.ok = await_n<2>(p1, GW, 0, P.spin_limit, w);
-        merge_round(w, lane < GW, n);
         if (GW > 64) {
-            // members 64..127 were requested with the first 64; larger teams ask for the rest here
+            // members 64..127 were requested with the first 64: a lane adds its two members before the
+            // one reduction over the wavefront; larger teams ask for the rest afterwards
             if (!await_n<2>(p1, GW, 64, P.spin_limit, w2)) n.ok = false;
-            merge_round(w2, 64 + lane < GW, n);
+            float at, ad, at2, ad2;
+            member_terms(w, lane < GW, n, at, ad);
+            member_terms(w2, 64 + lane < GW, n, at2, ad2);
+            at += at2;
+            ad += ad2;
+            wave_sumf2(at, ad);
+            n.zt += at;
+            n.zd += ad;
             if (GW > 128) n = merge_more_rounds(p1, GW, P.spin_limit, n);
+        } else {
+            merge_round(w, lane < GW, n);
         }
         const bool ok = n.ok;
         // the row's sum relative to this wavefront's own reference exponent: p = e / sum.  The
