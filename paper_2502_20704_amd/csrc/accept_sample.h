@@ -319,17 +319,17 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
         // write the whole L2 back, which costs far more than the kernel's arithmetic).  The reader
         // uses device-scope atomic loads, so it needs no invalidate either.
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        const unsigned prev = __hip_atomic_fetch_add(P.ws.sdone + b, 1u, __ATOMIC_RELAXED, AGENT);
+        const unsigned prev = __hip_atomic_fetch_add(P.ws.sdone + static_cast<size_t>(b) * kSdoneStride, 1u, __ATOMIC_RELAXED, AGENT);
         s_last = (prev == static_cast<unsigned>(P.GS) - 1u) ? 1 : 0;
     }
     __syncthreads();
     if (!s_last) return;
 
     // ---- the last workgroup of the sequence merges the shares and writes the outputs
-    if (tid == 0) {
+    if (wave == 0) {   // one share per lane: the loads of all shares are in flight together
         Best m{neg_inf(), 0x7FFFFFFF}, r{neg_inf(), 0x7FFFFFFF};
         int bd = 0;
-        for (int k = 0; k < P.GS; ++k) {
+        for (int k = lane; k < P.GS; k += 64) {
             const unsigned long long* slot = P.ws.spart + (static_cast<size_t>(b) * P.GS + k) * 4;
             const unsigned long long w0 = __hip_atomic_load(slot + 0, __ATOMIC_RELAXED, AGENT);
             const unsigned long long w1 = __hip_atomic_load(slot + 1, __ATOMIC_RELAXED, AGENT);
@@ -337,11 +337,16 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
             m = better(m, Best{__uint_as_float(static_cast<unsigned>(w0 >> 32)), static_cast<int>(static_cast<unsigned>(w0))});
             r = better(r, Best{__uint_as_float(static_cast<unsigned>(w1 >> 32)), static_cast<int>(static_cast<unsigned>(w1))});
         }
-        int st = status;
-        if (!st && (bd || m.idx == 0x7FFFFFFF)) st |= FSD_ROW_NONFINITE;
-        const int tok = (residual && r.idx != 0x7FFFFFFF) ? r.idx : m.idx;
-        s_st = st;
-        s_key = tok;
+        m = wave_best(m);
+        r = wave_best(r);
+        bd = __any(bd);
+        if (lane == 0) {
+            int st = status;
+            if (!st && (bd || m.idx == 0x7FFFFFFF)) st |= FSD_ROW_NONFINITE;
+            const int tok = (residual && r.idx != 0x7FFFFFFF) ? r.idx : m.idx;
+            s_st = st;
+            s_key = tok;
+        }
     }
     __syncthreads();
     status = s_st;

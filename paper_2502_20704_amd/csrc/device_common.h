@@ -15,6 +15,11 @@ namespace {
 
 constexpr int kWG = 256;          // threads per workgroup (4 wavefronts of 64)
 constexpr int kMaxRows = 2048;    // K or N
+constexpr int kSampleWGs = 1024;  // sampler workgroups aimed at per call (all sequences together): more cost
+                                  // more in launch and posting than their parallelism returns
+constexpr int kSdoneStride = 64;  // 32-bit words between the sampler's per-sequence counters: one 256-byte
+                                  // line each, so that the counting atomics of different sequences do not
+                                  // queue at one memory channel
 constexpr int kWalkShare = 8;     // workgroups that share a sequence's passes in the tree walk (at most)
 constexpr float kLog2e = 1.44269504088896340736f;
 constexpr double kLn2 = 0.69314718055994530942;
@@ -291,8 +296,8 @@ __device__ __forceinline__ float gumbel(unsigned w) {
 // workspace view
 
 struct Ws {
-    unsigned* counters;  // 64 words ([1]: a bounded wait expired), then sdone[B]
-    unsigned* sdone;     // [B] sampler workgroups that posted
+    unsigned* counters;  // 64 words ([1]: a bounded wait expired), then sdone
+    unsigned* sdone;     // [B][kSdoneStride], first word: sampler workgroups that posted
     unsigned long long* part1;  // [R][G][4]: (kt,kd) | St | Sd | W
     double* part2;       // [R][G][4] divergence words (one used, four for TV)
     float* div;          // [R]

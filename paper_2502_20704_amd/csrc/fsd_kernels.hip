@@ -70,7 +70,7 @@ bool make_plan(int B, int rows, long V, int dtype, Plan& p) {
     if (G > kMaxTeam) return false;
     p.G = static_cast<int>(G);
     p.spm = static_cast<int>((p.nslots + G - 1) / G);
-    long GS = (1024 + B - 1) / B;
+    long GS = (kSampleWGs + B - 1) / B;
     const long maxgs = (p.nslots + kWG - 1) / kWG;
     if (GS > maxgs) GS = maxgs;
     if (GS > 64) GS = 64;
@@ -79,7 +79,7 @@ bool make_plan(int B, int rows, long V, int dtype, Plan& p) {
     p.sps = static_cast<int>((p.nslots + GS - 1) / GS);
     const size_t R = static_cast<size_t>(B) * rows;
     size_t o = 0;
-    p.off_counters = o; p.n_counters = 64 + B; o = align_up(o + p.n_counters * 4, 256);
+    p.off_counters = o; p.n_counters = 64 + static_cast<size_t>(B) * kSdoneStride; o = align_up(o + p.n_counters * 4, 256);
     p.off_part1 = o; o = align_up(o + R * p.G * 32, 256);
     p.off_part2 = o; o = align_up(o + R * p.G * 32, 256);
     p.off_wz = o; o = align_up(o + R * kWalkShare * 8, 256);
