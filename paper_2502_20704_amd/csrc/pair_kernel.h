@@ -200,7 +200,7 @@ void pair_kernel(PairParams P) {
     constexpr int LAG = (TWO_PHASE && !BF16 && NV == 8) ? 2 : 1;
     constexpr int NB = LAG + 1;                      // sets of kept exponentials
     constexpr int NC = (NE + 3) / 4;                 // chunks of four per row
-    constexpr float kTiny = 2e-38f;   // keeps p + q > 0 without changing any result
+    constexpr float kTiny = 2e-38f;   // floor of u and v under the logarithm (their weights are then zero or negligible)
     constexpr int kWavesPerWG = kWG / 64;
 
     // the wavefront's number as a scalar: everything derived from it (member, slot range, exchange
@@ -486,6 +486,15 @@ void pair_kernel(PairParams P) {
         // Only relative errors enter p and q, and the divergences below are functions of (p, q)
         // alone, second order in r = (p - q)/(p + q): the result is the divergence of a slightly
         // perturbed input.  u = 1 + r = 2p/s and v = 2 - u = 2q/s (exact subtraction).
+        //
+        // All of them are homogeneous of degree one in (p, q), so only one side is scaled entry by
+        // entry: with c = fd/ft the pair (e_t, e_d c) = (p, q)/ft, and the wavefront's sum takes the
+        // factor ft once.  Factors below 2^-80 (a wavefront whose share of the row is that small) are
+        // raised to it, which moves the result by less than 1e-20; equal factors give c = 1 exactly,
+        // so equal rows still give p == q entry by entry.  The exponentials are zero or normal numbers
+        // (the hardware exponential flushes), hence so is a positive p - q and its p + q.
+        const float ftc = fmaxf(ft, 0x1p-80f), fdc = fmaxf(fd, 0x1p-80f);   // max() drops NaN: see below
+        const float cq = (ftc == fdc) ? 1.0f : fdc * __builtin_amdgcn_rcpf(ftc);
         unsigned long long word[PW];
         if constexpr (MODE == MODE_TV) {
             float A = 0.0f, Bn = 0.0f, MA = 0.0f, MB = 0.0f;
@@ -495,7 +504,7 @@ void pair_kernel(PairParams P) {
                 get4(S, c, t4, d4);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const float p = t4[i] * ft, q = d4[i] * fd;   // separately rounded: p == q for equal rows
+                    const float p = t4[i], q = d4[i] * cq;
                     const float d = p - q, sum = p + q;
                     A += fmaxf(d, 0.0f);
                     Bn += fmaxf(-d, 0.0f);
@@ -504,9 +513,10 @@ void pair_kernel(PairParams P) {
                 }
             }
             // max() drops NaN: an unusable row (NaN factor) is made to reach the side selection
-            if (ft != ft || fd != fd) { A = ft + fd; Bn = A; MA = A; MB = A; }
             wave_sumf2(A, Bn);
             wave_sumf2(MA, MB);
+            A *= ftc; Bn *= ftc; MA *= ftc; MB *= ftc;
+            if (ft != ft || fd != fd) { A = ft + fd; Bn = A; MA = A; MB = A; }
             if (!ok) { A = __builtin_nanf(""); MA = A; }
             word[0] = pack2(A, Bn);
             word[1] = pack2(MA, MB);
@@ -518,8 +528,9 @@ void pair_kernel(PairParams P) {
               get4(S, c, t4, d4);
 #pragma unroll
               for (int i = 0; i < 4; ++i) {
-                const float p = fmaf(t4[i], ft, kTiny), q = fmaf(d4[i], fd, kTiny);
+                const float p = t4[i], q = d4[i] * cq;
                 const float d = p - q, sum = p + q;
+                // p = q = 0: 0 * inf = NaN, which max() drops (u = kTiny, v = 2, both weights zero)
                 const float inv = __builtin_amdgcn_rcpf(sum);
                 float u = fmaxf(fmaf(d, inv, 1.0f), kTiny), v = fmaxf(2.0f - u, kTiny);
                 if constexpr (MODE == MODE_KLP) {
@@ -545,7 +556,8 @@ void pair_kernel(PairParams P) {
                 }
               }
             }
-            acc = wave_sumf(acc);
+            acc = wave_sumf(acc) * ftc;
+            if (ft != ft || fd != fd) acc = ft + fd;   // an unusable row stays NaN
             if constexpr (MODE == MODE_KLP) {
                 if (__any(pp.mask)) acc += __builtin_inff();   // draft masks an entry the target keeps; NaN stays NaN
             }
