@@ -192,11 +192,20 @@ __device__ __forceinline__ uint4 slot_neg_inf() {
 
 // ALIGNED: rows start on 16-byte boundaries and V is a multiple of the slot width.
 // Otherwise elements are fetched one by one and the ragged tail is padded with -inf.
-template <bool BF16, bool ALIGNED>
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+template <bool BF16, bool ALIGNED, bool STREAM = false>
 __device__ __forceinline__ uint4 load_slot(const char* row, long slot, long V) {
     if constexpr (ALIGNED) {
         // a 32-bit offset from the row (rows are at most 2 MiB): the row pointer stays scalar
-        return *reinterpret_cast<const uint4*>(row + static_cast<size_t>(static_cast<unsigned>(slot) * 16u));
+        const char* at = row + static_cast<size_t>(static_cast<unsigned>(slot) * 16u);
+        if constexpr (STREAM) {
+            // read once by this kernel: marked non-temporal
+            const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(at));
+            return make_uint4(v.x, v.y, v.z, v.w);
+        } else {
+            return *reinterpret_cast<const uint4*>(at);
+        }
     } else if constexpr (BF16) {
         const unsigned short* p = reinterpret_cast<const unsigned short*>(row);
         unsigned w[4];

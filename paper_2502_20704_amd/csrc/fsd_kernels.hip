@@ -173,23 +173,29 @@ Residency residency_of(Kernel kernel, int threads, Residency (&cache)[16]) {
     return cache[dev];
 }
 
-template <bool BF16, int NV, int MODE, bool ALIGNED>
+template <bool BF16, int NV, int MODE, bool ALIGNED, bool TSHARED = false>
 void launch_pair_k(hipStream_t st, const PairParams& P) {
     // persistent grid: whole teams only, never more than fits on the device at once
     static Residency cache[16] = {};
-    const Residency res = residency_of(pair_kernel<BF16, NV, MODE, ALIGNED>, kWG, cache);
+    const Residency res = residency_of(pair_kernel<BF16, NV, MODE, ALIGNED, TSHARED>, kWG, cache);
     const long wgs_per_team = P.G / (kWG / 64);
     const long want = static_cast<long>(P.npairs) * wgs_per_team;
     long cap = res.total / wgs_per_team * wgs_per_team;
     if (cap < wgs_per_team) cap = wgs_per_team;
     const long grid = want < cap ? want : cap;
     g_last_grid = static_cast<int>(grid);
-    hipLaunchKernelGGL((pair_kernel<BF16, NV, MODE, ALIGNED>), dim3(static_cast<unsigned>(grid)), dim3(kWG), res.pad_lds, st, P);
+    hipLaunchKernelGGL((pair_kernel<BF16, NV, MODE, ALIGNED, TSHARED>), dim3(static_cast<unsigned>(grid)), dim3(kWG), res.pad_lds, st, P);
 }
 template <bool BF16, int NV, int MODE>
 void launch_pair_a(bool aligned, hipStream_t st, const PairParams& P) {
-    if (aligned) launch_pair_k<BF16, NV, MODE, true>(st, P);
-    else launch_pair_k<BF16, NV, MODE, false>(st, P);
+    if (!aligned) {
+        launch_pair_k<BF16, NV, MODE, false>(st, P);
+    } else if constexpr (BF16) {
+        launch_pair_k<BF16, NV, MODE, true>(st, P);
+    } else {
+        if (P.parent != nullptr) launch_pair_k<BF16, NV, MODE, true, true>(st, P);   // a tree: shared target rows
+        else launch_pair_k<BF16, NV, MODE, true>(st, P);
+    }
 }
 template <bool BF16, int NV>
 void launch_pair_m(int mode, bool aligned, hipStream_t st, const PairParams& P) {

@@ -178,7 +178,10 @@ constexpr int pair_kernel_waves(bool bf16, int nv, int mode) {
     return (bf16 && nv == 5 && (mode == MODE_JS || mode == MODE_TV)) ? 2 : 1;
 }
 
-template <bool BF16, int NV, int MODE, bool ALIGNED>
+// TSHARED (binary32 only): target rows are shared between pairs (a tree) and are loaded to stay cached.
+// The bfloat16 kernels take that decision at run time; in the binary32 ones, whose loads run a
+// step ahead into rotating registers, the two-way code costs a tenth of the kernel's time.
+template <bool BF16, int NV, int MODE, bool ALIGNED, bool TSHARED = false>
 __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(pair_kernel_waves(BF16, NV, MODE))))
 void pair_kernel(PairParams P) {
     constexpr int VE = Slot<BF16>::VE;
@@ -266,12 +269,35 @@ void pair_kernel(PairParams P) {
     auto load_item = [&](uint4 (&ra)[NV], uint4 (&rb)[NV], int pair, bool wanted = true) __attribute__((always_inline)) {
         const char *tptr, *dptr;
         row_ptrs(pair, tptr, dptr);
+        // A draft row is read once.  So is a target row of a chain (but for the one the token is drawn
+        // from); in a tree the children of a node share their parent's target row, which should stay
+        // cached.
+        if constexpr (BF16) {
+            if (P.parent == nullptr) {
 #pragma unroll
-        for (int k = 0; k < NV; ++k) {
-            const int sk = sl0 + 64 * k;
-            const long sl = wanted ? (sk < sl_end ? sk : sl_last) : 0;   // not wanted: one cached slot for all lanes
-            ra[k] = load_slot<BF16, ALIGNED>(tptr, sl, P.V);
-            rb[k] = load_slot<BF16, ALIGNED>(dptr, sl, P.V);
+                for (int k = 0; k < NV; ++k) {
+                    const int sk = sl0 + 64 * k;
+                    const long sl = wanted ? (sk < sl_end ? sk : sl_last) : 0;   // not wanted: one cached slot for all lanes
+                    ra[k] = load_slot<BF16, ALIGNED, true>(tptr, sl, P.V);
+                    rb[k] = load_slot<BF16, ALIGNED, true>(dptr, sl, P.V);
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < NV; ++k) {
+                    const int sk = sl0 + 64 * k;
+                    const long sl = wanted ? (sk < sl_end ? sk : sl_last) : 0;
+                    ra[k] = load_slot<BF16, ALIGNED, false>(tptr, sl, P.V);
+                    rb[k] = load_slot<BF16, ALIGNED, true>(dptr, sl, P.V);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < NV; ++k) {
+                const int sk = sl0 + 64 * k;
+                const long sl = wanted ? (sk < sl_end ? sk : sl_last) : 0;
+                ra[k] = load_slot<BF16, ALIGNED, !TSHARED>(tptr, sl, P.V);
+                rb[k] = load_slot<BF16, ALIGNED, true>(dptr, sl, P.V);
+            }
         }
     };
     auto fill_unowned = [&](uint4 (&ra)[NV], uint4 (&rb)[NV]) __attribute__((always_inline)) {
