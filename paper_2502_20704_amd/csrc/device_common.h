@@ -264,7 +264,9 @@ __device__ __forceinline__ U4 philox4x32_10(unsigned c0, unsigned c1, unsigned c
         const unsigned long long p1 = static_cast<unsigned long long>(0xCD9E8D57u) * c2;
         const unsigned hi0 = static_cast<unsigned>(p0 >> 32), lo0 = static_cast<unsigned>(p0);
         const unsigned hi1 = static_cast<unsigned>(p1 >> 32), lo1 = static_cast<unsigned>(p1);
-        const unsigned n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+        // a three-input bitwise operation with the truth table of a ^ b ^ c (0x96): one instruction
+        const unsigned n0 = __builtin_amdgcn_bitop3_b32(hi1, c1, k0, 0x96);
+        const unsigned n2 = __builtin_amdgcn_bitop3_b32(hi0, c3, k1, 0x96);
         c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
         k0 += 0x9E3779B9u;
         k1 += 0xBB67AE85u;
