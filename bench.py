@@ -80,8 +80,14 @@ def main() -> int:
         nsets = max(1, (24 << 30) // set_bytes)
 
     sets, host_sets = [], []
+    target_rows_read = []   # per input set: distinct target rows the pairs refer to
     for s in range(nsets):
         inp = synth.config_inputs(args.config, seed=100 + s)
+        if tree:   # the children of a node share its target row: it counts once
+            par = inp["parent"].reshape(B, rows)
+            target_rows_read.append(sum(len(set(par[b].tolist())) for b in range(B)))
+        else:
+            target_rows_read.append(B * rows)
         if s < 4:
             host_sets.append(inp)
         if tree:
@@ -142,7 +148,8 @@ def main() -> int:
     positions = B * rows
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = positions * args.steps / (t1 - t0)
-    alg_bytes = 2 * V * es * positions          # one target row + one draft row per position, read once
+    # one draft row per position and every distinct target row, each read once (mean over the sets)
+    alg_bytes = int(V * es * (positions + sum(target_rows_read) / len(target_rows_read)))
     achieved = alg_bytes / (k1_mean_ms * 1e-3) / 1e9 if n_ev else None
     rule = {"fsd": f"{args.div.upper()} T={T}", "sd": "strict SD", "rfsd": f"reducible {args.div.upper()} T={T}"}[args.method]
     workload = (f"{args.config}: {'tree' if tree else 'chain'} verify B={B} {'N' if tree else 'K'}={rows} V={V} "

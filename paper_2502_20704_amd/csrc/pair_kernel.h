@@ -203,7 +203,8 @@ void pair_kernel(PairParams P) {
     constexpr int LAG = (TWO_PHASE && !BF16 && NV == 8) ? 2 : 1;
     constexpr int NB = LAG + 1;                      // sets of kept exponentials
     constexpr int NC = (NE + 3) / 4;                 // chunks of four per row
-    constexpr float kTiny = 2e-38f;   // floor of u and v under the logarithm (their weights are then zero or negligible)
+    constexpr float kTiny = 2e-38f;   // floor of u and v under the logarithm (their weights are then zero or negligible),
+                                      // and of p and q where both are normalised (KL)
     constexpr int kWavesPerWG = kWG / 64;
 
     // the wavefront's number as a scalar: everything derived from it (member, slot range, exchange
@@ -513,7 +514,7 @@ void pair_kernel(PairParams P) {
         // alone, second order in r = (p - q)/(p + q): the result is the divergence of a slightly
         // perturbed input.  u = 1 + r = 2p/s and v = 2 - u = 2q/s (exact subtraction).
         //
-        // All of them are homogeneous of degree one in (p, q), so only one side is scaled entry by
+        // JS and TV are homogeneous of degree one in (p, q) and bounded, so only one side is scaled entry by
         // entry: with c = fd/ft the pair (e_t, e_d c) = (p, q)/ft, and the wavefront's sum takes the
         // factor ft once.  Factors below 2^-80 (a wavefront whose share of the row is that small) are
         // raised to it, which moves the result by less than 1e-20; equal factors give c = 1 exactly,
@@ -554,9 +555,13 @@ void pair_kernel(PairParams P) {
               get4(S, c, t4, d4);
 #pragma unroll
               for (int i = 0; i < 4; ++i) {
-                const float p = t4[i], q = d4[i] * cq;
+                // KL is not bounded: where q/p leaves binary32's range its terms saturate (ln of the range),
+                // and raised factors would lower that point from 87 to 55; it keeps both factors, and a
+                // floor under p and q instead
+                const float p = (MODE == MODE_KLP) ? fmaf(t4[i], ft, kTiny) : t4[i];
+                const float q = (MODE == MODE_KLP) ? fmaf(d4[i], fd, kTiny) : d4[i] * cq;
                 const float d = p - q, sum = p + q;
-                // p = q = 0: 0 * inf = NaN, which max() drops (u = kTiny, v = 2, both weights zero)
+                // (JS) p = q = 0: 0 * inf = NaN, which max() drops (u = kTiny, v = 2, both weights zero)
                 const float inv = __builtin_amdgcn_rcpf(sum);
                 float u = fmaxf(fmaf(d, inv, 1.0f), kTiny), v = fmaxf(2.0f - u, kTiny);
                 if constexpr (MODE == MODE_KLP) {
@@ -582,7 +587,8 @@ void pair_kernel(PairParams P) {
                 }
               }
             }
-            acc = wave_sumf(acc) * ftc;
+            acc = wave_sumf(acc);
+            if constexpr (MODE != MODE_KLP) acc *= ftc;
             if (ft != ft || fd != fd) acc = ft + fd;   // an unusable row stays NaN
             if constexpr (MODE == MODE_KLP) {
                 if (__any(pp.mask)) acc += __builtin_inff();   // draft masks an entry the target keeps; NaN stays NaN

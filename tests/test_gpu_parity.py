@@ -170,6 +170,34 @@ def test_wide_dynamic_range_across_the_team(torch_cuda, oracle):
             assert (g["divergences"][1] == 0).all()
 
 
+def test_mass_in_opposite_halves(torch_cuda, oracle):
+    """target and draft put their mass on different halves of the vocabulary, `gap` units apart: in
+    every slice one side's normalising factor vanishes (or nearly) while the other's does not.  JS goes
+    to ln 2 and TV to 1.  KL is about `gap`: the bfloat16 path (one pass, log domain) follows it all
+    the way; the binary32 path forms p/q entry by entry and is exact while q/p stays a normal number."""
+    rng = np.random.default_rng(34)
+    B, K, V = 2, 3, 70000
+    for gap in (40.0, 330.0):
+        base = np.where(np.arange(V) < V // 2, -gap / 2, gap / 2).astype(np.float32)
+        t = (base + rng.standard_normal((B, K + 1, V)).astype(np.float32) * 2).astype(np.float32)
+        d = (base[::-1] + rng.standard_normal((B, K, V)).astype(np.float32) * 2).astype(np.float32)
+        cand = rng.integers(0, V, (B, K)).astype(np.int32)
+        for dtype in ("f32", "bf16"):
+            inp = dict(target=t, draft=d, cand=cand)
+            if dtype == "bf16":
+                inp = dict(target=synth.to_bf16_bits(t), draft=synth.to_bf16_bits(d), cand=cand)
+            for div in (fsd.DIV_JS, fsd.DIV_TV, fsd.DIV_KL):
+                g = run_chain(torch_cuda, inp, 0.3, div, seed=2)
+                o = oracle.verify_chain(inp["target"], inp["draft"], inp["cand"], 0.3, div, seed=2)
+                assert (g["row_status"] == 0).all()
+                if div == fsd.DIV_KL and dtype == "f32" and gap > 80:
+                    # beyond binary32's range for q/p the entry-wise form saturates: large, finite, rejected
+                    assert (g["divergences"] > 60).all() and (g["divergences"] < o["divs"]).all()
+                    assert (g["accept_len"] == 0).all() and (o["accept_len"] == 0).all()
+                    continue
+                pu.check_chain(g, o, 0.3, pu.rel_tol(dtype), f"opposite halves gap={gap} {dtype} div={div}")
+
+
 def test_accuracy_envelope_on_nearly_identical_rows(torch_cuda, oracle):
     """The kernels evaluate p and q in binary32, so a divergence carries an absolute error of about 1e-7
     times the mass involved, whatever its size: the relative bar (1e-5 binary32 logits, 2e-3 bfloat16)
