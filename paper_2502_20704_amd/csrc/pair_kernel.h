@@ -231,6 +231,14 @@ void pair_kernel(PairParams P) {
     // ended together but no sooner: the kernel is bound by vector-ALU issue either way.)
     const int nteams = static_cast<int>(gridDim.x) / wgs_per_team;
     const int team = static_cast<int>(blockIdx.x) / wgs_per_team;
+    // Which pairs a team takes.  A chain: every nteams-th pair.  A tree: a run of consecutive pairs,
+    // because the children of a node are numbered in a row and share their target row: the second
+    // child's loads then find it in the cache its first child's loads filled one step earlier.
+    const bool runs = (P.parent != nullptr);
+    const int per_team = (P.npairs + nteams - 1) / nteams;
+    const int pstep = runs ? 1 : nteams;
+    const int pair0 = runs ? team * per_team : team;
+    const int pair_end = runs ? ((pair0 + per_team < P.npairs) ? pair0 + per_team : P.npairs) : P.npairs;
     const int wg_in_team = static_cast<int>(blockIdx.x) % wgs_per_team;
     const int member = wg_in_team * kWavesPerWG + wave;
     const long s0 = static_cast<long>(member) * P.spm;
@@ -654,8 +662,8 @@ void pair_kernel(PairParams P) {
         request_n<FW>(finw + static_cast<size_t>(fpair >= 0 ? fpair : pair) * GW * 4, GW, 0, fw, fpair >= 0);
         if constexpr (DEEP) {
             // this pair's logits arrived in (ra, rb) during the last step; ask for the next pair's now
-            const bool more = pair + nteams < P.npairs;
-            load_item(rna, rnb, more ? pair + nteams : pair, more);
+            const bool more = pair + pstep < pair_end;
+            load_item(rna, rnb, more ? pair + pstep : pair, more);
         }
         asm volatile("" ::: "memory");
         fill_unowned(ra, rb);
@@ -708,8 +716,8 @@ void pair_kernel(PairParams P) {
         // unconditional: the last step asks for one slot of its own pair, which the caches hold)
         asm volatile("" ::: "memory");
         if constexpr (!DEEP) {
-            const bool more = pair + nteams < P.npairs;
-            load_item(rna, rnb, more ? pair + nteams : pair, more);
+            const bool more = pair + pstep < pair_end;
+            load_item(rna, rnb, more ? pair + pstep : pair, more);
         }
         __builtin_amdgcn_s_setprio(0);
         asm volatile("" ::: "memory");
@@ -768,29 +776,29 @@ void pair_kernel(PairParams P) {
     static_assert(!DEEP || NB == 3, "the logit sets rotate with the sets of exponentials");
     constexpr int NR = DEEP ? 3 : 1;
     uint4 rta[NR][NV], rtb[NR][NV];
-    int pair = team;
-    if (pair < P.npairs) load_item(rta[0], rtb[0], pair);
+    int pair = pair0;
+    if (pair < pair_end) load_item(rta[0], rtb[0], pair);
     auto one_step = [&](auto SC, auto SP, int pr) __attribute__((always_inline)) {
         constexpr int c = decltype(SC)::value % NR, n = (decltype(SC)::value + 1) % NR;
         step(SC, SP, rta[c], rtb[c], rta[n], rtb[n], pr);
     };
     if constexpr (TWO_PHASE) {
         // step i keeps its exponentials in set i % NB and reads the set written LAG steps earlier
-        bool live = pair < P.npairs;
+        bool live = pair < pair_end;
         while (live) {
             one_step(SetId<0>{}, SetId<1 % NB>{}, pair);
-            pair += nteams;
-            live = pair < P.npairs;
+            pair += pstep;
+            live = pair < pair_end;
             if (live) {
                 one_step(SetId<1>{}, SetId<2 % NB>{}, pair);
-                pair += nteams;
-                live = pair < P.npairs;
+                pair += pstep;
+                live = pair < pair_end;
             }
             if constexpr (NB == 3) {
                 if (live) {
                     one_step(SetId<2>{}, SetId<0>{}, pair);
-                    pair += nteams;
-                    live = pair < P.npairs;
+                    pair += pstep;
+                    live = pair < pair_end;
                 }
             }
         }
@@ -815,7 +823,7 @@ void pair_kernel(PairParams P) {
             if (fin[i] >= 0) finish_now(fin[i]);
         }
     } else {
-        for (; pair < P.npairs; pair += nteams) one_step(SetId<0>{}, SetId<1>{}, pair);
+        for (; pair < pair_end; pair += pstep) one_step(SetId<0>{}, SetId<1>{}, pair);
         if (sp_pair >= 0) finish_now(sp_pair);
     }
 #ifdef FSD_PHASE_TIMING
