@@ -631,6 +631,21 @@ def test_tree_small_random(torch_cuda, oracle):
                 pu.check_tree(g, o, T, pu.rel_tol(dtype), f"tree N={N} V={V} T={T} div={div}")
 
 
+def test_tree_runs_of_pairs_with_idle_teams(torch_cuda, oracle):
+    """At the full vocabulary a team is 13 workgroups and about 39 teams are resident; a tree call hands
+    each team a run of consecutive pairs.  111 pairs make runs of 3 that use up the pairs before the
+    last teams get any; 126 pairs make runs of 4 that end in a run of 2 and leave more teams idle."""
+    B, V = 3, 128256
+    for N, seed in ((37, 21), (42, 22)):
+        inp = synth.tree_inputs(B, N, V, "bf16", 1.0, seed=seed)
+        md = int(inp["max_depth"])
+        for div, T in ((fsd.DIV_JS, 0.15), (fsd.DIV_TV, 0.4)):
+            print(f"tree runs N={N} div={div}", flush=True)
+            g = run_tree(torch_cuda, inp, T, div, md, seed=seed)
+            o = oracle.verify_tree(inp["target"], inp["draft"], inp["node_tokens"], inp["parent"], md, T, div, seed=seed)
+            pu.check_tree(g, o, T, pu.rel_tol("bf16"), f"tree runs N={N} div={div}")
+
+
 def test_chain_shaped_tree_equals_chain(torch_cuda):
     inp = synth.chain_inputs(4, 6, 9000, "bf16", "peaked", 1.0, seed=4)
     parent = np.broadcast_to(np.arange(-1, 5, dtype=np.int32), (4, 6)).copy()
