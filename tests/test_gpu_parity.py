@@ -198,6 +198,34 @@ def test_mass_in_opposite_halves(torch_cuda, oracle):
                 pu.check_chain(g, o, 0.3, pu.rel_tol(dtype), f"opposite halves gap={gap} {dtype} div={div}")
 
 
+def test_exponentials_in_the_subnormal_range(torch_cuda, oracle):
+    """logits spread evenly over 120 units: next to its largest entry every slice has entries whose
+    exponential lies in binary32's subnormal range (87 to 103 below) or underflows altogether, on one
+    side, on the other or on both.  Such entries carry no weight, and must not turn into inf or NaN."""
+    rng = np.random.default_rng(35)
+    B, K, V = 2, 3, 30000
+    t = rng.uniform(-120.0, 0.0, (B, K + 1, V)).astype(np.float32)
+    d = rng.uniform(-120.0, 0.0, (B, K, V)).astype(np.float32)
+    d[1, 0] = t[1, 0]
+    cand = rng.integers(0, V, (B, K)).astype(np.int32)
+    for dtype in ("f32", "bf16"):
+        inp = dict(target=t, draft=d, cand=cand)
+        if dtype == "bf16":
+            inp = dict(target=synth.to_bf16_bits(t), draft=synth.to_bf16_bits(d), cand=cand)
+        for div in (fsd.DIV_JS, fsd.DIV_TV, fsd.DIV_KL):
+            g = run_chain(torch_cuda, inp, 0.3, div, seed=3)
+            o = oracle.verify_chain(inp["target"], inp["draft"], inp["cand"], 0.3, div, seed=3)
+            assert (g["row_status"] == 0).all() and np.isfinite(g["divergences"]).all()
+            assert g["divergences"][1, 0] == 0
+            if div == fsd.DIV_KL and dtype == "f32":
+                # entries with q/p beyond binary32's range carry mass here: a lower bound (see
+                # test_mass_in_opposite_halves), same decisions
+                assert (g["divergences"] <= o["divs"] * (1 + 1e-5)).all() and (g["divergences"] >= 0.5 * o["divs"]).all()
+                assert (g["accept_len"] == o["accept_len"]).all() and (g["out_tokens"] == o["out_tokens"]).all()
+                continue
+            pu.check_chain(g, o, 0.3, pu.rel_tol(dtype), f"subnormal range {dtype} div={div}")
+
+
 def test_accuracy_envelope_on_nearly_identical_rows(torch_cuda, oracle):
     """The kernels evaluate p and q in binary32, so a divergence carries an absolute error of about 1e-7
     times the mass involved, whatever its size: the relative bar (1e-5 binary32 logits, 2e-3 bfloat16)
