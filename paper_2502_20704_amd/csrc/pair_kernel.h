@@ -188,7 +188,7 @@ void pair_kernel(PairParams P) {
     constexpr int ES = BF16 ? 2 : 4;
     constexpr bool TWO_PHASE = (MODE == MODE_JS || MODE == MODE_TV || MODE == MODE_KLP);
     constexpr int NE = TWO_PHASE ? NV * VE : 1;   // exponentials kept per row and lane
-    constexpr int PW = (MODE == MODE_TV) ? 2 : 1;   // divergence words a member posts (two sums each)
+    constexpr int PW = (MODE == MODE_TV || MODE == MODE_KLP) ? 2 : 1;   // divergence words a member posts (two sums each)
     constexpr int FW = TWO_PHASE ? PW : 4;          // words per member the finisher reads
     // binary32 logits: the two-phase kernels hold 8 slots of each row per lane and one wavefront per
     // SIMD anyway, which leaves registers for a second set of logits
@@ -363,13 +363,15 @@ void pair_kernel(PairParams P) {
         } else {
             value = 0.5 * kLn2 * s.lo[0];
         }
+        bool log_domain = false;
+        if constexpr (MODE == MODE_KLP) log_domain = s.lo[1] > 0.0 && value < __builtin_inf();   // some term saturated
         int status = 0;
         if (value != value) status |= FSD_ROW_NONFINITE;   // NaN / +inf logits, or a row without mass
         if (!s.ok) status |= FSD_ROW_INTERNAL;
         if (value < 0.0) value = 0.0;
         if (status) value = __builtin_nan("");
         double lse2_t = 0.0, lse2_d = 0.0;
-        if (P.want_ratio) {
+        if (P.want_ratio || log_domain) {
             // reducible FSD also needs the rows' normalisers: the team's phase-1 words once more, this
             // time merged in float64 (they were all posted before the divergence words read above)
             const unsigned long long* p1 = part1 + static_cast<size_t>(pair) * GW * 4;
@@ -392,6 +394,15 @@ void pair_kernel(PairParams P) {
             if (!ok) status |= FSD_ROW_INTERNAL;
             lse2_t = static_cast<double>(Kt) + log2(Zt);
             lse2_d = static_cast<double>(Kd) + log2(Zd);
+            if constexpr (MODE == MODE_KLP) {
+                if (log_domain && !status) {
+                    // the saturated form is a lower bound; the log-domain value replaces it where it is
+                    // larger by more than its own rounding can explain
+                    const double dl = (lse2_t - lse2_d) * kLn2;
+                    const double v = s.hi[0] - dl;
+                    if (v == v && v - value > 4e-7 * (fabs(s.hi[0]) + fabs(dl))) value = v;
+                }
+            }
         }
         if (lane == 0) {
             if (P.want_ratio) status |= write_ratio(pair, lse2_t, lse2_d, status, P.user_ratio);
@@ -468,10 +479,10 @@ void pair_kernel(PairParams P) {
     };
 
     // ---- state of the previous pair, whose phase 2 is still to come (two-phase modes)
-    struct Pend { int pair; float kt, kd; bool mass_t, mass_d, mask; };
+    struct Pend { int pair; float kt, kd; bool mass_t, mass_d, mask; float wsum, dmax; };   // wsum, dmax: pointwise KL only
     Pend pend[LAG];   // [0] the last step's pair ... [LAG-1] the one whose phase 2 is due
 #pragma unroll
-    for (int i = 0; i < LAG; ++i) pend[i] = Pend{-1, 0.0f, 0.0f, false, false, false};
+    for (int i = 0; i < LAG; ++i) pend[i] = Pend{-1, 0.0f, 0.0f, false, false, false, 0.0f, 0.0f};
     // pairs this wavefront has to finish: fin[0] now, fin[i] i steps from now.  A two-phase pair
     // is finished NF steps after its phase 1.  Whoever starts step n has merged the team words of
     // step n - 1, so every member has ended step n - 2 - LAG and with it phase 2 of the pair of step
@@ -602,7 +613,20 @@ void pair_kernel(PairParams P) {
                 if (__any(pp.mask)) acc += __builtin_inff();   // draft masks an entry the target keeps; NaN stays NaN
             }
             if (!ok) acc = __builtin_nanf("");
-            word[0] = pack2(acc, 0.0f);
+            if constexpr (MODE == MODE_KLP) {
+                // Where q/p leaves binary32's range the terms above saturate.  Beside them goes this
+                // wavefront's share of sum p (a - b), from which the finisher can form the log-domain
+                // value sum p (a - b) - (lse_t - lse_d), and a mark that says it should look: an entry
+                // whose ln(p/q) = (a - b) - (lse_t - lse_d) passes 80 (or a draft side without any mass
+                // here).  log2 f = k - lse2 for both factors.  (The entry may carry no weight; the
+                // finisher compares the two values.)
+                const float dl = ((pp.kt - hw_log2(ft)) - (pp.kd - hw_log2(fd))) * static_cast<float>(kLn2);
+                const bool sat = (ft > 0.0f) && pp.dmax > neg_inf() && (fd == 0.0f || pp.dmax - dl > 80.0f);
+                word[0] = pack2(acc, pp.wsum * ft);
+                word[1] = pack2(sat ? 1.0f : 0.0f, 0.0f);
+            } else {
+                word[0] = pack2(acc, 0.0f);
+            }
         }
         if (!ok && lane == 0) atomicOr(P.ws.counters + 1, 1u);
         if (lane < PW) {
@@ -699,7 +723,14 @@ void pair_kernel(PairParams P) {
                 if constexpr (MODE == MODE_KL || MODE == MODE_KLP) {
                     const float diff = a[e] - c[e];
                     dmax = fmaxf(dmax, diff);   // +inf iff the draft masks an entry the target does not
-                    if constexpr (MODE == MODE_KL) wacc = fmaf(xa, fminf(fmaxf(diff, -FLT_MAX), FLT_MAX), wacc);
+                    if constexpr (MODE == MODE_KL) {
+                        wacc = fmaf(xa, fminf(fmaxf(diff, -FLT_MAX), FLT_MAX), wacc);
+                    } else {
+                        // only used where the pointwise terms saturate, and checked there: the median
+                        // instruction clamps in one operation (a NaN difference, -inf on both sides,
+                        // has the weight 0 either way)
+                        wacc = fmaf(xa, __builtin_amdgcn_fmed3f(diff, -FLT_MAX, FLT_MAX), wacc);
+                    }
                 }
             }
             if constexpr (TWO_PHASE) {
@@ -727,6 +758,7 @@ void pair_kernel(PairParams P) {
         unsigned long long mine;
         if constexpr (TWO_PHASE) {
             wave_sumf2(st, sd);
+            if constexpr (MODE == MODE_KLP) { wacc = wave_sumf(wacc); dmax = wave_max(dmax); }
             mine = (lane == 0) ? w0 : pack2(st, sd);
         } else {
             const double pst_ = wave_sum(static_cast<double>(st));
@@ -755,7 +787,7 @@ void pair_kernel(PairParams P) {
             asm volatile("" ::"v"(mine), "v"(post_at));
 #pragma unroll
             for (int i = LAG - 1; i > 0; --i) pend[i] = pend[i - 1];
-            pend[0] = Pend{pair, kt, kd, (st > 0.0f) || (st != st), (sd > 0.0f) || (sd != sd), dmax == __builtin_inff()};
+            pend[0] = Pend{pair, kt, kd, (st > 0.0f) || (st != st), (sd > 0.0f) || (sd != sd), dmax == __builtin_inff(), wacc, dmax};
         }
         // ---- finishing duties: the pair whose turn has come, then note this pair if it is ours
         if (fpair >= 0) finish(fpair, fw);

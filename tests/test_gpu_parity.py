@@ -173,8 +173,9 @@ def test_wide_dynamic_range_across_the_team(torch_cuda, oracle):
 def test_mass_in_opposite_halves(torch_cuda, oracle):
     """target and draft put their mass on different halves of the vocabulary, `gap` units apart: in
     every slice one side's normalising factor vanishes (or nearly) while the other's does not.  JS goes
-    to ln 2 and TV to 1.  KL is about `gap`: the bfloat16 path (one pass, log domain) follows it all
-    the way; the binary32 path forms p/q entry by entry and is exact while q/p stays a normal number."""
+    to ln 2 and TV to 1.  KL is about `gap`: the bfloat16 path takes it in the log domain (one pass); the
+    binary32 path forms p/q entry by entry, which saturates once q/p leaves binary32's range, and then
+    has to fall back on the log-domain sums it carries along."""
     rng = np.random.default_rng(34)
     B, K, V = 2, 3, 70000
     for gap in (40.0, 330.0):
@@ -190,11 +191,6 @@ def test_mass_in_opposite_halves(torch_cuda, oracle):
                 g = run_chain(torch_cuda, inp, 0.3, div, seed=2)
                 o = oracle.verify_chain(inp["target"], inp["draft"], inp["cand"], 0.3, div, seed=2)
                 assert (g["row_status"] == 0).all()
-                if div == fsd.DIV_KL and dtype == "f32" and gap > 80:
-                    # beyond binary32's range for q/p the entry-wise form saturates: large, finite, rejected
-                    assert (g["divergences"] > 60).all() and (g["divergences"] < o["divs"]).all()
-                    assert (g["accept_len"] == 0).all() and (o["accept_len"] == 0).all()
-                    continue
                 pu.check_chain(g, o, 0.3, pu.rel_tol(dtype), f"opposite halves gap={gap} {dtype} div={div}")
 
 
@@ -217,12 +213,6 @@ def test_exponentials_in_the_subnormal_range(torch_cuda, oracle):
             o = oracle.verify_chain(inp["target"], inp["draft"], inp["cand"], 0.3, div, seed=3)
             assert (g["row_status"] == 0).all() and np.isfinite(g["divergences"]).all()
             assert g["divergences"][1, 0] == 0
-            if div == fsd.DIV_KL and dtype == "f32":
-                # entries with q/p beyond binary32's range carry mass here: a lower bound (see
-                # test_mass_in_opposite_halves), same decisions
-                assert (g["divergences"] <= o["divs"] * (1 + 1e-5)).all() and (g["divergences"] >= 0.5 * o["divs"]).all()
-                assert (g["accept_len"] == o["accept_len"]).all() and (g["out_tokens"] == o["out_tokens"]).all()
-                continue
             pu.check_chain(g, o, 0.3, pu.rel_tol(dtype), f"subnormal range {dtype} div={div}")
 
 
