@@ -696,30 +696,77 @@ def run_sd_tree(torch, inp, max_depth, mode=fsd.SAMPLE, seed=0, offset=0):
     return pu.host(out, pu.TREESD_KEYS)
 
 
-def check_sd_tree(g, o, what):
+def _ratio_condition(inp, o, b, j):
+    """How strongly node j's log-ratio reacts to relative errors of the probabilities it is made of.
+    The first child of a context: ln p(x) - ln q(x), one unit each.  A later child is tested against
+    the residual chain r <- (r - q_m)+ / Z_m of the siblings rejected before it, and a difference
+    r - q_m that is small against r and q_m multiplies the errors they carry.  The kernels take the
+    rows' normalisers from binary32 exponentials (about 1e-7 relative), the oracle from float64."""
+    def row(a, idx):
+        z = a[b, idx]
+        z = synth.bf16_bits_to_f32(z) if z.dtype == np.uint16 else z
+        z = z.astype(np.float64)
+        e = np.exp(z - z.max())
+        return e / e.sum()
+    par, tok = inp["parent"][b], inp["node_tokens"][b]
+    x = int(tok[j])
+    p = row(inp["target"], par[j] + 1)
+    cond = 1.0
+    for m in range(j):
+        if par[m] != par[j] or np.isnan(o["log_ratio"][b, m]):
+            continue
+        # sibling m was tried before j and rejected (j would not have been tried otherwise)
+        q = row(inp["draft"], m)
+        if p[x] - q[x] <= 0:
+            return np.inf
+        cond = (p[x] * cond + q[x]) / (p[x] - q[x])
+        r = np.maximum(p - q, 0.0)
+        if r.sum() > 0:
+            p = r / r.sum()
+    return cond + 1.0
+
+
+def check_sd_tree(g, o, what, inp=None):
     """Paths and tokens are exact unless a test sits on its threshold (|margin| <= 1e-5 in the oracle)
     or the residual draw has a runner-up within 1e-4; log-ratios of the nodes that were tried agree to
-    5e-5 (those of later siblings carry the binary32 normalisers of the residual chain)."""
+    5e-5.  With the inputs at hand the bar follows the arithmetic instead: 5e-5 + 3e-7 times the
+    condition number of the node's log-ratio (a later sibling's can be large), for the values and
+    for what counts as sitting on the threshold."""
     assert (g["row_status"] == o["row_status"]).all(), what
     near = np.abs(np.nan_to_num(o["margin"], nan=1.0)) <= 1e-5
-    n_near = n_tie = 0
+    n_near = n_tie = n_cond = 0
     for b in range(o["path_len"].shape[0]):
         same = int(g["path_len"][b]) == int(o["path_len"][b]) and (g["path_nodes"][b] == o["path_nodes"][b]).all()
         if not same:
-            assert near[b].any(), f"{what}: tree {b} path gpu {g['path_nodes'][b]} oracle {o['path_nodes'][b]}"
+            ok = bool(near[b].any())
+            if not ok and inp is not None:
+                # the first node on which the two sides decided differently
+                for j in range(o["log_ratio"].shape[1]):
+                    tg_, to_ = not np.isnan(g["log_ratio"][b, j]), not np.isnan(o["log_ratio"][b, j])
+                    if tg_ and to_ and (j in g["path_nodes"][b]) != (j in o["path_nodes"][b]):
+                        ok = abs(o["margin"][b, j]) <= 1e-5 + 3e-7 * _ratio_condition(inp, o, b, j)
+                        break
+                    if tg_ != to_:
+                        break
+            assert ok, f"{what}: tree {b} path gpu {g['path_nodes'][b]} oracle {o['path_nodes'][b]}"
             n_near += 1
             continue
         tried = ~np.isnan(o["log_ratio"][b])
         assert (np.isnan(g["log_ratio"][b]) == ~tried).all(), f"{what}: tree {b} tried nodes differ"
         fin = np.isfinite(o["log_ratio"][b])
         assert (np.isfinite(g["log_ratio"][b]) == fin).all(), what
-        assert np.allclose(g["log_ratio"][b][fin], o["log_ratio"][b][fin], rtol=5e-5, atol=5e-5), \
-            f"{what}: tree {b} log_ratio gpu {g['log_ratio'][b][fin]} oracle {o['log_ratio'][b][fin]}"
+        for j in np.nonzero(fin)[0]:
+            gv, ov = float(g["log_ratio"][b, j]), float(o["log_ratio"][b, j])
+            tol = 5e-5 + 5e-5 * abs(ov)
+            if abs(gv - ov) > tol and inp is not None:
+                tol += 3e-7 * _ratio_condition(inp, o, b, int(j))
+                n_cond += 1
+            assert abs(gv - ov) <= tol, f"{what}: tree {b} node {j} log_ratio gpu {gv} oracle {ov} (allowed {tol:.2e})"
         if not (g["out_tokens"][b] == o["out_tokens"][b]).all():
             assert o["gap"][b] < 1e-4, f"{what}: tree {b} tokens gpu {g['out_tokens'][b]} oracle {o['out_tokens'][b]} gap {o['gap'][b]}"
             n_tie += 1
     assert n_near + n_tie <= max(2, o["path_len"].shape[0] // 20), what
-    return dict(near=n_near, ties=n_tie)
+    return dict(near=n_near, ties=n_tie, ill_conditioned=n_cond)
 
 
 def _random_tree_inputs(rng, B, N, V, dtype, star=False, noise=(0.2, 1.2)):
@@ -751,7 +798,7 @@ def test_sd_tree_small_random(torch_cuda, oracle):
             g = run_sd_tree(torch_cuda, inp, N, mode, seed=trial, offset=2)
             o = oracle.sd_verify_tree(inp["target"], inp["draft"], inp["node_tokens"], inp["parent"], N, mode,
                                       seed=trial, offset=2)
-            r = check_sd_tree(g, o, f"sd tree N={N} V={V} {dtype} mode={mode}")
+            r = check_sd_tree(g, o, f"sd tree N={N} V={V} {dtype} mode={mode}", inp)
             print("   ", r, "path_len", np.bincount(o["path_len"]), flush=True)
 
 
@@ -763,7 +810,7 @@ def test_sd_tree_star_many_rejections(torch_cuda, oracle):
         print(f"sd star N={N} V={V} {dtype}", flush=True)
         g = run_sd_tree(torch_cuda, inp, 1, seed=3, offset=1)
         o = oracle.sd_verify_tree(inp["target"], inp["draft"], inp["node_tokens"], inp["parent"], 1, seed=3, offset=1)
-        r = check_sd_tree(g, o, f"sd star N={N} V={V} {dtype}")
+        r = check_sd_tree(g, o, f"sd star N={N} V={V} {dtype}", inp)
         tried = (~np.isnan(o["log_ratio"])).sum(axis=1)
         print("   ", r, "nodes tried per tree", tried, flush=True)
         assert tried.max() >= 4          # the case is exercised
@@ -824,13 +871,17 @@ def test_sd_tree_bounded_wait_expires_cleanly(torch_cuda, oracle):
 
 
 def test_config_c4_strict_sd_tree(torch_cuda, oracle):
-    inp = synth.config_inputs("C4", seed=0)
-    md = int(inp["max_depth"])
-    g = run_sd_tree(torch_cuda, inp, md, seed=6, offset=2)
-    o = oracle.sd_verify_tree(inp["target"], inp["draft"], inp["node_tokens"], inp["parent"], md, seed=6, offset=2)
-    r = check_sd_tree(g, o, "C4 strict SD")
-    print("C4 strict SD", r, "path_len histogram", np.bincount(o["path_len"]),
-          "nodes tried", (~np.isnan(o["log_ratio"])).sum(axis=1), flush=True)
+    # the second set holds a later sibling whose token has nearly the same probability under the target
+    # and under the sibling rejected before it: its log-ratio is ill-conditioned (see check_sd_tree)
+    for inputs_seed, seed, offset in ((0, 6, 2), (400, 400, 3)):
+        inp = synth.config_inputs("C4", seed=inputs_seed)
+        md = int(inp["max_depth"])
+        g = run_sd_tree(torch_cuda, inp, md, seed=seed, offset=offset)
+        o = oracle.sd_verify_tree(inp["target"], inp["draft"], inp["node_tokens"], inp["parent"], md, seed=seed,
+                                  offset=offset)
+        r = check_sd_tree(g, o, f"C4 strict SD inputs {inputs_seed}", inp)
+        print("C4 strict SD", r, "path_len histogram", np.bincount(o["path_len"]),
+              "nodes tried", (~np.isnan(o["log_ratio"])).sum(axis=1), flush=True)
 
 
 # ------------------------------------------------------------------------------- robustness
