@@ -313,7 +313,12 @@ void pair_kernel(PairParams P) {
         if (fill_needed) {
 #pragma unroll
             for (int k = 0; k < NV; ++k) {
-                if (sl0 + 64 * k >= sl_end) { ra[k] = slot_neg_inf<BF16>(); rb[k] = slot_neg_inf<BF16>(); }
+                // first the question that has one answer for the whole wavefront (does slot k reach past
+                // the slice at all?): a scalar branch skips the full slots, and only the one or two at the
+                // end of the slice go through the per-lane selection
+                if (s0 + 64 * (k + 1) > s1) {
+                    if (sl0 + 64 * k >= sl_end) { ra[k] = slot_neg_inf<BF16>(); rb[k] = slot_neg_inf<BF16>(); }
+                }
             }
         }
     };
