@@ -931,6 +931,41 @@ def test_sd_tree_bounded_wait_expires_cleanly(torch_cuda, oracle):
     check_sd_tree(g, o, "after restoring the poll budget")
 
 
+def test_random_small_shapes_warped_and_tree_sd(torch_cuda, oracle):
+    """150 random draws: the chain call with a random set of warpers, and strict SD over a random tree
+    (or star), each against the oracle."""
+    rng = np.random.default_rng(777)
+    for it in range(150):
+        B, K = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        V = int(rng.choice([rng.integers(2, 40), rng.integers(40, 3000), rng.integers(3000, 140000),
+                            8 * rng.integers(1, 16000)]))
+        dtype = str(rng.choice(["f32", "bf16"]))
+        kind = str(rng.choice(["gauss2", "peaked", "zipf"]))
+        seed = int(rng.integers(0, 10**6))
+        inp = synth.chain_inputs(B, K, V, dtype, kind, 1.0, seed=seed)
+        kw = {}
+        if rng.random() < 0.6:
+            kw["temperature"] = float(rng.choice([0.3, 0.7, 1.0, 1.5]))
+        if rng.random() < 0.6:
+            kw["top_k"] = int(rng.choice([1, 2, 10, 50, 500, 5000, 200000]))
+        if rng.random() < 0.6:
+            kw["top_p"] = float(rng.choice([0.1, 0.5, 0.9, 0.99, 1.0]))
+        what = f"it={it} B={B} K={K} V={V} {dtype} {kind} seed={seed} {kw}"
+        print(what, flush=True)
+        g = run_warped(torch_cuda, inp, 0.1, fsd.DIV_JS, fsd.SAMPLE, seed, it, **kw)
+        o = oracle.verify_chain_warped(inp["target"], inp["draft"], inp["cand"], 0.1, fsd.DIV_JS, fsd.SAMPLE, seed, it,
+                                       **kw)
+        active = 0 < kw.get("top_k", 0) < V or kw.get("top_p", 1.0) < 1.0
+        check_warped(_inside_envelope(g, o, dtype, what), o, 0.1, pu.rel_tol(dtype), what, cut_active=active)
+        N = int(rng.integers(1, 30))
+        Vt = int(rng.choice([rng.integers(2, 60), rng.integers(60, 5000), rng.integers(5000, 60000)]))
+        tin = _random_tree_inputs(rng, B, N, Vt, dtype, star=bool(rng.random() < 0.3), noise=(0.3, 2.5))
+        g = run_sd_tree(torch_cuda, tin, N, seed=seed, offset=it)
+        o = oracle.sd_verify_tree(tin["target"], tin["draft"], tin["node_tokens"], tin["parent"], N, seed=seed,
+                                  offset=it)
+        check_sd_tree(g, o, f"sd tree it={it} N={N} V={Vt} {dtype}", tin)
+
+
 def test_config_c4_strict_sd_tree(torch_cuda, oracle):
     # the second set holds a later sibling whose token has nearly the same probability under the target
     # and under the sibling rejected before it: its log-ratio is ill-conditioned (see check_sd_tree)
