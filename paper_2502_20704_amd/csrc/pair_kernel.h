@@ -363,8 +363,10 @@ void pair_kernel(PairParams P) {
             // the sums of (p - q)+ and of (q - p)+ are the same number; the side that avoids the
             // heavy entries (smaller sum of p + q over its entries) carries the smaller rounding
             // error, which matters for nearly one-hot rows
-            const double A = s.lo[0], Bn = s.hi[0], MA = s.lo[1], MB = s.hi[1];
-            value = (MA != MA || MB != MB) ? __builtin_nan("") : (MA <= MB ? A : Bn);
+            // (the two rows' masses add up to 2, so the side of (p - q)+ is the lighter one when the
+            // p + q it covers is at most 1)
+            const double A = s.lo[0], Bn = s.hi[0], MA = s.lo[1];
+            value = (MA != MA) ? __builtin_nan("") : (MA <= 1.0 ? A : Bn);
         } else {
             value = 0.5 * kLn2 * s.lo[0];
         }
@@ -548,7 +550,7 @@ void pair_kernel(PairParams P) {
         const float cq = (ftc == fdc) ? 1.0f : fdc * __builtin_amdgcn_rcpf(ftc);
         unsigned long long word[PW];
         if constexpr (MODE == MODE_TV) {
-            float A = 0.0f, Bn = 0.0f, MA = 0.0f, MB = 0.0f;
+            float A = 0.0f, Bn = 0.0f, MA = 0.0f;
 #pragma unroll
             for (int c = 0; c < NC; ++c) {
                 float t4[4], d4[4];
@@ -559,18 +561,17 @@ void pair_kernel(PairParams P) {
                     const float d = p - q, sum = p + q;
                     A += fmaxf(d, 0.0f);
                     Bn += fmaxf(-d, 0.0f);
-                    MA += (d > 0.0f) ? sum : 0.0f;
-                    MB += (d < 0.0f) ? sum : 0.0f;
+                    MA += (d > 0.0f) ? sum : 0.0f;   // the other side's mass is what is left of 2
                 }
             }
             // max() drops NaN: an unusable row (NaN factor) is made to reach the side selection
             wave_sumf2(A, Bn);
-            wave_sumf2(MA, MB);
-            A *= ftc; Bn *= ftc; MA *= ftc; MB *= ftc;
-            if (ft != ft || fd != fd) { A = ft + fd; Bn = A; MA = A; MB = A; }
+            MA = wave_sumf(MA);
+            A *= ftc; Bn *= ftc; MA *= ftc;
+            if (ft != ft || fd != fd) { A = ft + fd; Bn = A; MA = A; }
             if (!ok) { A = __builtin_nanf(""); MA = A; }
             word[0] = pack2(A, Bn);
-            word[1] = pack2(MA, MB);
+            word[1] = pack2(MA, 0.0f);
         } else {
             float acc = 0.0f;
 #pragma unroll
