@@ -99,7 +99,11 @@ const char* fsd_status_string(int status);
  *   accept_len    [B]   out    n_b = number of leading accepted positions
  *   out_tokens    [B, K+1] out cand[b, :n_b], then the token drawn from
  *                              softmax(target[b, n_b]), then -1 padding
- *   divergences   [B, K] out   optional (NULL to skip), the chosen divergence
+ *   divergences   [B, K] out   optional (NULL to skip), the chosen divergence:
+ *                              evaluated in binary32, within 1e-5 (binary32
+ *                              logits) or 2e-3 (bfloat16) relative of the
+ *                              exact value, or 2.5e-7 absolute where that is
+ *                              the larger (nearly equal rows)
  *   row_status    [B]   out    optional (NULL to skip), see FSD_ROW_*
  *
  * A call only enqueues kernels on hip_stream (the workspace is cleared by a
