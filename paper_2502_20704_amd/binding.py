@@ -33,6 +33,11 @@ def library() -> ctypes.CDLL:
             raise FileNotFoundError(
                 f"{LIB_PATH} is missing: build it with `python -m paper_2502_20704_amd.build` "
                 "(there is no CPU fallback)")
+        # torch first: the library then binds to the HIP runtime torch has loaded.  Loaded before torch
+        # it would bring in the system's copy, and a process with two HIP runtimes has its device
+        # memory in one and this library's launches in the other.
+        import torch  # noqa: F401
+
         L = ctypes.CDLL(LIB_PATH)
         c = ctypes
         vp, i32, u64, f32, sz = c.c_void_p, c.c_int, c.c_uint64, c.c_float, c.c_size_t

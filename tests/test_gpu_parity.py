@@ -687,6 +687,27 @@ def test_tree_bad_parent_and_depth(torch_cuda, oracle):
     assert (g["path_len"] == 0).all() and (g["out_tokens"] == -1).all() and (g["path_nodes"] == -1).all()
 
 
+def test_reduction_kernel_shapes_agree(torch_cuda, oracle):
+    """the tuning hook: every shape of the reduction kernel gives the same decisions and tokens, and
+    divergences that differ only by the rounding order of the partial sums"""
+    try:
+        for dtype, shapes in (("bf16", (2, 4, 5)), ("f32", (2, 4, 8))):
+            inp = synth.chain_inputs(3, 4, 40000, dtype, "peaked", 1.0, seed=91)
+            for div in (fsd.DIV_KL, fsd.DIV_JS, fsd.DIV_TV):
+                fsd.debug_set_shape(0, 0)
+                ref = run_chain(torch_cuda, inp, 0.1, div, seed=9, offset=1)
+                o = oracle.verify_chain(inp["target"], inp["draft"], inp["cand"], 0.1, div, seed=9, offset=1)
+                pu.check_chain(ref, o, 0.1, pu.rel_tol(dtype), f"default shape {dtype} div={div}")
+                for nv in shapes:
+                    fsd.debug_set_shape(0, nv)
+                    g = run_chain(torch_cuda, inp, 0.1, div, seed=9, offset=1)
+                    what = f"{dtype} div={div} slots per lane {nv}"
+                    assert (g["accept_len"] == ref["accept_len"]).all() and (g["out_tokens"] == ref["out_tokens"]).all(), what
+                    assert np.allclose(g["divergences"], ref["divergences"], rtol=2e-6, atol=1e-7), what
+    finally:
+        fsd.debug_set_shape(0, 0)
+
+
 # ------------------------------------------------------------------ random shapes
 
 def _inside_envelope(g, o, dtype, what):
