@@ -51,7 +51,8 @@ typedef enum {
     FSD_ERR_DIV = -4,       /* div is not an fsd_div */
     FSD_ERR_WORKSPACE = -5, /* workspace NULL, misaligned or too small */
     FSD_ERR_MODE = -6,      /* mode is not an fsd_mode */
-    FSD_ERR_LAUNCH = -7     /* the HIP runtime refused a launch */
+    FSD_ERR_LAUNCH = -7,    /* the HIP runtime refused a launch */
+    FSD_ERR_TOO_LARGE = -8  /* fsd_verify_chain_static: sizes beyond its fixed scratch buffer */
 } fsd_status;
 
 typedef enum { FSD_F32 = 0, FSD_BF16 = 1 } fsd_dtype;
@@ -114,6 +115,28 @@ int fsd_verify_chain(const void* target_logits, const void* draft_logits, const 
                      int B, int K, int V, int dtype, int div, float T, int mode, uint64_t seed,
                      uint64_t offset, int32_t* accept_len, int32_t* out_tokens, float* divergences,
                      int32_t* row_status, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * fsd_verify_chain for callers that cannot allocate device memory or pass a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same inputs, outputs, kernels and results as
+ * fsd_verify_chain; the workspace is a buffer of FSD_STATIC_SCRATCH_BYTES bytes
+ * that is part of the loaded library (one copy per GPU, held until the process
+ * ends).  The call allocates and frees nothing.
+ *
+ *   - Sizes whose fsd_workspace_bytes(B, K, V, dtype) exceeds
+ *     FSD_STATIC_SCRATCH_BYTES are refused with FSD_ERR_TOO_LARGE before
+ *     anything is launched (B=64, K=8, V=128256 bfloat16 needs 2.1 MiB).
+ *   - Every call on a GPU uses that GPU's one buffer, which keeps the last
+ *     call's contents; the call clears what it needs cleared itself.  Calls that
+ *     overlap in time on one GPU (different streams, or threads) race on it:
+ *     keep them on one stream or serialise them.
+ */
+#define FSD_STATIC_SCRATCH_BYTES (4u << 20)
+int fsd_verify_chain_static(const void* target_logits, const void* draft_logits, const int32_t* cand_tokens,
+                            int B, int K, int V, int dtype, int div, float T, int mode, uint64_t seed,
+                            uint64_t offset, int32_t* accept_len, int32_t* out_tokens, float* divergences,
+                            int32_t* row_status, void* hip_stream);
 
 /*
  * FSD verification of a token tree (paper Sec. 6.4: FSD on top of a

@@ -50,6 +50,9 @@ def library() -> ctypes.CDLL:
         L.fsd_verify_chain.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, f32, i32, u64, u64,
                                        vp, vp, vp, vp, vp, sz, vp]
         L.fsd_verify_chain.restype = i32
+        L.fsd_verify_chain_static.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, f32, i32, u64, u64,
+                                              vp, vp, vp, vp, vp]
+        L.fsd_verify_chain_static.restype = i32
         L.fsd_verify_chain_warped.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, f32, i32, u64, u64, f32, i32, f32,
                                               vp, vp, vp, vp, vp, sz, vp]
         L.fsd_verify_chain_warped.restype = i32
@@ -157,6 +160,28 @@ def fsd_verify_chain(target, draft, cand, T, div=DIV_JS, mode=SAMPLE, seed=0, of
     if st != 0:
         raise FsdError(st, "fsd_verify_chain")
     out["_workspace"] = workspace
+    return out
+
+
+STATIC_SCRATCH_BYTES = 4 << 20
+
+
+def fsd_verify_chain_static(target, draft, cand, T, div=DIV_JS, mode=SAMPLE, seed=0, offset=0, *, out, stream=None):
+    """fsd_verify_chain on the library's own fixed scratch buffer: nothing is allocated, so the caller
+    passes the output tensors (`out`: accept_len, out_tokens and optionally divergences, row_status)."""
+    import torch
+
+    B, K1, V = target.shape
+    K = K1 - 1
+    dt = _dtype_code(target)
+    _check(target, "target")
+    _check(draft, "draft", (B, K, V), target.dtype)
+    _check(cand, "cand", (B, K), torch.int32)
+    st = library().fsd_verify_chain_static(_ptr(target), _ptr(draft), _ptr(cand), B, K, V, dt, div, float(T), mode,
+                                           seed, offset, _ptr(out["accept_len"]), _ptr(out["out_tokens"]),
+                                           _ptr(out.get("divergences")), _ptr(out.get("row_status")), _stream(stream))
+    if st != 0:
+        raise FsdError(st, "fsd_verify_chain_static")
     return out
 
 

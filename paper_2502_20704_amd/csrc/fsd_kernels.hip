@@ -23,6 +23,8 @@
 #include <float.h>
 #include <math.h>
 
+#include <atomic>
+
 #include "fsd.h"
 
 #include "device_common.h"
@@ -31,6 +33,12 @@
 #include "tree_sd_walk.h"
 #include "warp_select.h"
 #include "calibrate.h"
+
+// Workspace of fsd_verify_chain_static, the entry point for callers that cannot allocate: device
+// memory that exists from the moment the library is loaded until the process ends, one copy per
+// GPU.  Host code never uses this name as an address (on the host it is only a stand-in for the
+// symbol): static_scratch() asks the runtime for the array's device address once per device.
+static __device__ __align__(256) unsigned char scratch[FSD_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -274,12 +282,30 @@ bool is_aligned(const void* a, const void* b, long V, int VE) {
            (b == nullptr || reinterpret_cast<uintptr_t>(b) % 16 == 0);
 }
 
-// the common body of the three entry points
+// Device address of the static scratch array on the current device (nullptr if the runtime will not
+// give it).  Every GPU holds its own copy of the array at its own address, so the address is looked
+// up once per device, with that device current, and kept.
+void* static_scratch() {
+    static std::atomic<void*> ptr[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    void* p = ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        ptr[dev].store(p, std::memory_order_release);
+    }
+    return p;
+}
+
+// the common body of the entry points
 int run(int kind, const void* target, const void* draft, const int32_t* tokens, const int32_t* parent, int B,
         int rows, int max_depth, int V, int dtype, int div, float T, int mode, uint64_t seed, uint64_t offset,
         int32_t* out_len, int32_t* path_nodes, int32_t* out_tokens, float* user_vals, float* user_ratio,
         int32_t* row_status, void* workspace, size_t workspace_bytes, void* hip_stream,
-        float temperature = 1.0f, int top_k = 0, float top_p = 1.0f) {
+        float temperature = 1.0f, int top_k = 0, float top_p = 1.0f, bool static_ws = false) {
     if (!target || !draft || !tokens || !out_len || !out_tokens) return FSD_ERR_NULL;
     const bool tree = (kind == KIND_TREE || kind == KIND_TREESD);
     if (tree && (!parent || !path_nodes)) return FSD_ERR_NULL;
@@ -291,8 +317,14 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
     if (!(temperature >= 1e-3f && temperature <= 1e3f) || top_k < 0 || !(top_p > 0.0f && top_p <= 1.0f)) return FSD_ERR_SHAPE;
     Plan p;
     if (!make_plan(B, rows, V, dtype, p)) return FSD_ERR_SHAPE;
-    if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 != 0 || workspace_bytes < p.bytes)
+    if (static_ws) {
+        // the library's own buffer instead of the caller's
+        if (p.bytes > static_cast<size_t>(FSD_STATIC_SCRATCH_BYTES)) return FSD_ERR_TOO_LARGE;
+        workspace = static_scratch();
+        if (!workspace) return FSD_ERR_LAUNCH;
+    } else if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 != 0 || workspace_bytes < p.bytes) {
         return FSD_ERR_WORKSPACE;
+    }
 
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const Ws ws = carve(workspace, p, B, rows);
@@ -482,6 +514,7 @@ const char* fsd_status_string(int status) {
         case FSD_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case FSD_ERR_MODE: return "unknown sampling mode";
         case FSD_ERR_LAUNCH: return "kernel launch failed";
+        case FSD_ERR_TOO_LARGE: return "sizes need more scratch memory than the static buffer holds (FSD_STATIC_SCRATCH_BYTES)";
         default: return "unknown status";
     }
 }
@@ -550,6 +583,15 @@ int rfsd_verify_chain(const void* target_logits, const void* draft_logits, const
     return run(KIND_RFSD, target_logits, draft_logits, cand_tokens, nullptr, B, K, 0, V, dtype, div, T, mode, seed,
                offset, accept_len, nullptr, out_tokens, divergences, log_ratio, row_status, workspace,
                workspace_bytes, hip_stream);
+}
+
+int fsd_verify_chain_static(const void* target_logits, const void* draft_logits, const int32_t* cand_tokens, int B,
+                            int K, int V, int dtype, int div, float T, int mode, uint64_t seed, uint64_t offset,
+                            int32_t* accept_len, int32_t* out_tokens, float* divergences, int32_t* row_status,
+                            void* hip_stream) {
+    return run(KIND_CHAIN, target_logits, draft_logits, cand_tokens, nullptr, B, K, 0, V, dtype, div, T, mode, seed,
+               offset, accept_len, nullptr, out_tokens, divergences, nullptr, row_status, nullptr, 0, hip_stream,
+               1.0f, 0, 1.0f, true);
 }
 
 int fsd_profile_enable(int on) {
