@@ -309,8 +309,9 @@ __device__ __forceinline__ float gumbel(unsigned w) {
 struct Ws {
     unsigned* counters;  // 64 words ([1]: a bounded wait expired), then sdone
     unsigned* sdone;     // [B][kSdoneStride], first word: sampler workgroups that posted
-    unsigned long long* part1;  // [R][G][4]: (kt,kd) | St | Sd | W
-    double* part2;       // [R][G][4] divergence words (one used, four for TV)
+    unsigned long long* part1;  // [R][G][n1] phase-1 words, dense: (kt,kd) | (St,Sd) in the two-phase modes (n1 = 2),
+                                // (kt,kd) | St | Sd | W in the single-pass ones (n1 = 4)
+    double* part2;       // [R][G][n2] divergence words of the two-phase modes (n2 = 1, or 2 for TV and pointwise KL)
     float* div;          // [R]
     int* pst;            // [R] status bits per pair
     double* lse2;        // [R][2] log2-sum-exp2 of the target / draft row of the pair

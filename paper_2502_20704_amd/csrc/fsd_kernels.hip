@@ -48,7 +48,7 @@ namespace {
 struct Plan {
     int VE, NV, G, spm, GS, sps;   // G = wavefronts per pair
     long nslots;
-    size_t off_counters, n_counters, off_part1, off_part2, off_wz, zero_bytes, off_div, off_pst, off_lse2, off_lr, off_spart,
+    size_t off_counters, n_counters, off_wz, off_part1, zero_bytes, off_div, off_pst, off_lse2, off_lr, off_spart,
         off_thr, off_tsd, off_tsdz, bytes;
 };
 
@@ -88,9 +88,10 @@ bool make_plan(int B, int rows, long V, int dtype, Plan& p) {
     const size_t R = static_cast<size_t>(B) * rows;
     size_t o = 0;
     p.off_counters = o; p.n_counters = 64 + static_cast<size_t>(B) * kSdoneStride; o = align_up(o + p.n_counters * 4, 256);
-    p.off_part1 = o; o = align_up(o + R * p.G * 32, 256);
-    p.off_part2 = o; o = align_up(o + R * p.G * 32, 256);
     p.off_wz = o; o = align_up(o + R * kWalkShare * 8, 256);
+    // the two exchange arrays, sized for the mode that posts most (4 words per member in each); a call
+    // lays them out densely for its own mode (see carve) and clears only that much
+    p.off_part1 = o; o = align_up(o + R * p.G * 32, 256) + align_up(R * p.G * 32, 256);
     p.zero_bytes = o;
     p.off_div = o; o = align_up(o + R * 4, 256);
     p.off_pst = o; o = align_up(o + R * 4, 256);
@@ -104,14 +105,18 @@ bool make_plan(int B, int rows, long V, int dtype, Plan& p) {
     return true;
 }
 
-Ws carve(void* workspace, const Plan& p, int B, int rows) {
+// G, n1, n2: wavefronts per pair and exchange words per member of this call's reduction kernel (never
+// more than the plan allowed for); zero_bytes: how much of the workspace's head the call has to clear
+Ws carve(void* workspace, const Plan& p, int B, int rows, int G, int n1, int n2, size_t& zero_bytes) {
     char* base = static_cast<char*>(workspace);
     const size_t R = static_cast<size_t>(B) * rows;
     Ws w;
     w.counters = reinterpret_cast<unsigned*>(base + p.off_counters);
     w.sdone = w.counters + 64;
     w.part1 = reinterpret_cast<unsigned long long*>(base + p.off_part1);
-    w.part2 = reinterpret_cast<double*>(base + p.off_part2);
+    const size_t off_part2 = align_up(p.off_part1 + R * G * n1 * 8, 256);
+    w.part2 = reinterpret_cast<double*>(base + off_part2);
+    zero_bytes = align_up(off_part2 + R * G * n2 * 8, 256);
     w.div = reinterpret_cast<float*>(base + p.off_div);
     w.pst = reinterpret_cast<int*>(base + p.off_pst);
     w.lse2 = reinterpret_cast<double*>(base + p.off_lse2);
@@ -327,11 +332,28 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
     }
 
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const Ws ws = carve(workspace, p, B, rows);
     const bool aligned = is_aligned(target, draft, V, p.VE);
     const int R = B * rows;
 
-    const long n16 = static_cast<long>(p.zero_bytes / 16);
+    // which reduction kernel, and its shape
+    int k1mode = (kind == KIND_SD || kind == KIND_TREESD) ? MODE_LSE : div;
+    if (k1mode == MODE_KL && dtype == FSD_F32) k1mode = MODE_KLP;
+    if (dtype == FSD_BF16 && !g_shape_nv && (k1mode == MODE_JS || k1mode == MODE_TV)) {
+        // The bfloat16 two-phase kernels are bound by instruction issue, a third of it per step and not
+        // per entry: 5 slots per lane instead of 4 is the most that fits two wavefronts per SIMD (256
+        // registers).  The workspace is laid out for the larger team of the 4-slot shape.
+        p.NV = 5;
+        p.G = static_cast<int>(team_size(p.nslots, 5));
+        p.spm = static_cast<int>((p.nslots + p.G - 1) / p.G);
+    }
+    // exchange words a member posts in this mode: only those are laid out and cleared
+    const bool two_phase = (k1mode == MODE_JS || k1mode == MODE_TV || k1mode == MODE_KLP);
+    const int n1 = two_phase ? 2 : 4;
+    const int n2 = (k1mode == MODE_TV || k1mode == MODE_KLP) ? 2 : two_phase ? 1 : 0;
+    size_t zero_bytes = 0;
+    const Ws ws = carve(workspace, p, B, rows, p.G, n1, n2, zero_bytes);
+
+    const long n16 = static_cast<long>(zero_bytes / 16);
     hipLaunchKernelGGL(zero_counters, dim3(static_cast<unsigned>((n16 + 255) / 256)), dim3(256), 0, st,
                        reinterpret_cast<uint4*>(ws.counters), n16);
 
@@ -354,18 +376,6 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
     pp.user_ratio = user_ratio;
     pp.want_ratio = (kind == KIND_RFSD) ? 1 : 0;
     pp.ws = ws;
-    int k1mode = (kind == KIND_SD || kind == KIND_TREESD) ? MODE_LSE : div;
-    if (k1mode == MODE_KL && dtype == FSD_F32) k1mode = MODE_KLP;
-    if (dtype == FSD_BF16 && !g_shape_nv && (k1mode == MODE_JS || k1mode == MODE_TV)) {
-        // The bfloat16 two-phase kernels are bound by instruction issue, a third of it per step and not
-        // per entry: 5 slots per lane instead of 4 is the most that fits two wavefronts per SIMD (256
-        // registers).  The workspace is laid out for the larger team of the 4-slot shape.
-        p.NV = 5;
-        p.G = static_cast<int>(team_size(p.nslots, 5));
-        p.spm = static_cast<int>((p.nslots + p.G - 1) / p.G);
-        pp.spm = p.spm;
-        pp.G = p.G;
-    }
     launch_pair(dtype, p.NV, k1mode, aligned, st, pp);
 
     SampleParams sp;

@@ -73,7 +73,7 @@ __device__ __forceinline__ unsigned long long pack2(float lo, float hi) {
 __device__ __forceinline__ float lo_f(unsigned long long w) { return __uint_as_float(static_cast<unsigned>(w)); }
 __device__ __forceinline__ float hi_f(unsigned long long w) { return __uint_as_float(static_cast<unsigned>(w >> 32)); }
 
-// A pair owns 4 GW words of an exchange array, of which a mode uses N per member: word k of member
+// A pair owns N GW words of an exchange array, N per member (what the mode uses): word k of member
 // m sits at [m N + k], so that a member's post is one contiguous store and the 64 lanes of a
 // request touch consecutive words.  Lane l reads the N words of member (base + l); lanes beyond
 // the team re-read the last member's (no branch around the loads, see load_item).  Nothing looks at the values here, so the loads stay in flight until they are
@@ -131,10 +131,9 @@ struct TeamNorm { float Kt, Kd, zt, zd; bool ok; };
 
 // one member's sums moved to the references (0 for a lane beyond the team; NaN stays NaN)
 __device__ __forceinline__ void member_terms(const unsigned long long (&w)[2], bool in, const TeamNorm& n, float& at, float& ad) {
-    const float tk_t = lo_f(w[0]), tk_d = hi_f(w[0]);
-    const float tSt = in ? lo_f(w[1]) : 0.0f, tSd = in ? hi_f(w[1]) : 0.0f;
-    at = (tSt > 0.0f) ? ldexpf(tSt, kdiff(tk_t, n.Kt)) : (tSt != tSt ? tSt : 0.0f);
-    ad = (tSd > 0.0f) ? ldexpf(tSd, kdiff(tk_d, n.Kd)) : (tSd != tSd ? tSd : 0.0f);
+    // (a zero stays zero and a NaN stays NaN under the scaling: no case distinction is needed)
+    at = ldexpf(in ? lo_f(w[1]) : 0.0f, kdiff(lo_f(w[0]), n.Kt));
+    ad = ldexpf(in ? hi_f(w[1]) : 0.0f, kdiff(hi_f(w[0]), n.Kd));
 }
 __device__ __forceinline__ void merge_round(const unsigned long long (&w)[2], bool in, TeamNorm& n) {
     float at, ad;
@@ -190,6 +189,8 @@ void pair_kernel(PairParams P) {
     constexpr int NE = TWO_PHASE ? NV * VE : 1;   // exponentials kept per row and lane
     constexpr int PW = (MODE == MODE_TV || MODE == MODE_KLP) ? 2 : 1;   // divergence words a member posts (two sums each)
     constexpr int FW = TWO_PHASE ? PW : 4;          // words per member the finisher reads
+    constexpr int N1 = TWO_PHASE ? 2 : 4;           // phase-1 words a member posts; both exchange arrays are
+                                                    // dense, [pair][member][word]: only what a mode uses is cleared
     // binary32 logits: the two-phase kernels hold 8 slots of each row per lane and one wavefront per
     // SIMD anyway, which leaves registers for a second set of logits
     constexpr bool DEEP = !BF16 && TWO_PHASE && NV == 8;
@@ -254,9 +255,8 @@ void pair_kernel(PairParams P) {
     unsigned long long pt_last = pt_first;
 #endif
 
-    auto row_ptrs = [&](int pair, const char*& tptr, const char*& dptr) __attribute__((always_inline)) {
-        const int b = pair / P.rows;
-        const int j = pair - b * P.rows;
+    // the rows of pair (sequence b, position or node j)
+    auto row_ptrs_bj = [&](int pair, int b, int j, const char*& tptr, const char*& dptr) __attribute__((always_inline)) {
         int trow = j;
         if (P.parent) {
             const int par = P.parent[pair];
@@ -265,6 +265,14 @@ void pair_kernel(PairParams P) {
         tptr = P.target + (static_cast<size_t>(b) * (P.rows + 1) + trow) * static_cast<size_t>(P.V) * ES;
         dptr = P.draft + static_cast<size_t>(pair) * static_cast<size_t>(P.V) * ES;
     };
+    auto row_ptrs = [&](int pair, const char*& tptr, const char*& dptr) __attribute__((always_inline)) {
+        const int b = pair / P.rows;
+        row_ptrs_bj(pair, b, pair - b * P.rows, tptr, dptr);
+    };
+    // (sequence, row) of the pair whose logits are requested next: the pairs of a team are an arithmetic
+    // sequence, so these advance by a fixed amount and no step pays for a division
+    const int step_b = pstep / P.rows, step_j = pstep - step_b * P.rows;
+    int load_pair = pair0, load_b = pair0 / P.rows, load_j = pair0 - load_b * P.rows;
     // ---- the only HBM reads of the reduction: NV slots of each row per lane
     // Every lane always loads (a lane without a slot of its own re-reads a valid one and the value is
     // replaced by -inf afterwards): loads that sit inside branches would make the compiler wait for
@@ -277,7 +285,14 @@ void pair_kernel(PairParams P) {
     const bool fill_needed = s0 + NV * 64 > s1;   // wavefront-uniform: some lane lacks a slot
     auto load_item = [&](uint4 (&ra)[NV], uint4 (&rb)[NV], int pair, bool wanted = true) __attribute__((always_inline)) {
         const char *tptr, *dptr;
-        row_ptrs(pair, tptr, dptr);
+        // the requests come in the order of the team's pairs (the last one may be repeated)
+        while (load_pair < pair) {
+            load_pair += pstep;
+            load_j += step_j;
+            load_b += step_b;
+            if (load_j >= P.rows) { load_j -= P.rows; ++load_b; }
+        }
+        row_ptrs_bj(pair, load_b, load_j, tptr, dptr);
         // A draft row is read once.  So is a target row of a chain (but for the one the token is drawn
         // from); in a tree the children of a node share their parent's target row, which should stay
         // cached.
@@ -346,7 +361,7 @@ void pair_kernel(PairParams P) {
     // ---- finishing a pair: add what the team posted for it, in member order.  fw holds the words of
     // the first 64 members, requested earlier.
     auto finish_two_phase = [&](int pair, unsigned long long (&fw)[FW]) __attribute__((always_inline)) {
-        const unsigned long long* p2 = part2 + static_cast<size_t>(pair) * GW * 4;
+        const unsigned long long* p2 = part2 + static_cast<size_t>(pair) * GW * PW;
         unsigned long long f[PW];
 #pragma unroll
         for (int k = 0; k < PW; ++k) f[k] = fw[k % FW];
@@ -381,7 +396,7 @@ void pair_kernel(PairParams P) {
         if (P.want_ratio || log_domain) {
             // reducible FSD also needs the rows' normalisers: the team's phase-1 words once more, this
             // time merged in float64 (they were all posted before the divergence words read above)
-            const unsigned long long* p1 = part1 + static_cast<size_t>(pair) * GW * 4;
+            const unsigned long long* p1 = part1 + static_cast<size_t>(pair) * GW * N1;
             float Kt = neg_inf(), Kd = neg_inf();
             double Zt = 0.0, Zd = 0.0;
             bool ok = true;
@@ -421,7 +436,7 @@ void pair_kernel(PairParams P) {
         }
     };
     auto finish_single_pass = [&](int pair, unsigned long long (&fw)[FW]) __attribute__((always_inline)) {
-        const unsigned long long* p1 = part1 + static_cast<size_t>(pair) * GW * 4;
+        const unsigned long long* p1 = part1 + static_cast<size_t>(pair) * GW * N1;
         // online merge over rounds of 64 members, float64, exact rescaling between references
         float Kt = neg_inf(), Kd = neg_inf();
         double Zt = 0.0, Zd = 0.0, Wt = 0.0;
@@ -503,7 +518,7 @@ void pair_kernel(PairParams P) {
     // the previous pair's row-wide normalisers from the team's words (w holds the first 64 members'):
     // factors ft, fd with p = e_t ft, q = e_d fd
     auto merge_team = [&](const Pend& pp, unsigned long long (&w)[2], unsigned long long (&w2)[2], float& ft, float& fd) __attribute__((always_inline)) -> bool {
-        const unsigned long long* p1 = part1 + static_cast<size_t>(pp.pair) * GW * 4;
+        const unsigned long long* p1 = part1 + static_cast<size_t>(pp.pair) * GW * N1;
         // binary32 is enough: the normalisers enter p and q as common factors
         TeamNorm n{pp.kt, pp.kd, 0.0f, 0.0f, true};
         n.ok = await_n<2>(p1, GW, 0, P.spin_limit, w);
@@ -643,13 +658,13 @@ void pair_kernel(PairParams P) {
             // the loop it would be spilled, and the reload would wait for every load in flight
             int l = lane;
             asm volatile("" : "+v"(l));
-            post64(part2 + static_cast<size_t>(pp.pair) * GW * 4 + member * PW + l, mine);
+            post64(part2 + static_cast<size_t>(pp.pair) * GW * PW + member * PW + l, mine);
         }
     };
 
     auto finish_now = [&](int pair) __attribute__((always_inline)) {
         unsigned long long fw[FW];
-        request_n<FW>(finw + static_cast<size_t>(pair) * GW * 4, GW, 0, fw);
+        request_n<FW>(finw + static_cast<size_t>(pair) * GW * FW, GW, 0, fw);
         finish(pair, fw);
     };
     // Single-pass modes: nothing makes the members of a team wait for each other, so they drift
@@ -685,11 +700,11 @@ void pair_kernel(PairParams P) {
         asm volatile("" ::: "memory");
         if constexpr (TWO_PHASE)
         {
-            const unsigned long long* const p1 = part1 + static_cast<size_t>(due.pair >= 0 ? due.pair : pair) * GW * 4;
+            const unsigned long long* const p1 = part1 + static_cast<size_t>(due.pair >= 0 ? due.pair : pair) * GW * N1;
             request_n<2>(p1, GW, 0, w);
             request_n<2>(p1, GW, 64, w2, GW > 64);
         }
-        request_n<FW>(finw + static_cast<size_t>(fpair >= 0 ? fpair : pair) * GW * 4, GW, 0, fw, fpair >= 0);
+        request_n<FW>(finw + static_cast<size_t>(fpair >= 0 ? fpair : pair) * GW * FW, GW, 0, fw, fpair >= 0);
         if constexpr (DEEP) {
             // this pair's logits arrived in (ra, rb) during the last step; ask for the next pair's now
             const bool more = pair + pstep < pair_end;
@@ -776,9 +791,8 @@ void pair_kernel(PairParams P) {
             }
             mine = (lane == 0) ? w0 : (lane == 1) ? dbits(pst_) : (lane == 2) ? dbits(psd_) : dbits(pw_);
         }
-        constexpr int kPosted = TWO_PHASE ? 2 : 4;
-        unsigned long long* const post_at = part1 + static_cast<size_t>(pair) * GW * 4 + member * kPosted + (lane & 3);
-        if (lane < kPosted) post64(post_at, mine);
+        unsigned long long* const post_at = part1 + static_cast<size_t>(pair) * GW * N1 + member * N1 + (lane & 3);
+        if (lane < N1) post64(post_at, mine);
         PT(3);   // wave sums, prefetch issue, post
         if constexpr (TWO_PHASE) {
             // ---- the previous pair's normalisers, then its phase 2
@@ -847,8 +861,8 @@ void pair_kernel(PairParams P) {
             if (pp.pair >= 0) {
                 unsigned long long w[2], w2[2];
                 float ft, fd;
-                request_n<2>(part1 + static_cast<size_t>(pp.pair) * GW * 4, GW, 0, w);
-                request_n<2>(part1 + static_cast<size_t>(pp.pair) * GW * 4, GW, 64, w2, GW > 64);
+                request_n<2>(part1 + static_cast<size_t>(pp.pair) * GW * N1, GW, 0, w);
+                request_n<2>(part1 + static_cast<size_t>(pp.pair) * GW * N1, GW, 64, w2, GW > 64);
                 const bool ok2 = merge_team(pp, w, w2, ft, fd);
                 const int b = (iter + NB - d) % NB;   // written at step iter - d
                 if (b == 0) phase2(pp, SetId<0>{}, ft, fd, ok2);
