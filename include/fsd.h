@@ -28,6 +28,15 @@
  *     no initialisation and mean nothing afterwards.
  *   - The return value is an fsd_status.  Argument errors are found before
  *     anything is launched and leave all outputs untouched.
+ *   - The vocabulary-reduction kernel is persistent: the wavefronts that share a
+ *     row pair wait for each other's partial results, so its grid is sized to
+ *     what an otherwise idle device holds at once.  If other work occupies the
+ *     GPU while a call runs (another stream, another process), some of its
+ *     workgroups may start late; every wait is bounded (see
+ *     fsd_debug_set_spin_limit), and a wait that expires ends the call with
+ *     FSD_ROW_INTERNAL in row_status for every sequence (lengths 0, tokens -1)
+ *     instead of hanging.  Run verify calls on a GPU that is theirs while they
+ *     run, and treat FSD_ROW_INTERNAL as "call again".
  *   - Random numbers: Philox4x32-10 keyed by `seed`; `offset` selects the
  *     decode step (counter words 2,3), the sequence index is counter word 1 and
  *     the vocabulary (or position) index picks counter word 0 and the lane.
@@ -100,11 +109,14 @@ const char* fsd_status_string(int status);
  *   accept_len    [B]   out    n_b = number of leading accepted positions
  *   out_tokens    [B, K+1] out cand[b, :n_b], then the token drawn from
  *                              softmax(target[b, n_b]), then -1 padding
- *   divergences   [B, K] out   optional (NULL to skip), the chosen divergence:
- *                              evaluated in binary32, within 1e-5 (binary32
- *                              logits) or 2e-3 (bfloat16) relative of the
- *                              exact value, or 2.5e-7 absolute where that is
- *                              the larger (nearly equal rows)
+ *   divergences   [B, K] out   optional (NULL to skip), the chosen divergence.
+ *                              p and q are evaluated in binary32: the value is
+ *                              within 1e-5 (binary32 logits) or 2e-3 (bfloat16)
+ *                              relative of the exact one from 2e-2 (binary32)
+ *                              or 1e-4 (bfloat16) upwards; below that (nearly
+ *                              equal rows) its ABSOLUTE error stays under
+ *                              2.5e-7, measured on rows that differ by noise of
+ *                              0.001 to 0.3, and bit-identical rows give 0
  *   row_status    [B]   out    optional (NULL to skip), see FSD_ROW_*
  *
  * A call only enqueues kernels on hip_stream (the workspace is cleared by a

@@ -30,6 +30,7 @@ struct SampleParams {
     int32_t* row_status;      // optional
     const float* thr;         // optional [B]: warpers, smallest kept scaled logit of the sampled row
     float inv_temp;           // warpers: binary32(1 / temperature), 1 otherwise
+    unsigned spin_limit;      // bounded wait for the other workgroups' shares
     Ws ws;
 };
 
@@ -310,15 +311,14 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
         Best m = s_best[0], r = s_best[4];
         int bd = s_bad[0];
         for (int k = 1; k < 4; ++k) { m = better(m, s_best[k]); r = better(r, s_best[4 + k]); bd |= s_bad[k]; }
+        // The share of this workgroup: three words that say by themselves whether they have arrived.  The
+        // sampler's shares are cleared with the exchange words at the start of the call and a posted
+        // word is never zero (the index goes out plus one, the flag with bit 1 set), so nothing has to
+        // order these stores before the count below: whoever merges looks until the words are there.
         unsigned long long* slot = P.ws.spart + (static_cast<size_t>(b) * P.GS + gs) * 4;
-        __hip_atomic_store(slot + 0, (static_cast<unsigned long long>(__float_as_uint(m.score)) << 32) | static_cast<unsigned>(m.idx), __ATOMIC_RELAXED, AGENT);
-        __hip_atomic_store(slot + 1, (static_cast<unsigned long long>(__float_as_uint(r.score)) << 32) | static_cast<unsigned>(r.idx), __ATOMIC_RELAXED, AGENT);
-        __hip_atomic_store(slot + 2, static_cast<unsigned long long>(bd), __ATOMIC_RELAXED, AGENT);
-        // The three words above are device-scope atomic stores, performed at the memory side; the
-        // wait for their completion orders them before the count (a device-scope release would also
-        // write the whole L2 back, which costs far more than the kernel's arithmetic).  The reader
-        // uses device-scope atomic loads, so it needs no invalidate either.
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __hip_atomic_store(slot + 0, (static_cast<unsigned long long>(__float_as_uint(m.score)) << 32) | (static_cast<unsigned>(m.idx) + 1u), __ATOMIC_RELAXED, AGENT);
+        __hip_atomic_store(slot + 1, (static_cast<unsigned long long>(__float_as_uint(r.score)) << 32) | (static_cast<unsigned>(r.idx) + 1u), __ATOMIC_RELAXED, AGENT);
+        __hip_atomic_store(slot + 2, static_cast<unsigned long long>(bd ? 3 : 2), __ATOMIC_RELAXED, AGENT);
         const unsigned prev = __hip_atomic_fetch_add(P.ws.sdone + static_cast<size_t>(b) * kSdoneStride, 1u, __ATOMIC_RELAXED, AGENT);
         s_last = (prev == static_cast<unsigned>(P.GS) - 1u) ? 1 : 0;
     }
@@ -329,19 +329,31 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
     if (wave == 0) {   // one share per lane: the loads of all shares are in flight together
         Best m{neg_inf(), 0x7FFFFFFF}, r{neg_inf(), 0x7FFFFFFF};
         int bd = 0;
+        bool late = false;
         for (int k = lane; k < P.GS; k += 64) {
             const unsigned long long* slot = P.ws.spart + (static_cast<size_t>(b) * P.GS + k) * 4;
-            const unsigned long long w0 = __hip_atomic_load(slot + 0, __ATOMIC_RELAXED, AGENT);
-            const unsigned long long w1 = __hip_atomic_load(slot + 1, __ATOMIC_RELAXED, AGENT);
-            bd |= static_cast<int>(__hip_atomic_load(slot + 2, __ATOMIC_RELAXED, AGENT));
-            m = better(m, Best{__uint_as_float(static_cast<unsigned>(w0 >> 32)), static_cast<int>(static_cast<unsigned>(w0))});
-            r = better(r, Best{__uint_as_float(static_cast<unsigned>(w1 >> 32)), static_cast<int>(static_cast<unsigned>(w1))});
+            // every workgroup of the sequence has counted itself, so its words are on their way: normally
+            // they are there at the first look (bounded wait otherwise)
+            unsigned long long w0 = 0, w1 = 0, w2 = 0;
+            for (unsigned polls = 0;; ++polls) {
+                w0 = __hip_atomic_load(slot + 0, __ATOMIC_RELAXED, AGENT);
+                w1 = __hip_atomic_load(slot + 1, __ATOMIC_RELAXED, AGENT);
+                w2 = __hip_atomic_load(slot + 2, __ATOMIC_RELAXED, AGENT);
+                if ((w0 != 0 && w1 != 0 && w2 != 0) || polls >= P.spin_limit) break;
+                __builtin_amdgcn_s_sleep(1);
+            }
+            if (w0 == 0 || w1 == 0 || w2 == 0) { late = true; continue; }
+            bd |= static_cast<int>(w2 & 1);
+            m = better(m, Best{__uint_as_float(static_cast<unsigned>(w0 >> 32)), static_cast<int>(static_cast<unsigned>(w0) - 1u)});
+            r = better(r, Best{__uint_as_float(static_cast<unsigned>(w1 >> 32)), static_cast<int>(static_cast<unsigned>(w1) - 1u)});
         }
         m = wave_best(m);
         r = wave_best(r);
         bd = __any(bd);
+        late = __any(late);
         if (lane == 0) {
             int st = status;
+            if (late) st |= FSD_ROW_INTERNAL;   // a share never arrived (never expected)
             if (!st && (bd || m.idx == 0x7FFFFFFF)) st |= FSD_ROW_NONFINITE;
             const int tok = (residual && r.idx != 0x7FFFFFFF) ? r.idx : m.idx;
             s_st = st;

@@ -89,6 +89,7 @@ bool make_plan(int B, int rows, long V, int dtype, Plan& p) {
     size_t o = 0;
     p.off_counters = o; p.n_counters = 64 + static_cast<size_t>(B) * kSdoneStride; o = align_up(o + p.n_counters * 4, 256);
     p.off_wz = o; o = align_up(o + R * kWalkShare * 8, 256);
+    p.off_spart = o; o = align_up(o + static_cast<size_t>(B) * p.GS * 32, 256);
     // the two exchange arrays, sized for the mode that posts most (4 words per member in each); a call
     // lays them out densely for its own mode (see carve) and clears only that much
     p.off_part1 = o; o = align_up(o + R * p.G * 32, 256) + align_up(R * p.G * 32, 256);
@@ -97,7 +98,6 @@ bool make_plan(int B, int rows, long V, int dtype, Plan& p) {
     p.off_pst = o; o = align_up(o + R * 4, 256);
     p.off_lse2 = o; o = align_up(o + R * 16, 256);
     p.off_lr = o; o = align_up(o + R * 8, 256);
-    p.off_spart = o; o = align_up(o + static_cast<size_t>(B) * p.GS * 32, 256);
     p.off_thr = o; o = align_up(o + static_cast<size_t>(B) * 4, 256);
     p.off_tsd = o; o = align_up(o + static_cast<size_t>(B) * (4 + rows) * 4, 256);
     p.off_tsdz = o; o = align_up(o + static_cast<size_t>(B) * rows * 4, 256);
@@ -400,6 +400,7 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
     sp.path_nodes = path_nodes;
     sp.row_status = row_status;
     sp.ws = ws;
+    sp.spin_limit = g_spin_limit;
     sp.thr = nullptr;
     sp.inv_temp = 1.0f;
     const bool warped = (temperature != 1.0f) || (top_k > 0 && top_k < V) || (top_p < 1.0f);

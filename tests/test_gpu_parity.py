@@ -336,15 +336,15 @@ def test_strict_sd_small(torch_cuda, oracle):
             check_sd(g, o, f"SD B={B} K={K} V={V} {dtype} mode={mode}")
 
 
-def check_rfsd(g, o, T, tol, what):
+def check_rfsd(g, o, T, tol, what, envelope=None):
     """reducible FSD: a position is decided by div <= T or by the SD margin; a sequence may differ
     from the oracle only where the deciding quantity sits on its threshold."""
     assert (g["row_status"] == o["row_status"]).all(), what
-    pu.check_divs(g["divergences"], o["divs"], tol, what)
+    pu.check_divs(g["divergences"], o["divs"], tol, what, envelope)
     fin = np.isfinite(o["log_ratio"])
     assert (np.isfinite(g["log_ratio"]) == fin).all()
     assert np.allclose(g["log_ratio"][fin], o["log_ratio"][fin], rtol=2e-5, atol=2e-5), what
-    near = pu.near_threshold(o["divs"], T) | (np.abs(o["margin"]) <= 1e-5)
+    near = pu.near_threshold(o["divs"], T, envelope) | (np.abs(o["margin"]) <= 1e-5)
     n_near = n_tie = 0
     for b in range(o["accept_len"].shape[0]):
         ng, no = int(g["accept_len"][b]), int(o["accept_len"][b])
@@ -419,12 +419,12 @@ def run_warped(torch_cuda, inp, T, div, mode, seed, offset, **kw):
     return g
 
 
-def check_warped(g, o, T, tol, what, sampled=True, cut_active=True):
+def check_warped(g, o, T, tol, what, sampled=True, cut_active=True, envelope=None):
     """as check_chain; a token may differ where the nucleus mass sat on top_p (the kept set then
     differs by one value) or where two scores tie to 1e-6"""
     assert (g["row_status"] == o["row_status"]).all(), what
-    pu.check_divs(g["divergences"], o["divs"], tol, what)
-    assert (g["accept_len"] == o["accept_len"]).all() or pu.near_threshold(o["divs"], T).any(), what
+    pu.check_divs(g["divergences"], o["divs"], tol, what, envelope)
+    assert (g["accept_len"] == o["accept_len"]).all() or pu.near_threshold(o["divs"], T, envelope).any(), what
     n_soft = 0
     for b in range(o["accept_len"].shape[0]):
         if g["accept_len"][b] != o["accept_len"][b]:
@@ -586,30 +586,25 @@ def test_calibrated_threshold_matches_strict_sd_share(torch_cuda, oracle):
     print("strict SD share", share, "-> T", float(T.item()), "FSD share", got, flush=True)
 
 
-def test_config_c3_sampled(torch_cuda, oracle):
-    """full-size C3 on the GPU; the oracle checks a sample of its sequences one by one."""
+def test_config_c3_full(torch_cuda, oracle):
+    """full-size C3 (B=256, K=16, V=151936, float32: teams of 76 wavefronts, merged in two rounds): every
+    sequence against the oracle, all three divergences."""
     c = synth.CONFIGS["C3"]
     inp = synth.config_inputs("C3", seed=0)
     print("C3 inputs ready", flush=True)
-    for div in (fsd.DIV_JS, fsd.DIV_KL):
+    for div in (fsd.DIV_JS, fsd.DIV_KL, fsd.DIV_TV):
         g = run_chain(torch_cuda, inp, 0.3, div, seed=5)
         assert (g["row_status"] == 0).all()
-        for b in (0, 1, 97, 255):
-            o = oracle.verify_chain(inp["target"][b:b + 1], inp["draft"][b:b + 1], inp["cand"][b:b + 1], 0.3, div,
-                                    seed=5, seq_offset=b)
-            gb = {k: v[b:b + 1] for k, v in g.items()}
-            r = pu.check_chain(gb, o, 0.3, 1e-5, f"C3 div={div} b={b}")
-            print("C3", div, b, r, o["accept_len"], flush=True)
-        # properties that hold for every sequence
-        d = g["divergences"]
-        assert (d >= 0).all() and np.isfinite(d).all()
-        ok = d <= np.float32(0.3)
-        first_rej = np.where(ok.all(axis=1), c["K"], np.argmin(ok, axis=1))
-        assert (g["accept_len"] == first_rej).all()
-        for b in range(c["B"]):
-            n = g["accept_len"][b]
-            assert (g["out_tokens"][b, :n] == inp["cand"][b, :n]).all()
-            assert 0 <= g["out_tokens"][b, n] < c["V"] and (g["out_tokens"][b, n + 1:] == -1).all()
+        worst, n_near = 0.0, 0
+        for b0 in range(0, c["B"], 32):   # the oracle in slices of 32 sequences (its working set stays small)
+            sl = slice(b0, b0 + 32)
+            o = oracle.verify_chain(inp["target"][sl], inp["draft"][sl], inp["cand"][sl], 0.3, div, seed=5, seq_offset=b0)
+            r = pu.check_chain({k: v[sl] for k, v in g.items()}, o, 0.3, 1e-5, f"C3 div={div} b={b0}..{b0 + 31}")
+            worst = max(worst, r["max_rel_err"])
+            n_near += r["near_T_rows"]
+        print("C3 div", div, "max rel err", worst, "near-T rows", n_near, "accept_len histogram",
+              np.bincount(g["accept_len"], minlength=c["K"] + 1), flush=True)
+        assert n_near <= 2
 
 
 def test_config_c4_tree_full(torch_cuda, oracle):
@@ -710,25 +705,11 @@ def test_reduction_kernel_shapes_agree(torch_cuda, oracle):
 
 # ------------------------------------------------------------------ random shapes
 
-def _inside_envelope(g, o, dtype, what):
-    """Divergences meet the relative bar or the absolute floor of binary32 evaluation (2.5e-7, see
-    test_accuracy_envelope_on_nearly_identical_rows).  Returns the HIP outputs with those divergences
-    replaced by the oracle's, so that the usual comparison then checks everything else."""
-    gd = np.asarray(g["divergences"], dtype=np.float64)
-    od = np.asarray(o["divs"], dtype=np.float64)
-    fin = np.isfinite(od) & np.isfinite(gd)
-    err = np.abs(np.where(fin, gd, 0.0) - np.where(fin, od, 0.0))
-    ok = ~fin | (err <= 2.5e-7) | (err <= pu.rel_tol(dtype) * np.maximum(np.abs(od), pu.DIV_FLOOR))
-    assert ok.all(), f"{what}: divergence error {err[~ok]} at oracle values {od[~ok]}"
-    g2 = dict(g)
-    g2["divergences"] = np.where(fin, od, gd)
-    return g2
-
-
 def test_random_small_shapes(torch_cuda, oracle):
     """200 random draws of (B, K, V, dtype, input kind, noise, masks, divergence, T): the chain call, and in
     turn reducible FSD, strict SD and a random tree over the same rows, each against the oracle."""
     rng = np.random.default_rng(2024)
+    env = {"f32": pu.Envelope("f32"), "bf16": pu.Envelope("bf16")}
     for it in range(200):
         B, K = int(rng.integers(1, 6)), int(rng.integers(1, 7))
         V = int(rng.choice([rng.integers(1, 40), rng.integers(40, 3000), rng.integers(3000, 70000),
@@ -748,11 +729,11 @@ def test_random_small_shapes(torch_cuda, oracle):
         tol = pu.rel_tol(dtype)
         g = run_chain(torch_cuda, inp, T, div, seed=seed, offset=it)
         o = oracle.verify_chain(inp["target"], inp["draft"], inp["cand"], T, div, seed=seed, offset=it)
-        pu.check_chain(_inside_envelope(g, o, dtype, what), o, T, tol, what)
+        pu.check_chain(g, o, T, tol, what, env[dtype])
         if it % 3 == 0:
             g = run_rfsd(torch_cuda, inp, T, div, seed=seed, offset=it)
             o = oracle.rfsd_verify_chain(inp["target"], inp["draft"], inp["cand"], T, div, seed=seed, offset=it)
-            check_rfsd(_inside_envelope(g, o, dtype, what), o, T, tol, "reducible " + what)
+            check_rfsd(g, o, T, tol, "reducible " + what, env[dtype])
         elif it % 3 == 1:
             d = pu.to_dev(inp, ("target", "draft", "cand"))
             out = fsd.sd_verify_chain(d["target"], d["draft"], d["cand"], seed=seed, offset=it)
@@ -766,7 +747,11 @@ def test_random_small_shapes(torch_cuda, oracle):
             g = run_tree(torch_cuda, tin, T, div, K, seed=seed, offset=it)
             o = oracle.verify_tree(tin["target"], tin["draft"], tin["node_tokens"], parent, K, T, div, seed=seed,
                                    offset=it)
-            pu.check_tree(_inside_envelope(g, o, dtype, what), o, T, tol, "tree " + what)
+            pu.check_tree(g, o, T, tol, "tree " + what, env[dtype])
+    for dtype, e in env.items():
+        e.report(f"random small shapes, {dtype} logits")
+        # the rows that only meet the absolute bound are the ones drawn with little noise: a minority
+        assert e.below <= 0.35 * (e.met + e.below), dtype
 
 
 # ------------------------------------------------------------------ strict SD over a token tree
@@ -956,6 +941,7 @@ def test_random_small_shapes_warped_and_tree_sd(torch_cuda, oracle):
     """150 random draws: the chain call with a random set of warpers, and strict SD over a random tree
     (or star), each against the oracle."""
     rng = np.random.default_rng(777)
+    env = {"f32": pu.Envelope("f32"), "bf16": pu.Envelope("bf16")}
     for it in range(150):
         B, K = int(rng.integers(1, 6)), int(rng.integers(1, 6))
         V = int(rng.choice([rng.integers(2, 40), rng.integers(40, 3000), rng.integers(3000, 140000),
@@ -977,7 +963,7 @@ def test_random_small_shapes_warped_and_tree_sd(torch_cuda, oracle):
         o = oracle.verify_chain_warped(inp["target"], inp["draft"], inp["cand"], 0.1, fsd.DIV_JS, fsd.SAMPLE, seed, it,
                                        **kw)
         active = 0 < kw.get("top_k", 0) < V or kw.get("top_p", 1.0) < 1.0
-        check_warped(_inside_envelope(g, o, dtype, what), o, 0.1, pu.rel_tol(dtype), what, cut_active=active)
+        check_warped(g, o, 0.1, pu.rel_tol(dtype), what, cut_active=active, envelope=env[dtype])
         N = int(rng.integers(1, 30))
         Vt = int(rng.choice([rng.integers(2, 60), rng.integers(60, 5000), rng.integers(5000, 60000)]))
         tin = _random_tree_inputs(rng, B, N, Vt, dtype, star=bool(rng.random() < 0.3), noise=(0.3, 2.5))
@@ -985,6 +971,9 @@ def test_random_small_shapes_warped_and_tree_sd(torch_cuda, oracle):
         o = oracle.sd_verify_tree(tin["target"], tin["draft"], tin["node_tokens"], tin["parent"], N, seed=seed,
                                   offset=it)
         check_sd_tree(g, o, f"sd tree it={it} N={N} V={Vt} {dtype}", tin)
+    for dtype, e in env.items():
+        e.report(f"random warped shapes, {dtype} logits")
+        assert e.below <= 0.35 * (e.met + e.below), dtype
 
 
 def test_config_c4_strict_sd_tree(torch_cuda, oracle):
