@@ -43,6 +43,8 @@ def lib() -> ctypes.CDLL:
         c = ctypes
         vp, i32, i64, u32, u64, dbl = c.c_void_p, c.c_int, c.c_long, c.c_uint32, c.c_uint64, c.c_double
         L.fsd_oracle_num_threads.restype = c.c_int
+        L.fsd_oracle_set_num_threads.argtypes = [c.c_int]
+        L.fsd_oracle_set_num_threads.restype = None
         L.fsd_oracle_philox4x32_10.argtypes = [vp, vp, vp]
         L.fsd_oracle_random_word.argtypes = [u64, u64, u32, u32, u32]
         L.fsd_oracle_random_word.restype = u32
@@ -81,6 +83,11 @@ def lib() -> ctypes.CDLL:
 
 def num_threads() -> int:
     return int(lib().fsd_oracle_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    """threads of the loops over sequences (for timing the oracle on one core; results do not depend on it)"""
+    lib().fsd_oracle_set_num_threads(int(n))
 
 
 def _dt(a: np.ndarray) -> int:

@@ -64,6 +64,15 @@
 #define ST_TOO_DEEP 4   /* tree: a node deeper than max_depth */
 #define ST_BAD_TOKEN 8  /* strict SD: candidate token id outside [0, V) */
 
+/* thread count of the loops over sequences (timing only: the arithmetic does not depend on it) */
+void fsd_oracle_set_num_threads(int n) {
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 int fsd_oracle_num_threads(void) {
 #ifdef _OPENMP
     return omp_get_max_threads();

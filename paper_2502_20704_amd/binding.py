@@ -87,8 +87,15 @@ def library() -> ctypes.CDLL:
     return _lib
 
 
+_ws_bytes = {}
+
+
 def fsd_workspace_bytes(B: int, rows_per_seq: int, V: int, dtype: int) -> int:
-    return int(library().fsd_workspace_bytes(B, rows_per_seq, V, dtype))
+    key = (B, rows_per_seq, V, dtype)
+    n = _ws_bytes.get(key)
+    if n is None:   # the library's answer for a shape does not change: asked once
+        n = _ws_bytes[key] = int(library().fsd_workspace_bytes(B, rows_per_seq, V, dtype))
+    return n
 
 
 def _dtype_code(t) -> int:

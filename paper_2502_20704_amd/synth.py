@@ -191,6 +191,8 @@ CONFIGS = {
                T=[0.1]),
     "C3": dict(shape="chain", B=256, K=16, V=151936, dtype="f32", kind="zipf", sigma=1.0, T=[0.3]),
     "C4": dict(shape="tree", B=32, N=60, V=128256, dtype="bf16", kind="peaked", sigma=1.0, T=[0.15]),
+    # the largest vocabulary among the paper's model pairs (its third family), C2's recipe otherwise
+    "C5": dict(shape="chain", B=64, K=8, V=256000, dtype="bf16", kind="peaked", sigma=(0.25, 4.0), T=[0.1]),
 }
 
 
