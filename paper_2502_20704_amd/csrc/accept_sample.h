@@ -197,11 +197,15 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
         float thr = neg_inf(), rthr = neg_inf();
         const float thr_b = P.thr ? P.thr[b] : neg_inf();
         // the trip count is the same for every lane: the thresholds are wavefront reductions
+        // the next round's slot is requested before this round's is worked on: the loads of the rounds
+        // overlap with the arithmetic instead of each being waited for in turn
+        uint4 raw_next = load_slot<BF16, ALIGNED>(trow, (s0 + tid < s1) ? s0 + tid : s1 - 1, P.V);
         for (long sb = s0; sb < s1; sb += kWG) {
             const long s = sb + tid;
             const bool live = s < s1;
             float z[VE], zd[VE];
-            const uint4 raw = load_slot<BF16, ALIGNED>(trow, live ? s : s1 - 1, P.V);
+            const uint4 raw = raw_next;
+            if (sb + kWG < s1) raw_next = load_slot<BF16, ALIGNED>(trow, (s + kWG < s1) ? s + kWG : s1 - 1, P.V);
             unpack<BF16>(raw, z);
             if (P.thr && P.mode == FSD_SAMPLE) {
                 // temperature, then the kept set of top-k / top-p: everything else leaves the draw

@@ -145,7 +145,17 @@ __global__ __launch_bounds__(kWalkWG) void tree_sd_walk(WalkParams P) {
             for (int j2 = j + 1; j2 < N; ++j2) more |= (par[j2] == cur);
             if (!more) break;
             // ---- the normaliser of the positive part of p - q_j, p being the distribution in force
-            const float ltf = static_cast<float>(lt2), ldf = static_cast<float>(ld2);
+            // p and q of an entry: 2^(z log2e - lse2) with the argument formed in float64 and split into a
+            // binary32 part for the hardware exponential and a remainder applied as 1 + ln2 * rest.  A
+            // binary32 argument would carry the rounding of lse2 (about 1e-6 at |lse2| = 20) into every
+            // entry of the row alike, and a later sibling's log-ratio multiplies such a common error by
+            // p/(p - q); this way only the exponential's own rounding is left, which averages out in the sums.
+            auto prob = [&](float z, double lse2) __attribute__((always_inline)) -> float {
+                const double x = fma(static_cast<double>(z), kLog2eD, -lse2);
+                const float xh = static_cast<float>(x);
+                const float xl = static_cast<float>(x - static_cast<double>(xh));
+                return hw_exp2(xh) * fmaf(xl, static_cast<float>(kLn2), 1.0f);
+            };
             // CH slots per thread at a time, row by row: the CH loads of a row are in flight together
             // (one slot at a time, each load waited for the one before it)
             constexpr int CH = BF16 ? 4 : 8;
@@ -167,21 +177,22 @@ __global__ __launch_bounds__(kWalkWG) void tree_sd_walk(WalkParams P) {
                     float z[VE];
                     unpack<BF16>(raw[c], z);
 #pragma unroll
-                    for (int e = 0; e < VE; ++e) pv[c][e] = in[c] ? hw_exp2(fmaf(z[e], kLog2e, -ltf)) : 0.0f;
+                    for (int e = 0; e < VE; ++e) pv[c][e] = in[c] ? prob(z[e], lt2) : 0.0f;
                 }
                 for (int m = 0; m < nrej; ++m) {
                     const size_t pc = static_cast<size_t>(b) * N + chain[m];
                     const char* cr = P.draft + pc * rowb;
 #pragma unroll
                     for (int c = 0; c < CH; ++c) raw[c] = load_slot<BF16, ALIGNED>(cr, slc[c], P.V);
-                    const float ldm = static_cast<float>(lse_of[2 * chain[m] + 1]), izm = s_invz[m];
+                    const double ldm = lse_of[2 * chain[m] + 1];
+                    const float izm = s_invz[m];
 #pragma unroll
                     for (int c = 0; c < CH; ++c) {
                         float zd[VE];
                         unpack<BF16>(raw[c], zd);
 #pragma unroll
                         for (int e = 0; e < VE; ++e)
-                            pv[c][e] = fmaxf(pv[c][e] - hw_exp2(fmaf(zd[e], kLog2e, -ldm)), 0.0f) * izm;
+                            pv[c][e] = fmaxf(pv[c][e] - prob(zd[e], ldm), 0.0f) * izm;
                     }
                 }
 #pragma unroll
@@ -192,7 +203,7 @@ __global__ __launch_bounds__(kWalkWG) void tree_sd_walk(WalkParams P) {
                     unpack<BF16>(raw[c], zd);
                     float part = 0.0f;
 #pragma unroll
-                    for (int e = 0; e < VE; ++e) part += fmaxf(pv[c][e] - hw_exp2(fmaf(zd[e], kLog2e, -ldf)), 0.0f);
+                    for (int e = 0; e < VE; ++e) part += fmaxf(pv[c][e] - prob(zd[e], ld2), 0.0f);
                     acc += static_cast<double>(part);
                 }
             }

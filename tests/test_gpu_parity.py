@@ -796,9 +796,9 @@ def _ratio_condition(inp, o, b, j):
 def check_sd_tree(g, o, what, inp=None):
     """Paths and tokens are exact unless a test sits on its threshold (|margin| <= 1e-5 in the oracle)
     or the residual draw has a runner-up within 1e-4; log-ratios of the nodes that were tried agree to
-    5e-5.  With the inputs at hand the bar follows the arithmetic instead: 5e-5 + 3e-7 times the
-    condition number of the node's log-ratio (a later sibling's can be large), for the values and
-    for what counts as sitting on the threshold."""
+    5e-5 (plus 5e-5 of their size).  With the inputs at hand the condition number of a node's log-ratio
+    is printed where the error comes near the bar (a later sibling's can be large): a diagnostic, no
+    allowance is made for it."""
     assert (g["row_status"] == o["row_status"]).all(), what
     near = np.abs(np.nan_to_num(o["margin"], nan=1.0)) <= 1e-5
     n_near = n_tie = n_cond = 0
@@ -811,7 +811,9 @@ def check_sd_tree(g, o, what, inp=None):
                 for j in range(o["log_ratio"].shape[1]):
                     tg_, to_ = not np.isnan(g["log_ratio"][b, j]), not np.isnan(o["log_ratio"][b, j])
                     if tg_ and to_ and (j in g["path_nodes"][b]) != (j in o["path_nodes"][b]):
-                        ok = abs(o["margin"][b, j]) <= 1e-5 + 3e-7 * _ratio_condition(inp, o, b, j)
+                        ok = abs(o["margin"][b, j]) <= 1e-5
+                        print(f"{what}: tree {b} node {j} decided differently, margin {o['margin'][b, j]:.3e}, "
+                              f"condition number {_ratio_condition(inp, o, b, j):.3g}", flush=True)
                         break
                     if tg_ != to_:
                         break
@@ -825,9 +827,13 @@ def check_sd_tree(g, o, what, inp=None):
         for j in np.nonzero(fin)[0]:
             gv, ov = float(g["log_ratio"][b, j]), float(o["log_ratio"][b, j])
             tol = 5e-5 + 5e-5 * abs(ov)
-            if abs(gv - ov) > tol and inp is not None:
-                tol += 3e-7 * _ratio_condition(inp, o, b, int(j))
-                n_cond += 1
+            if abs(gv - ov) > 0.2 * tol and inp is not None:
+                # diagnostic only: how ill-conditioned the node's log-ratio is (no allowance is made for it)
+                kappa = _ratio_condition(inp, o, b, int(j))
+                if kappa > 1e3:
+                    n_cond += 1
+                    print(f"{what}: tree {b} node {j} log_ratio error {abs(gv - ov):.2e} of {tol:.2e} allowed, "
+                          f"condition number {kappa:.3g}", flush=True)
             assert abs(gv - ov) <= tol, f"{what}: tree {b} node {j} log_ratio gpu {gv} oracle {ov} (allowed {tol:.2e})"
         if not (g["out_tokens"][b] == o["out_tokens"][b]).all():
             assert o["gap"][b] < 1e-4, f"{what}: tree {b} tokens gpu {g['out_tokens'][b]} oracle {o['out_tokens'][b]} gap {o['gap'][b]}"
@@ -978,7 +984,8 @@ def test_random_small_shapes_warped_and_tree_sd(torch_cuda, oracle):
 
 def test_config_c4_strict_sd_tree(torch_cuda, oracle):
     # the second set holds a later sibling whose token has nearly the same probability under the target
-    # and under the sibling rejected before it: its log-ratio is ill-conditioned (see check_sd_tree)
+    # and under the sibling rejected before it: its log-ratio is ill-conditioned (condition number 5e3),
+    # and still inside the plain bar since the walk forms its probabilities from float64 arguments
     for inputs_seed, seed, offset in ((0, 6, 2), (400, 400, 3)):
         inp = synth.config_inputs("C4", seed=inputs_seed)
         md = int(inp["max_depth"])
