@@ -251,7 +251,7 @@ int fsd_verify_tree_warped(const void* target_logits, const void* draft_logits, 
                            void* hip_stream);
 
 /*
- * Reducible FSD (paper Sec. 4.2, "Reducing FSD to standard SD"): position i is
+ * Reducible FSD (paper Sec. 4.3, "Reducing FSD to standard SD"): position i is
  * accepted iff div(p_i, q_i) <= T (the rule of fsd_verify_chain) OR the strict
  * SD test of sd_verify_chain accepts the candidate token, with the same uniform
  * numbers; at the first rejection the token is drawn from the normalised
@@ -268,7 +268,7 @@ int rfsd_verify_chain(const void* target_logits, const void* draft_logits, const
                       void* hip_stream);
 
 /*
- * Threshold tuning on a dev set (paper Sec. 5.3 "Tuning T on small dev set";
+ * Threshold tuning on a dev set (paper Sec. 6.2 "Selecting T", paragraph "Tuning T on small dev set";
  * App. A: the threshold that accepts about the same share of candidate tokens
  * as strict SD).  From the divergences of a batch of candidate sequences (the
  * `divergences` output of fsd_verify_chain, any T) it finds the smallest
@@ -288,6 +288,14 @@ int rfsd_verify_chain(const void* target_logits, const void* draft_logits, const
 size_t fsd_calibrate_workspace_bytes(int B, int K);
 int fsd_calibrate_threshold(const float* divergences, int B, int K, float target_fraction, float* T_out,
                             float* fraction_out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * Everything below is for tests, tuning and benchmarks, not for serving code.
+ * These calls set or read PROCESS-WIDE state inside the library (the only such
+ * state it has; the verify calls themselves keep none between calls, apart from
+ * per-device constants looked up once).  They are not thread-safe: use them from
+ * one thread while no verify call is in flight on another.
+ * ------------------------------------------------------------------------- */
 
 /*
  * Timing of the vocabulary-reduction kernel, for benchmarks.  After

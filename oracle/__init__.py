@@ -235,7 +235,7 @@ def sd_verify_tree(target, draft, node_tokens, parent, max_depth, mode=SAMPLE, s
 
 
 def rfsd_verify_chain(target, draft, cand, T, div, mode=SAMPLE, seed=0, offset=0, seq_offset=0):
-    """Reducible FSD (Sec. 4.2): accept iff div <= T or the strict SD test accepts."""
+    """Reducible FSD (Sec. 4.3): accept iff div <= T or the strict SD test accepts."""
     target, draft = _c(target), _c(draft)
     cand = _c(np.asarray(cand, dtype=np.int32))
     B, K1, V = target.shape
@@ -267,7 +267,7 @@ def accepted_fraction(divs, T):
 
 
 def calibrate_threshold(divs, fraction):
-    """Threshold tuning on a dev set (Sec. 5.3 "Tuning T on small dev set"; App. A: the T that accepts
+    """Threshold tuning on a dev set (Sec. 6.2 "Selecting T", paragraph "Tuning T on small dev set"; App. A: the T that accepts
     about the same share of candidate tokens as strict SD): the smallest T, among the divergences that
     occur (and +inf), at which the chain rule accepts at least `fraction` of all candidate positions.
     Plain search over every candidate value; returns (T, accepted fraction at T).  0 < fraction <= 1."""

@@ -623,7 +623,7 @@ int sd_oracle_verify_tree(const void* target, const void* draft, const int32_t* 
 
 /* ------------------------------------------------- reducible FSD (rFSD) */
 
-/* Sec. 4.2 ("Reducing FSD to standard SD"): position i is accepted iff the
+/* Sec. 4.3 ("Reducing FSD to standard SD"): position i is accepted iff the
  * divergence of its two distributions is within T (the FSD rule, with the same
  * "<=" reading as fsd_oracle_verify_chain) OR the strict SD test of Sec. 3
  * eq. 1-2 accepts the candidate token (same uniforms as sd_oracle_verify_chain).

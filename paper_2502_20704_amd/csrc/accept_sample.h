@@ -77,7 +77,7 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
             if constexpr (KIND == KIND_CHAIN || KIND == KIND_RFSD) {
                 ok = (P.ws.div[pr] <= P.T);   // Sec. 4 eq. 4 (NaN compares false)
             }
-            if constexpr (KIND == KIND_SD || KIND == KIND_RFSD) {   // reducible FSD (Sec. 4.2): either rule accepts
+            if constexpr (KIND == KIND_SD || KIND == KIND_RFSD) {   // reducible FSD (Sec. 4.3): either rule accepts
                 // Sec. 3 eq. 1-2 in the log domain: min(1, p/q) > u  <=>  min(0, ln p - ln q) - ln u > 0
                 const double ratio = P.ws.lr[pr];
                 const U4 r = philox4x32_10((static_cast<unsigned>(i) >> 2) | (1u << 30), static_cast<unsigned>(b),

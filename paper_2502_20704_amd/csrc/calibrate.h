@@ -8,7 +8,7 @@
 namespace {
 
 // ------------------------------------------------------------------------------------------
-// threshold tuning on a dev set (Sec. 5.3, App. A): the smallest occurring T at which the chain rule
+// threshold tuning on a dev set (Sec. 6.2, App. A): the smallest occurring T at which the chain rule
 // accepts a given share of all candidate positions.  A position is accepted iff every divergence up
 // to it is <= T, i.e. iff the running maximum of its sequence is: T is the ceil(fraction n)-th
 // smallest running maximum.  Non-negative binary32 values order like their bit patterns, so the

@@ -381,7 +381,7 @@ def test_rfsd_small(torch_cuda, oracle):
 
 
 def test_rfsd_reduces_to_strict_sd_and_to_fsd(torch_cuda, oracle):
-    """Sec. 4.2: with T = 0 the rule is strict SD's (bit-identical outputs); with a threshold nothing
+    """Sec. 4.3: with T = 0 the rule is strict SD's (bit-identical outputs); with a threshold nothing
     exceeds it is FSD's."""
     inp = synth.chain_inputs(16, 6, 32000, "bf16", "peaked", (0.25, 4.0), seed=33)
     d = pu.to_dev(inp, ("target", "draft", "cand"))

@@ -566,7 +566,7 @@ def test_sd_tree_flags_bad_input(oracle):
     assert oracle.sd_verify_tree(t2, d, cand, ok, max_depth=3)["row_status"][0] & oracle.ST_NONFINITE
 
 
-# ---- reducible FSD (Sec. 4.2): "div <= T or the strict SD test"
+# ---- reducible FSD (Sec. 4.3): "div <= T or the strict SD test"
 
 def test_rfsd_reduces_to_sd_and_to_fsd(oracle):
     t, d, cand = _small_chain(21, B=60, K=6)
