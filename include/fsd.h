@@ -313,6 +313,16 @@ int fsd_profile_collect(float* mean_ms, float* min_ms);
  * flags FSD_ROW_INTERNAL (default 1<<22).  Returns the previous value. */
 unsigned fsd_debug_set_spin_limit(unsigned polls);
 
+/* Test hooks of the bfloat16 Jensen-Shannon reduction.  It evaluates App. C.2 in
+ * entropy form (one logarithm per entry), whose absolute error of about 1e-6
+ * does not shrink with the result; results below a floor (default 2e-3 nats)
+ * are evaluated again in the pointwise form, whose error does.
+ * fsd_debug_set_js_floor sets that floor (0: never again; +inf: always) and
+ * returns the previous one; fsd_debug_set_exact_js(1) makes every bfloat16 JS
+ * call use the pointwise form only and returns the previous setting. */
+float fsd_debug_set_js_floor(float floor_nats);
+int fsd_debug_set_exact_js(int on);
+
 /* Tuning hook: shape of the vocabulary-reduction kernel.  `wavefronts` per
  * workgroup must be 4 (or 0 = default); `slots_per_thread` is the number of
  * 16-byte slots of each row a lane holds: 2, 4 or 8 (bfloat16: 2, 4 or 5), 0 =

@@ -81,6 +81,10 @@ def library() -> ctypes.CDLL:
         L.fsd_profile_collect.restype = i32
         L.fsd_debug_set_shape.argtypes = [i32, i32]
         L.fsd_debug_set_shape.restype = i32
+        L.fsd_debug_set_js_floor.argtypes = [f32]
+        L.fsd_debug_set_js_floor.restype = f32
+        L.fsd_debug_set_exact_js.argtypes = [i32]
+        L.fsd_debug_set_exact_js.restype = i32
         L.fsd_debug_set_spin_limit.argtypes = [c.c_uint]
         L.fsd_debug_set_spin_limit.restype = c.c_uint
         _lib = L
@@ -428,7 +432,18 @@ def debug_warp_thresholds(out, B: int, rows: int, V: int, dtype_code: int):
     return ws[base + off: base + off + 4 * B].view(torch.float32).clone()
 
 
+def debug_set_js_floor(floor_nats: float) -> float:
+    """floor (nats) below which the bfloat16 JS reduction evaluates a pair again in the pointwise form"""
+    return float(library().fsd_debug_set_js_floor(float(floor_nats)))
+
+
+def debug_set_exact_js(on: bool) -> bool:
+    """bfloat16 JS in the pointwise form only (test hook); returns the previous setting"""
+    return bool(library().fsd_debug_set_exact_js(1 if on else 0))
+
+
 def debug_set_shape(wavefronts: int, slots_per_thread: int) -> None:
     st = library().fsd_debug_set_shape(wavefronts, slots_per_thread)
+    _ws_bytes.clear()   # the workspace a shape needs depends on the hook's setting
     if st != 0:
         raise FsdError(st, "fsd_debug_set_shape")

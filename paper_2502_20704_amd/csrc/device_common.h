@@ -26,8 +26,9 @@ constexpr double kLn2 = 0.69314718055994530942;
 constexpr double kLog2eD = 1.44269504088896340736;
 
 // MODE_KL: single-pass KL (absolute error ~1e-7, enough for bfloat16 inputs); MODE_KLP: two-phase,
-// pointwise non-negative KL for binary32 inputs; MODE_LSE: normalisers only (strict SD)
-enum { MODE_KL = 0, MODE_JS = 1, MODE_TV = 2, MODE_LSE = 3, MODE_KLP = 4 };
+// pointwise non-negative KL for binary32 inputs; MODE_LSE: normalisers only (strict SD); MODE_JSE: JS in
+// entropy form for bfloat16 inputs (one logarithm per entry; small results are evaluated again pointwise)
+enum { MODE_KL = 0, MODE_JS = 1, MODE_TV = 2, MODE_LSE = 3, MODE_KLP = 4, MODE_JSE = 5 };
 enum { KIND_CHAIN = 0, KIND_TREE = 1, KIND_SD = 2, KIND_RFSD = 3, KIND_TREESD = 4 };
 
 #define AGENT __HIP_MEMORY_SCOPE_AGENT
@@ -312,6 +313,8 @@ struct Ws {
     unsigned long long* part1;  // [R][G][n1] phase-1 words, dense: (kt,kd) | (St,Sd) in the two-phase modes (n1 = 2),
                                 // (kt,kd) | St | Sd | W in the single-pass ones (n1 = 4)
     double* part2;       // [R][G][n2] divergence words of the two-phase modes (n2 = 1, or 2 for TV and pointwise KL)
+    unsigned long long* state;  // [R] entropy-form JS: 0 = pair not finished yet, all ones = done, else the rows'
+                                // log2-sum-exp2 (two binary32) of a pair the team evaluates again pointwise
     float* div;          // [R]
     int* pst;            // [R] status bits per pair
     double* lse2;        // [R][2] log2-sum-exp2 of the target / draft row of the pair
@@ -342,6 +345,7 @@ struct PairParams {
     float* user_div;        // optional [R]
     float* user_ratio;      // optional [R], reducible FSD only
     int want_ratio;         // 1: the finisher also writes ln p(x) - ln q(x) at the candidate token (reducible FSD)
+    float js_floor;         // entropy-form JS: results below this (nats) are evaluated again in the pointwise form
     Ws ws;
 };
 

@@ -48,7 +48,7 @@ namespace {
 struct Plan {
     int VE, NV, G, spm, GS, sps;   // G = wavefronts per pair
     long nslots;
-    size_t off_counters, n_counters, off_wz, off_part1, zero_bytes, off_div, off_pst, off_lse2, off_lr, off_spart,
+    size_t off_counters, n_counters, off_state, off_wz, off_part1, zero_bytes, off_div, off_pst, off_lse2, off_lr, off_spart,
         off_thr, off_tsd, off_tsdz, bytes;
 };
 
@@ -88,6 +88,7 @@ bool make_plan(int B, int rows, long V, int dtype, Plan& p) {
     const size_t R = static_cast<size_t>(B) * rows;
     size_t o = 0;
     p.off_counters = o; p.n_counters = 64 + static_cast<size_t>(B) * kSdoneStride; o = align_up(o + p.n_counters * 4, 256);
+    p.off_state = o; o = align_up(o + R * 8, 256);
     p.off_wz = o; o = align_up(o + R * kWalkShare * 8, 256);
     p.off_spart = o; o = align_up(o + static_cast<size_t>(B) * p.GS * 32, 256);
     // the two exchange arrays, sized for the mode that posts most (4 words per member in each); a call
@@ -113,6 +114,7 @@ Ws carve(void* workspace, const Plan& p, int B, int rows, int G, int n1, int n2,
     Ws w;
     w.counters = reinterpret_cast<unsigned*>(base + p.off_counters);
     w.sdone = w.counters + 64;
+    w.state = reinterpret_cast<unsigned long long*>(base + p.off_state);
     w.part1 = reinterpret_cast<unsigned long long*>(base + p.off_part1);
     const size_t off_part2 = align_up(p.off_part1 + R * G * n1 * 8, 256);
     w.part2 = reinterpret_cast<double*>(base + off_part2);
@@ -130,6 +132,11 @@ Ws carve(void* workspace, const Plan& p, int B, int rows, int G, int n1, int n2,
 }
 
 unsigned g_spin_limit = 1u << 22;
+// The entropy form of JS (bfloat16 logits) carries an absolute error of about 1.5e-6 whatever the
+// result: below this floor (nats) a pair is evaluated again in the pointwise form, so that what the
+// caller sees is within 2e-3 relative everywhere.
+float g_js_floor = 2e-3f;
+bool g_exact_js = false;   // test hook: bfloat16 JS in the pointwise form only
 #ifdef FSD_PHASE_TIMING
 unsigned long long* g_dbg = nullptr;
 #endif
@@ -202,9 +209,7 @@ void launch_pair_k(hipStream_t st, const PairParams& P) {
 template <bool BF16, int NV, int MODE>
 void launch_pair_a(bool aligned, hipStream_t st, const PairParams& P) {
     if (!aligned) {
-        launch_pair_k<BF16, NV, MODE, false>(st, P);
-    } else if constexpr (BF16) {
-        launch_pair_k<BF16, NV, MODE, true>(st, P);
+        launch_pair_k<BF16, NV, MODE, false>(st, P);   // (rows that are not 16-byte aligned: no tree variant, a tree's target rows are then not kept cached)
     } else {
         if (P.parent != nullptr) launch_pair_k<BF16, NV, MODE, true, true>(st, P);   // a tree: shared target rows
         else launch_pair_k<BF16, NV, MODE, true>(st, P);
@@ -217,6 +222,10 @@ void launch_pair_m(int mode, bool aligned, hipStream_t st, const PairParams& P) 
         case MODE_JS: launch_pair_a<BF16, NV, MODE_JS>(aligned, st, P); break;
         case MODE_TV: launch_pair_a<BF16, NV, MODE_TV>(aligned, st, P); break;
         case MODE_KLP: launch_pair_a<BF16, NV, MODE_KLP>(aligned, st, P); break;
+        case MODE_JSE:
+            if constexpr (BF16 && NV == 5) launch_pair_a<BF16, NV, MODE_JSE>(aligned, st, P);
+            else launch_pair_a<BF16, NV, MODE_JS>(aligned, st, P);
+            break;
         default: launch_pair_a<BF16, NV, MODE_LSE>(aligned, st, P); break;
     }
 }
@@ -338,16 +347,22 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
     // which reduction kernel, and its shape
     int k1mode = (kind == KIND_SD || kind == KIND_TREESD) ? MODE_LSE : div;
     if (k1mode == MODE_KL && dtype == FSD_F32) k1mode = MODE_KLP;
-    if (dtype == FSD_BF16 && !g_shape_nv && (k1mode == MODE_JS || k1mode == MODE_TV)) {
+    // bfloat16 JS: the entropy form (reducible FSD, whose finisher also forms the candidates' log-ratios,
+    // and the shapes of the tuning hook stay with the pointwise form)
+    if (k1mode == MODE_JS && dtype == FSD_BF16 && kind != KIND_RFSD && !g_exact_js && !g_shape_nv) k1mode = MODE_JSE;
+    if (dtype == FSD_BF16 && !g_shape_nv && (k1mode == MODE_JS || k1mode == MODE_TV || k1mode == MODE_JSE)) {
         // The bfloat16 two-phase kernels are bound by instruction issue, a third of it per step and not
         // per entry: 5 slots per lane instead of 4 is the most that fits two wavefronts per SIMD (256
         // registers).  The workspace is laid out for the larger team of the 4-slot shape.
         p.NV = 5;
         p.G = static_cast<int>(team_size(p.nslots, 5));
         p.spm = static_cast<int>((p.nslots + p.G - 1) / p.G);
+        // entropy form: whole chunks of 64 NV slots per member, so that only the last one with any
+        // slots has lanes without one (those lanes cost it selections the others do not pay for)
+        if (k1mode == MODE_JSE) p.spm = 64 * p.NV;
     }
     // exchange words a member posts in this mode: only those are laid out and cleared
-    const bool two_phase = (k1mode == MODE_JS || k1mode == MODE_TV || k1mode == MODE_KLP);
+    const bool two_phase = (k1mode == MODE_JS || k1mode == MODE_TV || k1mode == MODE_KLP || k1mode == MODE_JSE);
     const int n1 = two_phase ? 2 : 4;
     const int n2 = (k1mode == MODE_TV || k1mode == MODE_KLP) ? 2 : two_phase ? 1 : 0;
     size_t zero_bytes = 0;
@@ -375,6 +390,7 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
     pp.user_div = user_vals;
     pp.user_ratio = user_ratio;
     pp.want_ratio = (kind == KIND_RFSD) ? 1 : 0;
+    pp.js_floor = g_js_floor;
     pp.ws = ws;
     launch_pair(dtype, p.NV, k1mode, aligned, st, pp);
 
@@ -645,6 +661,18 @@ size_t fsd_debug_warp_threshold_offset(int B, int rows_per_seq, int V, int dtype
 void fsd_debug_last_launch(int* grid, int* resident) {
     if (grid) *grid = g_last_grid;
     if (resident) *resident = g_last_total;
+}
+
+float fsd_debug_set_js_floor(float floor_nats) {
+    const float prev = g_js_floor;
+    g_js_floor = floor_nats;
+    return prev;
+}
+
+int fsd_debug_set_exact_js(int on) {
+    const int prev = g_exact_js ? 1 : 0;
+    g_exact_js = (on != 0);
+    return prev;
 }
 
 unsigned fsd_debug_set_spin_limit(unsigned polls) {

@@ -170,22 +170,133 @@ __device__ __noinline__ Sums<N> sum_more_rounds(const unsigned long long* p2, in
     return s;
 }
 
+// ------------------------------------------------------------------------------------------
+// JS in entropy form (MODE_JSE, bfloat16 logits).  With p, q the two softmaxes and s = p + q,
+//
+//     JS = ln2 + (1/2) [ sum p ln p + sum q ln q - sum s ln s ]        (App. C.2, rearranged)
+//
+// Phase 1 keeps e = 2^x per entry (x = z log2e - k) and adds up S = sum e and A = sum e x, one fused
+// multiply-add per logit more than the normalisers need.  Phase 2 knows the row sums, hence the
+// member's factors f_t, f_d and c = f_d/f_t, forms u = e_t + c e_d = s/f_t and adds up U = sum u log2 u:
+// one logarithm per entry where the pointwise form p ln(2p/s) + q ln(2q/s) needs a reciprocal and
+// two.  With W = S_t + c S_d the mass of u, a member's share of 2 JS/ln2 is then
+//
+//     C = f_t [ A_t + c A_d - U + W + c S_d log2 c ]
+//
+// (write every logarithm as log2 f + log2 e: the terms in log2 f_t cancel because W is the mass of
+// u, and log2 of 2 gives the W).  C is formed in float64 from the binary32 sums, a dozen operations
+// per pair and member, and posted as one word; the pair's finisher only adds the team's C.
+// The kernel is bound by vector-ALU issue, and this removes a third of its instructions.  The
+// price is cancellation: A, U are of the size of the entropies, so the result carries an ABSOLUTE
+// error of about 1e-6 whatever its size.  Results below P.js_floor are therefore evaluated a
+// second time in the pointwise form, by the same team, after its last pair (bit-identical rows give
+// exactly 0 that way).
+//
+// Exchange words of this mode (zero = not posted yet):
+//   part1 [pair][member][2]   (kt, kd) reference exponents | (St, Sd) sums of exponentials
+//                             -- second evaluation: word 1 becomes (partial, -1); a sum is never -1
+//   part2 [pair][member]      C as float64 bits
+//   state [pair]              all ones = finished; else (L_t, L_d), the rows' log2-sum-exp2: evaluate again
+constexpr unsigned long long kJsDone = ~0ull;
+constexpr unsigned kJsFill = 0xF149F149u; // two bfloat16 of about -1e30: an entry no lane owns (exponential 0, e x = 0)
+
+// The rows' log2-sum-exp2 from a pair's phase-1 words, merged in float64 over rounds of 64 members
+// (exact rescaling between reference exponents).  Not inlined: used where a pair is evaluated a
+// second time, which is rare.
+struct RowNorms { double lse2_t, lse2_d; bool ok, usable; };
+__device__ __noinline__ RowNorms row_norms(const unsigned long long* p1, int GW, unsigned limit) {
+    const int lane = threadIdx.x & 63;
+    float Kt = neg_inf(), Kd = neg_inf();
+    double Zt = 0.0, Zd = 0.0;
+    RowNorms r;
+    r.ok = true;
+    bool bad = false;
+    for (int base = 0; base < GW; base += 64) {
+        const WordsN<2> q = repoll_n<2>(p1, GW, base, limit);
+        r.ok &= q.ok;
+        const bool in = base + lane < GW;
+        const float kt = lo_f(q.w[0]), kd = hi_f(q.w[0]);
+        const double St = in ? static_cast<double>(lo_f(q.w[1])) : 0.0, Sd = in ? static_cast<double>(hi_f(q.w[1])) : 0.0;
+        bad |= __any(!(St >= 0.0 && St < __builtin_inf() && Sd >= 0.0 && Sd < __builtin_inf())) != 0;
+        const float nKt = fmaxf(Kt, wave_max((St > 0.0) ? kt : neg_inf()));
+        const float nKd = fmaxf(Kd, wave_max((Sd > 0.0) ? kd : neg_inf()));
+        Zt = ((Zt > 0.0) ? ldexp(Zt, kdiff(Kt, nKt)) : Zt) + wave_sum((St > 0.0) ? ldexp(St, kdiff(kt, nKt)) : 0.0);
+        Zd = ((Zd > 0.0) ? ldexp(Zd, kdiff(Kd, nKd)) : Zd) + wave_sum((Sd > 0.0) ? ldexp(Sd, kdiff(kd, nKd)) : 0.0);
+        Kt = nKt;
+        Kd = nKd;
+    }
+    r.usable = !bad && Zt > 0.0 && Zd > 0.0 && Zt < __builtin_inf() && Zd < __builtin_inf() && Kt < __builtin_inff() &&
+               Kd < __builtin_inff();
+    r.lse2_t = static_cast<double>(Kt) + log2(Zt);
+    r.lse2_d = static_cast<double>(Kd) + log2(Zd);
+    return r;
+}
+
+// further rounds of 64 members of a sum of float64 words (teams of more than 64)
+struct SumMore { double sum; bool ok; };
+__device__ __noinline__ SumMore sum_f64_more_rounds(const unsigned long long* p2, int GW, unsigned limit, double sum) {
+    const int lane = threadIdx.x & 63;
+    SumMore r{sum, true};
+    for (int base = 64; base < GW; base += 64) {
+        const WordsN<1> q = repoll_n<1>(p2, GW, base, limit);
+        r.ok &= q.ok;
+        r.sum += wave_sum((base + lane < GW) ? __longlong_as_double(static_cast<long long>(q.w[0])) : 0.0);
+    }
+    return r;
+}
+
+// The pointwise form of App. C.2 over this wavefront's slice of one pair, from the rows' log2-sum-exp2:
+// p = 2^(a log2e - L_t), q likewise, sum of p log2(2p/s) + q log2(2q/s).  Not pipelined: used for the
+// few pairs whose entropy-form result is below the floor.
+template <int NV, bool ALIGNED>
+__device__ __noinline__ float js_pointwise_slice(const char* tptr, const char* dptr, long V, int sl0, int sl_end,
+                                                 int sl_last, float Lt, float Ld) {
+    float acc = 0.0f;
+#pragma unroll 1
+    for (int k = 0; k < NV; ++k) {
+        const int sk = sl0 + 64 * k;
+        const bool own = sk < sl_end;
+        const long sl = own ? sk : sl_last;
+        uint4 ra = load_slot<true, ALIGNED, false>(tptr, sl, V);
+        uint4 rb = load_slot<true, ALIGNED, false>(dptr, sl, V);
+        if (!own) { ra = slot_neg_inf<true>(); rb = slot_neg_inf<true>(); }
+        float a[8], c[8];
+        unpack<true>(ra, a);
+        unpack<true>(rb, c);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float p = hw_exp2(fmaf(a[e], kLog2e, -Lt));
+            const float q = hw_exp2(fmaf(c[e], kLog2e, -Ld));
+            const float d = p - q, sum = p + q;
+            // p = q = 0: 0 * inf = NaN, which max() drops (u = tiny, v = 2, both weights zero)
+            const float inv = __builtin_amdgcn_rcpf(sum);
+            const float u = fmaxf(fmaf(d, inv, 1.0f), 2e-38f), v = fmaxf(2.0f - u, 2e-38f);
+            acc = fmaf(p, hw_log2(u), acc);
+            acc = fmaf(q, hw_log2(v), acc);
+        }
+    }
+    return wave_sumf(acc);
+}
+
 template <int I> struct SetId { static constexpr int value = I; };
+#ifndef FSD_JSE_LDS_CHUNKS
+#define FSD_JSE_LDS_CHUNKS 2
+#endif
 
 // wavefronts per SIMD the register allocation has to leave room for
 constexpr int pair_kernel_waves(bool bf16, int nv, int mode) {
-    return (bf16 && nv == 5 && (mode == MODE_JS || mode == MODE_TV)) ? 2 : 1;
+    return (bf16 && nv == 5 && (mode == MODE_JS || mode == MODE_TV || mode == MODE_JSE)) ? 2 : 1;
 }
 
-// TSHARED (binary32 only): target rows are shared between pairs (a tree) and are loaded to stay cached.
-// The bfloat16 kernels take that decision at run time; in the binary32 ones, whose loads run a
-// step ahead into rotating registers, the two-way code costs a tenth of the kernel's time.
+// TSHARED: target rows are shared between pairs (a tree) and are loaded to stay cached (a template
+// parameter, not a run-time decision: see load_item).
 template <bool BF16, int NV, int MODE, bool ALIGNED, bool TSHARED = false>
 __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(pair_kernel_waves(BF16, NV, MODE))))
 void pair_kernel(PairParams P) {
     constexpr int VE = Slot<BF16>::VE;
     constexpr int ES = BF16 ? 2 : 4;
-    constexpr bool TWO_PHASE = (MODE == MODE_JS || MODE == MODE_TV || MODE == MODE_KLP);
+    constexpr bool TWO_PHASE = (MODE == MODE_JS || MODE == MODE_TV || MODE == MODE_KLP || MODE == MODE_JSE);
+    constexpr bool JSE = (MODE == MODE_JSE);   // bfloat16 only (the host sends binary32 JS to MODE_JS)
     constexpr int NE = TWO_PHASE ? NV * VE : 1;   // exponentials kept per row and lane
     constexpr int PW = (MODE == MODE_TV || MODE == MODE_KLP) ? 2 : 1;   // divergence words a member posts (two sums each)
     constexpr int FW = TWO_PHASE ? PW : 4;          // words per member the finisher reads
@@ -214,13 +325,31 @@ void pair_kernel(PairParams P) {
     // NB sets of kept exponentials, named by SetId<> so that every index is a constant and the
     // arrays stay in registers; accessed four at a time
     float et[NB][NE], ed[NB][NE];
+    // The entropy form needs a few registers more than the two sets leave: the last NL chunks of each set
+    // live in LDS instead (each lane reads back only what it wrote itself: no barrier; LDS traffic is counted
+    // apart from the loads of the logits, so waiting for it does not wait for the prefetch as a spill would)
+    constexpr int NL = JSE ? FSD_JSE_LDS_CHUNKS : 0;
+    __shared__ float4 lds_keep[NL ? NB * NL * 2 * kWG : 1];
     auto put4 = [&](auto S, int c, const float (&t4)[4], const float (&d4)[4]) __attribute__((always_inline)) {
         constexpr int s_ = decltype(S)::value;
+        if (NL > 0 && c >= NC - NL) {
+            float4* const at = lds_keep + ((s_ * NL + (c - (NC - NL))) * 2) * kWG + threadIdx.x;
+            at[0] = make_float4(t4[0], t4[1], t4[2], t4[3]);
+            at[kWG] = make_float4(d4[0], d4[1], d4[2], d4[3]);
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < 4; ++i) { et[s_][4 * c + i] = t4[i]; ed[s_][4 * c + i] = d4[i]; }
     };
     auto get4 = [&](auto S, int c, float (&t4)[4], float (&d4)[4]) __attribute__((always_inline)) {
         constexpr int s_ = decltype(S)::value;
+        if (NL > 0 && c >= NC - NL) {
+            const float4* const at = lds_keep + ((s_ * NL + (c - (NC - NL))) * 2) * kWG + threadIdx.x;
+            const float4 a = at[0], b = at[kWG];
+            t4[0] = a.x; t4[1] = a.y; t4[2] = a.z; t4[3] = a.w;
+            d4[0] = b.x; d4[1] = b.y; d4[2] = b.z; d4[3] = b.w;
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < 4; ++i) { t4[i] = et[s_][4 * c + i]; d4[i] = ed[s_][4 * c + i]; }
     };
@@ -259,7 +388,11 @@ void pair_kernel(PairParams P) {
     auto row_ptrs_bj = [&](int pair, int b, int j, const char*& tptr, const char*& dptr) __attribute__((always_inline)) {
         int trow = j;
         if (P.parent) {
-            const int par = P.parent[pair];
+            // an input nobody writes, read at an address all lanes share: through the constant address
+            // space it is a scalar load, which is not counted with the vector loads (waiting for a vector
+            // load here would wait for every request in flight, and make every later wait conservative)
+            typedef const int __attribute__((address_space(4))) * ConstInts;
+            const int par = ((ConstInts)(P.parent))[pair];
             trow = (par >= -1 && par < j) ? par + 1 : 0;   // invalid parents are reported by the next kernel
         }
         tptr = P.target + (static_cast<size_t>(b) * (P.rows + 1) + trow) * static_cast<size_t>(P.V) * ES;
@@ -295,33 +428,15 @@ void pair_kernel(PairParams P) {
         row_ptrs_bj(pair, load_b, load_j, tptr, dptr);
         // A draft row is read once.  So is a target row of a chain (but for the one the token is drawn
         // from); in a tree the children of a node share their parent's target row, which should stay
-        // cached.
-        if constexpr (BF16) {
-            if (P.parent == nullptr) {
+        // cached (TSHARED).  One copy of these loads, whatever the input: with two, in the arms of a
+        // run-time branch, the compiler's count of requests in flight is no longer exact after the join,
+        // and every later wait for an exchange word also waits for most of this prefetch.
 #pragma unroll
-                for (int k = 0; k < NV; ++k) {
-                    const int sk = sl0 + 64 * k;
-                    const long sl = wanted ? (sk < sl_end ? sk : sl_last) : 0;   // not wanted: one cached slot for all lanes
-                    ra[k] = load_slot<BF16, ALIGNED, true>(tptr, sl, P.V);
-                    rb[k] = load_slot<BF16, ALIGNED, true>(dptr, sl, P.V);
-                }
-            } else {
-#pragma unroll
-                for (int k = 0; k < NV; ++k) {
-                    const int sk = sl0 + 64 * k;
-                    const long sl = wanted ? (sk < sl_end ? sk : sl_last) : 0;
-                    ra[k] = load_slot<BF16, ALIGNED, false>(tptr, sl, P.V);
-                    rb[k] = load_slot<BF16, ALIGNED, true>(dptr, sl, P.V);
-                }
-            }
-        } else {
-#pragma unroll
-            for (int k = 0; k < NV; ++k) {
-                const int sk = sl0 + 64 * k;
-                const long sl = wanted ? (sk < sl_end ? sk : sl_last) : 0;
-                ra[k] = load_slot<BF16, ALIGNED, !TSHARED>(tptr, sl, P.V);
-                rb[k] = load_slot<BF16, ALIGNED, true>(dptr, sl, P.V);
-            }
+        for (int k = 0; k < NV; ++k) {
+            const int sk = sl0 + 64 * k;
+            const long sl = wanted ? (sk < sl_end ? sk : sl_last) : 0;   // not wanted: one cached slot for all lanes
+            ra[k] = load_slot<BF16, ALIGNED, !TSHARED>(tptr, sl, P.V);
+            rb[k] = load_slot<BF16, ALIGNED, true>(dptr, sl, P.V);
         }
     };
     auto fill_unowned = [&](uint4 (&ra)[NV], uint4 (&rb)[NV]) __attribute__((always_inline)) {
@@ -332,7 +447,16 @@ void pair_kernel(PairParams P) {
                 // the slice at all?): a scalar branch skips the full slots, and only the one or two at the
                 // end of the slice go through the per-lane selection
                 if (s0 + 64 * (k + 1) > s1) {
-                    if (sl0 + 64 * k >= sl_end) { ra[k] = slot_neg_inf<BF16>(); rb[k] = slot_neg_inf<BF16>(); }
+                    if constexpr (JSE) {
+                        // (a finite logit far below everything: exponential 0 and e x = 0, where -inf gives NaN)
+                        asm volatile("");   // stays a branch: only a team's last member with slots has such lanes
+                        if (sl0 + 64 * k >= sl_end) {
+                            ra[k] = make_uint4(kJsFill, kJsFill, kJsFill, kJsFill);
+                            rb[k] = make_uint4(kJsFill, kJsFill, kJsFill, kJsFill);
+                        }
+                    } else {
+                        if (sl0 + 64 * k >= sl_end) { ra[k] = slot_neg_inf<BF16>(); rb[k] = slot_neg_inf<BF16>(); }
+                    }
                 }
             }
         }
@@ -496,15 +620,55 @@ void pair_kernel(PairParams P) {
             P.ws.pst[pair] = status;
         }
     };
+    auto finish_jse = [&](int pair, unsigned long long (&fw)[FW]) __attribute__((always_inline)) {
+        const unsigned long long* p2 = part2 + static_cast<size_t>(pair) * GW;
+        unsigned long long f[1] = {fw[0]};
+        bool ok = await_n<1>(p2, GW, 0, P.spin_limit, f);
+        double sum = wave_sum((lane < GW) ? __longlong_as_double(static_cast<long long>(f[0])) : 0.0);
+        if (GW > 64) {
+            const SumMore m = sum_f64_more_rounds(p2, GW, P.spin_limit, sum);
+            sum = m.sum;
+            ok &= m.ok;
+        }
+        double value = 0.5 * kLn2 * sum;
+        int status = ok ? 0 : FSD_ROW_INTERNAL;
+        unsigned long long state = kJsDone;
+        // below the floor (cancellation), or anything but a plain number (unusable rows, or sums the
+        // masked entries of usable rows have spoilt): the pointwise form decides, if the rows are usable
+        if (ok && (!(value >= static_cast<double>(P.js_floor)) || !(value < 1.0))) {
+            asm volatile("");   // stays a branch
+            const RowNorms n = row_norms(part1 + static_cast<size_t>(pair) * GW * N1, GW, P.spin_limit);
+            if (!n.ok) status |= FSD_ROW_INTERNAL;
+            else if (!n.usable) status |= FSD_ROW_NONFINITE;
+            else state = pack2(static_cast<float>(n.lse2_t), static_cast<float>(n.lse2_d));
+        }
+        if (value < 0.0) value = 0.0;
+        if (status) value = __builtin_nan("");
+        if (lane == 0) {
+            P.ws.lse2[2 * pair] = 0.0;
+            P.ws.lse2[2 * pair + 1] = 0.0;
+            if (state == kJsDone) {
+                P.ws.div[pair] = static_cast<float>(value);
+                if (P.user_div) P.user_div[pair] = static_cast<float>(value);
+                P.ws.pst[pair] = status;
+                if (status & FSD_ROW_INTERNAL) atomicOr(P.ws.counters + 1, 1u);
+            }
+            // the word every member of the team looks at before it leaves
+            post64(P.ws.state + pair, state);
+        }
+    };
     auto finish = [&](int pair, unsigned long long (&fw)[FW]) __attribute__((always_inline)) {
-        if constexpr (TWO_PHASE) finish_two_phase(pair, fw); else finish_single_pass(pair, fw);
+        if constexpr (JSE) finish_jse(pair, fw);
+        else if constexpr (TWO_PHASE) finish_two_phase(pair, fw);
+        else finish_single_pass(pair, fw);
     };
 
     // ---- state of the previous pair, whose phase 2 is still to come (two-phase modes)
-    struct Pend { int pair; float kt, kd; bool mass_t, mass_d, mask; float wsum, dmax; };   // wsum, dmax: pointwise KL only
+    struct Pend { int pair; float kt, kd; bool mass_t, mass_d, mask; float wsum, dmax, st, sd; };   // wsum, dmax: pointwise KL (entropy-form JS: the sums of e x)
     Pend pend[LAG];   // [0] the last step's pair ... [LAG-1] the one whose phase 2 is due
 #pragma unroll
-    for (int i = 0; i < LAG; ++i) pend[i] = Pend{-1, 0.0f, 0.0f, false, false, false, 0.0f, 0.0f};
+    for (int i = 0; i < LAG; ++i) pend[i] = Pend{-1, 0.0f, 0.0f, false, false, false, 0.0f, 0.0f, 0.0f, 0.0f};
+    bool js_clamp2 = false;   // entropy-form JS: phase 2 keeps u above the smallest normal number (see phase2)
     // pairs this wavefront has to finish: fin[0] now, fin[i] i steps from now.  A two-phase pair
     // is finished NF steps after its phase 1.  Whoever starts step n has merged the team words of
     // step n - 1, so every member has ended step n - 2 - LAG and with it phase 2 of the pair of step
@@ -564,7 +728,59 @@ void pair_kernel(PairParams P) {
         const float ftc = fmaxf(ft, 0x1p-80f), fdc = fmaxf(fd, 0x1p-80f);   // max() drops NaN: see below
         const float cq = (ftc == fdc) ? 1.0f : fdc * __builtin_amdgcn_rcpf(ftc);
         unsigned long long word[PW];
-        if constexpr (MODE == MODE_TV) {
+        if constexpr (JSE) {
+            // U = sum u log2 u with u = e_t + c e_d = (p + q)/ft
+            float acc = 0.0f;
+            if (!js_clamp2) {
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
+                    float t4[4], d4[4];
+                    get4(S, c, t4, d4);
+                    // (the four logarithms first: a logarithm's result cannot be used by the very next instruction)
+                    float u[4], l[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) u[i] = fmaf(d4[i], cq, t4[i]);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) l[i] = hw_log2(u[i]);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) acc = fmaf(u[i], l[i], acc);
+                }
+                // an entry without mass in either row (both exponentials flushed to zero, or masked) gives
+                // 0 log 0 = NaN: from then on this wavefront keeps u above the smallest normal number, whose
+                // term is nothing, at one more instruction per entry (the kept exponentials are still there,
+                // so this pair is done again right away)
+                if (__any(acc != acc)) js_clamp2 = true;
+            }
+            if (js_clamp2) {
+                acc = 0.0f;
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
+                    float t4[4], d4[4];
+                    get4(S, c, t4, d4);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float u = fmaxf(fmaf(d4[i], cq, t4[i]), 0x1p-126f);
+                        acc = fmaf(u, hw_log2(u), acc);
+                    }
+                }
+            }
+            acc = wave_sumf(acc);
+            // the member's share C = f_t [A_t + c A_d - U + W + c S_d log2 c] in float64 (products of two
+            // binary32 numbers are exact there).  log2 c = exponent + log2 of the mantissa in [1/2, 1), which
+            // the hardware logarithm gives to 6e-8 absolute (and c = 1 gives exactly 0)
+            const double dc = static_cast<double>(cq);
+            const double l2c = static_cast<double>(__builtin_amdgcn_frexp_expf(cq)) +
+                               static_cast<double>(hw_log2(__builtin_amdgcn_frexp_mantf(cq)));
+            const double csd = dc * static_cast<double>(pp.sd);
+            double share = static_cast<double>(pp.wsum) + dc * static_cast<double>(pp.dmax);
+            share -= static_cast<double>(acc);
+            share += static_cast<double>(pp.st) + csd;
+            share += csd * l2c;
+            share *= static_cast<double>(ftc);
+            if (ft != ft || fd != fd) share = static_cast<double>(ft + fd);   // an unusable row stays NaN (max() drops it above)
+            if (!ok) share = __builtin_nan("");
+            word[0] = dbits(share);
+        } else if constexpr (MODE == MODE_TV) {
             float A = 0.0f, Bn = 0.0f, MA = 0.0f;
 #pragma unroll
             for (int c = 0; c < NC; ++c) {
@@ -726,7 +942,7 @@ void pair_kernel(PairParams P) {
         wave_max2(mt, md);
         const float kt = (mt == neg_inf()) ? 0.0f : ceilf(mt * kLog2e);
         const float kd = (md == neg_inf()) ? 0.0f : ceilf(md * kLog2e);
-        float st = 0.0f, sd = 0.0f, wacc = 0.0f, dmax = neg_inf();
+        float st = 0.0f, sd = 0.0f, wacc = 0.0f, dmax = JSE ? 0.0f : neg_inf();
 #pragma unroll
         for (int k = 0; k < NV; ++k) {
             float a[VE], c[VE];
@@ -735,12 +951,17 @@ void pair_kernel(PairParams P) {
             float xa_[VE], xb_[VE];
 #pragma unroll
             for (int e = 0; e < VE; ++e) {
-                const float xa = hw_exp2(fmaf(a[e], kLog2e, -kt));
-                const float xb = hw_exp2(fmaf(c[e], kLog2e, -kd));
+                const float ya = fmaf(a[e], kLog2e, -kt), yb = fmaf(c[e], kLog2e, -kd);
+                const float xa = hw_exp2(ya);
+                const float xb = hw_exp2(yb);
                 xa_[e] = xa;
                 xb_[e] = xb;
                 st += xa;
                 sd += xb;
+                if constexpr (JSE) {   // the entropies' sums of e x (wacc: target, dmax: draft)
+                    wacc = fmaf(xa, ya, wacc);
+                    dmax = fmaf(xb, yb, dmax);
+                }
                 if constexpr (MODE == MODE_KL || MODE == MODE_KLP) {
                     const float diff = a[e] - c[e];
                     dmax = fmaxf(dmax, diff);   // +inf iff the draft masks an entry the target does not
@@ -763,6 +984,26 @@ void pair_kernel(PairParams P) {
                 }
             }
         }
+        if constexpr (JSE) {
+            // A -inf logit is legal (a masked entry) and has the exponential 0, but its 0 * x is NaN: the sums
+            // of e x are then formed once more from the kept exponentials, as e log2 e with 0 log 0 = 0 (the
+            // logits' registers are free by now; the hardware logarithm of e is x to 1e-7)
+            if (__any((wacc != wacc) || (dmax != dmax))) {
+                asm volatile("");   // keeps this a branch (as straight-line code with selections it would run every step)
+                wacc = 0.0f;
+                dmax = 0.0f;
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
+                    float t4[4], d4[4];
+                    get4(SC, c, t4, d4);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        wacc = fmaf(t4[i], hw_log2((t4[i] == 0.0f) ? 1.0f : t4[i]), wacc);   // NaN stays NaN
+                        dmax = fmaf(d4[i], hw_log2((d4[i] == 0.0f) ? 1.0f : d4[i]), dmax);
+                    }
+                }
+            }
+        }
         PT(1);   // reductions + exp pass
         // ---- the registers that held the logits are free: fetch the next pair (the request is
         // unconditional: the last step asks for one slot of its own pair, which the caches hold)
@@ -780,6 +1021,7 @@ void pair_kernel(PairParams P) {
         if constexpr (TWO_PHASE) {
             wave_sumf2(st, sd);
             if constexpr (MODE == MODE_KLP) { wacc = wave_sumf(wacc); dmax = wave_max(dmax); }
+            if constexpr (JSE) wave_sumf2(wacc, dmax);
             mine = (lane == 0) ? w0 : pack2(st, sd);
         } else {
             const double pst_ = wave_sum(static_cast<double>(st));
@@ -807,7 +1049,7 @@ void pair_kernel(PairParams P) {
             asm volatile("" ::"v"(mine), "v"(post_at));
 #pragma unroll
             for (int i = LAG - 1; i > 0; --i) pend[i] = pend[i - 1];
-            pend[0] = Pend{pair, kt, kd, (st > 0.0f) || (st != st), (sd > 0.0f) || (sd != sd), dmax == __builtin_inff(), wacc, dmax};
+            pend[0] = Pend{pair, kt, kd, (st > 0.0f) || (st != st), (sd > 0.0f) || (sd != sd), dmax == __builtin_inff(), wacc, dmax, st, sd};
         }
         // ---- finishing duties: the pair whose turn has come, then note this pair if it is ours
         if (fpair >= 0) finish(fpair, fw);
@@ -878,8 +1120,75 @@ void pair_kernel(PairParams P) {
         for (; pair < pair_end; pair += pstep) one_step(SetId<0>{}, SetId<1>{}, pair);
         if (sp_pair >= 0) finish_now(sp_pair);
     }
-#ifdef FSD_PHASE_TIMING
     PT(6);   // drain
+    if constexpr (JSE) {
+        // ---- the team's pairs whose entropy-form result was below the floor, once more in the pointwise
+        // form.  Every member walks the team's pairs in the same order and waits (bounded) for each pair's
+        // state word; member (index mod GW) adds the team's partial sums in member order.
+        const int n_mine = (pair_end > pair0) ? (pair_end - pair0 + pstep - 1) / pstep : 0;
+        for (int base = 0; base < n_mine; base += 64) {
+            const int idx = base + lane;
+            const bool valid = idx < n_mine;
+            const unsigned long long* sp = P.ws.state + (valid ? pair0 + idx * pstep : pair0);
+            unsigned long long sw = read64(sp);
+            unsigned polls = 0;
+            while (__any(valid && sw == 0)) {
+                if (polls++ >= P.spin_limit) break;
+                __builtin_amdgcn_s_sleep(2);
+                sw = read64(sp);
+            }
+            if (__any(valid && sw == 0)) {
+                if (lane == 0) atomicOr(P.ws.counters + 1, 1u);   // a finisher never came: the call reports it
+            }
+            unsigned long long todo = __ballot(valid && sw != 0 && sw != kJsDone);
+            while (todo) {
+                const int i = __builtin_ctzll(todo);
+                todo &= todo - 1;
+                const int rp = pair0 + (base + i) * pstep;
+                const unsigned lo = __builtin_amdgcn_readlane(static_cast<unsigned>(sw), i);
+                const unsigned hi = __builtin_amdgcn_readlane(static_cast<unsigned>(sw >> 32), i);
+                const char *tptr, *dptr;
+                row_ptrs(rp, tptr, dptr);
+                const float part = js_pointwise_slice<NV, ALIGNED>(tptr, dptr, P.V, sl0, sl_end, sl_last, __uint_as_float(lo),
+                                                                   __uint_as_float(hi));
+                // the partial replaces this member's sums of exponentials, which nobody reads any more once the
+                // pair's state word is out (a sum is never -1)
+                unsigned long long* const p2 = part1 + static_cast<size_t>(rp) * GW * N1 + 1;
+                if (lane == 0) post64(p2 + member * N1, pack2(part, -1.0f));
+                if ((base + i) % GW == member) {
+                    double sum = 0.0;
+                    bool ok = true;
+                    for (int mb = 0; mb < GW; mb += 64) {
+                        const int m = mb + lane;
+                        const bool in = m < GW;
+                        const unsigned long long* wp = p2 + (in ? m : GW - 1) * N1;
+                        unsigned long long v = read64(wp);
+                        unsigned tries = 0;
+                        while (__any(hi_f(v) != -1.0f)) {
+                            if (tries++ >= P.spin_limit) { ok = false; break; }
+                            __builtin_amdgcn_s_sleep(2);
+                            v = read64(wp);
+                        }
+                        sum += wave_sum(in ? static_cast<double>(lo_f(v)) : 0.0);
+                    }
+                    double value = 0.5 * kLn2 * sum;
+                    int status = 0;
+                    if (value != value) status |= FSD_ROW_NONFINITE;
+                    if (!ok) status |= FSD_ROW_INTERNAL;
+                    if (value < 0.0) value = 0.0;
+                    if (status) value = __builtin_nan("");
+                    if (lane == 0) {
+                        P.ws.div[rp] = static_cast<float>(value);
+                        if (P.user_div) P.user_div[rp] = static_cast<float>(value);
+                        P.ws.pst[rp] = status;
+                        if (!ok) atomicOr(P.ws.counters + 1, 1u);
+                    }
+                }
+            }
+        }
+    }
+#ifdef FSD_PHASE_TIMING
+    PT(7);   // second evaluations (entropy-form JS)
     if (P.dbg && lane == 0) {
         unsigned long long* o = P.dbg + (static_cast<size_t>(blockIdx.x) * kWavesPerWG + wave) * 10;
         for (int i = 0; i < 8; ++i) o[i] = pt_acc[i];

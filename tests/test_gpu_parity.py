@@ -394,7 +394,11 @@ def test_rfsd_reduces_to_strict_sd_and_to_fsd(torch_cuda, oracle):
         f = run_chain(torch_cuda, inp, 1e9, div, seed=12, offset=5)
         g = run_rfsd(torch_cuda, inp, 1e9, div, seed=12, offset=5)
         assert (g["accept_len"] == 6).all() and (g["out_tokens"] == f["out_tokens"]).all()
-        assert np.array_equal(g["divergences"], f["divergences"])
+        if div == fsd.DIV_JS:
+            # (bfloat16 JS: FSD evaluates the entropy form, reducible FSD the pointwise one)
+            assert np.allclose(g["divergences"], f["divergences"], rtol=0, atol=2e-6)
+        else:
+            assert np.array_equal(g["divergences"], f["divergences"])
 
 
 def test_config_c2_rfsd(torch_cuda, oracle):
@@ -698,9 +702,83 @@ def test_reduction_kernel_shapes_agree(torch_cuda, oracle):
                     g = run_chain(torch_cuda, inp, 0.1, div, seed=9, offset=1)
                     what = f"{dtype} div={div} slots per lane {nv}"
                     assert (g["accept_len"] == ref["accept_len"]).all() and (g["out_tokens"] == ref["out_tokens"]).all(), what
-                    assert np.allclose(g["divergences"], ref["divergences"], rtol=2e-6, atol=1e-7), what
+                    # (the default bfloat16 JS kernel evaluates the entropy form, the hook's shapes the
+                    # pointwise one: they agree to the former's absolute error)
+                    atol = 2e-6 if (dtype == "bf16" and div == fsd.DIV_JS) else 1e-7
+                    assert np.allclose(g["divergences"], ref["divergences"], rtol=2e-6, atol=atol), what
     finally:
         fsd.debug_set_shape(0, 0)
+
+
+def _js_inputs():
+    """(name, target, draft, cand) cases for the two evaluations of bfloat16 JS: rows from nearly equal to far
+    apart, masked entries on one and on both sides, bit-identical rows, a vocabulary that is no multiple of the
+    slot size, the headline vocabulary, and a team of more than 64 wavefronts"""
+    cases = []
+    for name, (B, K, V, kind, sigma, seed) in (("V=40000 sigma 0.02..3", (3, 6, 40000, "peaked", (0.02, 3.0), 5)),
+                                               ("V=4097", (2, 4, 4097, "gauss2", (0.1, 2.0), 6)),
+                                               ("V=128256", (2, 3, 128256, "peaked", (0.25, 4.0), 7)),
+                                               ("V=524288", (1, 2, 524288, "peaked", (0.1, 1.0), 8))):
+        inp = synth.chain_inputs(B, K, V, "bf16", kind, sigma, seed=seed)
+        cases.append((name, inp["target"], inp["draft"], inp["cand"]))
+    inp = synth.chain_inputs(3, 4, 40000, "bf16", "peaked", 1.0, seed=9)
+    t, d = inp["target"].copy(), inp["draft"].copy()
+    t[0, :, 100:5000] = 0xFF80
+    d[0, :, 100:5000] = 0xFF80       # masked on both sides
+    d[2, :, 7000:30000] = 0xFF80     # masked by the draft only
+    d[1] = t[1, :4]                  # bit-identical rows
+    cases.append(("masks and identical rows", t, d, inp["cand"]))
+    return cases
+
+
+def test_js_bf16_both_evaluations(torch_cuda, oracle):
+    """bfloat16 JS: the entropy form alone (floor 0), the pointwise second evaluation alone (floor +inf), the
+    pointwise kernel, and the default mix, each against the oracle.  The entropy form is held to its absolute
+    error, everything else to the relative bar."""
+    try:
+        for name, t, d, cand in _js_inputs():
+            o = oracle.verify_chain(t, d, cand, 0.1, fsd.DIV_JS, seed=3, offset=2)
+            inp = dict(target=t, draft=d, cand=cand)
+            fin = np.isfinite(o["divs"])
+            for what, floor, exact in (("entropy form", 0.0, False), ("second evaluation", float("inf"), False),
+                                       ("pointwise kernel", None, True), ("default", None, False)):
+                prev = fsd.debug_set_js_floor(floor) if floor is not None else None
+                fsd.debug_set_exact_js(exact)
+                print(f"{name}: {what}", flush=True)
+                g = run_chain(torch_cuda, inp, 0.1, fsd.DIV_JS, seed=3, offset=2)
+                if prev is not None:
+                    fsd.debug_set_js_floor(prev)
+                fsd.debug_set_exact_js(False)
+                assert (g["row_status"] == o["row_status"]).all(), f"{name} {what}"
+                assert (np.isfinite(g["divergences"]) == fin).all(), f"{name} {what}"
+                err = np.abs(g["divergences"].astype(np.float64) - o["divs"])[fin]
+                print(f"   max abs error {err.max():.3e}", flush=True)
+                if what == "entropy form":
+                    assert err.max() <= 2e-6, f"{name} {what}: {err.max()}"
+                else:
+                    env = pu.Envelope("bf16")
+                    pu.check_chain(g, o, 0.1, pu.rel_tol("bf16"), f"{name} {what}", envelope=env)
+                if what != "entropy form" and name == "masks and identical rows":
+                    assert (g["divergences"][1] == 0.0).all(), f"{name} {what}: identical rows"
+    finally:
+        fsd.debug_set_exact_js(False)
+        fsd.debug_set_js_floor(2e-3)
+
+
+def test_js_bf16_second_evaluation_in_a_tree(torch_cuda, oracle):
+    """the second evaluation where pairs share target rows: a tree whose drafts are close to their targets, so
+    that most nodes fall below the floor, with the floor at its default and at +inf"""
+    inp = synth.tree_inputs(3, 12, 40000, "bf16", 0.05, seed=21)
+    md = int(inp["max_depth"])
+    o = oracle.verify_tree(inp["target"], inp["draft"], inp["node_tokens"], inp["parent"], md, 0.001, fsd.DIV_JS, seed=4)
+    assert (o["divs"] < 2e-3).mean() > 0.5
+    try:
+        for floor in (2e-3, float("inf")):
+            fsd.debug_set_js_floor(floor)
+            g = run_tree(torch_cuda, inp, 0.001, fsd.DIV_JS, md, seed=4)
+            pu.check_tree(g, o, 0.001, pu.rel_tol("bf16"), f"tree, floor {floor}", envelope=pu.Envelope("bf16"))
+    finally:
+        fsd.debug_set_js_floor(2e-3)
 
 
 # ------------------------------------------------------------------ random shapes
