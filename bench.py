@@ -59,6 +59,10 @@ def main() -> int:
     ap.add_argument("--settle-ms", type=float, default=300.0,
                     help="untimed calls before the warm-up until the device has been busy this long (0 = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--phase-split", action="store_true",
+                    help="load the development library built with `python -m paper_2502_20704_amd.build "
+                         "--phase-timing` and also print the reduction kernel's cycles per phase (its counters "
+                         "cost time: the rates of such a run are not the headline)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (reference kernel for scaling rocprofv3's byte counters)")
     args = ap.parse_args()
@@ -75,6 +79,14 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         return 2
+    if args.phase_split:
+        from paper_2502_20704_amd import binding, build as fsd_build
+
+        if not os.path.exists(fsd_build.LIB_PHASE_TIMING):
+            print(f"{fsd_build.LIB_PHASE_TIMING} is missing: python -m paper_2502_20704_amd.build --phase-timing",
+                  file=sys.stderr)
+            return 2
+        binding.LIB_PATH = fsd_build.LIB_PHASE_TIMING
     fsd.library()
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.config]
@@ -170,6 +182,34 @@ def main() -> int:
     n_ev, k1_mean_ms, k1_min_ms = fsd.profile_collect()
     fsd.profile_enable(False)
 
+    phase_split = None
+    if args.phase_split:
+        # one more call with a buffer the kernel's wavefronts write their cycle counts to: per wavefront,
+        # cycles between the marks in the step (summed over its steps), its start time and its lifetime
+        import ctypes
+
+        lib = fsd.library()
+        lib.fsd_debug_set_dbg.argtypes = [ctypes.c_void_p]
+        lib.fsd_debug_set_dbg.restype = None
+        dbg = torch.zeros(16384 * 10, dtype=torch.int64, device="cuda")
+        torch.cuda.synchronize()
+        lib.fsd_debug_set_dbg(ctypes.c_void_p(dbg.data_ptr()))
+        step(0)
+        torch.cuda.synchronize()
+        lib.fsd_debug_set_dbg(None)
+        a = dbg.cpu().numpy().reshape(-1, 10)
+        a = a[a[:, 9] > 0]
+        names = ["wait for the logits + maximum pass", "exponential pass", "team merge (waiting for the team's words included)",
+                 "wave sums, request of the next pair, post", "phase 2", "finishing duty", "drain", "second evaluations"]
+        phase_split = {"wavefronts": int(len(a)), "lifetime_cycles_median": float(np.median(a[:, 9])),
+                       "mean_cycles_per_wavefront": {n: float(v) for n, v in zip(names, a[:, :8].mean(0))}}
+        print(f"reduction kernel, {len(a)} wavefronts, median lifetime {np.median(a[:, 9]):.0f} cycles "
+              f"(p10 {np.percentile(a[:, 9], 10):.0f}, p90 {np.percentile(a[:, 9], 90):.0f}); mean cycles per "
+              "wavefront between the marks of a step, summed over its steps (the compiler moves arithmetic "
+              "across the marks: neighbouring phases are only roughly apart):", file=sys.stderr)
+        for n, v in zip(names, a[:, :8].mean(0)):
+            print(f"  {n:<55} {v:>10.0f}", file=sys.stderr)
+
     positions = B * rows
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = positions * args.steps / (t1 - t0)
@@ -203,6 +243,8 @@ def main() -> int:
                      "kernel_ms_mean": k1_mean_ms, "kernel_ms_min": k1_min_ms, "launches_timed": n_ev,
                      "algorithmic_bytes_per_launch": alg_bytes},
     }
+    if phase_split:
+        result["phase_split"] = phase_split
 
     if not args.no_cpu_baseline:
         import oracle

@@ -21,14 +21,19 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = False) -> str:
-    cmd = ["hipcc", *FLAGS, "-o", LIB, SRC]
+# a development variant with cycle counters between the phases of the reduction kernel
+# (`python -m paper_2502_20704_amd.build --phase-timing`, read by `bench.py --phase-split`)
+LIB_PHASE_TIMING = os.path.join(HERE, "libfsd_phase_timing.so")
+
+
+def build(verbose: bool = False, phase_timing: bool = False) -> str:
+    lib = LIB_PHASE_TIMING if phase_timing else LIB
+    cmd = ["hipcc", *FLAGS, *(["-DFSD_PHASE_TIMING"] if phase_timing else []), "-o", lib, SRC]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":
-    build(verbose=True)
-    print(LIB)
+    print(build(verbose=True, phase_timing="--phase-timing" in sys.argv[1:]))

@@ -355,7 +355,7 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
         // per entry: 5 slots per lane instead of 4 is the most that fits two wavefronts per SIMD (256
         // registers).  The workspace is laid out for the larger team of the 4-slot shape.
         p.NV = 5;
-        p.G = static_cast<int>(team_size(p.nslots, 5));
+        p.G = static_cast<int>(team_size(p.nslots, p.NV));
         p.spm = static_cast<int>((p.nslots + p.G - 1) / p.G);
         // entropy form: whole chunks of 64 NV slots per member, so that only the last one with any
         // slots has lanes without one (those lanes cost it selections the others do not pay for)

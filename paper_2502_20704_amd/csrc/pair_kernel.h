@@ -279,9 +279,7 @@ __device__ __noinline__ float js_pointwise_slice(const char* tptr, const char* d
 }
 
 template <int I> struct SetId { static constexpr int value = I; };
-#ifndef FSD_JSE_LDS_CHUNKS
-#define FSD_JSE_LDS_CHUNKS 2
-#endif
+template <bool B> struct BoolTag { static constexpr bool value = B; };
 
 // wavefronts per SIMD the register allocation has to leave room for
 constexpr int pair_kernel_waves(bool bf16, int nv, int mode) {
@@ -297,6 +295,7 @@ void pair_kernel(PairParams P) {
     constexpr int ES = BF16 ? 2 : 4;
     constexpr bool TWO_PHASE = (MODE == MODE_JS || MODE == MODE_TV || MODE == MODE_KLP || MODE == MODE_JSE);
     constexpr bool JSE = (MODE == MODE_JSE);   // bfloat16 only (the host sends binary32 JS to MODE_JS)
+    constexpr bool SHARE = JSE && TSHARED;     // consecutive pairs with one target row share its phase 1 (see step)
     constexpr int NE = TWO_PHASE ? NV * VE : 1;   // exponentials kept per row and lane
     constexpr int PW = (MODE == MODE_TV || MODE == MODE_KLP) ? 2 : 1;   // divergence words a member posts (two sums each)
     constexpr int FW = TWO_PHASE ? PW : 4;          // words per member the finisher reads
@@ -311,7 +310,8 @@ void pair_kernel(PairParams P) {
     // every member's words have long been posted when they are looked at.  That takes a third set
     // of kept exponentials: the binary32 kernels with 8 slots per lane run one wavefront per SIMD
     // and have the registers.  (The bfloat16 kernels run two per SIMD and are bound by vector-ALU
-    // issue: a third set kept in LDS removed their waits and left their time unchanged.)
+    // issue: a third set kept in LDS removed their waits and left their time unchanged, for the
+    // pointwise kernels and again for the entropy-form one at 4 slots per lane.)
     constexpr int LAG = (TWO_PHASE && !BF16 && NV == 8) ? 2 : 1;
     constexpr int NB = LAG + 1;                      // sets of kept exponentials
     constexpr int NC = (NE + 3) / 4;                 // chunks of four per row
@@ -328,7 +328,7 @@ void pair_kernel(PairParams P) {
     // The entropy form needs a few registers more than the two sets leave: the last NL chunks of each set
     // live in LDS instead (each lane reads back only what it wrote itself: no barrier; LDS traffic is counted
     // apart from the loads of the logits, so waiting for it does not wait for the prefetch as a spill would)
-    constexpr int NL = JSE ? FSD_JSE_LDS_CHUNKS : 0;
+    constexpr int NL = JSE ? (TSHARED ? 3 : 2) : 0;   // (the least that leaves no register spilled, per variant)
     __shared__ float4 lds_keep[NL ? NB * NL * 2 * kWG : 1];
     auto put4 = [&](auto S, int c, const float (&t4)[4], const float (&d4)[4]) __attribute__((always_inline)) {
         constexpr int s_ = decltype(S)::value;
@@ -416,6 +416,9 @@ void pair_kernel(PairParams P) {
     const int sl_last = (s1 > s0) ? static_cast<int>(s1) - 1 : 0;
     const int sl_end = static_cast<int>(s1);
     const bool fill_needed = s0 + NV * 64 > s1;   // wavefront-uniform: some lane lacks a slot
+    // target rows of the pair in work, of the one before it and of the one requested last (entropy-form JS on
+    // a tree: a pair whose target row is its predecessor's takes over that row's exponentials and sums)
+    const char *tp_prev = nullptr, *tp_cur = nullptr, *tp_next = nullptr;
     auto load_item = [&](uint4 (&ra)[NV], uint4 (&rb)[NV], int pair, bool wanted = true) __attribute__((always_inline)) {
         const char *tptr, *dptr;
         // the requests come in the order of the team's pairs (the last one may be repeated)
@@ -426,6 +429,7 @@ void pair_kernel(PairParams P) {
             if (load_j >= P.rows) { load_j -= P.rows; ++load_b; }
         }
         row_ptrs_bj(pair, load_b, load_j, tptr, dptr);
+        tp_next = tptr;
         // A draft row is read once.  So is a target row of a chain (but for the one the token is drawn
         // from); in a tree the children of a node share their parent's target row, which should stay
         // cached (TSHARED).  One copy of these loads, whatever the input: with two, in the arms of a
@@ -929,60 +933,95 @@ void pair_kernel(PairParams P) {
         asm volatile("" ::: "memory");
         fill_unowned(ra, rb);
         // ---- phase 1: maximum, then sums of 2^(z log2e - k) with k = ceil(max log2e)
-        float mt = neg_inf(), md = neg_inf();
+        // SHARE (entropy-form JS on a tree): the children of a node come one after the other and share their
+        // target row.  A pair whose target row is the previous pair's takes that row's exponentials from
+        // the previous step's set, and its reference exponent and sums from that step's record: half of
+        // phase 1 is not computed again (the loads are still made: they hit the cache, and a request that
+        // is only made sometimes would make the count of requests in flight inexact).
+        tp_prev = tp_cur;
+        tp_cur = tp_next;
+        const bool same_target = SHARE && iter > 0 && tp_cur == tp_prev;
+        float kt, kd, st = 0.0f, sd = 0.0f, wacc = 0.0f, dmax = JSE ? 0.0f : neg_inf();
+        auto phase1 = [&](auto SAME_T) __attribute__((always_inline)) {
+            constexpr bool SAME = decltype(SAME_T)::value;
+            float mt = neg_inf(), md = neg_inf();
 #pragma unroll
-        for (int k = 0; k < NV; ++k) {
-            float a[VE], c[VE];
-            unpack<BF16>(ra[k], a);
-            unpack<BF16>(rb[k], c);
+            for (int k = 0; k < NV; ++k) {
+                float a[VE], c[VE];
+                if constexpr (!SAME) unpack<BF16>(ra[k], a);
+                unpack<BF16>(rb[k], c);
 #pragma unroll
-            for (int e = 0; e < VE; e += 2) { mt = fmaxf(fmaxf(mt, a[e]), a[e + 1]); md = fmaxf(fmaxf(md, c[e]), c[e + 1]); }
-        }
-        PT(0);   // load wait + max pass
-        wave_max2(mt, md);
-        const float kt = (mt == neg_inf()) ? 0.0f : ceilf(mt * kLog2e);
-        const float kd = (md == neg_inf()) ? 0.0f : ceilf(md * kLog2e);
-        float st = 0.0f, sd = 0.0f, wacc = 0.0f, dmax = JSE ? 0.0f : neg_inf();
-#pragma unroll
-        for (int k = 0; k < NV; ++k) {
-            float a[VE], c[VE];
-            unpack<BF16>(ra[k], a);
-            unpack<BF16>(rb[k], c);
-            float xa_[VE], xb_[VE];
-#pragma unroll
-            for (int e = 0; e < VE; ++e) {
-                const float ya = fmaf(a[e], kLog2e, -kt), yb = fmaf(c[e], kLog2e, -kd);
-                const float xa = hw_exp2(ya);
-                const float xb = hw_exp2(yb);
-                xa_[e] = xa;
-                xb_[e] = xb;
-                st += xa;
-                sd += xb;
-                if constexpr (JSE) {   // the entropies' sums of e x (wacc: target, dmax: draft)
-                    wacc = fmaf(xa, ya, wacc);
-                    dmax = fmaf(xb, yb, dmax);
+                for (int e = 0; e < VE; e += 2) {
+                    if constexpr (!SAME) mt = fmaxf(fmaxf(mt, a[e]), a[e + 1]);
+                    md = fmaxf(fmaxf(md, c[e]), c[e + 1]);
                 }
-                if constexpr (MODE == MODE_KL || MODE == MODE_KLP) {
-                    const float diff = a[e] - c[e];
-                    dmax = fmaxf(dmax, diff);   // +inf iff the draft masks an entry the target does not
-                    if constexpr (MODE == MODE_KL) {
-                        wacc = fmaf(xa, fminf(fmaxf(diff, -FLT_MAX), FLT_MAX), wacc);
-                    } else {
-                        // only used where the pointwise terms saturate, and checked there: the median
-                        // instruction clamps in one operation (a NaN difference, -inf on both sides,
-                        // has the weight 0 either way)
-                        wacc = fmaf(xa, __builtin_amdgcn_fmed3f(diff, -FLT_MAX, FLT_MAX), wacc);
+            }
+            PT(0);   // load wait + max pass
+            if constexpr (SAME) md = wave_max(md); else wave_max2(mt, md);
+            kt = SAME ? due.kt : ((mt == neg_inf()) ? 0.0f : ceilf(mt * kLog2e));
+            kd = (md == neg_inf()) ? 0.0f : ceilf(md * kLog2e);
+#pragma unroll
+            for (int k = 0; k < NV; ++k) {
+                float a[VE], c[VE];
+                if constexpr (!SAME) unpack<BF16>(ra[k], a);
+                unpack<BF16>(rb[k], c);
+                float xa_[VE], xb_[VE];
+#pragma unroll
+                for (int e = 0; e < VE; ++e) {
+                    const float yb = fmaf(c[e], kLog2e, -kd);
+                    const float xb = hw_exp2(yb);
+                    xb_[e] = xb;
+                    sd += xb;
+                    float ya = 0.0f, xa = 0.0f;
+                    if constexpr (!SAME) {
+                        ya = fmaf(a[e], kLog2e, -kt);
+                        xa = hw_exp2(ya);
+                        xa_[e] = xa;
+                        st += xa;
+                    }
+                    if constexpr (JSE) {   // the entropies' sums of e x (wacc: target, dmax: draft)
+                        if constexpr (!SAME) wacc = fmaf(xa, ya, wacc);
+                        dmax = fmaf(xb, yb, dmax);
+                    }
+                    if constexpr (MODE == MODE_KL || MODE == MODE_KLP) {
+                        const float diff = a[e] - c[e];
+                        dmax = fmaxf(dmax, diff);   // +inf iff the draft masks an entry the target does not
+                        if constexpr (MODE == MODE_KL) {
+                            wacc = fmaf(xa, fminf(fmaxf(diff, -FLT_MAX), FLT_MAX), wacc);
+                        } else {
+                            // only used where the pointwise terms saturate, and checked there: the median
+                            // instruction clamps in one operation (a NaN difference, -inf on both sides,
+                            // has the weight 0 either way)
+                            wacc = fmaf(xa, __builtin_amdgcn_fmed3f(diff, -FLT_MAX, FLT_MAX), wacc);
+                        }
+                    }
+                }
+                if constexpr (TWO_PHASE) {
+#pragma unroll
+                    for (int h = 0; h < VE / 4; ++h) {
+                        float t4[4], d4[4];
+                        if constexpr (SAME) {
+                            get4(SP, k * (VE / 4) + h, t4, d4);   // the previous pair's target exponentials
+                        } else {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) t4[i] = xa_[4 * h + i];
+                        }
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) d4[i] = xb_[4 * h + i];
+                        put4(SC, k * (VE / 4) + h, t4, d4);
                     }
                 }
             }
-            if constexpr (TWO_PHASE) {
-#pragma unroll
-                for (int h = 0; h < VE / 4; ++h) {
-                    const float t4[4] = {xa_[4 * h], xa_[4 * h + 1], xa_[4 * h + 2], xa_[4 * h + 3]};
-                    const float d4[4] = {xb_[4 * h], xb_[4 * h + 1], xb_[4 * h + 2], xb_[4 * h + 3]};
-                    put4(SC, k * (VE / 4) + h, t4, d4);
-                }
+        };
+        if constexpr (SHARE) {
+            if (same_target) {
+                asm volatile("");
+                phase1(BoolTag<true>{});
+            } else {
+                phase1(BoolTag<false>{});
             }
+        } else {
+            phase1(BoolTag<false>{});
         }
         if constexpr (JSE) {
             // A -inf logit is legal (a masked entry) and has the exponential 0, but its 0 * x is NaN: the sums
@@ -1022,6 +1061,9 @@ void pair_kernel(PairParams P) {
             wave_sumf2(st, sd);
             if constexpr (MODE == MODE_KLP) { wacc = wave_sumf(wacc); dmax = wave_max(dmax); }
             if constexpr (JSE) wave_sumf2(wacc, dmax);
+            if constexpr (SHARE) {
+                if (same_target) { st = due.st; wacc = due.wsum; }   // the target row's sums, as the previous step formed them
+            }
             mine = (lane == 0) ? w0 : pack2(st, sd);
         } else {
             const double pst_ = wave_sum(static_cast<double>(st));

@@ -781,6 +781,23 @@ def test_js_bf16_second_evaluation_in_a_tree(torch_cuda, oracle):
         fsd.debug_set_js_floor(2e-3)
 
 
+def test_js_bf16_siblings_share_their_target_row(torch_cuda, oracle):
+    """a tree's children follow each other and share their parent's target row, whose exponentials and sums the
+    entropy-form kernel takes over from the previous pair: wide trees (many siblings), masked entries in target
+    and draft rows, and a vocabulary whose last team member owns only a few slots"""
+    for V, seed in ((40000, 31), (128256, 32), (4097, 33)):
+        inp = synth.tree_inputs(2, 20, V, "bf16", 1.0, seed=seed, depth=3, topk=8)
+        t, d = inp["target"].copy(), inp["draft"].copy()
+        t[0, :, 10:V // 3] = 0xFF80          # masked in every target row of the first tree
+        d[1, ::2, V // 2:] = 0xFF80          # masked in every other draft row of the second
+        md = int(inp["max_depth"])
+        case = dict(inp, target=t, draft=d)
+        for T in (0.05, 0.3):
+            o = oracle.verify_tree(t, d, inp["node_tokens"], inp["parent"], md, T, fsd.DIV_JS, seed=5)
+            g = run_tree(torch_cuda, case, T, fsd.DIV_JS, md, seed=5)
+            pu.check_tree(g, o, T, pu.rel_tol("bf16"), f"siblings V={V} T={T}", envelope=pu.Envelope("bf16"))
+
+
 # ------------------------------------------------------------------ random shapes
 
 def test_random_small_shapes(torch_cuda, oracle):
