@@ -338,6 +338,7 @@ struct PairParams {
     long nslots;
     int spm;                // slots per team member
     int G;
+    int nteams;             // teams of G consecutive wavefronts in the grid (set by the launch)
     unsigned spin_limit;
 #ifdef FSD_PHASE_TIMING
     unsigned long long* dbg;   // [grid][4 wavefronts][10]

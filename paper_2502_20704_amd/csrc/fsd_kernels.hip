@@ -57,11 +57,12 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 constexpr int kMaxTeam = 256;     // wavefronts per pair (merged in rounds of 64)
 int g_shape_nv = 0;               // 0 = chosen by make_plan (see fsd_debug_set_shape)
 
-// wavefronts per pair when every lane holds nv slots of each row: whole workgroups
+// wavefronts per pair when every lane holds nv slots of each row.  A team is a run of consecutive
+// wavefronts of the grid, not of whole workgroups: at V = 128256 (bfloat16, 5 slots per lane) 51
+// members do, 40 teams fit the device instead of the 39 of 52, and 512 pairs take 13 rounds, not 14.
 long team_size(long nslots, int nv) {
     const long per_wave = 64L * nv;
-    const long G = (nslots + per_wave - 1) / per_wave;
-    return (G + 3) / 4 * 4;
+    return (nslots + per_wave - 1) / per_wave;
 }
 
 bool make_plan(int B, int rows, long V, int dtype, Plan& p) {
@@ -194,15 +195,18 @@ Residency residency_of(Kernel kernel, int threads, Residency (&cache)[16]) {
 }
 
 template <bool BF16, int NV, int MODE, bool ALIGNED, bool TSHARED = false>
-void launch_pair_k(hipStream_t st, const PairParams& P) {
-    // persistent grid: whole teams only, never more than fits on the device at once
+void launch_pair_k(hipStream_t st, const PairParams& P0) {
+    // persistent grid: as many whole teams as fit on the device at once (at least one, whose workgroups
+    // fit by the limit on the team size), in whole workgroups; the wavefronts left over leave at once
     static Residency cache[16] = {};
     const Residency res = residency_of(pair_kernel<BF16, NV, MODE, ALIGNED, TSHARED>, kWG, cache);
-    const long wgs_per_team = P.G / (kWG / 64);
-    const long want = static_cast<long>(P.npairs) * wgs_per_team;
-    long cap = res.total / wgs_per_team * wgs_per_team;
-    if (cap < wgs_per_team) cap = wgs_per_team;
-    const long grid = want < cap ? want : cap;
+    const long waves_per_wg = kWG / 64;
+    long nteams = res.total * waves_per_wg / P0.G;
+    if (nteams > P0.npairs) nteams = P0.npairs;
+    if (nteams < 1) nteams = 1;
+    const long grid = (nteams * P0.G + waves_per_wg - 1) / waves_per_wg;
+    PairParams P = P0;
+    P.nteams = static_cast<int>(nteams);
     g_last_grid = static_cast<int>(grid);
     hipLaunchKernelGGL((pair_kernel<BF16, NV, MODE, ALIGNED, TSHARED>), dim3(static_cast<unsigned>(grid)), dim3(kWG), res.pad_lds, st, P);
 }

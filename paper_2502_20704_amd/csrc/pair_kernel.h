@@ -311,7 +311,8 @@ void pair_kernel(PairParams P) {
     // of kept exponentials: the binary32 kernels with 8 slots per lane run one wavefront per SIMD
     // and have the registers.  (The bfloat16 kernels run two per SIMD and are bound by vector-ALU
     // issue: a third set kept in LDS removed their waits and left their time unchanged, for the
-    // pointwise kernels and again for the entropy-form one at 4 slots per lane.)
+    // pointwise kernels and again for the entropy-form one at 4 slots per lane, also with the team's
+    // words requested a whole step before they are used.)
     constexpr int LAG = (TWO_PHASE && !BF16 && NV == 8) ? 2 : 1;
     constexpr int NB = LAG + 1;                      // sets of kept exponentials
     constexpr int NC = (NE + 3) / 4;                 // chunks of four per row
@@ -354,13 +355,20 @@ void pair_kernel(PairParams P) {
         for (int i = 0; i < 4; ++i) { t4[i] = et[s_][4 * c + i]; d4[i] = ed[s_][4 * c + i]; }
     };
     const int GW = P.G;                                   // wavefronts per pair
-    const int wgs_per_team = GW / kWavesPerWG;
-    // A team is a run of consecutive workgroups, which the dispatcher spreads over the XCDs.  (Two
+    // first exchange word of a pair in an array of n words per member
+    auto words_at = [&](int pr, int n) __attribute__((always_inline)) -> size_t {
+        return static_cast<size_t>(pr) * static_cast<size_t>(GW * n);
+    };
+    // A team is a run of GW consecutive wavefronts of the grid (workgroup boundaries do not matter: the
+    // wavefronts of a workgroup share nothing), which the dispatcher spreads over the XCDs.  (Two
     // other deals were measured at C2 and dropped: teams whose workgroups all sit on one XCD ran a
     // third slower, and teams made half of early and half of late arrivals on the compute units
-    // ended together but no sooner: the kernel is bound by vector-ALU issue either way.)
-    const int nteams = static_cast<int>(gridDim.x) / wgs_per_team;
-    const int team = static_cast<int>(blockIdx.x) / wgs_per_team;
+    // ended together but no sooner.)  The grid is rounded up to whole workgroups: the wavefronts
+    // beyond the last team leave at once.
+    const int nteams = P.nteams;
+    const int gwave = static_cast<int>(blockIdx.x) * kWavesPerWG + wave;
+    const int team = gwave / GW;
+    if (team >= nteams) return;
     // Which pairs a team takes.  A chain: every nteams-th pair.  A tree: a run of consecutive pairs,
     // because the children of a node are numbered in a row and share their target row: the second
     // child's loads then find it in the cache its first child's loads filled one step earlier.
@@ -369,8 +377,7 @@ void pair_kernel(PairParams P) {
     const int pstep = runs ? 1 : nteams;
     const int pair0 = runs ? team * per_team : team;
     const int pair_end = runs ? ((pair0 + per_team < P.npairs) ? pair0 + per_team : P.npairs) : P.npairs;
-    const int wg_in_team = static_cast<int>(blockIdx.x) % wgs_per_team;
-    const int member = wg_in_team * kWavesPerWG + wave;
+    const int member = gwave - team * GW;
     const long s0 = static_cast<long>(member) * P.spm;
     const long s1 = (s0 + P.spm < P.nslots) ? s0 + P.spm : P.nslots;
     unsigned long long* const part1 = P.ws.part1;
@@ -489,7 +496,7 @@ void pair_kernel(PairParams P) {
     // ---- finishing a pair: add what the team posted for it, in member order.  fw holds the words of
     // the first 64 members, requested earlier.
     auto finish_two_phase = [&](int pair, unsigned long long (&fw)[FW]) __attribute__((always_inline)) {
-        const unsigned long long* p2 = part2 + static_cast<size_t>(pair) * GW * PW;
+        const unsigned long long* p2 = part2 + words_at(pair, PW);
         unsigned long long f[PW];
 #pragma unroll
         for (int k = 0; k < PW; ++k) f[k] = fw[k % FW];
@@ -524,7 +531,7 @@ void pair_kernel(PairParams P) {
         if (P.want_ratio || log_domain) {
             // reducible FSD also needs the rows' normalisers: the team's phase-1 words once more, this
             // time merged in float64 (they were all posted before the divergence words read above)
-            const unsigned long long* p1 = part1 + static_cast<size_t>(pair) * GW * N1;
+            const unsigned long long* p1 = part1 + words_at(pair, N1);
             float Kt = neg_inf(), Kd = neg_inf();
             double Zt = 0.0, Zd = 0.0;
             bool ok = true;
@@ -564,7 +571,7 @@ void pair_kernel(PairParams P) {
         }
     };
     auto finish_single_pass = [&](int pair, unsigned long long (&fw)[FW]) __attribute__((always_inline)) {
-        const unsigned long long* p1 = part1 + static_cast<size_t>(pair) * GW * N1;
+        const unsigned long long* p1 = part1 + words_at(pair, N1);
         // online merge over rounds of 64 members, float64, exact rescaling between references
         float Kt = neg_inf(), Kd = neg_inf();
         double Zt = 0.0, Zd = 0.0, Wt = 0.0;
@@ -625,7 +632,7 @@ void pair_kernel(PairParams P) {
         }
     };
     auto finish_jse = [&](int pair, unsigned long long (&fw)[FW]) __attribute__((always_inline)) {
-        const unsigned long long* p2 = part2 + static_cast<size_t>(pair) * GW;
+        const unsigned long long* p2 = part2 + words_at(pair, 1);
         unsigned long long f[1] = {fw[0]};
         bool ok = await_n<1>(p2, GW, 0, P.spin_limit, f);
         double sum = wave_sum((lane < GW) ? __longlong_as_double(static_cast<long long>(f[0])) : 0.0);
@@ -641,7 +648,7 @@ void pair_kernel(PairParams P) {
         // masked entries of usable rows have spoilt): the pointwise form decides, if the rows are usable
         if (ok && (!(value >= static_cast<double>(P.js_floor)) || !(value < 1.0))) {
             asm volatile("");   // stays a branch
-            const RowNorms n = row_norms(part1 + static_cast<size_t>(pair) * GW * N1, GW, P.spin_limit);
+            const RowNorms n = row_norms(part1 + words_at(pair, N1), GW, P.spin_limit);
             if (!n.ok) status |= FSD_ROW_INTERNAL;
             else if (!n.usable) status |= FSD_ROW_NONFINITE;
             else state = pack2(static_cast<float>(n.lse2_t), static_cast<float>(n.lse2_d));
@@ -686,7 +693,7 @@ void pair_kernel(PairParams P) {
     // the previous pair's row-wide normalisers from the team's words (w holds the first 64 members'):
     // factors ft, fd with p = e_t ft, q = e_d fd
     auto merge_team = [&](const Pend& pp, unsigned long long (&w)[2], unsigned long long (&w2)[2], float& ft, float& fd) __attribute__((always_inline)) -> bool {
-        const unsigned long long* p1 = part1 + static_cast<size_t>(pp.pair) * GW * N1;
+        const unsigned long long* p1 = part1 + words_at(pp.pair, N1);
         // binary32 is enough: the normalisers enter p and q as common factors
         TeamNorm n{pp.kt, pp.kd, 0.0f, 0.0f, true};
         n.ok = await_n<2>(p1, GW, 0, P.spin_limit, w);
@@ -878,13 +885,13 @@ void pair_kernel(PairParams P) {
             // the loop it would be spilled, and the reload would wait for every load in flight
             int l = lane;
             asm volatile("" : "+v"(l));
-            post64(part2 + static_cast<size_t>(pp.pair) * GW * PW + member * PW + l, mine);
+            post64(part2 + words_at(pp.pair, PW) + member * PW + l, mine);
         }
     };
 
     auto finish_now = [&](int pair) __attribute__((always_inline)) {
         unsigned long long fw[FW];
-        request_n<FW>(finw + static_cast<size_t>(pair) * GW * FW, GW, 0, fw);
+        request_n<FW>(finw + words_at(pair, FW), GW, 0, fw);
         finish(pair, fw);
     };
     // Single-pass modes: nothing makes the members of a team wait for each other, so they drift
@@ -920,11 +927,11 @@ void pair_kernel(PairParams P) {
         asm volatile("" ::: "memory");
         if constexpr (TWO_PHASE)
         {
-            const unsigned long long* const p1 = part1 + static_cast<size_t>(due.pair >= 0 ? due.pair : pair) * GW * N1;
+            const unsigned long long* const p1 = part1 + words_at(due.pair >= 0 ? due.pair : pair, N1);
             request_n<2>(p1, GW, 0, w);
             request_n<2>(p1, GW, 64, w2, GW > 64);
         }
-        request_n<FW>(finw + static_cast<size_t>(fpair >= 0 ? fpair : pair) * GW * FW, GW, 0, fw, fpair >= 0);
+        request_n<FW>(finw + words_at(fpair >= 0 ? fpair : pair, FW), GW, 0, fw, fpair >= 0);
         if constexpr (DEEP) {
             // this pair's logits arrived in (ra, rb) during the last step; ask for the next pair's now
             const bool more = pair + pstep < pair_end;
@@ -945,15 +952,39 @@ void pair_kernel(PairParams P) {
         auto phase1 = [&](auto SAME_T) __attribute__((always_inline)) {
             constexpr bool SAME = decltype(SAME_T)::value;
             float mt = neg_inf(), md = neg_inf();
+            if constexpr (BF16) {
+                // A 32-bit word holds two bfloat16 logits.  Read as binary32 it is its upper logit plus a
+                // perturbation below that logit's last place, so the maximum over the words as they are has
+                // the largest upper logit in its upper half: only the lower logits need a shift.  (A word
+                // whose upper logit is +-inf or NaN reads as NaN and is dropped: a masked entry is never
+                // the maximum, and the exponential pass still sees the +inf or NaN that spoils a row.)
+                float th = neg_inf(), tl = neg_inf(), dh = neg_inf(), dl = neg_inf();
 #pragma unroll
-            for (int k = 0; k < NV; ++k) {
-                float a[VE], c[VE];
-                if constexpr (!SAME) unpack<BF16>(ra[k], a);
-                unpack<BF16>(rb[k], c);
+                for (int k = 0; k < NV; ++k) {
+                    if constexpr (!SAME) {
+                        th = fmaxf(fmaxf(th, __uint_as_float(ra[k].x)), __uint_as_float(ra[k].y));
+                        th = fmaxf(fmaxf(th, __uint_as_float(ra[k].z)), __uint_as_float(ra[k].w));
+                        tl = fmaxf(fmaxf(tl, __uint_as_float(ra[k].x << 16)), __uint_as_float(ra[k].y << 16));
+                        tl = fmaxf(fmaxf(tl, __uint_as_float(ra[k].z << 16)), __uint_as_float(ra[k].w << 16));
+                    }
+                    dh = fmaxf(fmaxf(dh, __uint_as_float(rb[k].x)), __uint_as_float(rb[k].y));
+                    dh = fmaxf(fmaxf(dh, __uint_as_float(rb[k].z)), __uint_as_float(rb[k].w));
+                    dl = fmaxf(fmaxf(dl, __uint_as_float(rb[k].x << 16)), __uint_as_float(rb[k].y << 16));
+                    dl = fmaxf(fmaxf(dl, __uint_as_float(rb[k].z << 16)), __uint_as_float(rb[k].w << 16));
+                }
+                if constexpr (!SAME) mt = fmaxf(__uint_as_float(__float_as_uint(th) & 0xFFFF0000u), tl);
+                md = fmaxf(__uint_as_float(__float_as_uint(dh) & 0xFFFF0000u), dl);
+            } else {
 #pragma unroll
-                for (int e = 0; e < VE; e += 2) {
-                    if constexpr (!SAME) mt = fmaxf(fmaxf(mt, a[e]), a[e + 1]);
-                    md = fmaxf(fmaxf(md, c[e]), c[e + 1]);
+                for (int k = 0; k < NV; ++k) {
+                    float a[VE], c[VE];
+                    if constexpr (!SAME) unpack<BF16>(ra[k], a);
+                    unpack<BF16>(rb[k], c);
+#pragma unroll
+                    for (int e = 0; e < VE; e += 2) {
+                        if constexpr (!SAME) mt = fmaxf(fmaxf(mt, a[e]), a[e + 1]);
+                        md = fmaxf(fmaxf(md, c[e]), c[e + 1]);
+                    }
                 }
             }
             PT(0);   // load wait + max pass
@@ -1075,7 +1106,7 @@ void pair_kernel(PairParams P) {
             }
             mine = (lane == 0) ? w0 : (lane == 1) ? dbits(pst_) : (lane == 2) ? dbits(psd_) : dbits(pw_);
         }
-        unsigned long long* const post_at = part1 + static_cast<size_t>(pair) * GW * N1 + member * N1 + (lane & 3);
+        unsigned long long* const post_at = part1 + words_at(pair, N1) + member * N1 + (lane & 3);
         if (lane < N1) post64(post_at, mine);
         PT(3);   // wave sums, prefetch issue, post
         if constexpr (TWO_PHASE) {
@@ -1145,8 +1176,8 @@ void pair_kernel(PairParams P) {
             if (pp.pair >= 0) {
                 unsigned long long w[2], w2[2];
                 float ft, fd;
-                request_n<2>(part1 + static_cast<size_t>(pp.pair) * GW * N1, GW, 0, w);
-                request_n<2>(part1 + static_cast<size_t>(pp.pair) * GW * N1, GW, 64, w2, GW > 64);
+                request_n<2>(part1 + words_at(pp.pair, N1), GW, 0, w);
+                request_n<2>(part1 + words_at(pp.pair, N1), GW, 64, w2, GW > 64);
                 const bool ok2 = merge_team(pp, w, w2, ft, fd);
                 const int b = (iter + NB - d) % NB;   // written at step iter - d
                 if (b == 0) phase2(pp, SetId<0>{}, ft, fd, ok2);
@@ -1195,7 +1226,7 @@ void pair_kernel(PairParams P) {
                                                                    __uint_as_float(hi));
                 // the partial replaces this member's sums of exponentials, which nobody reads any more once the
                 // pair's state word is out (a sum is never -1)
-                unsigned long long* const p2 = part1 + static_cast<size_t>(rp) * GW * N1 + 1;
+                unsigned long long* const p2 = part1 + words_at(rp, N1) + 1;
                 if (lane == 0) post64(p2 + member * N1, pack2(part, -1.0f));
                 if ((base + i) % GW == member) {
                     double sum = 0.0;
