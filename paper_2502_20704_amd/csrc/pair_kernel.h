@@ -326,10 +326,10 @@ void pair_kernel(PairParams P) {
     // NB sets of kept exponentials, named by SetId<> so that every index is a constant and the
     // arrays stay in registers; accessed four at a time
     float et[NB][NE], ed[NB][NE];
-    // The entropy form needs a few registers more than the two sets leave: the last NL chunks of each set
+    // The entropy form (and TV at 5 slots per lane) needs a few registers more than the two sets leave: the last NL chunks of each set
     // live in LDS instead (each lane reads back only what it wrote itself: no barrier; LDS traffic is counted
     // apart from the loads of the logits, so waiting for it does not wait for the prefetch as a spill would)
-    constexpr int NL = JSE ? (TSHARED ? 3 : 2) : 0;   // (the least that leaves no register spilled, per variant)
+    constexpr int NL = JSE ? (TSHARED ? 3 : 2) : (BF16 && NV == 5 && MODE == MODE_TV) ? 1 : 0;   // (the least that leaves no register spilled, per variant)
     __shared__ float4 lds_keep[NL ? NB * NL * 2 * kWG : 1];
     auto put4 = [&](auto S, int c, const float (&t4)[4], const float (&d4)[4]) __attribute__((always_inline)) {
         constexpr int s_ = decltype(S)::value;
@@ -921,8 +921,9 @@ void pair_kernel(PairParams P) {
         unsigned long long fw[FW];
         const int fpair = TWO_PHASE ? fin[0] : ((sp_pair >= 0 && iter >= sp_due) ? sp_pair : -1);
         const Pend due = pend[LAG - 1];
-        // Phase 1 and the request for the next pair's logits are what the whole team waits for: they
-        // run at raised priority; what follows overlaps with the memory latency and does not need it.
+        // Phase 1, the request for the next pair's logits and the post of this wavefront's sums are what
+        // the whole team waits for: they run at raised priority; what follows overlaps with the memory
+        // latency and does not need it.
         __builtin_amdgcn_s_setprio(3);
         asm volatile("" ::: "memory");
         if constexpr (TWO_PHASE)
@@ -1075,14 +1076,16 @@ void pair_kernel(PairParams P) {
             }
         }
         PT(1);   // reductions + exp pass
-        // ---- the registers that held the logits are free: fetch the next pair (the request is
-        // unconditional: the last step asks for one slot of its own pair, which the caches hold)
         asm volatile("" ::: "memory");
-        if constexpr (!DEEP) {
+        // ---- the registers that held the logits are free: fetch the next pair (the request is
+        // unconditional: the last step asks for one slot of its own pair, which the caches hold).  In the
+        // two-phase modes only after the post below: every member's post is what the whole team's next
+        // step waits for (bfloat16 JS: C2 -2 %, C4 -4 % against the request first).
+        if constexpr (!DEEP && !TWO_PHASE) {
             const bool more = pair + pstep < pair_end;
             load_item(rna, rnb, more ? pair + pstep : pair, more);
+            __builtin_amdgcn_s_setprio(0);
         }
-        __builtin_amdgcn_s_setprio(0);
         asm volatile("" ::: "memory");
         // ---- post this wavefront's partial.  The two-phase modes need the normalisers to a relative
         // 1e-7 only (common factors of p and q); the single-pass modes take them through a logarithm.
@@ -1091,9 +1094,8 @@ void pair_kernel(PairParams P) {
         if constexpr (TWO_PHASE) {
             wave_sumf2(st, sd);
             if constexpr (MODE == MODE_KLP) { wacc = wave_sumf(wacc); dmax = wave_max(dmax); }
-            if constexpr (JSE) wave_sumf2(wacc, dmax);
             if constexpr (SHARE) {
-                if (same_target) { st = due.st; wacc = due.wsum; }   // the target row's sums, as the previous step formed them
+                if (same_target) st = due.st;   // the target row's sum, as the previous step formed it
             }
             mine = (lane == 0) ? w0 : pack2(st, sd);
         } else {
@@ -1108,6 +1110,19 @@ void pair_kernel(PairParams P) {
         }
         unsigned long long* const post_at = part1 + words_at(pair, N1) + member * N1 + (lane & 3);
         if (lane < N1) post64(post_at, mine);
+        asm volatile("" ::: "memory");
+        if constexpr (TWO_PHASE) {
+            if constexpr (!DEEP) {
+                const bool more = pair + pstep < pair_end;
+                load_item(rna, rnb, more ? pair + pstep : pair, more);
+            }
+            __builtin_amdgcn_s_setprio(0);   // only now does the priority drop
+        }
+        asm volatile("" ::: "memory");
+        if constexpr (JSE) wave_sumf2(wacc, dmax);   // (phase 2 of a later step needs them: not before the post)
+        if constexpr (SHARE) {
+            if (same_target) wacc = due.wsum;
+        }
         PT(3);   // wave sums, prefetch issue, post
         if constexpr (TWO_PHASE) {
             // ---- the previous pair's normalisers, then its phase 2
