@@ -909,8 +909,10 @@ void pair_kernel(PairParams P) {
     // what can overlap: the small exchange words (the previous pair's team words, and the words of a
     // pair this wavefront has to finish) are requested first, at the top of the step, where they sit
     // behind the logits that are about to be used anyway; the logits of the next pair are requested
-    // as soon as phase 1 has consumed the registers; and nothing after that waits on memory unless a
-    // team member is late (then the words are asked for again, behind the prefetch).
+    // once phase 1 has consumed the registers (in the two-phase modes after this wavefront's sums are
+    // posted: the team's next step waits for every member's post, so nothing that can wait comes
+    // before it); and nothing after that waits on memory unless a team member is late (then the
+    // words are asked for again, behind the prefetch).
     // (ra, rb) hold the logits of `pair`, the next pair's go to (rna, rnb).  Where registers allow
     // (DEEP) these are different sets and the next pair is requested at the top of the step, a whole
     // step ahead; otherwise both names are the same set and the request follows phase 1.
@@ -921,9 +923,9 @@ void pair_kernel(PairParams P) {
         unsigned long long fw[FW];
         const int fpair = TWO_PHASE ? fin[0] : ((sp_pair >= 0 && iter >= sp_due) ? sp_pair : -1);
         const Pend due = pend[LAG - 1];
-        // Phase 1, the request for the next pair's logits and the post of this wavefront's sums are what
-        // the whole team waits for: they run at raised priority; what follows overlaps with the memory
-        // latency and does not need it.
+        // Phase 1 and the post of this wavefront's sums are what the whole team waits for: they run at
+        // raised priority (and the request for the next pair's logits right behind them); what follows
+        // overlaps with the memory latency and does not need it.
         __builtin_amdgcn_s_setprio(3);
         asm volatile("" ::: "memory");
         if constexpr (TWO_PHASE)
