@@ -226,10 +226,7 @@ void launch_pair_m(int mode, bool aligned, hipStream_t st, const PairParams& P) 
         case MODE_JS: launch_pair_a<BF16, NV, MODE_JS>(aligned, st, P); break;
         case MODE_TV: launch_pair_a<BF16, NV, MODE_TV>(aligned, st, P); break;
         case MODE_KLP: launch_pair_a<BF16, NV, MODE_KLP>(aligned, st, P); break;
-        case MODE_JSE:
-            if constexpr (BF16 && NV == 5) launch_pair_a<BF16, NV, MODE_JSE>(aligned, st, P);
-            else launch_pair_a<BF16, NV, MODE_JS>(aligned, st, P);
-            break;
+        case MODE_JSE: launch_pair_a<BF16, NV, MODE_JS>(aligned, st, P); break;   // (its own shape is launched by launch_pair)
         default: launch_pair_a<BF16, NV, MODE_LSE>(aligned, st, P); break;
     }
 }
@@ -244,6 +241,7 @@ void launch_pair(int dtype, int NV, int mode, bool aligned, hipStream_t st, cons
     }
     if (dtype == FSD_BF16) {
         if (NV == 2) launch_pair_m<true, 2>(mode, aligned, st, P);
+        else if (NV == 6) launch_pair_a<true, 6, MODE_JSE>(aligned, st, P);   // (the entropy form is the only mode at 6 slots)
         else if (NV == 5) launch_pair_m<true, 5>(mode, aligned, st, P);
         else launch_pair_m<true, 4>(mode, aligned, st, P);
     } else {
@@ -359,6 +357,8 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
         // per entry: 5 slots per lane instead of 4 is the most that fits two wavefronts per SIMD (256
         // registers).  The workspace is laid out for the larger team of the 4-slot shape.
         p.NV = 5;
+        // (the entropy form, which keeps part of its exponentials in LDS, holds 6)
+        if (k1mode == MODE_JSE) p.NV = 6;
         p.G = static_cast<int>(team_size(p.nslots, p.NV));
         p.spm = static_cast<int>((p.nslots + p.G - 1) / p.G);
         // entropy form: whole chunks of 64 NV slots per member, so that only the last one with any
