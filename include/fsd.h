@@ -326,8 +326,8 @@ int fsd_debug_set_exact_js(int on);
 /* Tuning hook: shape of the vocabulary-reduction kernel.  `wavefronts` per
  * workgroup must be 4 (or 0 = default); `slots_per_thread` is the number of
  * 16-byte slots of each row a lane holds: 2, 4 or 8 (bfloat16: 2, 4 or 5), 0 =
- * the library's own choice (32 vocabulary entries per lane and row; 40 for the
- * bfloat16 TV kernel, 48 for the bfloat16 JS kernel).  A shape
+ * the library's own choice (32 vocabulary entries per lane and row; 48 for the
+ * bfloat16 JS and TV kernels).  A shape
  * that would need more than 256 wavefronts per row pair is ignored.  Results
  * do not depend on the shape beyond the rounding order of the partial sums. */
 int fsd_debug_set_shape(int wavefronts, int slots_per_thread);

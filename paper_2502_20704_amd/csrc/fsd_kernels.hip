@@ -241,7 +241,11 @@ void launch_pair(int dtype, int NV, int mode, bool aligned, hipStream_t st, cons
     }
     if (dtype == FSD_BF16) {
         if (NV == 2) launch_pair_m<true, 2>(mode, aligned, st, P);
-        else if (NV == 6) launch_pair_a<true, 6, MODE_JSE>(aligned, st, P);   // (the entropy form is the only mode at 6 slots)
+        else if (NV == 6) {   // the library's own shape of the two-phase kernels
+            if (mode == MODE_JSE) launch_pair_a<true, 6, MODE_JSE>(aligned, st, P);
+            else if (mode == MODE_TV) launch_pair_a<true, 6, MODE_TV>(aligned, st, P);
+            else launch_pair_a<true, 6, MODE_JS>(aligned, st, P);
+        }
         else if (NV == 5) launch_pair_m<true, 5>(mode, aligned, st, P);
         else launch_pair_m<true, 4>(mode, aligned, st, P);
     } else {
@@ -354,11 +358,10 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
     if (k1mode == MODE_JS && dtype == FSD_BF16 && kind != KIND_RFSD && !g_exact_js && !g_shape_nv) k1mode = MODE_JSE;
     if (dtype == FSD_BF16 && !g_shape_nv && (k1mode == MODE_JS || k1mode == MODE_TV || k1mode == MODE_JSE)) {
         // The bfloat16 two-phase kernels are bound by instruction issue, a third of it per step and not
-        // per entry: 5 slots per lane instead of 4 is the most that fits two wavefronts per SIMD (256
-        // registers).  The workspace is laid out for the larger team of the 4-slot shape.
-        p.NV = 5;
-        // (the entropy form, which keeps part of its exponentials in LDS, holds 6)
-        if (k1mode == MODE_JSE) p.NV = 6;
+        // per entry: they hold 6 slots of each row per lane (96 logits a step), which fits two wavefronts
+        // per SIMD (256 registers) because 5 of the 12 chunks of each set of kept exponentials live in
+        // LDS.  The workspace is laid out for the larger team of the 4-slot shape.
+        p.NV = 6;
         p.G = static_cast<int>(team_size(p.nslots, p.NV));
         p.spm = static_cast<int>((p.nslots + p.G - 1) / p.G);
         // entropy form: whole chunks of 64 NV slots per member, so that only the last one with any

@@ -283,7 +283,7 @@ template <bool B> struct BoolTag { static constexpr bool value = B; };
 
 // wavefronts per SIMD the register allocation has to leave room for
 constexpr int pair_kernel_waves(bool bf16, int nv, int mode) {
-    return (bf16 && ((nv == 5 && (mode == MODE_JS || mode == MODE_TV)) || mode == MODE_JSE)) ? 2 : 1;
+    return (bf16 && (((nv == 5 || nv == 6) && (mode == MODE_JS || mode == MODE_TV)) || mode == MODE_JSE)) ? 2 : 1;
 }
 
 // TSHARED: target rows are shared between pairs (a tree) and are loaded to stay cached (a template
@@ -328,10 +328,11 @@ void pair_kernel(PairParams P) {
     float et[NB][NE], ed[NB][NE];
     // The last NL chunks of each set live in LDS instead of registers (each lane reads back only what it
     // wrote itself: no barrier; LDS traffic is counted apart from the loads of the logits, so waiting for it
-    // does not wait for the prefetch as a spill would).  The entropy form keeps 5 of its 12 chunks there:
-    // that is what lets it hold 6 slots per lane (96 logits a step) in 256 registers, and with two
-    // workgroups of 80 KB it takes all of a compute unit's LDS.  TV at 5 slots per lane keeps one.
-    constexpr int NL = JSE ? 5 : (BF16 && NV == 5 && MODE == MODE_TV) ? 1 : 0;   // (the least that leaves no register spilled, per variant)
+    // does not wait for the prefetch as a spill would).  The bfloat16 two-phase kernels keep 5 of their 12
+    // chunks there: that is what lets them hold 6 slots per lane (96 logits a step) in 256 registers,
+    // and with two workgroups of 80 KB it takes all of a compute unit's LDS.  (TV at 5 slots per lane,
+    // a shape of the tuning hook, keeps one.)
+    constexpr int NL = (JSE || (BF16 && NV == 6 && TWO_PHASE)) ? 5 : (BF16 && NV == 5 && MODE == MODE_TV) ? 1 : 0;   // (the least that leaves no register spilled, per variant)
     __shared__ float4 lds_keep[NL ? NB * NL * 2 * kWG : 1];
     auto put4 = [&](auto S, int c, const float (&t4)[4], const float (&d4)[4]) __attribute__((always_inline)) {
         constexpr int s_ = decltype(S)::value;
