@@ -79,13 +79,21 @@ __device__ __forceinline__ float hi_f(unsigned long long w) { return __uint_as_f
 // the team re-read the last member's (no branch around the loads, see load_item).  Nothing looks at the values here, so the loads stay in flight until they are
 // awaited.  With spread == false every lane reads member 0 (a request whose result is not needed
 // costs one cache line).
+// word i of a pair's words: a 32-bit byte offset added to a pointer that stays scalar
+__device__ __forceinline__ unsigned long long* word_at(unsigned long long* p, unsigned i) {
+    return reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(p) + i * 8u);
+}
+__device__ __forceinline__ const unsigned long long* word_at(const unsigned long long* p, unsigned i) {
+    return reinterpret_cast<const unsigned long long*>(reinterpret_cast<const char*>(p) + i * 8u);
+}
 template <int N>
 __device__ __forceinline__ void request_n(const unsigned long long* p, int GW, int base, unsigned long long (&w)[N],
                                           bool spread = true) {
     const int m = base + static_cast<int>(threadIdx.x & 63);
     const int mm = spread ? ((m < GW) ? m : GW - 1) : 0;
+    const unsigned long long* const mine = word_at(p, static_cast<unsigned>(mm * N));
 #pragma unroll
-    for (int k = 0; k < N; ++k) w[k] = read64(p + mm * N + k);
+    for (int k = 0; k < N; ++k) w[k] = read64(mine + k);
 }
 // The words are normally there when they are looked at.  Everything that loops over memory (asking
 // again, further rounds of 64 members) lives in functions that are NOT inlined: the compiler's
@@ -295,6 +303,7 @@ void pair_kernel(PairParams P) {
     constexpr int ES = BF16 ? 2 : 4;
     constexpr bool TWO_PHASE = (MODE == MODE_JS || MODE == MODE_TV || MODE == MODE_KLP || MODE == MODE_JSE);
     constexpr bool JSE = (MODE == MODE_JSE);   // bfloat16 only (the host sends binary32 JS to MODE_JS)
+    constexpr bool RECOMPUTE_SLOTS = JSE && TSHARED;   // (the tree variant of the entropy form is the one short of registers)
     constexpr bool SHARE = JSE && TSHARED;     // consecutive pairs with one target row share its phase 1 (see step)
     constexpr int NE = TWO_PHASE ? NV * VE : 1;   // exponentials kept per row and lane
     constexpr int PW = (MODE == MODE_TV || MODE == MODE_KLP) ? 2 : 1;   // divergence words a member posts (two sums each)
@@ -445,9 +454,13 @@ void pair_kernel(PairParams P) {
         // cached (TSHARED).  One copy of these loads, whatever the input: with two, in the arms of a
         // run-time branch, the compiler's count of requests in flight is no longer exact after the join,
         // and every later wait for an exchange word also waits for most of this prefetch.
+        // (where registers are short the lane's slots are formed again at every request instead of
+        // being kept: hidden from the hoisting of loop invariants)
+        int first = sl0;
+        if constexpr (RECOMPUTE_SLOTS) asm volatile("" : "+v"(first));
 #pragma unroll
         for (int k = 0; k < NV; ++k) {
-            const int sk = sl0 + 64 * k;
+            const int sk = first + 64 * k;
             const long sl = wanted ? (sk < sl_end ? sk : sl_last) : 0;   // not wanted: one cached slot for all lanes
             ra[k] = load_slot<BF16, ALIGNED, !TSHARED>(tptr, sl, P.V);
             rb[k] = load_slot<BF16, ALIGNED, true>(dptr, sl, P.V);
@@ -649,7 +662,10 @@ void pair_kernel(PairParams P) {
         unsigned long long state = kJsDone;
         // below the floor (cancellation), or anything but a plain number (unusable rows, or sums the
         // masked entries of usable rows have spoilt): the pointwise form decides, if the rows are usable
-        if (ok && (!(value >= static_cast<double>(P.js_floor)) || !(value < 1.0))) {
+        // (the floor is read where it is used: as a double kept across the loop it would be spilled)
+        float floor_here = P.js_floor;
+        asm volatile("" : "+v"(floor_here));
+        if (ok && (!(value >= static_cast<double>(floor_here)) || !(value < 1.0))) {
             asm volatile("");   // stays a branch
             const RowNorms n = row_norms(part1 + words_at(pair, N1), GW, P.spin_limit);
             if (!n.ok) status |= FSD_ROW_INTERNAL;
@@ -659,8 +675,10 @@ void pair_kernel(PairParams P) {
         if (value < 0.0) value = 0.0;
         if (status) value = __builtin_nan("");
         if (lane == 0) {
-            P.ws.lse2[2 * pair] = 0.0;
-            P.ws.lse2[2 * pair + 1] = 0.0;
+            double zero = 0.0;   // (made here, for the same reason)
+            asm volatile("" : "+v"(zero));
+            P.ws.lse2[2 * pair] = zero;
+            P.ws.lse2[2 * pair + 1] = zero;
             if (state == kJsDone) {
                 P.ws.div[pair] = static_cast<float>(value);
                 if (P.user_div) P.user_div[pair] = static_cast<float>(value);
@@ -888,7 +906,7 @@ void pair_kernel(PairParams P) {
             // the loop it would be spilled, and the reload would wait for every load in flight
             int l = lane;
             asm volatile("" : "+v"(l));
-            post64(part2 + words_at(pp.pair, PW) + member * PW + l, mine);
+            post64(word_at(part2 + words_at(pp.pair, PW), static_cast<unsigned>(member * PW + l)), mine);
         }
     };
 
@@ -1113,8 +1131,11 @@ void pair_kernel(PairParams P) {
             }
             mine = (lane == 0) ? w0 : (lane == 1) ? dbits(pst_) : (lane == 2) ? dbits(psd_) : dbits(pw_);
         }
-        unsigned long long* const post_at = part1 + words_at(pair, N1) + member * N1 + (lane & 3);
-        if (lane < N1) post64(post_at, mine);
+        // (the lane's word is addressed by a 32-bit offset from the pair's scalar pointer, formed here)
+        int pl = lane;
+        asm volatile("" : "+v"(pl));
+        unsigned long long* const post_at = word_at(part1 + words_at(pair, N1), static_cast<unsigned>(member * N1 + (pl & 3)));
+        if (pl < N1) post64(post_at, mine);
         asm volatile("" ::: "memory");
         if constexpr (TWO_PHASE) {
             if constexpr (!DEEP) {
