@@ -133,10 +133,10 @@ Ws carve(void* workspace, const Plan& p, int B, int rows, int G, int n1, int n2,
 }
 
 unsigned g_spin_limit = 1u << 22;
-// The entropy form of JS (bfloat16 logits) carries an absolute error of about 1.5e-6 whatever the
+// The entropy form of JS (bfloat16 logits) carries an absolute error of a few 1e-7 whatever the
 // result: below this floor (nats) a pair is evaluated again in the pointwise form, so that what the
-// caller sees is within 2e-3 relative everywhere.
-float g_js_floor = 2e-3f;
+// caller sees is within 2e-3 relative everywhere (with a margin of five to ten).
+float g_js_floor = 1e-3f;
 bool g_exact_js = false;   // test hook: bfloat16 JS in the pointwise form only
 #ifdef FSD_PHASE_TIMING
 unsigned long long* g_dbg = nullptr;

@@ -192,11 +192,13 @@ __device__ __noinline__ Sums<N> sum_more_rounds(const unsigned long long* p2, in
 //     C = f_t [ A_t + c A_d - U + W + c S_d log2 c ]
 //
 // (write every logarithm as log2 f + log2 e: the terms in log2 f_t cancel because W is the mass of
-// u, and log2 of 2 gives the W).  C is formed in float64 from the binary32 sums, a dozen operations
-// per pair and member, and posted as one word; the pair's finisher only adds the team's C.
-// The kernel is bound by vector-ALU issue, and this removes a third of its instructions.  The
-// price is cancellation: A, U are of the size of the entropies, so the result carries an ABSOLUTE
-// error of about 1e-6 whatever its size.  Results below P.js_floor are therefore evaluated a
+// u, and log2 of 2 gives the W).  All five sums run over the same entries, so a lane combines its
+// own five first (its part of the bracket is the sum of its entries' pointwise terms: small, where
+// the separate sums are of the size of the entropies and cancel), one reduction over the wavefront
+// follows, and C is posted as one word; the pair's finisher only adds the team's C.
+// This removes a third of the kernel's instructions.  The price is what is left of the
+// cancellation: the result carries an ABSOLUTE error of a few 1e-7 (2.2e-7 was the largest seen
+// over vocabularies of 32 000 to 256 000 and divergences from 1e-5 to 0.5) whatever its size.  Results below P.js_floor are therefore evaluated a
 // second time in the pointwise form, by the same team, after its last pair (bit-identical rows give
 // exactly 0 that way).
 //
@@ -696,7 +698,8 @@ void pair_kernel(PairParams P) {
     };
 
     // ---- state of the previous pair, whose phase 2 is still to come (two-phase modes)
-    struct Pend { int pair; float kt, kd; bool mass_t, mass_d, mask; float wsum, dmax, st, sd; };   // wsum, dmax: pointwise KL (entropy-form JS: the sums of e x)
+    // wsum, dmax: pointwise KL; entropy-form JS: this lane's A_t + S_t and A_d, and sd is this lane's S_d
+    struct Pend { int pair; float kt, kd; bool mass_t, mass_d, mask; float wsum, dmax, st, sd; };
     Pend pend[LAG];   // [0] the last step's pair ... [LAG-1] the one whose phase 2 is due
 #pragma unroll
     for (int i = 0; i < LAG; ++i) pend[i] = Pend{-1, 0.0f, 0.0f, false, false, false, 0.0f, 0.0f, 0.0f, 0.0f};
@@ -796,19 +799,15 @@ void pair_kernel(PairParams P) {
                     }
                 }
             }
-            acc = wave_sumf(acc);
-            // the member's share C = f_t [A_t + c A_d - U + W + c S_d log2 c] in float64 (products of two
-            // binary32 numbers are exact there).  log2 c = exponent + log2 of the mantissa in [1/2, 1), which
-            // the hardware logarithm gives to 6e-8 absolute (and c = 1 gives exactly 0)
-            const double dc = static_cast<double>(cq);
-            const double l2c = static_cast<double>(__builtin_amdgcn_frexp_expf(cq)) +
-                               static_cast<double>(hw_log2(__builtin_amdgcn_frexp_mantf(cq)));
-            const double csd = dc * static_cast<double>(pp.sd);
-            double share = static_cast<double>(pp.wsum) + dc * static_cast<double>(pp.dmax);
-            share -= static_cast<double>(acc);
-            share += static_cast<double>(pp.st) + csd;
-            share += csd * l2c;
-            share *= static_cast<double>(ftc);
+            // the member's share C = f_t [A_t + c A_d - U + W + c S_d log2 c] with W = S_t + c S_d.  Every sum
+            // in it runs over the same entries, so a lane forms its own part first, from its own sums
+            // (pp.wsum = A_t + S_t, pp.dmax = A_d, pp.sd = S_d of this lane), and one reduction over the
+            // wavefront follows: a lane's part is its entries' pointwise terms, small and not negative up to
+            // rounding, where the separate sums are large and cancel.  1 + log2 c = exponent + (1 + log2 of
+            // the mantissa in [1/2, 1)); c = 1 gives exactly 1.
+            const float g = static_cast<float>(__builtin_amdgcn_frexp_expf(cq)) + (1.0f + hw_log2(__builtin_amdgcn_frexp_mantf(cq)));
+            const float part = fmaf(cq, fmaf(pp.sd, g, pp.dmax), pp.wsum) - acc;
+            double share = static_cast<double>(wave_sumf(part)) * static_cast<double>(ftc);
             if (ft != ft || fd != fd) share = static_cast<double>(ft + fd);   // an unusable row stays NaN (max() drops it above)
             if (!ok) share = __builtin_nan("");
             word[0] = dbits(share);
@@ -1114,6 +1113,7 @@ void pair_kernel(PairParams P) {
         // 1e-7 only (common factors of p and q); the single-pass modes take them through a logarithm.
         const unsigned long long w0 = pack2(kt, kd);
         unsigned long long mine;
+        [[maybe_unused]] const float st_lane = st, sd_lane = sd;
         if constexpr (TWO_PHASE) {
             wave_sumf2(st, sd);
             if constexpr (MODE == MODE_KLP) { wacc = wave_sumf(wacc); dmax = wave_max(dmax); }
@@ -1145,7 +1145,7 @@ void pair_kernel(PairParams P) {
             __builtin_amdgcn_s_setprio(0);   // only now does the priority drop
         }
         asm volatile("" ::: "memory");
-        if constexpr (JSE) wave_sumf2(wacc, dmax);   // (phase 2 of a later step needs them: not before the post)
+        if constexpr (JSE) wacc += st_lane;   // the lane's A_t + S_t (phase 2 of a later step combines the lanes' sums)
         if constexpr (SHARE) {
             if (same_target) wacc = due.wsum;
         }
@@ -1163,7 +1163,7 @@ void pair_kernel(PairParams P) {
             asm volatile("" ::"v"(mine), "v"(post_at));
 #pragma unroll
             for (int i = LAG - 1; i > 0; --i) pend[i] = pend[i - 1];
-            pend[0] = Pend{pair, kt, kd, (st > 0.0f) || (st != st), (sd > 0.0f) || (sd != sd), dmax == __builtin_inff(), wacc, dmax, st, sd};
+            pend[0] = Pend{pair, kt, kd, (st > 0.0f) || (st != st), (sd > 0.0f) || (sd != sd), dmax == __builtin_inff(), wacc, dmax, st, JSE ? sd_lane : sd};
         }
         // ---- finishing duties: the pair whose turn has come, then note this pair if it is ours
         if (fpair >= 0) finish(fpair, fw);

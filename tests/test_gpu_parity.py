@@ -731,6 +731,9 @@ def _js_inputs():
     return cases
 
 
+JS_FLOOR = 1e-3   # the library's default floor of the entropy form (nats)
+
+
 def test_js_bf16_both_evaluations(torch_cuda, oracle):
     """bfloat16 JS: the entropy form alone (floor 0), the pointwise second evaluation alone (floor +inf), the
     pointwise kernel, and the default mix, each against the oracle.  The entropy form is held to its absolute
@@ -754,7 +757,7 @@ def test_js_bf16_both_evaluations(torch_cuda, oracle):
                 err = np.abs(g["divergences"].astype(np.float64) - o["divs"])[fin]
                 print(f"   max abs error {err.max():.3e}", flush=True)
                 if what == "entropy form":
-                    assert err.max() <= 2e-6, f"{name} {what}: {err.max()}"
+                    assert err.max() <= 1e-6, f"{name} {what}: {err.max()}"
                 else:
                     env = pu.Envelope("bf16")
                     pu.check_chain(g, o, 0.1, pu.rel_tol("bf16"), f"{name} {what}", envelope=env)
@@ -762,7 +765,7 @@ def test_js_bf16_both_evaluations(torch_cuda, oracle):
                     assert (g["divergences"][1] == 0.0).all(), f"{name} {what}: identical rows"
     finally:
         fsd.debug_set_exact_js(False)
-        fsd.debug_set_js_floor(2e-3)
+        fsd.debug_set_js_floor(JS_FLOOR)
 
 
 def test_js_bf16_second_evaluation_in_a_tree(torch_cuda, oracle):
@@ -773,12 +776,12 @@ def test_js_bf16_second_evaluation_in_a_tree(torch_cuda, oracle):
     o = oracle.verify_tree(inp["target"], inp["draft"], inp["node_tokens"], inp["parent"], md, 0.001, fsd.DIV_JS, seed=4)
     assert (o["divs"] < 2e-3).mean() > 0.5
     try:
-        for floor in (2e-3, float("inf")):
+        for floor in (JS_FLOOR, 2e-3, float("inf")):
             fsd.debug_set_js_floor(floor)
             g = run_tree(torch_cuda, inp, 0.001, fsd.DIV_JS, md, seed=4)
             pu.check_tree(g, o, 0.001, pu.rel_tol("bf16"), f"tree, floor {floor}", envelope=pu.Envelope("bf16"))
     finally:
-        fsd.debug_set_js_floor(2e-3)
+        fsd.debug_set_js_floor(JS_FLOOR)
 
 
 def test_js_bf16_siblings_share_their_target_row(torch_cuda, oracle):
