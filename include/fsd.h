@@ -314,8 +314,8 @@ int fsd_profile_collect(float* mean_ms, float* min_ms);
 unsigned fsd_debug_set_spin_limit(unsigned polls);
 
 /* Test hooks of the bfloat16 Jensen-Shannon reduction.  It evaluates App. C.2 in
- * entropy form (one logarithm per entry), whose absolute error of a few 1e-7
- * does not shrink with the result; results below a floor (default 1e-3 nats)
+ * entropy form (one logarithm per entry), whose absolute error (about 1e-7
+ * for small results) does not shrink with the result; results below a floor (default 1e-3 nats)
  * are evaluated again in the pointwise form, whose error does.
  * fsd_debug_set_js_floor sets that floor (0: never again; +inf: always) and
  * returns the previous one; fsd_debug_set_exact_js(1) makes every bfloat16 JS

@@ -197,8 +197,9 @@ __device__ __noinline__ Sums<N> sum_more_rounds(const unsigned long long* p2, in
 // the separate sums are of the size of the entropies and cancel), one reduction over the wavefront
 // follows, and C is posted as one word; the pair's finisher only adds the team's C.
 // This removes a third of the kernel's instructions.  The price is what is left of the
-// cancellation: the result carries an ABSOLUTE error of a few 1e-7 (2.2e-7 was the largest seen
-// over vocabularies of 32 000 to 256 000 and divergences from 1e-5 to 0.5) whatever its size.  Results below P.js_floor are therefore evaluated a
+// cancellation: the result carries an ABSOLUTE error that does not shrink with it (measured over
+// vocabularies of 32 000 to 256 000: at most 1.4e-7 for results below 0.05, up to 1e-6 for results
+// of order 0.5, which is 2e-6 of them).  Results below P.js_floor are therefore evaluated a
 // second time in the pointwise form, by the same team, after its last pair (bit-identical rows give
 // exactly 0 that way).
 //
