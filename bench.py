@@ -9,7 +9,7 @@ T=0.1); several distinct input sets are rotated so that the working set exceeds 
 Order of a run: an untimed settle phase (calls until the device has been busy for --settle-ms, so
 that the timed steps do not fall into the clock ramp of an idle GPU; its length is reported in
 `config`), the W warm-up steps, the K timed steps between two synchronisations, and then a
-separate pass of the same K steps with HIP events around the vocabulary-reduction kernel (the
+separate pass of the same K steps with a start and a stop event on the vocabulary-reduction kernel's launch (the
 events stay out of the timed region).
 
 Prints one JSON line: verified candidate positions per second, plus the roofline of the

@@ -299,8 +299,9 @@ int fsd_calibrate_threshold(const float* divergences, int B, int K, float target
 
 /*
  * Timing of the vocabulary-reduction kernel, for benchmarks.  After
- * fsd_profile_enable(1) every verify call brackets that kernel with a pair of
- * events on the call's stream (up to 4096 pairs are kept; later calls are
+ * fsd_profile_enable(1) every verify call launches that kernel with a pair of
+ * events that take the start and the end of its dispatch on the call's stream
+ * (what a kernel trace shows; up to 4096 pairs are kept; later calls are
  * not recorded).  fsd_profile_collect waits for the recorded events, returns
  * the number of pairs and their mean / minimum duration in milliseconds, and
  * forgets them.  Not thread-safe; meant for a single benchmarking thread.
