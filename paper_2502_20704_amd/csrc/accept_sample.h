@@ -189,11 +189,7 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
     if (!status) {
         const long s0 = static_cast<long>(gs) * P.sps;
         const long s1 = (s0 + P.sps < P.nslots) ? s0 + P.sps : P.nslots;
-        // Scores already seen anywhere in the wavefront: an entry whose score cannot reach them cannot
-        // be the argmax, and its Gumbel variate (two logarithms) is not evaluated.  The bound:
-        // G = -ln(-ln u) <= -ln(1 - u), and 1 - u = m 2^-24 with the integer m below, so
-        // G <= ln2 (24 - floor(log2 m)) = ln2 (clz(m) - 7); 1e-3 covers the rounding of the
-        // logarithm routine by a wide margin.
+        // thr, rthr: scores the winner is known to reach (see the bounds below)
         float thr = neg_inf(), rthr = neg_inf();
         const float thr_b = P.thr ? P.thr[b] : neg_inf();
         // the trip count is the same for every lane: the thresholds are wavefront reductions
@@ -203,7 +199,7 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
         for (long sb = s0; sb < s1; sb += kWG) {
             const long s = sb + tid;
             const bool live = s < s1;
-            float z[VE], zd[VE];
+            float z[VE], zd[VE], lnr[VE];
             const uint4 raw = raw_next;
             if (sb + kWG < s1) raw_next = load_slot<BF16, ALIGNED>(trow, (s + kWG < s1) ? s + kWG : s1 - 1, P.V);
             unpack<BF16>(raw, z);
@@ -215,15 +211,6 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
                     const float sv = __fmul_rn(z[e], P.inv_temp);
                     z[e] = (sv >= thr_b) ? sv : neg_inf();
                 }
-            }
-            if (P.mode == FSD_SAMPLE) {
-                // No variate is below -ln(24 ln 2) = -2.8116 (u >= 2^-24), so the largest logit seen minus
-                // 2.82 is already a score the winner must reach: most entries are ruled out before any
-                // variate has been evaluated at all.
-                float zm = neg_inf();
-#pragma unroll
-                for (int e = 0; e < VE; ++e) zm = fmaxf(zm, z[e]);
-                thr = fmaxf(thr, wave_max(live ? zm : neg_inf()) - 2.82f);
             }
             if (live) {
             float rres[VE];   // strict SD on a tree: p after the chain's rejections, minus the last draft row
@@ -254,51 +241,95 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
                 const uint4 rawd = load_slot<BF16, ALIGNED>(drow, s, P.V);
                 unpack<BF16>(rawd, zd);
             }
+            // ln of the residual's entries (-inf where it has no mass)
 #pragma unroll
-            for (int blk = 0; blk < VE / 4; ++blk) {
-                const long e0 = s * VE + blk * 4;
-                unsigned w4[4] = {0u, 0u, 0u, 0u};
-                if (P.mode == FSD_SAMPLE) {
-                    const U4 r = philox4x32_10(static_cast<unsigned>(e0 >> 2), static_cast<unsigned>(b), P.off_lo,
-                                               P.off_hi, P.seed_lo, P.seed_hi);
-                    w4[0] = r.x; w4[1] = r.y; w4[2] = r.z; w4[3] = r.w;
-                }
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float zz = z[blk * 4 + q];
-                    const int idx = static_cast<int>(e0 + q);
-                    bad |= !(zz < __builtin_inff());
-                    float lnr = neg_inf();
-                    if (residual) {
-                        float r;
-                        if constexpr (KIND == KIND_TREESD) {
-                            r = rres[blk * 4 + q];
-                        } else {
-                            const float p = hw_exp2(fmaf(zz, kLog2e, -lt));
-                            const float qq = hw_exp2(fmaf(zd[blk * 4 + q], kLog2e, -ld));
-                            r = p - qq;
-                        }
-                        if (r > 0.0f) lnr = hw_log2(r) * static_cast<float>(kLn2);
-                    }
-                    if (P.mode == FSD_SAMPLE) {
-                        const unsigned m = 0x00FFFFFFu ^ ((w4[q] >> 9) << 1);   // (1 - u) 2^24, odd, >= 1
-                        const float gb = fmaf(static_cast<float>(__clz(static_cast<int>(m)) - 7), 0.693148f, 1e-3f);
-                        const bool may = !(__fadd_rn(zz, gb) < thr) || (residual && !(__fadd_rn(lnr, gb) < rthr));
-                        if (may) {
-                            const float g = gumbel(w4[q]);
-                            const float score = __fadd_rn(zz, g);
-                            if (score > best.score) best = Best{score, idx};
-                            if (lnr > neg_inf()) {
-                                const float rs = __fadd_rn(lnr, g);
-                                if (rs > rbest.score) rbest = Best{rs, idx};
-                            }
-                        }
+            for (int e = 0; e < VE; ++e) {
+                bad |= !(z[e] < __builtin_inff());
+                lnr[e] = neg_inf();
+                if (residual) {
+                    float r;
+                    if constexpr (KIND == KIND_TREESD) {
+                        r = rres[e];
                     } else {
-                        if (zz > best.score) best = Best{zz, idx};
-                        if (lnr > rbest.score) rbest = Best{lnr, idx};
+                        const float p = hw_exp2(fmaf(z[e], kLog2e, -lt));
+                        const float qq = hw_exp2(fmaf(zd[e], kLog2e, -ld));
+                        r = p - qq;
                     }
+                    if (r > 0.0f) lnr[e] = hw_log2(r) * static_cast<float>(kLn2);
                 }
             }
+            }
+            if (P.mode == FSD_SAMPLE) {
+                // Bounds of a variate from the position c of the leading one of m = (1 - u) 2^24 alone
+                // (c = clz(m) - 8, so 2^-(c+1) <= 1 - u < 2^-c), G = -ln(-ln u) and -ln u between 1 - u and
+                // (1 - u)/u:
+                //     (c - 1) ln2 <= G <= (c + 1) ln2       (c >= 1; G >= -ln(24 ln2) = -2.8116 always)
+                // The largest lower bound of a score in the wavefront is a score the winner must reach, so
+                // an entry whose upper bound stays below it (or below a score already seen) cannot be the
+                // argmax: its variate, two exact-operation logarithms, is never evaluated.  1e-3 covers
+                // the rounding of that routine by a wide margin.
+                float gub[VE];
+                unsigned w[VE];
+                float lo = neg_inf(), rlo = neg_inf();
+                if (live) {
+#pragma unroll
+                    for (int blk = 0; blk < VE / 4; ++blk) {
+                        const long e0 = s * VE + blk * 4;
+                        const U4 r = philox4x32_10(static_cast<unsigned>(e0 >> 2), static_cast<unsigned>(b), P.off_lo,
+                                                   P.off_hi, P.seed_lo, P.seed_hi);
+                        w[blk * 4 + 0] = r.x; w[blk * 4 + 1] = r.y; w[blk * 4 + 2] = r.z; w[blk * 4 + 3] = r.w;
+                    }
+#pragma unroll
+                    for (int e = 0; e < VE; ++e) {
+                        const unsigned m = 0x00FFFFFFu ^ ((w[e] >> 9) << 1);   // (1 - u) 2^24, odd, >= 1
+                        const float c = static_cast<float>(__clz(static_cast<int>(m)) - 8);
+                        gub[e] = fmaf(c, 0.693148f, 0.693148f + 1e-3f);
+                        const float glb = (c >= 1.0f) ? fmaf(c, 0.693147f, -0.693148f - 1e-3f) : -2.82f;
+                        lo = fmaxf(lo, __fadd_rn(z[e], glb));      // (max() drops the NaN of a NaN logit)
+                        rlo = fmaxf(rlo, __fadd_rn(lnr[e], glb));
+                    }
+                }
+                thr = fmaxf(thr, wave_max(lo));
+                if (residual) rthr = fmaxf(rthr, wave_max(rlo));
+                // The entries that are left, at most a few per wavefront: every lane works through its own,
+                // lowest index first (one pass of the loop serves one entry of every lane that has any).
+                unsigned todo = 0;
+                if (live) {
+#pragma unroll
+                    for (int e = 0; e < VE; ++e) {
+                        const bool may = !(__fadd_rn(z[e], gub[e]) < thr) || (residual && !(__fadd_rn(lnr[e], gub[e]) < rthr));
+                        todo |= may ? (1u << e) : 0u;
+                    }
+                }
+                while (__any(todo != 0)) {
+                    if (todo != 0) {
+                        const int e = __builtin_ctz(todo);
+                        todo &= todo - 1;
+                        float zz = z[0], ll = lnr[0];
+                        unsigned ww = w[0];
+#pragma unroll
+                        for (int i = 1; i < VE; ++i) {
+                            zz = (e == i) ? z[i] : zz;
+                            ll = (e == i) ? lnr[i] : ll;
+                            ww = (e == i) ? w[i] : ww;
+                        }
+                        const int idx = static_cast<int>(s * VE + e);
+                        const float g = gumbel(ww);
+                        const float score = __fadd_rn(zz, g);
+                        if (score > best.score) best = Best{score, idx};
+                        if (ll > neg_inf()) {
+                            const float rs = __fadd_rn(ll, g);
+                            if (rs > rbest.score) rbest = Best{rs, idx};
+                        }
+                    }
+                }
+            } else if (live) {
+#pragma unroll
+                for (int e = 0; e < VE; ++e) {
+                    const int idx = static_cast<int>(s * VE + e);
+                    if (z[e] > best.score) best = Best{z[e], idx};
+                    if (lnr[e] > rbest.score) rbest = Best{lnr[e], idx};
+                }
             }
             if (P.mode == FSD_SAMPLE) {
                 thr = fmaxf(thr, wave_max(best.score));
