@@ -85,6 +85,8 @@ def library() -> ctypes.CDLL:
         L.fsd_debug_set_js_floor.restype = f32
         L.fsd_debug_set_exact_js.argtypes = [i32]
         L.fsd_debug_set_exact_js.restype = i32
+        L.fsd_debug_set_self_clear.argtypes = [i32]
+        L.fsd_debug_set_self_clear.restype = i32
         L.fsd_debug_set_spin_limit.argtypes = [c.c_uint]
         L.fsd_debug_set_spin_limit.restype = c.c_uint
         _lib = L
@@ -440,6 +442,11 @@ def debug_set_js_floor(floor_nats: float) -> float:
 def debug_set_exact_js(on: bool) -> bool:
     """bfloat16 JS in the pointwise form only (test hook); returns the previous setting"""
     return bool(library().fsd_debug_set_exact_js(1 if on else 0))
+
+
+def debug_set_self_clear(on: bool) -> bool:
+    """Test hook: False makes every verify call launch the clearing kernel; returns the previous setting."""
+    return bool(library().fsd_debug_set_self_clear(1 if on else 0))
 
 
 def debug_set_shape(wavefronts: int, slots_per_thread: int) -> None:

@@ -31,6 +31,7 @@ struct SampleParams {
     const float* thr;         // optional [B]: warpers, smallest kept scaled logit of the sampled row
     float inv_temp;           // warpers: binary32(1 / temperature), 1 otherwise
     unsigned spin_limit;      // bounded wait for the other workgroups' shares
+    int clear_arrive;         // a call without a clearing kernel: the arrival slots are cleared here (see pair_kernel.h)
     Ws ws;
 };
 
@@ -62,6 +63,14 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
     const int rows = P.rows;
 
     if (tid == 0) { s_n = rows; s_st = 0; s_key = 0; }
+    if (P.clear_arrive) {
+        // the reduction kernel has ended: its wavefronts' slots go back to zero, so that the same call
+        // replayed from a captured graph, with the same number, does not find them set
+        uint4* const slots = reinterpret_cast<uint4*>(P.ws.arrive);
+        const long nthreads = static_cast<long>(gridDim.x) * gridDim.y * kWG;
+        for (long i = (static_cast<long>(b) * gridDim.x + gs) * kWG + tid; i < kMaxArrive / 2; i += nthreads)
+            slots[i] = make_uint4(0u, 0u, 0u, 0u);
+    }
     __syncthreads();
 
     // ---- which positions are accepted
@@ -98,7 +107,7 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
         // (if the walk gave up on a bounded wait it may have written nothing: the header is then
         // whatever an earlier call left, so nothing in it is trusted)
         const int* hdr = P.ws.tsd + static_cast<size_t>(b) * (4 + rows);
-        const bool gave_up = P.ws.counters[1] != 0;
+        const bool gave_up = failure_flagged(P.ws);
         if (tid == 0) s_st = gave_up ? FSD_ROW_INTERNAL : hdr[0];
         n = gave_up ? 0 : hdr[1];
         sample_row = gave_up ? 0 : hdr[2] + 1;
@@ -163,7 +172,7 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
     }
     int status = s_st;
     if (status & FSD_ROW_BAD_PARENT) status &= ~FSD_ROW_TOO_DEEP;   // depths mean nothing in a malformed tree
-    if (P.ws.counters[1]) status |= FSD_ROW_INTERNAL;   // a bounded wait of the reduction kernel expired
+    if (failure_flagged(P.ws)) status |= FSD_ROW_INTERNAL;   // a bounded wait of the reduction kernel expired
 
     // ---- Gumbel-max over this workgroup's share of the sampled target row
     const char* trow = P.target + (static_cast<size_t>(b) * (rows + 1) + sample_row) * static_cast<size_t>(P.V) * ES;

@@ -308,7 +308,7 @@ __device__ __forceinline__ float gumbel(unsigned w) {
 // workspace view
 
 struct Ws {
-    unsigned* counters;  // 64 words ([1]: a bounded wait expired), then sdone
+    unsigned* counters;  // 64 words (words 2-3: the failure word, see flag_failure), then sdone
     unsigned* sdone;     // [B][kSdoneStride], first word: sampler workgroups that posted
     unsigned long long* part1;  // [R][G][n1] phase-1 words, dense: (kt,kd) | (St,Sd) in the two-phase modes (n1 = 2),
                                 // (kt,kd) | St | Sd | W in the single-pass ones (n1 = 4)
@@ -325,7 +325,23 @@ struct Ws {
                          // last node (-1 = root), length of the residual chain, then the chain's nodes
     float* tsd_invz;     // [B][rows] 1 / normaliser of the chain's residuals (all but the last)
     unsigned long long* wz;     // [B][rows][kWalkShare] the walk's partial normalisers, one round per rejection
+    unsigned long long* arrive; // [kMaxArrive] a call without a clearing kernel: wavefront i of the reduction kernel
+                                // writes the call's number here once it has cleared its words (never cleared
+                                // by a kernel before the reduction: only a word equal to the number counts)
+    unsigned long long nonce;   // the call's number: never 0, different for every call of the process
 };
+
+constexpr int kMaxArrive = 16384;   // wavefronts of a reduction grid that can announce themselves
+
+// "A bounded wait expired somewhere in this call": the failure word holds the call's own number.
+// Whatever else it holds (zero, an earlier call's number, what the memory held before) says nothing,
+// so the word needs no clearing and a flag raised early cannot be lost to a late clear.
+__device__ __forceinline__ void flag_failure(const Ws& w) {
+    __hip_atomic_store(reinterpret_cast<unsigned long long*>(w.counters + 2), w.nonce, __ATOMIC_RELAXED, AGENT);
+}
+__device__ __forceinline__ bool failure_flagged(const Ws& w) {
+    return __hip_atomic_load(reinterpret_cast<const unsigned long long*>(w.counters + 2), __ATOMIC_RELAXED, AGENT) == w.nonce;
+}
 
 struct PairParams {
     const char* target;
@@ -347,6 +363,14 @@ struct PairParams {
     float* user_ratio;      // optional [R], reducible FSD only
     int want_ratio;         // 1: the finisher also writes ln p(x) - ln q(x) at the candidate token (reducible FSD)
     float js_floor;         // entropy-form JS: results below this (nats) are evaluated again in the pointwise form
+    // A call without a clearing kernel of its own (see the start of pair_kernel): the wavefronts clear
+    // what they and the sampler need, [clear_a, +clear_a16) and [clear_b, +clear_b16) in 16-byte units
+    // being the parts no team owns.  0: a kernel before this one has cleared everything.
+    int self_clear;
+    uint4* clear_a;
+    long clear_a16;
+    uint4* clear_b;
+    long clear_b16;
     Ws ws;
 };
 

@@ -25,6 +25,7 @@
 #include <math.h>
 
 #include <atomic>
+#include <chrono>
 
 #include "fsd.h"
 
@@ -49,7 +50,7 @@ namespace {
 struct Plan {
     int VE, NV, G, spm, GS, sps;   // G = wavefronts per pair
     long nslots;
-    size_t off_counters, n_counters, off_state, off_wz, off_part1, zero_bytes, off_div, off_pst, off_lse2, off_lr, off_spart,
+    size_t off_counters, n_counters, off_state, off_wz, off_part1, off_arrive, zero_bytes, off_div, off_pst, off_lse2, off_lr, off_spart,
         off_thr, off_tsd, off_tsdz, bytes;
 };
 
@@ -104,8 +105,33 @@ bool make_plan(int B, int rows, long V, int dtype, Plan& p) {
     p.off_thr = o; o = align_up(o + static_cast<size_t>(B) * 4, 256);
     p.off_tsd = o; o = align_up(o + static_cast<size_t>(B) * (4 + rows) * 4, 256);
     p.off_tsdz = o; o = align_up(o + static_cast<size_t>(B) * rows * 4, 256);
+    p.off_arrive = o; o = align_up(o + static_cast<size_t>(kMaxArrive) * 8, 256);
     p.bytes = o;
     return true;
+}
+
+// upper bound of the wavefronts a grid of this device can hold at once (32 per compute unit)
+long max_resident_wavefronts() {
+    static long cached[16] = {};
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    if (dev < 0 || dev >= 16) dev = 0;
+    if (cached[dev] == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 1024;
+        cached[dev] = static_cast<long>(cus) * 32;
+    }
+    return cached[dev];
+}
+
+// a number for every call: never 0, never the same twice in a process, and unlikely to be what
+// another process left in memory (the failure word and the arrival slots compare against it)
+unsigned long long next_nonce() {
+    static std::atomic<unsigned long long> counter{
+        static_cast<unsigned long long>(std::chrono::steady_clock::now().time_since_epoch().count()) * 0x9E3779B97F4A7C15ull};
+    unsigned long long n = 0;
+    while (n == 0) n = counter.fetch_add(0x9E3779B97F4A7C15ull, std::memory_order_relaxed);
+    return n;
 }
 
 // G, n1, n2: wavefronts per pair and exchange words per member of this call's reduction kernel (never
@@ -130,6 +156,8 @@ Ws carve(void* workspace, const Plan& p, int B, int rows, int G, int n1, int n2,
     w.tsd = reinterpret_cast<int*>(base + p.off_tsd);
     w.tsd_invz = reinterpret_cast<float*>(base + p.off_tsdz);
     w.wz = reinterpret_cast<unsigned long long*>(base + p.off_wz);
+    w.arrive = reinterpret_cast<unsigned long long*>(base + p.off_arrive);
+    w.nonce = next_nonce();
     return w;
 }
 
@@ -139,6 +167,7 @@ unsigned g_spin_limit = 1u << 22;
 // caller sees is within 2e-3 relative everywhere (with a margin of five to ten).
 float g_js_floor = 1e-3f;
 bool g_exact_js = false;   // test hook: bfloat16 JS in the pointwise form only
+bool g_self_clear = true;  // test hook: 0 = every call launches the clearing kernel
 #ifdef FSD_PHASE_TIMING
 unsigned long long* g_dbg = nullptr;
 #endif
@@ -384,11 +413,27 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
     size_t zero_bytes = 0;
     const Ws ws = carve(workspace, p, B, rows, p.G, n1, n2, zero_bytes);
 
-    const long n16 = static_cast<long>(zero_bytes / 16);
-    hipLaunchKernelGGL(zero_counters, dim3(static_cast<unsigned>((n16 + 255) / 256)), dim3(256), 0, st,
-                       reinterpret_cast<uint4*>(ws.counters), n16);
+    // The chain calls have no clearing kernel: the reduction clears what it and the sampler need (see
+    // clear_own_words in pair_kernel.h; C2: -3 us a call).  The calls with a walk or a selection kernel
+    // between the two, whose own words must be clear as well, keep it, and so do the tree calls (measured:
+    // their reduction kernel loses what the missing kernel saves) and grids too large for the arrival slots.
+    const bool warped = (temperature != 1.0f) || (top_k > 0 && top_k < V) || (top_p < 1.0f);
+    const bool self_clear = g_self_clear && !tree && !(warped && mode == FSD_SAMPLE) &&
+                            max_resident_wavefronts() <= kMaxArrive;
+    if (!self_clear) {
+        const long n16 = static_cast<long>(zero_bytes / 16);
+        hipLaunchKernelGGL(zero_counters, dim3(static_cast<unsigned>((n16 + 255) / 256)), dim3(256), 0, st,
+                           reinterpret_cast<uint4*>(ws.counters), n16);
+    }
 
     PairParams pp;
+    pp.self_clear = self_clear ? 1 : 0;
+    // what no team owns: the sampler's counters (behind the 64 words that hold the failure word, which is
+    // never cleared here: a flag raised early must not be lost) and its shares
+    pp.clear_a = reinterpret_cast<uint4*>(ws.sdone);
+    pp.clear_a16 = static_cast<long>((p.n_counters - 64) * 4 / 16);
+    pp.clear_b = reinterpret_cast<uint4*>(ws.spart);
+    pp.clear_b16 = static_cast<long>(static_cast<size_t>(B) * p.GS * 32 / 16);
     pp.target = static_cast<const char*>(target);
     pp.draft = static_cast<const char*>(draft);
     pp.parent = tree ? parent : nullptr;
@@ -435,7 +480,7 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
     sp.spin_limit = g_spin_limit;
     sp.thr = nullptr;
     sp.inv_temp = 1.0f;
-    const bool warped = (temperature != 1.0f) || (top_k > 0 && top_k < V) || (top_p < 1.0f);
+    sp.clear_arrive = self_clear ? 1 : 0;
     if (warped && mode == FSD_SAMPLE) {
         // warpers: one more kernel finds, per sequence, the smallest kept scaled logit
         WarpParams wp;
@@ -688,6 +733,12 @@ float fsd_debug_set_js_floor(float floor_nats) {
 int fsd_debug_set_exact_js(int on) {
     const int prev = g_exact_js ? 1 : 0;
     g_exact_js = (on != 0);
+    return prev;
+}
+
+int fsd_debug_set_self_clear(int on) {
+    const int prev = g_self_clear ? 1 : 0;
+    g_self_clear = (on != 0);
     return prev;
 }
 

@@ -299,6 +299,59 @@ constexpr int pair_kernel_waves(bool bf16, int nv, int mode) {
 
 // TSHARED: target rows are shared between pairs (a tree) and are loaded to stay cached (a template
 // parameter, not a run-time decision: see load_item).
+// ---- a call without a clearing kernel ---------------------------------------------------------
+// Every kernel in a stream costs 4-5 us before its first instruction, whatever it does, so the plain
+// calls do not launch one to clear the exchange words: the reduction's own wavefronts do it.  A
+// wavefront clears the words it will post itself (its own words of its team's pairs, and the state
+// words of the pairs it finishes) and a slice of what no team owns (the sampler's shares and
+// counters, which the sampler only touches after this kernel has ended), waits until those stores
+// have been performed, and writes the call's number into its slot of `arrive`.  Nobody reads a word
+// of a pair but the members of the pair's team, so a wavefront that has seen the call's number in
+// the slots of all members of its team can take any word of theirs that is not zero as posted.  The
+// slots are never cleared before a call: what an earlier call or the allocation left there is not
+// this call's number.  (A captured call is replayed with the same number: the sampler, which follows
+// in every call, clears the slots again.)
+template <int N1, int PW, bool TWO_PHASE, bool JSE>
+__device__ __noinline__ void clear_own_words(unsigned long long* part1, unsigned long long* part2, unsigned long long* state,
+                                             uint4* clear_a, long a16, uint4* clear_b, long b16, int gwave, int nwaves,
+                                             int member, int GW, int pair0, int pstep, int n_mine) {
+    const int lane = threadIdx.x & 63;
+    for (int idx = lane; idx < n_mine; idx += 64) {
+        const size_t pr = static_cast<size_t>(pair0) + static_cast<size_t>(idx) * pstep;
+        unsigned long long* const w1 = part1 + (pr * GW + member) * N1;
+#pragma unroll
+        for (int k = 0; k < N1; ++k) post64(w1 + k, 0ull);
+        if constexpr (TWO_PHASE) {
+            unsigned long long* const w2 = part2 + (pr * GW + member) * PW;
+#pragma unroll
+            for (int k = 0; k < PW; ++k) post64(w2 + k, 0ull);
+        }
+        if constexpr (JSE) {
+            if (idx % GW == member) post64(state + pr, 0ull);   // the pairs this member finishes
+        }
+    }
+    const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+    for (long i = static_cast<long>(gwave) * 64 + lane; i < a16; i += static_cast<long>(nwaves) * 64) clear_a[i] = zero;
+    for (long i = static_cast<long>(gwave) * 64 + lane; i < b16; i += static_cast<long>(nwaves) * 64) clear_b[i] = zero;
+    // (the stores are still on their way when this returns: see where the wavefront announces itself)
+}
+// all members of the team have announced themselves (bounded wait)
+__device__ __noinline__ bool team_arrived(const unsigned long long* slots, int GW, unsigned long long nonce, unsigned limit) {
+    const int lane = threadIdx.x & 63;
+    for (int base = 0; base < GW; base += 64) {
+        const int m = base + lane;
+        const unsigned long long* const p = slots + ((m < GW) ? m : GW - 1);
+        unsigned polls = 0;
+        for (;;) {
+            const unsigned long long v = read64(p);
+            if (!__any(v != nonce)) break;
+            if (polls++ >= limit) return false;
+            __builtin_amdgcn_s_sleep(1);
+        }
+    }
+    return true;
+}
+
 template <bool BF16, int NV, int MODE, bool ALIGNED, bool TSHARED = false>
 __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(pair_kernel_waves(BF16, NV, MODE))))
 void pair_kernel(PairParams P) {
@@ -686,7 +739,7 @@ void pair_kernel(PairParams P) {
                 P.ws.div[pair] = static_cast<float>(value);
                 if (P.user_div) P.user_div[pair] = static_cast<float>(value);
                 P.ws.pst[pair] = status;
-                if (status & FSD_ROW_INTERNAL) atomicOr(P.ws.counters + 1, 1u);
+                if (status & FSD_ROW_INTERNAL) flag_failure(P.ws);
             }
             // the word every member of the team looks at before it leaves
             post64(P.ws.state + pair, state);
@@ -897,7 +950,7 @@ void pair_kernel(PairParams P) {
                 word[0] = pack2(acc, 0.0f);
             }
         }
-        if (!ok && lane == 0) atomicOr(P.ws.counters + 1, 1u);
+        if (!ok && lane == 0) flag_failure(P.ws);
         if (lane < PW) {
             unsigned long long mine = word[0];
 #pragma unroll
@@ -1177,6 +1230,14 @@ void pair_kernel(PairParams P) {
             if (iter % GW == member) { sp_pair = pair; sp_due = iter + sp_delay; }
         }
         PT(5);   // finishing duty
+        if (iter == 0 && P.self_clear) {
+            // A call without a clearing kernel: nothing of the team's has been read so far; from the next
+            // step on it is, so every member must have cleared its words by now.  (Not at the start of the
+            // kernel: the workgroups of a team start microseconds apart, and this step's work is what
+            // absorbs that.)
+            asm volatile("");   // stays a branch
+            if (!team_arrived(P.ws.arrive + team * GW, GW, P.ws.nonce, P.spin_limit)) flag_failure(P.ws);
+        }
         ++iter;
     };
 
@@ -1186,7 +1247,27 @@ void pair_kernel(PairParams P) {
     constexpr int NR = DEEP ? 3 : 1;
     uint4 rta[NR][NV], rtb[NR][NV];
     int pair = pair0;
-    if (pair < pair_end) load_item(rta[0], rtb[0], pair);
+    if (P.self_clear) {
+        const int n_mine = (pair_end > pair0) ? (pair_end - pair0 + pstep - 1) / pstep : 0;
+        clear_own_words<N1, PW, TWO_PHASE, JSE>(part1, part2, P.ws.state, P.clear_a, P.clear_a16, P.clear_b, P.clear_b16,
+                                                gwave, nteams * GW, member, GW, pair0, pstep, n_mine);
+    }
+    // (a team without pairs, which a tree's last teams can be, posts nothing and nobody waits for it)
+    if (pair >= pair_end) return;
+    asm volatile("" ::: "memory");
+    load_item(rta[0], rtb[0], pair);
+    {
+        // The first pair's logits are requested before the clearing stores are waited for.  Vector memory
+        // operations complete in the order they were issued, so once all but the 2 NV requests above have
+        // completed the stores have been performed (the exchange words are cleared with the device-scope
+        // stores they are always written with, which are performed at the memory side: no write-back of
+        // the cache is needed, and a release fence here would write back all of it from every wavefront,
+        // +25 us at C2; the sampler's words are cleared with ordinary stores, which the end of the kernel
+        // publishes).  Then lane 0 announces the wavefront.
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NV) : "memory");
+        if (P.self_clear && lane == 0) post64(P.ws.arrive + gwave, P.ws.nonce);
+        asm volatile("" ::: "memory");
+    }
     auto one_step = [&](auto SC, auto SP, int pr) __attribute__((always_inline)) {
         constexpr int c = decltype(SC)::value % NR, n = (decltype(SC)::value + 1) % NR;
         step(SC, SP, rta[c], rtb[c], rta[n], rtb[n], pr);
@@ -1253,7 +1334,7 @@ void pair_kernel(PairParams P) {
                 sw = read64(sp);
             }
             if (__any(valid && sw == 0)) {
-                if (lane == 0) atomicOr(P.ws.counters + 1, 1u);   // a finisher never came: the call reports it
+                if (lane == 0) flag_failure(P.ws);   // a finisher never came: the call reports it
             }
             unsigned long long todo = __ballot(valid && sw != 0 && sw != kJsDone);
             while (todo) {
@@ -1296,7 +1377,7 @@ void pair_kernel(PairParams P) {
                         P.ws.div[rp] = static_cast<float>(value);
                         if (P.user_div) P.user_div[rp] = static_cast<float>(value);
                         P.ws.pst[rp] = status;
-                        if (!ok) atomicOr(P.ws.counters + 1, 1u);
+                        if (!ok) flag_failure(P.ws);
                     }
                 }
             }

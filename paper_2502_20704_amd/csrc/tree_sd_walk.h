@@ -95,7 +95,7 @@ __global__ __launch_bounds__(kWalkWG) void tree_sd_walk(WalkParams P) {
     __syncthreads();
     int status = s_st;
     if (status & FSD_ROW_BAD_PARENT) status &= ~FSD_ROW_TOO_DEEP;
-    if (P.ws.counters[1]) status |= FSD_ROW_INTERNAL;
+    if (failure_flagged(P.ws)) status |= FSD_ROW_INTERNAL;
     if (status) {
         if (writer && tid == 0) { hdr[0] = status; hdr[1] = 0; hdr[2] = -1; hdr[3] = 0; }
         return;
@@ -232,7 +232,7 @@ __global__ __launch_bounds__(kWalkWG) void tree_sd_walk(WalkParams P) {
                 Z = 0.0;
                 for (int w = 0; w < GSW; ++w) Z += s_red[w];
                 if (Z != Z) {   // a workgroup of this sequence never posted: give up, the call reports it
-                    if (tid == 0) atomicOr(P.ws.counters + 1, 1u);
+                    if (tid == 0) flag_failure(P.ws);
                     return;
                 }
             }

@@ -123,7 +123,7 @@ __global__ __launch_bounds__(kWarpWG) void warp_select(WarpParams P) {
         if (tid == 0) s_n = key ? (kMaxRows - 1 - static_cast<int>(key & (kMaxRows - 1))) + 1 : 0;
         __syncthreads();
     }
-    if (s_st || P.ws.counters[1]) {   // nothing will be drawn for this sequence
+    if (s_st || failure_flagged(P.ws)) {   // nothing will be drawn for this sequence
         if (tid == 0) P.thr[b] = neg_inf();
         return;
     }

@@ -1160,3 +1160,55 @@ def test_bounded_wait_expires_cleanly(torch_cuda, oracle):
         assert (g["accept_len"] == 0).all() and (g["out_tokens"] == -1).all()
     g = run_chain(torch_cuda, inp, 0.1, fsd.DIV_JS)
     pu.check_chain(g, o, 0.1, 2e-3, "after restoring the poll budget")
+
+
+def test_chain_calls_without_a_clearing_kernel_on_dirty_workspaces(torch_cuda, oracle):
+    """The chain calls do not launch a kernel to clear their workspace: the reduction kernel's wavefronts
+    clear their own exchange words and announce themselves with the call's number.  Whatever the
+    workspace held must not matter: random bytes, all ones, the words another call on other inputs
+    left behind (the realistic case: valid-looking words of the wrong call), and the same again with the
+    clearing kernel switched back on.  JS (entropy form), TV (pointwise, two words per member), KL
+    (single pass), binary32 logits, strict SD, and a shape with several team members per pair."""
+    torch = torch_cuda
+    cases = [(3, 5, 40004, "bf16", "peaked", 1.0), (2, 4, 128256, "bf16", "peaked", (0.25, 4.0)),
+             (2, 3, 40004, "f32", "gauss2", 0.5), (5, 2, 4097, "bf16", "zipf", 1.0)]
+    try:
+        for on in (True, False):
+            fsd.debug_set_self_clear(on)
+            for ci, (B, K, V, dtype, kind, sigma) in enumerate(cases):
+                inp = synth.chain_inputs(B, K, V, dtype, kind, sigma, seed=60 + ci)
+                other = synth.chain_inputs(B, K, V, dtype, kind, sigma, seed=90 + ci)
+                d = pu.to_dev(inp, ("target", "draft", "cand"))
+                do = pu.to_dev(other, ("target", "draft", "cand"))
+                dt = fsd.BF16 if dtype == "bf16" else fsd.F32
+                need = fsd.fsd_workspace_bytes(B, K, V, dt)
+                ws = torch.empty(need + 256, dtype=torch.uint8, device="cuda")
+                gen = torch.Generator(device="cuda")
+                gen.manual_seed(5 + ci)
+                for div in (fsd.DIV_JS, fsd.DIV_TV, fsd.DIV_KL):
+                    o = oracle.verify_chain(inp["target"], inp["draft"], inp["cand"], 0.1, div, seed=8, offset=1)
+                    for dirt in ("random", "ones", "other call", "same call"):
+                        print(f"self_clear={on} case {ci} div {div} workspace: {dirt}", flush=True)
+                        if dirt == "random":
+                            ws.random_(0, 256, generator=gen)
+                        elif dirt == "ones":
+                            ws.fill_(255)
+                        elif dirt == "other call":
+                            fsd.fsd_verify_chain(do["target"], do["draft"], do["cand"], 0.3, div, fsd.SAMPLE, 1, 2, workspace=ws)
+                        out = fsd.fsd_verify_chain(d["target"], d["draft"], d["cand"], 0.1, div, fsd.SAMPLE, 8, 1, workspace=ws)
+                        torch.cuda.synchronize()
+                        g = pu.host(out, pu.CHAIN_KEYS)
+                        pu.check_chain(g, o, 0.1, pu.rel_tol(dtype), f"{dirt} workspace, case {ci}, div {div}, self_clear={on}",
+                                       envelope=pu.Envelope(dtype))
+                o = oracle.sd_verify_chain(inp["target"], inp["draft"], inp["cand"], fsd.SAMPLE, seed=6, offset=3)
+                for dirt in ("random", "other call"):
+                    print(f"self_clear={on} case {ci} strict SD workspace: {dirt}", flush=True)
+                    if dirt == "random":
+                        ws.random_(0, 256, generator=gen)
+                    else:
+                        fsd.sd_verify_chain(do["target"], do["draft"], do["cand"], fsd.SAMPLE, seed=2, offset=9, workspace=ws)
+                    out = fsd.sd_verify_chain(d["target"], d["draft"], d["cand"], fsd.SAMPLE, seed=6, offset=3, workspace=ws)
+                    torch.cuda.synchronize()
+                    check_sd(pu.host(out, pu.SD_KEYS), o, f"SD {dirt} workspace, case {ci}, self_clear={on}")
+    finally:
+        fsd.debug_set_self_clear(True)
