@@ -446,6 +446,14 @@ __global__ __launch_bounds__(kWG) void accept_sample(SampleParams P) {
     if (tid == 0) {
         P.out_len[b] = n;
         if (P.row_status) P.row_status[b] = status;
+        // The last workgroup of the last sequence to finish: every workgroup of this kernel has posted its
+        // share by now, and so has looked at the failure word, which nothing looks at after this kernel.
+        // It goes back to zero, so that the same call replayed from a captured graph, with the same
+        // number, does not find a failure of the last time.
+        const unsigned done = atomicAdd(P.ws.counters + 4, 1u);
+        if (done == gridDim.y - 1) {
+            __hip_atomic_store(reinterpret_cast<unsigned long long*>(P.ws.counters + 2), 0ull, __ATOMIC_RELAXED, AGENT);
+        }
     }
 }
 

@@ -308,7 +308,7 @@ __device__ __forceinline__ float gumbel(unsigned w) {
 // workspace view
 
 struct Ws {
-    unsigned* counters;  // 64 words (words 2-3: the failure word, see flag_failure), then sdone
+    unsigned* counters;  // 64 words (words 2-3: the failure word, see flag_failure; word 4: sequences the sampler has finished), then sdone
     unsigned* sdone;     // [B][kSdoneStride], first word: sampler workgroups that posted
     unsigned long long* part1;  // [R][G][n1] phase-1 words, dense: (kt,kd) | (St,Sd) in the two-phase modes (n1 = 2),
                                 // (kt,kd) | St | Sd | W in the single-pass ones (n1 = 4)

@@ -428,10 +428,10 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
 
     PairParams pp;
     pp.self_clear = self_clear ? 1 : 0;
-    // what no team owns: the sampler's counters (behind the 64 words that hold the failure word, which is
-    // never cleared here: a flag raised early must not be lost) and its shares
-    pp.clear_a = reinterpret_cast<uint4*>(ws.sdone);
-    pp.clear_a16 = static_cast<long>((p.n_counters - 64) * 4 / 16);
+    // what no team owns: the sampler's counters (all but the first four words: the failure word, words 2-3,
+    // is never cleared here, so that a flag raised early cannot be lost) and its shares
+    pp.clear_a = reinterpret_cast<uint4*>(ws.counters + 4);
+    pp.clear_a16 = static_cast<long>((p.n_counters - 4) * 4 / 16);
     pp.clear_b = reinterpret_cast<uint4*>(ws.spart);
     pp.clear_b16 = static_cast<long>(static_cast<size_t>(B) * p.GS * 32 / 16);
     pp.target = static_cast<const char*>(target);
