@@ -324,11 +324,11 @@ unsigned fsd_debug_set_spin_limit(unsigned polls);
 float fsd_debug_set_js_floor(float floor_nats);
 int fsd_debug_set_exact_js(int on);
 
-/* Test hook: the chain calls without warpers launch no kernel of their own to
- * clear the workspace's exchange words (the reduction kernel's wavefronts
- * clear what they will post and wait for their team to have done so).  0
- * makes every call launch the clearing kernel again, as the tree calls and
- * the warped calls always do; returns the previous setting. */
+/* Test hook: the verify calls without warpers (strict SD over a tree apart)
+ * launch no kernel of their own to clear the workspace's exchange words: the
+ * reduction kernel's wavefronts clear them and wait for their team to have
+ * done so.  0 makes every call launch the clearing kernel again, as the warped
+ * calls and sd_verify_tree always do; returns the previous setting. */
 int fsd_debug_set_self_clear(int on);
 
 /* Tuning hook: shape of the vocabulary-reduction kernel.  `wavefronts` per

@@ -413,12 +413,12 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
     size_t zero_bytes = 0;
     const Ws ws = carve(workspace, p, B, rows, p.G, n1, n2, zero_bytes);
 
-    // The chain calls have no clearing kernel: the reduction clears what it and the sampler need (see
-    // clear_own_words in pair_kernel.h; C2: -3 us a call).  The calls with a walk or a selection kernel
-    // between the two, whose own words must be clear as well, keep it, and so do the tree calls (measured:
-    // their reduction kernel loses what the missing kernel saves) and grids too large for the arrival slots.
+    // The plain calls have no clearing kernel: the reduction clears what it and the sampler need (see
+    // clear_own_words in pair_kernel.h; C2: -3 us a call, C4: -2 us).  The calls with a walk or a
+    // selection kernel between the two, whose own words must be clear as well, keep it, and so do grids
+    // too large for the arrival slots.
     const bool warped = (temperature != 1.0f) || (top_k > 0 && top_k < V) || (top_p < 1.0f);
-    const bool self_clear = g_self_clear && !tree && !(warped && mode == FSD_SAMPLE) &&
+    const bool self_clear = g_self_clear && kind != KIND_TREESD && !(warped && mode == FSD_SAMPLE) &&
                             max_resident_wavefronts() <= kMaxArrive;
     if (!self_clear) {
         const long n16 = static_cast<long>(zero_bytes / 16);

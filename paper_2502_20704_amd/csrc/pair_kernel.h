@@ -302,12 +302,13 @@ constexpr int pair_kernel_waves(bool bf16, int nv, int mode) {
 // ---- a call without a clearing kernel ---------------------------------------------------------
 // Every kernel in a stream costs 4-5 us before its first instruction, whatever it does, so the plain
 // calls do not launch one to clear the exchange words: the reduction's own wavefronts do it.  A
-// wavefront clears the words it will post itself (its own words of its team's pairs, and the state
-// words of the pairs it finishes) and a slice of what no team owns (the sampler's shares and
-// counters, which the sampler only touches after this kernel has ended), waits until those stores
-// have been performed, and writes the call's number into its slot of `arrive`.  Nobody reads a word
-// of a pair but the members of the pair's team, so a wavefront that has seen the call's number in
-// the slots of all members of its team can take any word of theirs that is not zero as posted.  The
+// wavefront clears its share of the words of its team's pairs (below) and a slice of what no team
+// owns (the sampler's shares and counters, which the sampler only touches after this kernel has
+// ended), waits until those stores have been performed, and writes the call's number into its slot
+// of `arrive`.  Nobody reads or, after its first step, writes a word of a pair but the members of
+// the pair's team, so a wavefront that has seen the call's number in the slots of all members of
+// its team, which it waits for at the end of its first step, can take any word of theirs that is
+// not zero as posted, and post to any word of the team's later pairs.  The
 // slots are never cleared before a call: what an earlier call or the allocation left there is not
 // this call's number.  (A captured call is replayed with the same number: the sampler, which follows
 // in every call, clears the slots again.)
@@ -316,19 +317,31 @@ __device__ __noinline__ void clear_own_words(unsigned long long* part1, unsigned
                                              uint4* clear_a, long a16, uint4* clear_b, long b16, int gwave, int nwaves,
                                              int member, int GW, int pair0, int pstep, int n_mine) {
     const int lane = threadIdx.x & 63;
-    for (int idx = lane; idx < n_mine; idx += 64) {
-        const size_t pr = static_cast<size_t>(pair0) + static_cast<size_t>(idx) * pstep;
-        unsigned long long* const w1 = part1 + (pr * GW + member) * N1;
-#pragma unroll
-        for (int k = 0; k < N1; ++k) post64(w1 + k, 0ull);
+    if (n_mine > 0) {
+        // The team's first pair: every member its own words, because it posts them in its first step, before
+        // it knows that the others have started.
+        const size_t pr = static_cast<size_t>(pair0);
+        if (lane < N1) post64(part1 + (pr * GW + member) * N1 + lane, 0ull);
         if constexpr (TWO_PHASE) {
-            unsigned long long* const w2 = part2 + (pr * GW + member) * PW;
-#pragma unroll
-            for (int k = 0; k < PW; ++k) post64(w2 + k, 0ull);
+            if (lane < PW) post64(part2 + (pr * GW + member) * PW + lane, 0ull);
         }
-        if constexpr (JSE) {
-            if (idx % GW == member) post64(state + pr, 0ull);   // the pairs this member finishes
+    }
+    // The later pairs are posted to after the first step, when the whole team has announced itself: their
+    // words are dealt to the members pair by pair, all members' words of a pair in one run of stores
+    // (a member clearing its own word of every pair would write 8 bytes per memory line: +24 us at
+    // 4096 pairs of 76 members).
+    for (int idx = 1 + member; idx < n_mine; idx += GW) {
+        const size_t pr = static_cast<size_t>(pair0) + static_cast<size_t>(idx) * pstep;
+        unsigned long long* const w1 = part1 + pr * GW * N1;
+        for (int w = lane; w < GW * N1; w += 64) post64(w1 + w, 0ull);
+        if constexpr (TWO_PHASE) {
+            unsigned long long* const w2 = part2 + pr * GW * PW;
+            for (int w = lane; w < GW * PW; w += 64) post64(w2 + w, 0ull);
         }
+    }
+    if constexpr (JSE) {   // (a state word is posted by its pair's finisher, steps after the pair's phase 1)
+        for (int idx = member * 64 + lane; idx < n_mine; idx += GW * 64)
+            post64(state + static_cast<size_t>(pair0) + static_cast<size_t>(idx) * pstep, 0ull);
     }
     const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
     for (long i = static_cast<long>(gwave) * 64 + lane; i < a16; i += static_cast<long>(nwaves) * 64) clear_a[i] = zero;

@@ -1162,8 +1162,8 @@ def test_bounded_wait_expires_cleanly(torch_cuda, oracle):
     pu.check_chain(g, o, 0.1, 2e-3, "after restoring the poll budget")
 
 
-def test_chain_calls_without_a_clearing_kernel_on_dirty_workspaces(torch_cuda, oracle):
-    """The chain calls do not launch a kernel to clear their workspace: the reduction kernel's wavefronts
+def test_calls_without_a_clearing_kernel_on_dirty_workspaces(torch_cuda, oracle):
+    """The plain calls do not launch a kernel to clear their workspace: the reduction kernel's wavefronts
     clear their own exchange words and announce themselves with the call's number.  Whatever the
     workspace held must not matter: random bytes, all ones, the words another call on other inputs
     left behind (the realistic case: valid-looking words of the wrong call), and the same again with the
@@ -1210,5 +1210,29 @@ def test_chain_calls_without_a_clearing_kernel_on_dirty_workspaces(torch_cuda, o
                     out = fsd.sd_verify_chain(d["target"], d["draft"], d["cand"], fsd.SAMPLE, seed=6, offset=3, workspace=ws)
                     torch.cuda.synchronize()
                     check_sd(pu.host(out, pu.SD_KEYS), o, f"SD {dirt} workspace, case {ci}, self_clear={on}")
+            # a tree (runs of consecutive pairs per team, teams without pairs at the end)
+            tinp = synth.tree_inputs(3, 14, 40004, "bf16", 1.0, seed=71, depth=4, topk=4)
+            toth = synth.tree_inputs(3, 14, 40004, "bf16", 1.0, seed=72, depth=4, topk=4)
+            md = int(tinp["max_depth"])
+            td = pu.to_dev(tinp, ("target", "draft", "node_tokens", "parent"))
+            to = pu.to_dev(toth, ("target", "draft", "node_tokens", "parent"))
+            need = fsd.fsd_workspace_bytes(3, 14, 40004, fsd.BF16)
+            ws = torch.empty(need + 256, dtype=torch.uint8, device="cuda")
+            for div in (fsd.DIV_JS, fsd.DIV_TV):
+                o = oracle.verify_tree(tinp["target"], tinp["draft"], tinp["node_tokens"], tinp["parent"], md, 0.15, div, seed=4)
+                for dirt in ("random", "ones", "other call"):
+                    print(f"self_clear={on} tree div {div} workspace: {dirt}", flush=True)
+                    if dirt == "random":
+                        ws.random_(0, 256)
+                    elif dirt == "ones":
+                        ws.fill_(255)
+                    else:
+                        fsd.fsd_verify_tree(to["target"], to["draft"], to["node_tokens"], to["parent"], int(toth["max_depth"]),
+                                            0.3, div, fsd.SAMPLE, 9, 0, workspace=ws)
+                    out = fsd.fsd_verify_tree(td["target"], td["draft"], td["node_tokens"], td["parent"], md, 0.15, div,
+                                              fsd.SAMPLE, 4, 0, workspace=ws)
+                    torch.cuda.synchronize()
+                    pu.check_tree(pu.host(out, pu.TREE_KEYS), o, 0.15, pu.rel_tol("bf16"),
+                                  f"tree, {dirt} workspace, div {div}, self_clear={on}", envelope=pu.Envelope("bf16"))
     finally:
         fsd.debug_set_self_clear(True)
