@@ -418,8 +418,10 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
     // selection kernel between the two, whose own words must be clear as well, keep it, and so do grids
     // too large for the arrival slots.
     const bool warped = (temperature != 1.0f) || (top_k > 0 && top_k < V) || (top_p < 1.0f);
+    // (Nor do calls with more than 4 MB to clear: inside the reduction kernel that costs what the
+    // kernel of its own costs, C3: 7.5 MB.)
     const bool self_clear = g_self_clear && kind != KIND_TREESD && !(warped && mode == FSD_SAMPLE) &&
-                            max_resident_wavefronts() <= kMaxArrive;
+                            zero_bytes <= (4u << 20) && max_resident_wavefronts() <= kMaxArrive;
     if (!self_clear) {
         const long n16 = static_cast<long>(zero_bytes / 16);
         hipLaunchKernelGGL(zero_counters, dim3(static_cast<unsigned>((n16 + 255) / 256)), dim3(256), 0, st,
