@@ -119,9 +119,9 @@ const char* fsd_status_string(int status);
  *                              0.001 to 0.3, and bit-identical rows give 0
  *   row_status    [B]   out    optional (NULL to skip), see FSD_ROW_*
  *
- * A call only enqueues kernels on hip_stream (the workspace is cleared by a
- * kernel, not by a memset), so it may be recorded into a HIP graph; seed and
- * offset are then part of the recording.
+ * A call only enqueues kernels on hip_stream (what it needs clear in the
+ * workspace is cleared by its kernels, never by a memset), so it may be
+ * recorded into a HIP graph; seed and offset are then part of the recording.
  */
 int fsd_verify_chain(const void* target_logits, const void* draft_logits, const int32_t* cand_tokens,
                      int B, int K, int V, int dtype, int div, float T, int mode, uint64_t seed,
@@ -324,11 +324,11 @@ unsigned fsd_debug_set_spin_limit(unsigned polls);
 float fsd_debug_set_js_floor(float floor_nats);
 int fsd_debug_set_exact_js(int on);
 
-/* Test hook: the verify calls without warpers (strict SD over a tree apart)
- * launch no kernel of their own to clear the workspace's exchange words: the
- * reduction kernel's wavefronts clear them and wait for their team to have
- * done so.  0 makes every call launch the clearing kernel again, as the warped
- * calls and sd_verify_tree always do; returns the previous setting. */
+/* Test hook: the verify calls launch no kernel of their own to clear the
+ * workspace's exchange words: the reduction kernel's wavefronts clear them and
+ * wait for their team to have done so (calls with more than 4 MB of such words
+ * apart).  0 makes every call launch the clearing kernel again; returns the
+ * previous setting. */
 int fsd_debug_set_self_clear(int on);
 
 /* Tuning hook: shape of the vocabulary-reduction kernel.  `wavefronts` per

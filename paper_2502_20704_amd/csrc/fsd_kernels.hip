@@ -1,7 +1,8 @@
 // Host side and C ABI of libfsd, the FSD candidate-verification step for gfx950 (MI355X).
 //
 // A verify call launches
-//   zero_counters   (device_common.h) clears the counters and exchange words of the call
+//   zero_counters   (device_common.h) clears the counters and exchange words of the call (only where there
+//                   are more than 4 MB of them: otherwise the reduction kernel does it itself)
 //   pair_kernel     (pair_kernel.h) the vocabulary reduction: one (target row, draft row) pair is
 //                   split over a team of G wavefronts; every wavefront loads its slice of both rows
 //                   ONCE into registers with 128-bit loads, the team exchanges the softmax
@@ -413,15 +414,12 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
     size_t zero_bytes = 0;
     const Ws ws = carve(workspace, p, B, rows, p.G, n1, n2, zero_bytes);
 
-    // The plain calls have no clearing kernel: the reduction clears what it and the sampler need (see
-    // clear_own_words in pair_kernel.h; C2: -3 us a call, C4: -2 us).  The calls with a walk or a
-    // selection kernel between the two, whose own words must be clear as well, keep it, and so do grids
-    // too large for the arrival slots.
+    // The calls have no clearing kernel: the reduction clears what it and the kernels after it need (see
+    // clear_own_words in pair_kernel.h; C2: -3 us a call, C4: -2 us), unless there are more than 4 MB to
+    // clear (inside the reduction kernel that costs what the kernel of its own costs, C3: 7.5 MB) or
+    // the grid is too large for the arrival slots.
     const bool warped = (temperature != 1.0f) || (top_k > 0 && top_k < V) || (top_p < 1.0f);
-    // (Nor do calls with more than 4 MB to clear: inside the reduction kernel that costs what the
-    // kernel of its own costs, C3: 7.5 MB.)
-    const bool self_clear = g_self_clear && kind != KIND_TREESD && !(warped && mode == FSD_SAMPLE) &&
-                            zero_bytes <= (4u << 20) && max_resident_wavefronts() <= kMaxArrive;
+    const bool self_clear = g_self_clear && zero_bytes <= (4u << 20) && max_resident_wavefronts() <= kMaxArrive;
     if (!self_clear) {
         const long n16 = static_cast<long>(zero_bytes / 16);
         hipLaunchKernelGGL(zero_counters, dim3(static_cast<unsigned>((n16 + 255) / 256)), dim3(256), 0, st,
@@ -434,8 +432,9 @@ int run(int kind, const void* target, const void* draft, const int32_t* tokens, 
     // is never cleared here, so that a flag raised early cannot be lost) and its shares
     pp.clear_a = reinterpret_cast<uint4*>(ws.counters + 4);
     pp.clear_a16 = static_cast<long>((p.n_counters - 4) * 4 / 16);
-    pp.clear_b = reinterpret_cast<uint4*>(ws.spart);
-    pp.clear_b16 = static_cast<long>(static_cast<size_t>(B) * p.GS * 32 / 16);
+    // (the walk's shares lie right before the sampler's: strict SD over a tree has both cleared)
+    pp.clear_b = reinterpret_cast<uint4*>(kind == KIND_TREESD ? reinterpret_cast<char*>(ws.wz) : reinterpret_cast<char*>(ws.spart));
+    pp.clear_b16 = static_cast<long>((p.off_part1 - (kind == KIND_TREESD ? p.off_wz : p.off_spart)) / 16);
     pp.target = static_cast<const char*>(target);
     pp.draft = static_cast<const char*>(draft);
     pp.parent = tree ? parent : nullptr;

@@ -1234,5 +1234,41 @@ def test_calls_without_a_clearing_kernel_on_dirty_workspaces(torch_cuda, oracle)
                     torch.cuda.synchronize()
                     pu.check_tree(pu.host(out, pu.TREE_KEYS), o, 0.15, pu.rel_tol("bf16"),
                                   f"tree, {dirt} workspace, div {div}, self_clear={on}", envelope=pu.Envelope("bf16"))
+            # a warped chain call (selection kernel between the reduction and the sampler) and strict SD over a
+            # tree (walk kernel with shares of its own), each after another call of its kind on other inputs
+            winp = synth.chain_inputs(3, 4, 40004, "bf16", "peaked", 1.0, seed=75)
+            woth = synth.chain_inputs(3, 4, 40004, "bf16", "peaked", 1.0, seed=76)
+            kw = dict(temperature=0.8, top_k=40, top_p=0.9)
+            need = fsd.fsd_workspace_bytes(3, 4, 40004, fsd.BF16)
+            ws = torch.empty(need + 256, dtype=torch.uint8, device="cuda")
+            wd, wo = pu.to_dev(winp, ("target", "draft", "cand")), pu.to_dev(woth, ("target", "draft", "cand"))
+            o = oracle.verify_chain_warped(winp["target"], winp["draft"], winp["cand"], 0.1, fsd.DIV_JS, fsd.SAMPLE, 5, 2, **kw)
+            for dirt in ("random", "other call"):
+                print(f"self_clear={on} warped chain workspace: {dirt}", flush=True)
+                if dirt == "random":
+                    ws.random_(0, 256)
+                else:
+                    fsd.fsd_verify_chain_warped(wo["target"], wo["draft"], wo["cand"], 0.3, fsd.DIV_JS, fsd.SAMPLE, 1, 1, workspace=ws, **kw)
+                out = fsd.fsd_verify_chain_warped(wd["target"], wd["draft"], wd["cand"], 0.1, fsd.DIV_JS, fsd.SAMPLE, 5, 2, workspace=ws, **kw)
+                torch.cuda.synchronize()
+                g = pu.host(out, pu.CHAIN_KEYS)
+                g["threshold"] = fsd.debug_warp_thresholds(out, 3, 4, 40004, fsd.BF16).cpu().numpy()
+                check_warped(g, o, 0.1, pu.rel_tol("bf16"), f"warped, {dirt} workspace, self_clear={on}")
+            rng = np.random.default_rng(17)
+            sinp = _random_tree_inputs(rng, 4, 12, 9000, "bf16")
+            soth = _random_tree_inputs(rng, 4, 12, 9000, "bf16")
+            need = fsd.fsd_workspace_bytes(4, 12, 9000, fsd.BF16)
+            ws = torch.empty(need + 256, dtype=torch.uint8, device="cuda")
+            sd_, so_ = (pu.to_dev(x, ("target", "draft", "node_tokens", "parent")) for x in (sinp, soth))
+            o = oracle.sd_verify_tree(sinp["target"], sinp["draft"], sinp["node_tokens"], sinp["parent"], 12, fsd.SAMPLE, seed=2, offset=2)
+            for dirt in ("random", "other call"):
+                print(f"self_clear={on} strict SD over a tree workspace: {dirt}", flush=True)
+                if dirt == "random":
+                    ws.random_(0, 256)
+                else:
+                    fsd.sd_verify_tree(so_["target"], so_["draft"], so_["node_tokens"], so_["parent"], 12, fsd.SAMPLE, 7, 7, workspace=ws)
+                out = fsd.sd_verify_tree(sd_["target"], sd_["draft"], sd_["node_tokens"], sd_["parent"], 12, fsd.SAMPLE, 2, 2, workspace=ws)
+                torch.cuda.synchronize()
+                check_sd_tree(pu.host(out, pu.TREESD_KEYS), o, f"sd tree, {dirt} workspace, self_clear={on}", sinp)
     finally:
         fsd.debug_set_self_clear(True)
